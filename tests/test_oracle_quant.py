@@ -1,0 +1,210 @@
+"""Pins for the oracle's quantizer, nibble packer, record format and read path."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import srft_oracle as O
+from paper_2605_05699_amd import workloads as W
+
+
+# ---------------------------------------------------------------- nibble packing
+def test_unpack_then_pack_is_identity_on_all_bytes():
+    b = np.arange(256, dtype=np.uint8).reshape(256, 1)
+    q = O.unpack_nibbles(b)
+    assert q.shape == (256, 2) and q.min() == -8 and q.max() == 7
+    assert np.array_equal(O.pack_nibbles(q), b)
+
+
+def test_pack_formula_on_all_code_pairs():
+    # Sec. 3.2 (ii): byte = (q[2i+1] << 4) | (q[2i] & 0xF), evaluated here with Python ints
+    for q0 in range(-8, 8):
+        for q1 in range(-8, 8):
+            byte = ((q1 << 4) | (q0 & 0xF)) & 0xFF
+            got = O.pack_nibbles(np.array([[q0, q1]]))[0, 0]
+            assert int(got) == byte
+            assert list(O.unpack_nibbles(np.array([[byte]], dtype=np.uint8))[0]) == [q0, q1]
+
+
+def test_pack_layout_low_nibble_is_even_index():
+    q = np.array([[1, -2, 3, -4, 7, -7, 0, -8]])
+    assert list(O.pack_nibbles(q)[0]) == [0xE1, 0xC3, 0x97, 0x80]
+
+
+# ---------------------------------------------------------------- record size
+def _golden(golden_dir):
+    vals, table = {}, []
+    with open(os.path.join(golden_dir, "paper_record_sizes.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if not line:
+                continue
+            if line[0] == "table":
+                table.append((line[1], int(line[2]), int(line[3]), int(line[4]),
+                              float(line[5]), float(line[6]), float(line[7])))
+            else:
+                vals[line[0]] = float(line[1])
+    return vals, table
+
+
+def test_record_bytes_matches_the_papers_ratios(golden_dir):
+    vals, table = _golden(golden_dir)
+    assert O.record_bytes(128, 32) == 80
+    assert O.record_bytes(256, 32) == 160
+    assert O.record_bytes(96, 32) == 60
+    assert round(2 * 64 / O.record_bytes(64, 64), 2) == vals["ratio_per_token_d64"]
+    assert round(2 * 128 / O.record_bytes(128, 128), 2) == vals["ratio_per_token_d128"]
+    assert round(2 * 128 / O.record_bytes(128, 32), 1) == vals["ratio_g32_d128"]
+    for _, d, layers, heads, fp16_16k, fp16_128k, int4_128k in table:
+        per_tok_vectors = layers * heads * 2
+        assert round(per_tok_vectors * 2 * d * 15625 / 1e9, 2) == fp16_16k
+        assert round(per_tok_vectors * 2 * d * 125000 / 1e9, 2) == fp16_128k
+        assert round(per_tok_vectors * O.record_bytes(d, d) * 125000 / 1e9, 2) == int4_128k
+
+
+# ---------------------------------------------------------------- quantizer
+CASES = [(128, 32), (256, 32), (96, 32), (64, 32), (128, 16), (128, 128), (32, 32), (24, 8)]
+
+
+@pytest.mark.parametrize("d,g", CASES)
+def test_quantizer_properties(d, g):
+    x = W.gaussian_with_outliers(200, d, seed=d + g, outliers=2, gain=20.0)
+    s = O.signs_from_seed(d, d)
+    lam = W.lognormal_lambda(d, seed=g)
+    out = O.quantize(x, s, lam, g)
+    q, sc, w, r = out["q"], out["scales"], out["w"], out["r"]
+    assert out["codes"].shape == (200, d // 2) and out["codes"].dtype == np.uint8
+    assert sc.shape == (200, d // g) and sc.dtype == np.float32
+    assert q.min() >= -7 and q.max() <= 7
+    # w really is lambda * SRFT(x)
+    assert np.allclose(w, O.srft_forward(x, s, form="fft") * lam.astype(np.float64), atol=1e-10)
+    scd = np.repeat(sc.astype(np.float64), g, axis=1)
+    # half-a-step error bound, to fp32 rounding of the scale
+    assert np.all(np.abs(w - q * scd) <= 0.5 * scd * (1 + 1e-6))
+    # scale is abs-max / 7 per contiguous group of the packed index
+    amax = np.abs(w).reshape(200, d // g, g).max(-1)
+    assert np.allclose(sc, amax / 7.0, rtol=1e-6)
+    # the abs-max element of every non-zero group gets magnitude exactly 7
+    assert np.all(np.abs(q).reshape(200, d // g, g).max(-1) == 7)
+    # codes are the round-half-even of the reported ratios, and the bytes hold those codes
+    assert np.array_equal(q, np.clip(np.rint(r), -7, 7).astype(np.int8))
+    assert np.array_equal(O.unpack_nibbles(out["codes"]), q)
+
+
+def test_rounding_is_half_to_even():
+    # build w directly: with lambda = 1 and x = Q^T w the packed coefficients are w (to 1e-15);
+    # use exactly representable halves so that ties are real ties.
+    d, g = 8, 8
+    Q = O.srft_matrix(d)
+    w = np.array([[7.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5]])
+    s = np.ones(d, dtype=np.int8)
+    out = O.quantize(w @ Q, s, np.ones(d), g)      # fp64 input on purpose: no fp16 rounding of x
+    # amax = 7 -> scale = 1 -> r = w up to 1e-15: ties cannot be tested through the transform,
+    # so check the rounding primitive on exact ties and the path on near-ties either side.
+    assert list(np.rint(np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5]))) == [0, 2, 2, -0, -2, -2, 4]
+    assert out["scales"][0, 0] == np.float32(1.0)
+    w2 = w.copy(); w2[0, 1:] += 1e-9 * np.sign(w2[0, 1:])
+    q2 = O.quantize(w2 @ Q, s, np.ones(d), g)["q"][0]
+    assert list(q2) == [7, 1, 2, 3, -1, -2, -3, 4]
+    w3 = w.copy(); w3[0, 1:] -= 1e-9 * np.sign(w3[0, 1:])
+    q3 = O.quantize(w3 @ Q, s, np.ones(d), g)["q"][0]
+    assert list(q3) == [7, 0, 1, 2, 0, -1, -2, 3]
+
+
+def test_per_token_special_case_matches_the_papers_quantizer():
+    # lambda = 1, g = d: one scale = absmax / (2^(b-1) - 1) per vector, round, clip (Sec. 3.2 steps 3-4)
+    d = 64
+    x = W.gaussian_with_outliers(50, d, seed=4)
+    s = O.signs_from_seed(4, d)
+    out = O.quantize(x, s, np.ones(d), d)
+    z = np.fft.rfft(x.astype(np.float64) * s, norm="ortho", axis=-1)
+    h = d // 2
+    zz = np.concatenate([z[:, :1].real, math.sqrt(2) * z[:, 1:h].real, z[:, h:h + 1].real,
+                         math.sqrt(2) * z[:, 1:h].imag], axis=1)
+    scale = (np.abs(zz).max(1) / (2 ** 3 - 1)).astype(np.float32)
+    assert np.array_equal(out["scales"][:, 0], scale)
+    qq = np.rint(zz / scale.astype(np.float64)[:, None])
+    near_tie = np.abs(np.abs(zz / scale.astype(np.float64)[:, None] % 1.0) - 0.5) < 1e-9
+    assert np.array_equal(out["q"][~near_tie], qq[~near_tie].astype(np.int8))
+
+
+def test_groups_are_formed_after_lambda_on_the_packed_index():
+    d, g = 128, 32
+    x = W.gaussian_with_outliers(20, d, seed=8)
+    s = O.signs_from_seed(8, d)
+    lam = np.ones(d); lam[40] = 1000.0          # blows up packed coordinate 40 -> only group 1's scale moves
+    a = O.quantize(x, s, np.ones(d), g)["scales"]
+    b = O.quantize(x, s, lam, g)["scales"]
+    assert np.array_equal(a[:, [0, 2, 3]], b[:, [0, 2, 3]])
+    assert np.all(b[:, 1] > 10 * a[:, 1])
+
+
+def test_zero_group_and_zero_vector():
+    d, g = 128, 32
+    s = O.signs_from_seed(1, d)
+    out = O.quantize(np.zeros((3, d), dtype=np.float16), s, np.ones(d), g)
+    assert not out["scales"].any() and not out["codes"].any()
+    back = O.dequantize(out["codes"], out["scales"], s, np.ones(d), g)
+    assert back.dtype == np.float16 and not back.any() and np.isfinite(back).all()
+
+
+# ---------------------------------------------------------------- read path
+@pytest.mark.parametrize("d,g", CASES)
+def test_dequantize_error_bound_and_forms(d, g):
+    x = W.gaussian_with_outliers(100, d, seed=3 * d + g, outliers=1, gain=30.0)
+    s = O.signs_from_seed(d + 1, d)
+    lam = W.lognormal_lambda(d, seed=d)
+    out = O.quantize(x, s, lam, g)
+    xh = O.dequantize_f64(out["codes"], out["scales"], s, lam, g)
+    xh_fft = O.dequantize_f64(out["codes"], out["scales"], s, lam, g, form="fft")
+    assert np.max(np.abs(xh - xh_fft)) < 1e-11
+    # orthogonality: ||xhat - x||^2 = sum_k ((w_k - q_k scale)/lambda_k)^2 <= sum_k (scale_j/(2 lambda_k))^2
+    scd = np.repeat(out["scales"].astype(np.float64), g, axis=1)
+    lhs = ((xh - x.astype(np.float64)) ** 2).sum(1)
+    exact = (((out["w"] - out["q"] * scd) / lam) ** 2).sum(1)
+    bound = ((scd / (2 * lam)) ** 2).sum(1)
+    assert np.allclose(lhs, exact, rtol=1e-9)
+    assert np.all(lhs <= bound * (1 + 1e-6))
+    h16 = O.dequantize(out["codes"], out["scales"], s, lam, g)
+    assert h16.dtype == np.float16
+    assert np.array_equal(h16, xh.astype(np.float16))
+
+
+def test_read_path_written_out_by_hand():
+    # d = 4, g = 2: every step of the inverse evaluated with Python scalars.
+    d, g = 4, 2
+    s = np.array([1, -1, -1, 1], dtype=np.int8)
+    lam = np.array([2.0, 0.5, 1e-9, 4.0])          # third one is below the 1e-6 clamp
+    codes = np.array([[0x2F, 0x81]], dtype=np.uint8)   # q = [-1, 2, 1, -8]
+    scales = np.array([[0.25, 3.0]], dtype=np.float32)
+    q = [-1, 2, 1, -8]
+    w = [q[0] * 0.25, q[1] * 0.25, q[2] * 3.0, q[3] * 3.0]
+    z = [w[0] / 2.0, w[1] / 0.5, w[2] / 1e-6, w[3] / 4.0]
+    # d=4: Y0 = z0, Y2 = z2, Y1 = (z1 + i z3)/sqrt2 ; u_n = (1/2) sum_k Y_k e^{+2 pi i k n/4}, Y3 = conj(Y1)
+    Y = [complex(z[0]), complex(z[1], z[3]) / math.sqrt(2), complex(z[2]), complex(z[1], -z[3]) / math.sqrt(2)]
+    u = [sum(Y[k] * complex(math.cos(2 * math.pi * k * n / 4), math.sin(2 * math.pi * k * n / 4))
+             for k in range(4)).real / 2 for n in range(4)]
+    ref = np.array([u[n] * int(s[n]) for n in range(4)])
+    got = O.dequantize_f64(codes, scales, s, lam, g)[0]
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-6)
+
+
+def test_nibble_minus_eight_is_decoded():
+    d, g = 32, 32
+    codes = np.full((1, d // 2), 0x88, dtype=np.uint8)
+    scales = np.ones((1, 1), dtype=np.float32)
+    s = np.ones(d, dtype=np.int8)
+    xh = O.dequantize_f64(codes, scales, s, np.ones(d), g)[0]
+    assert np.allclose(xh, O.srft_inverse(np.full((1, d), -8.0), s)[0])
+
+
+# ---------------------------------------------------------------- planted mistakes are caught
+def test_pins_would_catch_a_transposed_or_conjugated_matrix():
+    d = 16
+    Q = O.srft_matrix(d)
+    x = np.zeros((1, d)); x[0, 1] = 1.0
+    z = x @ Q.T
+    assert not np.allclose(z, x @ Q)                 # transposed operand differs on an impulse
+    Qc = Q.copy(); Qc[d // 2 + 1:] *= -1             # conjugate convention differs on the Im rows
+    assert not np.allclose(z, x @ Qc.T)
