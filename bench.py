@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the SRFT int4 KV-cache write + read path on one MI355X.
+
+A step is one pass of the whole hot path over the workload's cache: every plan's fp16 K/V tensor is
+quantized (one launch per plan), then every plan's int4 record is dequantized (one launch per plan).
+Inputs are synthetic, seeded, and resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/), in bytes,
+# for launches of the default workload; None until a counter run has been recorded.
+MEASURED_TRAFFIC = {
+}
+
+PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
+    "d128_ns_per_vec": 24.6, "d256_ns_per_vec": 50.0, "d128_gflops": 182.0,
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama3-70b-128k")
+    ap.add_argument("--plans", type=int, default=0, help="use only the first N plans (debugging; 0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--max-workgroups", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (vectors are independent; more GPUs would each take a share "
+              "of the layers with no exchange); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2605_05699_amd import binding as B
+    from paper_2605_05699_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.lib()
+    w = W.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    n_plans = args.plans if args.plans > 0 else w.n_plans
+    n = w.vectors_per_plan
+    d, g, G = w.d, w.g, w.d // w.g
+    bytes_per_vec = 2 * d + d // 2 + 4 * G
+
+    # the whole cache, resident: fp16 in, int4 + scales record, fp16 out
+    x = torch.empty(n_plans, n, d, dtype=torch.float16, device=dev)
+    codes = torch.empty(n_plans, n, d // 2, dtype=torch.uint8, device=dev)
+    scales = torch.empty(n_plans, n, G, dtype=torch.float32, device=dev)
+    out = torch.empty(n_plans, n, d, dtype=torch.float16, device=dev)
+    plans = []
+    for p in range(n_plans):
+        seed, lam, _ = W.plan_constants(w, p)
+        plans.append(B.Plan(d, g, seed, lam))
+        if args.max_workgroups:
+            B.srft_plan_set_max_workgroups(plans[-1].handle, args.max_workgroups)
+        W.fill_kv(x[p], w, p)
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+    h = [pl.handle for pl in plans]
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        for p in range(n_plans):
+            B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
+        if ev:
+            ev[1].record(stream)
+        for p in range(n_plans):
+            B.srft_kv_dequantize(h[p], codes[p], scales[p], out[p], stream)
+        if ev:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    tq = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps / 1e3     # seconds per step, write path
+    td = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps / 1e3     # read path
+    total_vec = n_plans * n
+    ms_per_step = wall / args.steps * 1e3
+
+    def roof(t_phase):
+        per_launch_s = t_phase / n_plans
+        achieved = n * bytes_per_vec / per_launch_s / 1e9
+        return per_launch_s, achieved
+
+    ql, qa = roof(tq)
+    dl, da = roof(td)
+    dominant = "srft_quantize_kernel" if tq >= td else "srft_dequantize_kernel"
+    dom_l, dom_a = (ql, qa) if tq >= td else (dl, da)
+    result = {
+        "metric": "quantize+dequantize vectors/s (full write pass then full read pass over the cache)",
+        "value": total_vec / (wall / args.steps),
+        "unit": "vectors/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
+                   "total_vectors": total_vec, "bytes_per_vector_each_direction": bytes_per_vec,
+                   "launches_per_step": 2 * n_plans},
+        "quantize": {"vectors_per_s": total_vec / tq, "ns_per_vec": tq / total_vec * 1e9, "GBps": qa,
+                     "hbm_frac": qa / HBM_PEAK_GBPS, "avg_launch_ms": ql * 1e3},
+        "dequantize": {"vectors_per_s": total_vec / td, "ns_per_vec": td / total_vec * 1e9, "GBps": da,
+                       "hbm_frac": da / HBM_PEAK_GBPS, "avg_launch_ms": dl * 1e3},
+        "roofline": {"kernel": dominant, "bound": "hbm", "achieved": dom_a, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": dom_a / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get((w.name, dominant)),
+                     "algorithmic_bytes_per_launch": n * bytes_per_vec, "avg_launch_ms": dom_l * 1e3},
+        "paper_context_apple_m1": PAPER_CONTEXT,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, x[0], plans[0], W)
+    for pl in plans:
+        pl.close()
+    print(json.dumps(result))
+    return 0
+
+
+def cpu_baseline(w, x0, plan0, W):
+    """The oracle as it stands, timed on this host over a bounded sample of plan 0 (write + read path)."""
+    import numpy as np
+    from oracle import srft_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    sample = min(x0.shape[0], 1 << 17)
+    xs = x0[:sample].cpu().numpy()
+    _, lam, _ = W.plan_constants(w, 0)
+    s = plan0.signs
+    t0 = time.perf_counter()
+    q = O.quantize(xs, s, lam, w.g)
+    t1 = time.perf_counter()
+    O.dequantize(q["codes"], q["scales"], s, lam, w.g)
+    t2 = time.perf_counter()
+    return {"value": sample / (t2 - t0), "unit": "vectors/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {sample} vectors of plan 0 of {w.name}: oracle quantize {t1 - t0:.2f} s + "
+                      f"dequantize {t2 - t1:.2f} s (numpy, float64, dense d x d form)",
+            "quantize_vectors_per_s": sample / (t1 - t0), "dequantize_vectors_per_s": sample / (t2 - t1)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,124 @@
+/*
+ * srft_kv.h -- C ABI of the fused SRFT int4 KV-cache quantizer for AMD MI355X (gfx950).
+ *
+ * Write path (paper Sec. 3.2 steps 1-4, Sec. 5.1 item 1, Sec. 7.1), per head-dim vector x in fp16:
+ *     u = s * x                      s in {-1,+1}^d, fixed per plan                       (Eq. 1)
+ *     z = pack(F u)                  F the unitary DFT, real packing of Eq. 2             (Eq. 1-2)
+ *     w = lambda * z                 per-channel rescale                                  (Sec. 5.1)
+ *     scale_j = max_{k in group j} |w_k| / 7,  groups = runs of g packed indices          (Sec. 7.1)
+ *     q_k = rint(w_k / scale_j) in [-7, 7]   (round half to even)                         (Sec. 3.2 step 4)
+ *     byte_i = (q_{2i+1} << 4) | (q_{2i} & 0xF)                                           (Sec. 3.2 (ii))
+ * Read path (the "matching inverse" of Sec. 7.1): unpack nibbles (4-bit two's complement), times
+ * scale_j, divide by max(lambda_k, 1e-6), unpack Eq. 2, unitary inverse DFT, times s, round to fp16.
+ *
+ * Stored record per vector: d/2 code bytes and d/g fp32 scales, in two separate arrays.
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses on the GPU that was current when the plan was
+ *     created; "host" pointers are ordinary host memory.  The caller owns every buffer it passes;
+ *     the library allocates only the plan's own constant tables and frees them in srft_plan_destroy.
+ *   - Calls that take a stream enqueue on it and return without synchronising.  hip_stream is a
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - Every function returns SRFT_OK (0) or a negative srft_status; nothing aborts or throws.
+ *     All argument checks happen before the first HIP call.
+ *   - Supported shapes: d a multiple of 32 with 32 <= d <= 256 (so 96 = 2^5 * 3 is covered; the
+ *     transform is applied as a dense d x d contraction, which needs no power-of-two length);
+ *     group_size 32.
+ */
+#ifndef SRFT_KV_H
+#define SRFT_KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct srft_plan srft_plan_t;   /* opaque; owned by the library */
+
+typedef enum srft_status {
+    SRFT_OK             =  0,
+    SRFT_ERR_NULL       = -1,   /* a required pointer is NULL */
+    SRFT_ERR_BAD_D      = -2,   /* d not a multiple of 32 in [32, 256] */
+    SRFT_ERR_BAD_GROUP  = -3,   /* group_size not supported (must be 32) */
+    SRFT_ERR_BAD_LAMBDA = -4,   /* a lambda is not finite, not > 0, or max/min exceeds 2^16 */
+    SRFT_ERR_ALIGN      = -5,   /* a device pointer is not aligned as documented */
+    SRFT_ERR_HIP        = -6,   /* a HIP call failed; see srft_last_hip_error() */
+    SRFT_ERR_BAD_N      = -7    /* n_vec < 0 or byte count negative */
+} srft_status;
+
+/*
+ * Build a plan: the constants of one (layer, K|V) pair.                 (Eq. 1; Sec. 5.1; Sec. 7.1-7.2)
+ *   out          receives the plan (host pointer to a host pointer).
+ *   d            head dimension.
+ *   group_size   g, the number of consecutive packed indices sharing one scale.
+ *   sign_seed    the sign diagonal is the splitmix64 stream started at this seed: s_n = -1 iff the
+ *                top bit of the n-th output is set ("drawn at initialization", Sec. 3.1).
+ *   lambda_host  d floats > 0 on the host, or NULL for all ones.  Copied; not kept.
+ * Allocates device tables on the current GPU (about 4*d*d bytes) and copies them once.
+ */
+int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_seed,
+                     const float* lambda_host);
+
+/* Free the plan and its device tables.  NULL is accepted.  Work already enqueued must have finished. */
+int srft_plan_destroy(srft_plan_t* plan);
+
+/*
+ * Write path over n_vec vectors.                                        (Sec. 3.2 steps 1-4, Sec. 7.1)
+ *   x_f16_dev   [n_vec, d] row-major IEEE fp16, 16-byte aligned.        read only
+ *   codes_dev   [n_vec, d/2] bytes, 16-byte aligned.                    written
+ *   scales_dev  [n_vec, d/g] fp32, 4-byte aligned.                      written
+ * n_vec == 0 is a successful no-op.  Inputs must be finite.  A group whose abs-max / 7 is below
+ * 2^-100 is stored as scale 0 with all-zero codes.
+ */
+int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec,
+                     uint8_t* codes_dev, float* scales_dev, void* hip_stream);
+
+/*
+ * Read path over n_vec vectors: the inverse of srft_kv_quantize.        (Sec. 7.1; sentence after Eq. 2)
+ *   codes_dev   [n_vec, d/2] bytes, 16-byte aligned.                    read only
+ *   scales_dev  [n_vec, d/g] fp32, 4-byte aligned.                      read only
+ *   out_f16_dev [n_vec, d] fp16 (round to nearest even), 16-byte aligned.  written
+ * Nibble 0x8 decodes as -8.
+ */
+int srft_kv_dequantize(const srft_plan_t* plan, const uint8_t* codes_dev, const float* scales_dev,
+                       int64_t n_vec, void* out_f16_dev, void* hip_stream);
+
+/*
+ * The transform alone, quantization disabled: w = lambda * pack(F (s * x)) in fp32.  (Eq. 1-2, Sec. 5.1)
+ *   x_f16_dev [n_vec, d] fp16, 16-byte aligned; w_f32_dev [n_vec, d] fp32, 16-byte aligned, written.
+ * Same kernel as the write path up to the abs-max; exists so that the transform can be checked
+ * on its own (orthonormality, closed forms).
+ */
+int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec,
+                        float* w_f32_dev, void* hip_stream);
+
+/* Plan introspection (host side, no HIP calls). */
+int srft_plan_d(const srft_plan_t* plan);             /* d, or a negative status */
+int srft_plan_group_size(const srft_plan_t* plan);    /* g */
+int srft_plan_groups(const srft_plan_t* plan);        /* d / g: scales per vector */
+int srft_plan_code_bytes(const srft_plan_t* plan);    /* d / 2: code bytes per vector */
+int srft_plan_get_signs(const srft_plan_t* plan, int8_t* out_host /* d entries, each -1 or +1 */);
+
+/*
+ * Launch shape: both kernels are persistent (a fixed grid loops over tiles of 32 vectors).
+ * max_workgroups > 0 caps the grid of this plan's launches; 0 restores the default
+ * (compute units x resident workgroups per unit).  For tuning sweeps.
+ */
+int srft_plan_set_max_workgroups(srft_plan_t* plan, int max_workgroups);
+
+/*
+ * Measurement aid, not part of the method: a plain streaming copy of n_bytes (a multiple of 16,
+ * both pointers 16-byte aligned) with the same grid shape as the kernels.  Used to calibrate the
+ * profiler's HBM byte counters and to measure the copy ceiling of the machine.
+ */
+int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* hip_stream);
+
+const char* srft_status_string(int status);
+int srft_last_hip_error(void);    /* the hipError_t of the most recent SRFT_ERR_HIP on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SRFT_KV_H */

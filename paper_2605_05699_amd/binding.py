@@ -1,0 +1,190 @@
+"""ctypes binding over libsrft_kv.so: argument marshalling only.
+
+Functions carry the names of the C entry points declared in ``include/srft_kv.h``
+and take torch tensors (device memory) where the C side takes device pointers.
+Every step of the method runs inside the library's HIP kernels; there is no
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsrft_kv.so")
+_lib = None
+
+EXPORTS = [
+    "srft_plan_create", "srft_plan_destroy", "srft_kv_quantize", "srft_kv_dequantize",
+    "srft_kv_forward_f32", "srft_plan_d", "srft_plan_group_size", "srft_plan_groups",
+    "srft_plan_code_bytes", "srft_plan_get_signs", "srft_plan_set_max_workgroups",
+    "srft_stream_copy", "srft_status_string", "srft_last_hip_error",
+]
+
+
+class SrftError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().srft_status_string(status).decode()
+        if status == -6:
+            msg += f" [hipError {lib().srft_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def lib() -> C.CDLL:
+    """Load the library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2605_05699_amd.build` "
+            "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, i64, u64, ci = C.c_void_p, C.c_int64, C.c_uint64, C.c_int
+    L.srft_plan_create.argtypes = [C.POINTER(vp), ci, ci, u64, vp]
+    L.srft_plan_destroy.argtypes = [vp]
+    L.srft_kv_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
+    L.srft_kv_dequantize.argtypes = [vp, vp, vp, i64, vp, vp]
+    L.srft_kv_forward_f32.argtypes = [vp, vp, i64, vp, vp]
+    for name in ("srft_plan_d", "srft_plan_group_size", "srft_plan_groups", "srft_plan_code_bytes"):
+        getattr(L, name).argtypes = [vp]
+    L.srft_plan_get_signs.argtypes = [vp, vp]
+    L.srft_plan_set_max_workgroups.argtypes = [vp, ci]
+    L.srft_stream_copy.argtypes = [vp, vp, i64, vp]
+    L.srft_status_string.argtypes = [ci]
+    L.srft_status_string.restype = C.c_char_p
+    L.srft_last_hip_error.argtypes = []
+    for name in EXPORTS:
+        if name != "srft_status_string":
+            getattr(L, name).restype = ci
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise SrftError(status, where)
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev_ptr(t: torch.Tensor, dtype, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous {dtype} tensor")
+    return t.data_ptr()
+
+
+# ---------------------------------------------------------------------------- C entry points
+def srft_plan_create(d: int, group_size: int, sign_seed: int, lam=None) -> int:
+    """Returns the opaque plan handle.  ``lam``: d positive floats (host) or None for all ones."""
+    handle = C.c_void_p()
+    lam_ptr = None
+    if lam is not None:
+        lam_arr = np.ascontiguousarray(np.asarray(lam, dtype=np.float32))
+        if lam_arr.shape != (d,):
+            raise ValueError("lambda must have d entries")
+        lam_ptr = lam_arr.ctypes.data_as(C.c_void_p)
+    _check(lib().srft_plan_create(C.byref(handle), d, group_size, sign_seed & (2 ** 64 - 1), lam_ptr),
+           "srft_plan_create")
+    return handle.value
+
+
+def srft_plan_destroy(plan: int) -> None:
+    _check(lib().srft_plan_destroy(plan), "srft_plan_destroy")
+
+
+def srft_kv_quantize(plan: int, x: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, stream=None) -> None:
+    n = x.shape[0]
+    _check(lib().srft_kv_quantize(plan, _dev_ptr(x, torch.float16, "x"), n,
+                                  _dev_ptr(codes, torch.uint8, "codes"),
+                                  _dev_ptr(scales, torch.float32, "scales"), _stream_handle(stream)),
+           "srft_kv_quantize")
+
+
+def srft_kv_dequantize(plan: int, codes: torch.Tensor, scales: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    n = codes.shape[0]
+    _check(lib().srft_kv_dequantize(plan, _dev_ptr(codes, torch.uint8, "codes"),
+                                    _dev_ptr(scales, torch.float32, "scales"), n,
+                                    _dev_ptr(out, torch.float16, "out"), _stream_handle(stream)),
+           "srft_kv_dequantize")
+
+
+def srft_kv_forward_f32(plan: int, x: torch.Tensor, w: torch.Tensor, stream=None) -> None:
+    _check(lib().srft_kv_forward_f32(plan, _dev_ptr(x, torch.float16, "x"), x.shape[0],
+                                     _dev_ptr(w, torch.float32, "w"), _stream_handle(stream)),
+           "srft_kv_forward_f32")
+
+
+def srft_plan_get_signs(plan: int) -> np.ndarray:
+    d = lib().srft_plan_d(plan)
+    out = np.empty(d, dtype=np.int8)
+    _check(lib().srft_plan_get_signs(plan, out.ctypes.data_as(C.c_void_p)), "srft_plan_get_signs")
+    return out
+
+
+def srft_plan_set_max_workgroups(plan: int, n: int) -> None:
+    _check(lib().srft_plan_set_max_workgroups(plan, n), "srft_plan_set_max_workgroups")
+
+
+def srft_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and dst.is_cuda and src.is_cuda
+    _check(lib().srft_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream)),
+           "srft_stream_copy")
+
+
+# ---------------------------------------------------------------------------- convenience wrapper
+class Plan:
+    """One (layer, K|V) plan.  Allocates outputs with torch when none are passed; computes nothing itself."""
+
+    def __init__(self, d: int, group_size: int = 32, sign_seed: int = 0, lam=None):
+        self.handle = srft_plan_create(d, group_size, sign_seed, lam)
+        self.d, self.g = d, group_size
+        self.groups = lib().srft_plan_groups(self.handle)
+        self.code_bytes = lib().srft_plan_code_bytes(self.handle)
+
+    def close(self) -> None:
+        if self.handle:
+            srft_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def signs(self) -> np.ndarray:
+        return srft_plan_get_signs(self.handle)
+
+    def quantize(self, x, codes=None, scales=None, stream=None):
+        n = x.shape[0]
+        if codes is None:
+            codes = torch.empty(n, self.code_bytes, dtype=torch.uint8, device=x.device)
+        if scales is None:
+            scales = torch.empty(n, self.groups, dtype=torch.float32, device=x.device)
+        srft_kv_quantize(self.handle, x, codes, scales, stream)
+        return codes, scales
+
+    def dequantize(self, codes, scales, out=None, stream=None):
+        if out is None:
+            out = torch.empty(codes.shape[0], self.d, dtype=torch.float16, device=codes.device)
+        srft_kv_dequantize(self.handle, codes, scales, out, stream)
+        return out
+
+    def forward_f32(self, x, w=None, stream=None):
+        if w is None:
+            w = torch.empty(x.shape[0], self.d, dtype=torch.float32, device=x.device)
+        srft_kv_forward_f32(self.handle, x, w, stream)
+        return w

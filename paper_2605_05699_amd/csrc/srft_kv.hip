@@ -1,0 +1,601 @@
+// srft_kv.hip -- fused SRFT int4 KV-cache quantizer / dequantizer for MI355X (gfx950).
+//
+// How the path is mapped to CDNA4
+// -------------------------------
+// Per vector the method is: sign flip, unitary real DFT with the real packing of Eq. 2, per-channel
+// lambda, per-group abs-max, round to int4, nibble pack (Sec. 3.2, Sec. 5.1, Sec. 7.1).  Sign, DFT,
+// packing and lambda are all linear, so together they are ONE real d x d matrix
+//     W = diag(lambda) * Q * diag(s),        Q = pack o F   (orthogonal),
+// and the read path is the matrix  R = diag(s) * Q^T * diag(1 / max(lambda, 1e-6)).
+// At 5.6 TB/s a d = 128 vector has about 37 compute-unit clocks; a butterfly FFT plus the fp16
+// conversions needs about 3000 vector-ALU lane operations per vector, more than the 64 lanes x 37
+// clocks available, whereas the matrix cores do the dense product with time to spare.  So the
+// transform runs on MFMA (v_mfma_f32_32x32x16_f16) and the vector ALU only does the quantizer.
+//
+// Exactness: x is fp16, hence an exact MFMA operand.  W is split on the host into two fp16
+// matrices W = Whi + Wlo (after a power-of-two scaling that keeps Wlo out of the fp16 denormal
+// range); both products accumulate into the same fp32 accumulator, which gives about 22 bits of W.
+// On the read path the codes (integers in [-8, 7]) are exact fp16 operands; the per-(vector, group)
+// scale cannot enter the matrix, so each group's 32 codes are contracted separately (K = 32) and
+// the partial results are combined as  x = sum_j scale_j * P_j  on the vector ALU in fp32.
+//
+// Work decomposition: a workgroup has d/32 wavefronts and walks over tiles of 32 vectors
+// (persistent grid).  Wavefront w owns the 32 output rows 32w..32w+31 -- on the write path that is
+// exactly quantization group w, so the abs-max needs a single cross-lane step -- and keeps its
+// 32 x d slab of the matrix (hi and lo) in registers for the whole launch.  The 32 x d operand tile
+// (inputs, or decoded codes) is loaded once per workgroup with coalesced 16-byte accesses, staged in
+// LDS (double buffered, one barrier per tile, reached by every thread) and read by every wavefront.
+// The MFMA row order inside a slab is permuted on the host so that a lane ends up holding 16
+// CONSECUTIVE outputs: 16 nibbles = one 8-byte store on the write path, 16 fp16 = two 16-byte
+// stores on the read path, with no cross-lane shuffles.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "srft_kv.h"
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kTileVecs = 32;          // vectors per tile = N of the 32x32x16 MFMA
+constexpr int kMaxD = 256;
+constexpr float kMinScale = 7.888609052210118e-31f;   // 2^-100: below this a group is stored as zero
+
+// ------------------------------------------------------------------------------------------
+// device helpers
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float other_half_max(float m) {
+    // lanes l and l^32 hold the two halves of one vector's group: one v_permlane32_swap.
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// Eight values already multiplied by 1/scale -> eight two's-complement nibbles in one dword.
+// Adding 1.5*2^23 + 8 rounds to nearest-even and leaves q + 8 (1..15) in the low four bits above a
+// constant bit pattern; a shift-add chain concatenates the nibbles (no borrows because q + 8 > 0),
+// the constant is subtracted once and flipping bit 3 of each nibble turns q + 8 into q mod 16.
+__device__ __forceinline__ uint32_t pack8(const floatx16& acc, int base, float inv) {
+    constexpr float kMagic = 12582912.0f + 8.0f;
+    constexpr uint32_t kMagicBits = 0x4B400000u;
+    uint32_t p = __float_as_uint(fmaf(acc[base + 7], inv, kMagic));
+#pragma unroll
+    for (int i = 6; i >= 0; --i) p = (p << 4) + __float_as_uint(fmaf(acc[base + i], inv, kMagic));
+    uint32_t k = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) k += kMagicBits << (4 * i);
+    return (p - k) ^ 0x88888888u;
+}
+
+// ------------------------------------------------------------------------------------------
+// write path
+// ------------------------------------------------------------------------------------------
+// wfrag : [D/32 waves][D/16 k-steps][hi, lo][64 lanes] 16-byte A-operand fragments of W
+// x     : [n_vec][D/8] 16-byte units of fp16 input
+// RAW   : store the fp32 coefficients w instead of quantizing (srft_kv_forward_f32)
+template <int D, bool RAW>
+__global__ void __launch_bounds__(2 * D)
+srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
+                     uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
+                     float unscale) {
+    constexpr int G = D / 32;            // wavefronts per workgroup = groups per vector
+    constexpr int T = D / 16;            // MFMA k-steps
+    constexpr int U = D / 8;             // 16-byte units per input row
+    constexpr int ROW = U + 1;           // padded LDS row (odd number of units: conflict-free b128 reads)
+    constexpr int NT = 64 * G;
+    __shared__ uint4 lds[2][kTileVecs * ROW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
+
+    half8 ahi[T], alo[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        ahi[t] = __builtin_bit_cast(half8, wfrag[((wave * T + t) * 2 + 0) * 64 + lane]);
+        alo[t] = __builtin_bit_cast(half8, wfrag[((wave * T + t) * 2 + 1) * 64 + lane]);
+    }
+
+    // each thread moves two 16-byte units of the 32 x D tile (32 * U = 2 * NT units)
+    const int u0 = tid, u1 = tid + NT;
+    const int r0 = u0 / U, c0 = u0 % U, r1 = u1 / U, c1 = u1 % U;
+    uint4 pre0, pre1;
+    auto fetch = [&](long long tile) {
+        const long long row0 = tile * kTileVecs;
+        const uint4 zero = {0, 0, 0, 0};
+        pre0 = (row0 + r0 < n_vec) ? x[row0 * U + u0] : zero;
+        pre1 = (row0 + r1 < n_vec) ? x[row0 * U + u1] : zero;
+    };
+
+    long long tile = blockIdx.x;
+    if (tile < n_tiles) fetch(tile);
+    int buf = 0;
+    for (; tile < n_tiles; tile += gridDim.x) {
+        lds[buf][r0 * ROW + c0] = pre0;
+        lds[buf][r1 * ROW + c1] = pre1;
+        const long long next = tile + gridDim.x;
+        if (next < n_tiles) fetch(next);
+        __syncthreads();                     // uniform: every thread runs the same trip count
+
+        floatx16 acc = {0};
+        const uint4* rowp = &lds[buf][col * ROW + half];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const half8 b = __builtin_bit_cast(half8, rowp[2 * t]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[t], b, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[t], b, acc, 0, 0, 0);
+        }
+
+        const long long vec = tile * kTileVecs + col;
+        if constexpr (RAW) {
+            if (vec < n_vec) {
+                float4* o = wout + (vec * D + 32 * wave + 16 * half) / 4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    o[i] = make_float4(acc[4 * i] * unscale, acc[4 * i + 1] * unscale,
+                                       acc[4 * i + 2] * unscale, acc[4 * i + 3] * unscale);
+            }
+        } else {
+            float m = fmaxf(fabsf(acc[0]), fabsf(acc[1]));
+#pragma unroll
+            for (int v = 2; v < 16; ++v) m = fmaxf(m, fabsf(acc[v]));
+            m = other_half_max(m);
+            float scale = (m * unscale) / 7.0f;
+            float inv = unscale * __builtin_amdgcn_rcpf(scale);
+            if (!(scale >= kMinScale)) { scale = 0.0f; inv = 0.0f; }
+            uint2 packed;
+            packed.x = pack8(acc, 0, inv);
+            packed.y = pack8(acc, 8, inv);
+            if (vec < n_vec) {
+                codes[vec * (D / 16) + 2 * wave + half] = packed;
+                if (half == 0) scales[vec * G + wave] = scale;
+            }
+        }
+        buf ^= 1;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// read path
+// ------------------------------------------------------------------------------------------
+// One dword of eight nibbles -> eight exact fp16 codes, as four packed pairs (n_m, n_{m+4}).
+// 0x6400 | u is the fp16 number 1024 + u; with u = q + 8 a packed fp16 subtract of 1032 leaves q.
+__device__ __forceinline__ uint4 decode8(uint32_t v) {
+    v ^= 0x88888888u;
+    const half2v bias = {(_Float16)1032.0f, (_Float16)1032.0f};
+    uint4 o;
+    o.x = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, (v & 0x000F000Fu) | 0x64006400u) - bias);
+    o.y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, ((v >> 4) & 0x000F000Fu) | 0x64006400u) - bias);
+    o.z = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, ((v >> 8) & 0x000F000Fu) | 0x64006400u) - bias);
+    o.w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, ((v >> 12) & 0x000F000Fu) | 0x64006400u) - bias);
+    return o;
+}
+
+__device__ __forceinline__ uint32_t pack_half2(float a, float b) {
+    const half2v h = {(_Float16)a, (_Float16)b};      // round to nearest even
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// rfrag : [D/32 waves][D/32 groups][2 k-steps][hi, lo][64 lanes] 16-byte A-operand fragments of R
+// codes : [n_vec][D/16] 8-byte units; scales : [n_vec][D/32]; out : [n_vec][D/8] 16-byte units of fp16
+template <int D>
+__global__ void __launch_bounds__(2 * D)
+srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
+                       const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
+                       float unscale) {
+    constexpr int G = D / 32;
+    constexpr int U = D / 8;             // 16-byte units per decoded row (D fp16)
+    constexpr int ROW = U + 1;
+    constexpr int C = D / 16;            // 8-byte code units per row
+    __shared__ uint4 lds[2][kTileVecs * ROW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
+
+    half8 rhi[G][2], rlo[G][2];
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            rhi[j][t] = __builtin_bit_cast(half8, rfrag[(((wave * G + j) * 2 + t) * 2 + 0) * 64 + lane]);
+            rlo[j][t] = __builtin_bit_cast(half8, rfrag[(((wave * G + j) * 2 + t) * 2 + 1) * 64 + lane]);
+        }
+
+    // each thread decodes one 8-byte unit of the 32 x D/2 code tile (32 * C = 64 * G units)
+    const int r0 = tid / C, c0 = tid % C;
+    uint2 pre;
+    float sc[G];
+    auto fetch = [&](long long tile) {
+        const long long row0 = tile * kTileVecs;
+        const uint2 zero = {0, 0};
+        pre = (row0 + r0 < n_vec) ? codes[row0 * C + tid] : zero;
+        const bool ok = row0 + col < n_vec;
+#pragma unroll
+        for (int j = 0; j < G; ++j) sc[j] = ok ? scales[(row0 + col) * G + j] : 0.0f;
+    };
+
+    long long tile = blockIdx.x;
+    if (tile < n_tiles) fetch(tile);
+    int buf = 0;
+    for (; tile < n_tiles; tile += gridDim.x) {
+        lds[buf][r0 * ROW + 2 * c0] = decode8(pre.x);
+        lds[buf][r0 * ROW + 2 * c0 + 1] = decode8(pre.y);
+        float s[G];
+#pragma unroll
+        for (int j = 0; j < G; ++j) s[j] = sc[j] * unscale;
+        const long long next = tile + gridDim.x;
+        if (next < n_tiles) fetch(next);
+        __syncthreads();
+
+        floatx16 o = {0};
+        const uint4* rowp = &lds[buf][col * ROW + half];
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            floatx16 acc = {0};
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const half8 b = __builtin_bit_cast(half8, rowp[4 * j + 2 * t]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[j][t], b, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j][t], b, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[v] = fmaf(acc[v], s[j], o[v]);
+        }
+
+        const long long vec = tile * kTileVecs + col;
+        if (vec < n_vec) {
+            uint4* dst = out + vec * U + 4 * wave + 2 * half;
+            dst[0] = make_uint4(pack_half2(o[0], o[1]), pack_half2(o[2], o[3]),
+                                pack_half2(o[4], o[5]), pack_half2(o[6], o[7]));
+            dst[1] = make_uint4(pack_half2(o[8], o[9]), pack_half2(o[10], o[11]),
+                                pack_half2(o[12], o[13]), pack_half2(o[14], o[15]));
+        }
+        buf ^= 1;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+srft_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, long long n_units) {
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n_units; i += stride)
+        dst[i] = src[i];
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return SRFT_ERR_HIP;
+}
+#define SRFT_HIP(call)                                   \
+    do {                                                 \
+        hipError_t e_ = (call);                          \
+        if (e_ != hipSuccess) return hip_fail(e_);       \
+    } while (0)
+
+// double -> IEEE fp16 bits, round to nearest even, subnormals kept, overflow to infinity.
+uint16_t f16_bits(double v) {
+    const uint16_t sign = std::signbit(v) ? 0x8000u : 0u;
+    double a = std::fabs(v);
+    if (std::isnan(v)) return 0x7E00u;
+    if (a >= 65520.0) return sign | 0x7C00u;
+    if (a == 0.0) return sign;
+    int e;
+    std::frexp(a, &e);                    // a = m * 2^e, m in [0.5, 1)
+    int E = e - 1;                        // a in [2^E, 2^(E+1))
+    if (E < -14) E = -14;                 // subnormal range shares the quantum 2^-24
+    const double r = std::nearbyint(std::ldexp(a, 10 - E));   // exact scaling, ties to even
+    int mant = (int)r;                    // in [0, 2048]
+    if (mant >= 2048) { mant = 1024; ++E; }
+    if (mant < 1024) return sign | (uint16_t)mant;            // subnormal (E == -14)
+    return sign | (uint16_t)(((E + 15) << 10) | (mant - 1024));
+}
+
+double f16_value(uint16_t b) {
+    const int e = (b >> 10) & 0x1F, m = b & 0x3FF;
+    double v = (e == 0) ? std::ldexp((double)m, -24) : std::ldexp((double)(m + 1024), e - 25);
+    return (b & 0x8000u) ? -v : v;
+}
+
+uint64_t splitmix64_next(uint64_t& state) {
+    state += 0x9E3779B97F4A7C15ull;
+    uint64_t z = state;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Q[k][n] of the packed unitary real DFT (Eq. 1-2), rfft sign convention.
+double q_entry(int d, int k, int n) {
+    const int h = d / 2;
+    const double pi = 3.14159265358979323846;
+    if (k == 0) return 1.0 / std::sqrt((double)d);
+    if (k == h) return ((n & 1) ? -1.0 : 1.0) / std::sqrt((double)d);
+    const int kk = (k < h) ? k : k - h;
+    const double ang = 2.0 * pi * (double)((long long)kk * n % d) / (double)d;
+    return (k < h) ? std::sqrt(2.0 / d) * std::cos(ang) : -std::sqrt(2.0 / d) * std::sin(ang);
+}
+
+// slab row i of the 32x32 MFMA result (row = 8r + 4h + c) <-> output 16h + 4r + c of the slab,
+// so that the 16 accumulators of a lane (r = v / 4, c = v % 4) are outputs 16h .. 16h + 15.
+int slab_output_of_row(int i) {
+    const int r = i / 8, h = (i / 4) % 2, c = i % 4;
+    return 16 * h + 4 * r + c;
+}
+
+}  // namespace
+
+struct srft_plan {
+    int d = 0, g = 0, device = 0;
+    uint64_t seed = 0;
+    std::vector<int8_t> signs;
+    uint4* wfrag = nullptr;     // write-path matrix fragments (device)
+    uint4* rfrag = nullptr;     // read-path matrix fragments (device)
+    float unscale_w = 1.0f;     // 2^-e of the write matrix
+    float unscale_r = 1.0f;
+    int grid_q = 0, grid_dq = 0;    // default persistent grid sizes
+    int max_wgs = 0;
+};
+
+namespace {
+
+template <int D>
+int occupancy_grids(srft_plan* p, int cus) {
+    int bq = 0, bd = 0;
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, srft_quantize_kernel<D, false>, 2 * D, 0));
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, srft_dequantize_kernel<D>, 2 * D, 0));
+    p->grid_q = cus * (bq > 0 ? bq : 1);
+    p->grid_dq = cus * (bd > 0 ? bd : 1);
+    return SRFT_OK;
+}
+
+template <int D>
+int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* codes, float* scales,
+                    float* wout, hipStream_t st) {
+    const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
+    long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_q;
+    if (grid > n_tiles) grid = n_tiles;
+    if (wout)
+        hipLaunchKernelGGL((srft_quantize_kernel<D, true>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
+                           (const uint4*)x, n, (uint2*)nullptr, (float*)nullptr, (float4*)wout, p->unscale_w);
+    else
+        hipLaunchKernelGGL((srft_quantize_kernel<D, false>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
+                           (const uint4*)x, n, (uint2*)codes, scales, (float4*)nullptr, p->unscale_w);
+    SRFT_HIP(hipGetLastError());
+    return SRFT_OK;
+}
+
+template <int D>
+int launch_dequantize(const srft_plan* p, const uint8_t* codes, const float* scales, long long n, void* out,
+                      hipStream_t st) {
+    const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
+    long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_dq;
+    if (grid > n_tiles) grid = n_tiles;
+    hipLaunchKernelGGL((srft_dequantize_kernel<D>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->rfrag,
+                       (const uint2*)codes, scales, n, (uint4*)out, p->unscale_r);
+    SRFT_HIP(hipGetLastError());
+    return SRFT_OK;
+}
+
+#define SRFT_DISPATCH_D(d, fn, ...)                       \
+    switch (d) {                                          \
+        case 32:  return fn<32>(__VA_ARGS__);             \
+        case 64:  return fn<64>(__VA_ARGS__);             \
+        case 96:  return fn<96>(__VA_ARGS__);             \
+        case 128: return fn<128>(__VA_ARGS__);            \
+        case 160: return fn<160>(__VA_ARGS__);            \
+        case 192: return fn<192>(__VA_ARGS__);            \
+        case 224: return fn<224>(__VA_ARGS__);            \
+        case 256: return fn<256>(__VA_ARGS__);            \
+        default:  return SRFT_ERR_BAD_D;                  \
+    }
+
+int dispatch_occupancy(srft_plan* p, int cus) { SRFT_DISPATCH_D(p->d, occupancy_grids, p, cus) }
+int dispatch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* c, float* s, float* w,
+                      hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_quantize, p, x, n, c, s, w, st) }
+int dispatch_dequantize(const srft_plan* p, const uint8_t* c, const float* s, long long n, void* o,
+                        hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_dequantize, p, c, s, n, o, st) }
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Scale a matrix by the power of two that puts its largest magnitude in [2^13, 2^14) and split every
+// entry into fp16 hi + fp16 lo.  Returns the exponent e (entries were multiplied by 2^e).
+int split_hi_lo(const std::vector<double>& m, std::vector<uint16_t>& hi, std::vector<uint16_t>& lo) {
+    double mx = 0.0;
+    for (double v : m) mx = std::fmax(mx, std::fabs(v));
+    int e2;
+    std::frexp(mx, &e2);                 // mx in [2^(e2-1), 2^e2)
+    const int e = 14 - e2;
+    hi.resize(m.size());
+    lo.resize(m.size());
+    for (size_t i = 0; i < m.size(); ++i) {
+        const double v = std::ldexp(m[i], e);
+        hi[i] = f16_bits(v);
+        lo[i] = f16_bits(v - f16_value(hi[i]));
+    }
+    return e;
+}
+
+}  // namespace
+
+extern "C" {
+
+int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_seed, const float* lambda_host) {
+    if (!out) return SRFT_ERR_NULL;
+    *out = nullptr;
+    if (d < 32 || d > kMaxD || d % 32 != 0) return SRFT_ERR_BAD_D;
+    if (group_size != 32) return SRFT_ERR_BAD_GROUP;
+    std::vector<double> lam(d, 1.0);
+    if (lambda_host) {
+        double lo = INFINITY, hi = 0.0;
+        for (int k = 0; k < d; ++k) {
+            const float v = lambda_host[k];
+            if (!std::isfinite(v) || !(v > 0.0f)) return SRFT_ERR_BAD_LAMBDA;
+            lam[k] = (double)v;
+            lo = std::fmin(lo, lam[k]);
+            hi = std::fmax(hi, lam[k]);
+        }
+        if (hi / lo > 65536.0) return SRFT_ERR_BAD_LAMBDA;
+    }
+
+    srft_plan* p = new (std::nothrow) srft_plan();
+    if (!p) return SRFT_ERR_HIP;
+    p->d = d;
+    p->g = group_size;
+    p->seed = sign_seed;
+    p->signs.resize(d);
+    uint64_t state = sign_seed;
+    for (int n = 0; n < d; ++n) p->signs[n] = (splitmix64_next(state) >> 63) ? -1 : 1;
+
+    // W[k][n] = lambda_k Q[k][n] s_n ; R[n][k] = s_n Q[k][n] / max(lambda_k, 1e-6)
+    std::vector<double> W((size_t)d * d), R((size_t)d * d);
+    for (int k = 0; k < d; ++k)
+        for (int n = 0; n < d; ++n) {
+            const double q = q_entry(d, k, n) * (double)p->signs[n];
+            W[(size_t)k * d + n] = lam[k] * q;
+            R[(size_t)n * d + k] = q / std::fmax(lam[k], 1e-6);
+        }
+    std::vector<uint16_t> whi, wlo, rhi, rlo;
+    p->unscale_w = (float)std::ldexp(1.0, -split_hi_lo(W, whi, wlo));
+    p->unscale_r = (float)std::ldexp(1.0, -split_hi_lo(R, rhi, rlo));
+
+    // A-operand fragments: lane l holds row l % 32 of the slab and contraction indices 8 (l / 32) + e.
+    const int G = d / 32, T = d / 16;
+    std::vector<uint16_t> wf((size_t)G * T * 2 * 64 * 8), rf((size_t)G * G * 2 * 2 * 64 * 8);
+    for (int w = 0; w < G; ++w)
+        for (int l = 0; l < 64; ++l) {
+            const int row = 32 * w + slab_output_of_row(l % 32), kh = l / 32;
+            for (int t = 0; t < T; ++t)           // write path: contraction index = input position n
+                for (int e = 0; e < 8; ++e) {
+                    const size_t src = (size_t)row * d + (16 * t + 8 * kh + e);
+                    wf[((((size_t)w * T + t) * 2 + 0) * 64 + l) * 8 + e] = whi[src];
+                    wf[((((size_t)w * T + t) * 2 + 1) * 64 + l) * 8 + e] = wlo[src];
+                }
+            for (int j = 0; j < G; ++j)           // read path: group j, code dword 4j + 2t + kh,
+                for (int t = 0; t < 2; ++t)       // element e <-> nibble e/2 + 4 (e % 2) of that dword
+                    for (int e = 0; e < 8; ++e) {
+                        const int k = 8 * (4 * j + 2 * t + kh) + (e / 2) + 4 * (e % 2);
+                        const size_t src = (size_t)row * d + k;
+                        rf[(((((size_t)w * G + j) * 2 + t) * 2 + 0) * 64 + l) * 8 + e] = rhi[src];
+                        rf[(((((size_t)w * G + j) * 2 + t) * 2 + 1) * 64 + l) * 8 + e] = rlo[src];
+                    }
+        }
+
+    hipError_t e = hipGetDevice(&p->device);
+    int cus = 0;
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&p->wfrag, wf.size() * 2);
+    if (e == hipSuccess) e = hipMalloc((void**)&p->rfrag, rf.size() * 2);
+    if (e == hipSuccess) e = hipMemcpy(p->wfrag, wf.data(), wf.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(p->rfrag, rf.data(), rf.size() * 2, hipMemcpyHostToDevice);
+    int rc = (e == hipSuccess) ? dispatch_occupancy(p, cus) : hip_fail(e);
+    if (rc != SRFT_OK) {
+        srft_plan_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return SRFT_OK;
+}
+
+int srft_plan_destroy(srft_plan_t* plan) {
+    if (!plan) return SRFT_OK;
+    hipError_t e1 = plan->wfrag ? hipFree(plan->wfrag) : hipSuccess;
+    hipError_t e2 = plan->rfrag ? hipFree(plan->rfrag) : hipSuccess;
+    delete plan;
+    if (e1 != hipSuccess) return hip_fail(e1);
+    if (e2 != hipSuccess) return hip_fail(e2);
+    return SRFT_OK;
+}
+
+int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, uint8_t* codes_dev,
+                     float* scales_dev, void* hip_stream) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (n_vec < 0) return SRFT_ERR_BAD_N;
+    if (n_vec == 0) return SRFT_OK;
+    if (!x_f16_dev || !codes_dev || !scales_dev) return SRFT_ERR_NULL;
+    if (!aligned(x_f16_dev, 16) || !aligned(codes_dev, 16) || !aligned(scales_dev, 4)) return SRFT_ERR_ALIGN;
+    return dispatch_quantize(plan, x_f16_dev, n_vec, codes_dev, scales_dev, nullptr, (hipStream_t)hip_stream);
+}
+
+int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, float* w_f32_dev,
+                        void* hip_stream) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (n_vec < 0) return SRFT_ERR_BAD_N;
+    if (n_vec == 0) return SRFT_OK;
+    if (!x_f16_dev || !w_f32_dev) return SRFT_ERR_NULL;
+    if (!aligned(x_f16_dev, 16) || !aligned(w_f32_dev, 16)) return SRFT_ERR_ALIGN;
+    return dispatch_quantize(plan, x_f16_dev, n_vec, nullptr, nullptr, w_f32_dev, (hipStream_t)hip_stream);
+}
+
+int srft_kv_dequantize(const srft_plan_t* plan, const uint8_t* codes_dev, const float* scales_dev, int64_t n_vec,
+                       void* out_f16_dev, void* hip_stream) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (n_vec < 0) return SRFT_ERR_BAD_N;
+    if (n_vec == 0) return SRFT_OK;
+    if (!codes_dev || !scales_dev || !out_f16_dev) return SRFT_ERR_NULL;
+    if (!aligned(codes_dev, 16) || !aligned(scales_dev, 4) || !aligned(out_f16_dev, 16)) return SRFT_ERR_ALIGN;
+    return dispatch_dequantize(plan, codes_dev, scales_dev, n_vec, out_f16_dev, (hipStream_t)hip_stream);
+}
+
+int srft_plan_d(const srft_plan_t* plan) { return plan ? plan->d : SRFT_ERR_NULL; }
+int srft_plan_group_size(const srft_plan_t* plan) { return plan ? plan->g : SRFT_ERR_NULL; }
+int srft_plan_groups(const srft_plan_t* plan) { return plan ? plan->d / plan->g : SRFT_ERR_NULL; }
+int srft_plan_code_bytes(const srft_plan_t* plan) { return plan ? plan->d / 2 : SRFT_ERR_NULL; }
+
+int srft_plan_get_signs(const srft_plan_t* plan, int8_t* out_host) {
+    if (!plan || !out_host) return SRFT_ERR_NULL;
+    std::memcpy(out_host, plan->signs.data(), plan->signs.size());
+    return SRFT_OK;
+}
+
+int srft_plan_set_max_workgroups(srft_plan_t* plan, int max_workgroups) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (max_workgroups < 0) return SRFT_ERR_BAD_N;
+    plan->max_wgs = max_workgroups;
+    return SRFT_OK;
+}
+
+int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* hip_stream) {
+    if (n_bytes < 0 || n_bytes % 16 != 0) return SRFT_ERR_BAD_N;
+    if (n_bytes == 0) return SRFT_OK;
+    if (!dst_dev || !src_dev) return SRFT_ERR_NULL;
+    if (!aligned(dst_dev, 16) || !aligned(src_dev, 16)) return SRFT_ERR_ALIGN;
+    int dev = 0, cus = 0;
+    SRFT_HIP(hipGetDevice(&dev));
+    SRFT_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const long long units = n_bytes / 16;
+    long long grid = (long long)cus * 8;
+    if (grid > (units + 255) / 256) grid = (units + 255) / 256;
+    hipLaunchKernelGGL(srft_copy_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, (uint4*)dst_dev,
+                       (const uint4*)src_dev, units);
+    SRFT_HIP(hipGetLastError());
+    return SRFT_OK;
+}
+
+const char* srft_status_string(int status) {
+    switch (status) {
+        case SRFT_OK: return "ok";
+        case SRFT_ERR_NULL: return "required pointer is NULL";
+        case SRFT_ERR_BAD_D: return "unsupported head dimension (need a multiple of 32 in [32, 256])";
+        case SRFT_ERR_BAD_GROUP: return "unsupported group size (need 32)";
+        case SRFT_ERR_BAD_LAMBDA: return "lambda must be finite, > 0 and span at most 2^16";
+        case SRFT_ERR_ALIGN: return "device pointer is misaligned";
+        case SRFT_ERR_HIP: return "HIP call failed (see srft_last_hip_error)";
+        case SRFT_ERR_BAD_N: return "negative or malformed size";
+        default: return "unknown status";
+    }
+}
+
+int srft_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

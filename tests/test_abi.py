@@ -1,0 +1,89 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares,
+and rejects bad arguments before touching HIP."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2605_05699_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2605_05699_amd import build
+        build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "srft_kv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(srft_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert "srft_plan_create" in names and "srft_kv_quantize" in names and "srft_kv_dequantize" in names
+    for name in names:
+        assert hasattr(L, name), f"{name} declared in srft_kv.h but not exported"
+    from paper_2605_05699_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_status_strings(L):
+    for code in range(0, -9, -1):
+        assert L.srft_status_string(code)
+    assert L.srft_status_string(0) == b"ok"
+
+
+def test_plan_create_rejects_bad_arguments_before_any_hip_call(L):
+    h = C.c_void_p()
+    lam = (C.c_float * 256)(*([1.0] * 256))
+    assert L.srft_plan_create(None, 128, 32, 0, None) == -1
+    for d in (0, 2, 16, 31, 100, 130, 288, 512, -128):
+        assert L.srft_plan_create(C.byref(h), d, 32, 0, None) == -2, d
+        assert h.value is None
+    for g in (0, 16, 64, 128, 33):
+        assert L.srft_plan_create(C.byref(h), 128, g, 0, None) == -3, g
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        lam[17] = bad
+        assert L.srft_plan_create(C.byref(h), 128, 32, 0, lam) == -4, bad
+    lam[17] = 1.0
+    lam[3] = 1e-3
+    lam[4] = 1e3            # ratio 1e6 > 2^16
+    assert L.srft_plan_create(C.byref(h), 128, 32, 0, lam) == -4
+
+
+def test_null_plan_and_size_errors(L):
+    assert L.srft_kv_quantize(None, None, 1, None, None, None) == -1
+    assert L.srft_kv_dequantize(None, None, None, 1, None, None) == -1
+    assert L.srft_kv_forward_f32(None, None, 1, None, None) == -1
+    assert L.srft_plan_d(None) == -1
+    assert L.srft_plan_destroy(None) == 0
+    assert L.srft_stream_copy(None, None, 24, None) == -7
+    assert L.srft_stream_copy(None, None, 32, None) == -1
+    assert L.srft_stream_copy(None, None, 0, None) == 0
+
+
+def test_workload_table_matches_the_stated_shapes():
+    from paper_2605_05699_amd import workloads as W
+    w = W.WORKLOADS
+    assert w["tiny"].total_vectors == 512
+    assert w["qwen2.5-1.5b-4k"].total_vectors == 458_752
+    assert w["gemma3-1b-4k"].total_vectors == 212_992
+    assert w["decode-d96"].append_vectors_per_plan * w["decode-d96"].n_plans == 32_768
+    assert w["decode-d96"].vectors_per_plan == 4_194_304
+    assert w["llama3-70b-128k"].vectors_per_plan == 1_048_576
+    assert w["llama3-70b-128k"].total_vectors == 167_772_160
+    # generators are deterministic and plan-specific
+    a = W.make_kv(w["tiny"], 0)
+    b = W.make_kv(w["tiny"], 0)
+    c = W.make_kv(w["tiny"], 1)
+    assert a.shape == (256, 128) and bool((a == b).all()) and not bool((a == c).all())
+    seed, lam, gain = W.plan_constants(w["tiny"], 0)
+    assert lam.shape == (128,) and (lam > 0).all() and int((gain == 20).sum()) == 4
+    assert np.isclose(float(a.float().std()), float(np.sqrt((gain ** 2).mean())), rtol=0.1)
