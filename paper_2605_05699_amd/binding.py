@@ -14,7 +14,7 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libsrft_kv.so")
+LIB_PATH = os.environ.get("SRFT_KV_LIB") or os.path.join(_PKG, "libsrft_kv.so")
 _lib = None
 
 EXPORTS = [

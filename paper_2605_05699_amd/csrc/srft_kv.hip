@@ -34,6 +34,7 @@
 #include <cstdint>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "srft_kv.h"
@@ -57,6 +58,21 @@ __device__ __forceinline__ float other_half_max(float m) {
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// Make the loop-invariant matrix fragments "used" here, so that the wait for their loads is placed
+// before the main loop and not inside it (where it would also wait for the loop's own prefetches).
+template <int N>
+__device__ __forceinline__ void hold_in_registers(half8 (&a)[N], half8 (&b)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(a[i]), "+v"(b[i]));
+}
+template <int N, int M>
+__device__ __forceinline__ void hold_in_registers(half8 (&a)[N][M], half8 (&b)[N][M]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+#pragma unroll
+        for (int j = 0; j < M; ++j) asm volatile("" : "+v"(a[i][j]), "+v"(b[i][j]));
+}
+
 // Eight values already multiplied by 1/scale -> eight two's-complement nibbles in one dword.
 // Adding 1.5*2^23 + 8 rounds to nearest-even and leaves q + 8 (1..15) in the low four bits above a
 // constant bit pattern; a shift-add chain concatenates the nibbles (no borrows because q + 8 > 0),
@@ -74,6 +90,23 @@ __device__ __forceinline__ uint32_t pack8(const floatx16& acc, int base, float i
 }
 
 // ------------------------------------------------------------------------------------------
+// Both kernels are software pipelines over the tiles T_0, T_1, ... of a workgroup (T_k = blockIdx +
+// k * gridDim).  Stage k starts with the only barrier of the stage and then, in ONE straight-line
+// block, (1) contracts T_k from LDS buffer k % 2 on the matrix cores, (2) runs the vector-ALU tail of
+// T_{k-1} (quantizer and stores, or scaling / conversion / stores) on the accumulators the previous
+// stage left behind, and (3) moves T_{k+1} from its prefetch registers into LDS buffer (k+1) % 2 and
+// refills those registers with T_{k+3}.  (1) and (2) are independent, so one wavefront keeps the MFMA
+// pipe and the vector ALU busy together.  The barrier of stage k makes T_k visible and also proves
+// that every wavefront has finished reading buffer (k+1) % 2, which (3) overwrites.
+//
+// Rows past the end of the input alias to the last row, in the loads AND in the stores: surplus lanes
+// compute the last vector again and store the same bytes to the same place.  Prefetches past the last
+// tile re-read the last tile.  So no memory operation in the loop is conditional, the hardware wait
+// counters are exact, and stores and younger prefetches stay in flight while older data is consumed.
+// Every branch in the kernels is uniform over the workgroup.
+// ------------------------------------------------------------------------------------------
+
+// ------------------------------------------------------------------------------------------
 // write path
 // ------------------------------------------------------------------------------------------
 // wfrag : [D/32 waves][D/16 k-steps][hi, lo][64 lanes] 16-byte A-operand fragments of W
@@ -83,17 +116,19 @@ template <int D, bool RAW>
 __global__ void __launch_bounds__(2 * D)
 srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
                      uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
-                     float unscale) {
+                     float unscale, float scale_mul) {
     constexpr int G = D / 32;            // wavefronts per workgroup = groups per vector
     constexpr int T = D / 16;            // MFMA k-steps
     constexpr int U = D / 8;             // 16-byte units per input row
     constexpr int ROW = U + 1;           // padded LDS row (odd number of units: conflict-free b128 reads)
     constexpr int NT = 64 * G;
+    constexpr int TB = (T < 8) ? T : 8;  // B fragments read from LDS ahead of their MFMAs
     __shared__ uint4 lds[2][kTileVecs * ROW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
     const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
+    const long long last = n_vec - 1;
 
     half8 ahi[T], alo[T];
 #pragma unroll
@@ -105,59 +140,98 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
     // each thread moves two 16-byte units of the 32 x D tile (32 * U = 2 * NT units)
     const int u0 = tid, u1 = tid + NT;
     const int r0 = u0 / U, c0 = u0 % U, r1 = u1 / U, c1 = u1 % U;
-    uint4 pre0, pre1;
-    auto fetch = [&](long long tile) {
+    auto fetch = [&](uint4& pa, uint4& pb, long long tile) {
+        if (tile > n_tiles - 1) tile = n_tiles - 1;          // prefetch past the end re-reads the last tile
         const long long row0 = tile * kTileVecs;
-        const uint4 zero = {0, 0, 0, 0};
-        pre0 = (row0 + r0 < n_vec) ? x[row0 * U + u0] : zero;
-        pre1 = (row0 + r1 < n_vec) ? x[row0 * U + u1] : zero;
+        const long long ra = (row0 + r0 < last) ? row0 + r0 : last;
+        const long long rb = (row0 + r1 < last) ? row0 + r1 : last;
+        pa = x[ra * U + c0];
+        pb = x[rb * U + c1];
     };
-
-    long long tile = blockIdx.x;
-    if (tile < n_tiles) fetch(tile);
-    int buf = 0;
-    for (; tile < n_tiles; tile += gridDim.x) {
-        lds[buf][r0 * ROW + c0] = pre0;
-        lds[buf][r1 * ROW + c1] = pre1;
-        const long long next = tile + gridDim.x;
-        if (next < n_tiles) fetch(next);
-        __syncthreads();                     // uniform: every thread runs the same trip count
-
-        floatx16 acc = {0};
-        const uint4* rowp = &lds[buf][col * ROW + half];
+    auto to_lds = [&](int b, const uint4& pa, const uint4& pb) {
+        lds[b][r0 * ROW + c0] = pa;
+        lds[b][r1 * ROW + c1] = pb;
+    };
+    auto contract = [&](int b, floatx16& acc) {
+        const uint4* rowp = &lds[b][col * ROW + half];
+        acc = floatx16{0};
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const half8 b = __builtin_bit_cast(half8, rowp[2 * t]);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[t], b, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[t], b, acc, 0, 0, 0);
+        for (int t0 = 0; t0 < T; t0 += TB) {
+            half8 bf[TB];
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+                if (t0 + t < T) bf[t] = __builtin_bit_cast(half8, rowp[2 * (t0 + t)]);
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+                if (t0 + t < T) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[t0 + t], bf[t], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[t0 + t], bf[t], acc, 0, 0, 0);
+                }
         }
-
-        const long long vec = tile * kTileVecs + col;
+    };
+    // vector-ALU tail of one tile: per-group abs-max, scale, int4 codes, stores
+    auto finish = [&](const floatx16& acc, long long tile) {
+        const long long row0 = tile * kTileVecs;
+        const long long left = last - row0;                               // uniform
+        const int c = (left < col) ? (int)left : col;                     // alias rows past the end
         if constexpr (RAW) {
-            if (vec < n_vec) {
-                float4* o = wout + (vec * D + 32 * wave + 16 * half) / 4;
+            float4* o = wout + (row0 * D) / 4 + (c * D + 32 * wave + 16 * half) / 4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    o[i] = make_float4(acc[4 * i] * unscale, acc[4 * i + 1] * unscale,
-                                       acc[4 * i + 2] * unscale, acc[4 * i + 3] * unscale);
-            }
+            for (int i = 0; i < 4; ++i)
+                o[i] = make_float4(acc[4 * i] * unscale, acc[4 * i + 1] * unscale,
+                                   acc[4 * i + 2] * unscale, acc[4 * i + 3] * unscale);
         } else {
             float m = fmaxf(fabsf(acc[0]), fabsf(acc[1]));
 #pragma unroll
             for (int v = 2; v < 16; ++v) m = fmaxf(m, fabsf(acc[v]));
             m = other_half_max(m);
-            float scale = (m * unscale) / 7.0f;
+            float scale = m * scale_mul;                 // scale_mul = fl(2^-e / 7): abs-max / 7
             float inv = unscale * __builtin_amdgcn_rcpf(scale);
             if (!(scale >= kMinScale)) { scale = 0.0f; inv = 0.0f; }
             uint2 packed;
             packed.x = pack8(acc, 0, inv);
             packed.y = pack8(acc, 8, inv);
-            if (vec < n_vec) {
-                codes[vec * (D / 16) + 2 * wave + half] = packed;
-                if (half == 0) scales[vec * G + wave] = scale;
-            }
+            codes[row0 * (D / 16) + (c * (D / 16) + 2 * wave + half)] = packed;
+            scales[row0 * G + (c * G + wave)] = scale;   // both halves store the same value
         }
-        buf ^= 1;
+    };
+
+    const long long t0 = blockIdx.x, stride = gridDim.x;
+    const long long m = (n_tiles - 1 - t0) / stride + 1;     // tiles of this workgroup (the grid never exceeds n_tiles)
+    uint4 pa0, pa1, pb0, pb1;
+    floatx16 acc_a, acc_b;
+    fetch(pa0, pa1, t0);
+    fetch(pb0, pb1, t0 + stride);
+    hold_in_registers(ahi, alo);                 // the matrix slab has arrived before the pipeline starts
+    to_lds(0, pa0, pa1);
+    fetch(pa0, pa1, t0 + 2 * stride);
+    // stage 0
+    __syncthreads();
+    contract(0, acc_a);
+    to_lds(1, pb0, pb1);
+    fetch(pb0, pb1, t0 + 3 * stride);
+    long long k = 1;
+    for (; k + 1 < m; k += 2) {
+        const long long tk = t0 + k * stride;
+        __syncthreads();                         // stage k (odd)
+        contract(1, acc_b);
+        finish(acc_a, tk - stride);
+        to_lds(0, pa0, pa1);
+        fetch(pa0, pa1, tk + 3 * stride);
+        __syncthreads();                         // stage k + 1 (even)
+        contract(0, acc_a);
+        finish(acc_b, tk);
+        to_lds(1, pb0, pb1);
+        fetch(pb0, pb1, tk + 4 * stride);
+    }
+    if (k < m) {                                 // one more odd stage
+        const long long tk = t0 + k * stride;
+        __syncthreads();
+        contract(1, acc_b);
+        finish(acc_a, tk - stride);
+        finish(acc_b, tk);
+    } else {
+        finish(acc_a, t0 + (k - 1) * stride);
     }
 }
 
@@ -177,13 +251,23 @@ __device__ __forceinline__ uint4 decode8(uint32_t v) {
     return o;
 }
 
+// Two fp32 values -> packed fp16, round to nearest even.  The empty asm keeps the compiler from fusing
+// the preceding multiply-add into a mixed-precision fma in some copies of this code and not in others:
+// every path rounds fp32 -> fp16 the same way, so a vector's output does not depend on where in the
+// batch it sits or on the launch shape.
 __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
-    const half2v h = {(_Float16)a, (_Float16)b};      // round to nearest even
+    asm volatile("" : "+v"(a), "+v"(b));
+    const half2v h = {(_Float16)a, (_Float16)b};
     return __builtin_bit_cast(uint32_t, h);
 }
 
 // rfrag : [D/32 waves][D/32 groups][2 k-steps][hi, lo][64 lanes] 16-byte A-operand fragments of R
 // codes : [n_vec][D/16] 8-byte units; scales : [n_vec][D/32]; out : [n_vec][D/8] 16-byte units of fp16
+//
+// Within a tile the groups are contracted one after the other (K = 32 each), into accumulators that
+// alternate, so that  o += scale_j * P_j  of one group runs on the vector ALU while the next group is
+// on the matrix cores; the last group of a tile has an accumulator of its own and is folded in, and
+// the tile converted and stored, under the first group of the next tile.
 template <int D>
 __global__ void __launch_bounds__(2 * D)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
@@ -198,6 +282,7 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
     const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
+    const long long last = n_vec - 1;
 
     half8 rhi[G][2], rlo[G][2];
 #pragma unroll
@@ -210,54 +295,113 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
 
     // each thread decodes one 8-byte unit of the 32 x D/2 code tile (32 * C = 64 * G units)
     const int r0 = tid / C, c0 = tid % C;
-    uint2 pre;
-    float sc[G];
-    auto fetch = [&](long long tile) {
+    struct Pre { uint2 c; float s[G]; };
+    auto fetch = [&](Pre& p, long long tile) {
+        if (tile > n_tiles - 1) tile = n_tiles - 1;
         const long long row0 = tile * kTileVecs;
-        const uint2 zero = {0, 0};
-        pre = (row0 + r0 < n_vec) ? codes[row0 * C + tid] : zero;
-        const bool ok = row0 + col < n_vec;
+        const long long ra = (row0 + r0 < last) ? row0 + r0 : last;
+        const long long rs = (row0 + col < last) ? row0 + col : last;
+        p.c = codes[ra * C + c0];
 #pragma unroll
-        for (int j = 0; j < G; ++j) sc[j] = ok ? scales[(row0 + col) * G + j] : 0.0f;
+        for (int j = 0; j < G; ++j) p.s[j] = scales[rs * G + j];
     };
-
-    long long tile = blockIdx.x;
-    if (tile < n_tiles) fetch(tile);
-    int buf = 0;
-    for (; tile < n_tiles; tile += gridDim.x) {
-        lds[buf][r0 * ROW + 2 * c0] = decode8(pre.x);
-        lds[buf][r0 * ROW + 2 * c0 + 1] = decode8(pre.y);
-        float s[G];
+    // decoded codes of a prefetched tile -> LDS buffer b; its scales (times 2^-e) -> s
+    auto to_lds = [&](int b, const Pre& p, float (&s)[G]) {
+        lds[b][r0 * ROW + 2 * c0] = decode8(p.c.x);
+        lds[b][r0 * ROW + 2 * c0 + 1] = decode8(p.c.y);
 #pragma unroll
-        for (int j = 0; j < G; ++j) s[j] = sc[j] * unscale;
-        const long long next = tile + gridDim.x;
-        if (next < n_tiles) fetch(next);
-        __syncthreads();
-
-        floatx16 o = {0};
-        const uint4* rowp = &lds[buf][col * ROW + half];
+        for (int j = 0; j < G; ++j) s[j] = p.s[j] * unscale;
+    };
+    auto group = [&](int b, int j, floatx16& acc) {
+        const uint4* rowp = &lds[b][col * ROW + half];
+        acc = floatx16{0};
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const half8 bf = __builtin_bit_cast(half8, rowp[4 * j + 2 * t]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[j][t], bf, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j][t], bf, acc, 0, 0, 0);
+        }
+    };
+    auto store_tile = [&](const floatx16& o, long long tile) {
+        const long long row0 = tile * kTileVecs;
+        const long long left = last - row0;
+        const int c = (left < col) ? (int)left : col;
+        uint4* dst = out + row0 * U + (c * U + 4 * wave + 2 * half);
+        dst[0] = make_uint4(pack_half2(o[0], o[1]), pack_half2(o[2], o[3]),
+                            pack_half2(o[4], o[5]), pack_half2(o[6], o[7]));
+        dst[1] = make_uint4(pack_half2(o[8], o[9]), pack_half2(o[10], o[11]),
+                            pack_half2(o[12], o[13]), pack_half2(o[14], o[15]));
+    };
+    floatx16 o, acc0, acc1, acc_last;
+    // o (+)= s * acc
+    auto fold = [&](const floatx16& acc, float s, bool first) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[v] = first ? acc[v] * s : fmaf(acc[v], s, o[v]);
+    };
+    // all groups of the tile in LDS buffer b; `prev` : fold in and store the previous tile first
+    auto tile_body = [&](int b, const float (&s)[G], bool prev, float s_prev_last, long long tile_prev) {
 #pragma unroll
         for (int j = 0; j < G; ++j) {
-            floatx16 acc = {0};
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const half8 b = __builtin_bit_cast(half8, rowp[4 * j + 2 * t]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[j][t], b, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j][t], b, acc, 0, 0, 0);
+            floatx16& acc = (j == G - 1) ? acc_last : ((j & 1) ? acc1 : acc0);
+            if (j == 0 && prev) {
+                // acc_last still holds the last group of the previous tile
+                if constexpr (G > 1) {
+                    group(b, 0, acc);
+                    fold(acc_last, s_prev_last, false);
+                    store_tile(o, tile_prev);
+                } else {
+                    fold(acc_last, s_prev_last, true);
+                    store_tile(o, tile_prev);
+                    group(b, 0, acc);
+                }
+            } else {
+                group(b, j, acc);
             }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[v] = fmaf(acc[v], s[j], o[v]);
+            if (j >= 1) fold((j - 1) & 1 ? acc1 : acc0, s[j - 1], j == 1);
         }
+    };
 
-        const long long vec = tile * kTileVecs + col;
-        if (vec < n_vec) {
-            uint4* dst = out + vec * U + 4 * wave + 2 * half;
-            dst[0] = make_uint4(pack_half2(o[0], o[1]), pack_half2(o[2], o[3]),
-                                pack_half2(o[4], o[5]), pack_half2(o[6], o[7]));
-            dst[1] = make_uint4(pack_half2(o[8], o[9]), pack_half2(o[10], o[11]),
-                                pack_half2(o[12], o[13]), pack_half2(o[14], o[15]));
-        }
-        buf ^= 1;
+    const long long t0 = blockIdx.x, stride = gridDim.x;
+    const long long m = (n_tiles - 1 - t0) / stride + 1;
+    Pre pa, pb;
+    float sa[G], sb[G];
+    fetch(pa, t0);
+    fetch(pb, t0 + stride);
+    hold_in_registers(rhi, rlo);
+    to_lds(0, pa, sa);
+    fetch(pa, t0 + 2 * stride);
+    // stage 0
+    __syncthreads();
+    tile_body(0, sa, false, 0.0f, 0);
+    to_lds(1, pb, sb);
+    fetch(pb, t0 + 3 * stride);
+    long long k = 1;
+    for (; k + 1 < m; k += 2) {
+        const long long tk = t0 + k * stride;
+        const float sl_a = sa[G - 1];
+        __syncthreads();                         // stage k (odd): tile in buffer 1, scales sb
+        tile_body(1, sb, true, sl_a, tk - stride);
+        to_lds(0, pa, sa);
+        fetch(pa, tk + 3 * stride);
+        const float sl_b = sb[G - 1];
+        __syncthreads();                         // stage k + 1 (even)
+        tile_body(0, sa, true, sl_b, tk);
+        to_lds(1, pb, sb);
+        fetch(pb, tk + 4 * stride);
+    }
+    // the last tile's final group is still in acc_last
+    auto drain = [&](float s_last, long long tile) {
+        fold(acc_last, s_last, G == 1);
+        store_tile(o, tile);
+    };
+    if (k < m) {
+        const long long tk = t0 + k * stride;
+        const float sl_a = sa[G - 1];
+        __syncthreads();
+        tile_body(1, sb, true, sl_a, tk - stride);
+        drain(sb[G - 1], tk);
+    } else {
+        drain(sa[G - 1], t0 + (k - 1) * stride);
     }
 }
 
@@ -367,10 +511,10 @@ int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* cod
     if (grid > n_tiles) grid = n_tiles;
     if (wout)
         hipLaunchKernelGGL((srft_quantize_kernel<D, true>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
-                           (const uint4*)x, n, (uint2*)nullptr, (float*)nullptr, (float4*)wout, p->unscale_w);
+                           (const uint4*)x, n, (uint2*)nullptr, (float*)nullptr, (float4*)wout, p->unscale_w, p->unscale_w / 7.0f);
     else
         hipLaunchKernelGGL((srft_quantize_kernel<D, false>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
-                           (const uint4*)x, n, (uint2*)codes, scales, (float4*)nullptr, p->unscale_w);
+                           (const uint4*)x, n, (uint2*)codes, scales, (float4*)nullptr, p->unscale_w, p->unscale_w / 7.0f);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
