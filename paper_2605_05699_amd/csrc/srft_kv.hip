@@ -266,8 +266,14 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
 //
 // Within a tile the groups are contracted one after the other (K = 32 each), into accumulators that
 // alternate, so that  o += scale_j * P_j  of one group runs on the vector ALU while the next group is
-// on the matrix cores; the last group of a tile has an accumulator of its own and is folded in, and
-// the tile converted and stored, under the first group of the next tile.
+// on the matrix cores; the last group of a tile has an accumulator of its own and is folded in under
+// the first group of the next tile.
+//
+// A lane ends up with 16 consecutive fp16 of one vector (32 bytes); stored directly that would be 16-byte
+// pieces 256 bytes apart.  The finished tile is therefore staged in LDS (stage k stages T_{k-1}) and
+// written out one stage later by all threads as fully coalesced 16-byte-per-lane stores of the
+// contiguous 32 x 2D-byte block (stage k flushes T_{k-2}).  The per-vector scales reach the lanes through
+// LDS as well: they are loaded once per workgroup, coalesced, together with the codes.
 template <int D>
 __global__ void __launch_bounds__(2 * D)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
@@ -277,7 +283,11 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     constexpr int U = D / 8;             // 16-byte units per decoded row (D fp16)
     constexpr int ROW = U + 1;
     constexpr int C = D / 16;            // 8-byte code units per row
-    __shared__ uint4 lds[2][kTileVecs * ROW];
+    constexpr int NT = 64 * G;
+    constexpr int SROW = G + 1;          // padded row of the scale tile (floats)
+    __shared__ uint4 dec[2][kTileVecs * ROW];    // decoded codes of T_k in dec[k % 2]
+    __shared__ uint4 stg[2][kTileVecs * ROW];    // finished fp16 rows of T_k in stg[k % 2]
+    __shared__ float scl[2][kTileVecs * SROW];   // scales (times 2^-e) of T_k in scl[k % 2]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -293,27 +303,31 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
             rlo[j][t] = __builtin_bit_cast(half8, rfrag[(((wave * G + j) * 2 + t) * 2 + 1) * 64 + lane]);
         }
 
-    // each thread decodes one 8-byte unit of the 32 x D/2 code tile (32 * C = 64 * G units)
+    // each thread decodes one 8-byte unit of the 32 x D/2 code tile (32 * C = NT units) and carries one
+    // float of the 32 x G scale tile (the first 32 * G threads; the others re-read its last float)
     const int r0 = tid / C, c0 = tid % C;
-    struct Pre { uint2 c; float s[G]; };
+    const int se = (tid < 32 * G) ? tid : 32 * G - 1;
+    const int sr = se / G, sj = se % G;
+    struct Pre { uint2 c; float s; };
     auto fetch = [&](Pre& p, long long tile) {
         if (tile > n_tiles - 1) tile = n_tiles - 1;
         const long long row0 = tile * kTileVecs;
         const long long ra = (row0 + r0 < last) ? row0 + r0 : last;
-        const long long rs = (row0 + col < last) ? row0 + col : last;
+        const long long rs = (row0 + sr < last) ? row0 + sr : last;
         p.c = codes[ra * C + c0];
-#pragma unroll
-        for (int j = 0; j < G; ++j) p.s[j] = scales[rs * G + j];
+        p.s = scales[rs * G + sj];
     };
-    // decoded codes of a prefetched tile -> LDS buffer b; its scales (times 2^-e) -> s
-    auto to_lds = [&](int b, const Pre& p, float (&s)[G]) {
-        lds[b][r0 * ROW + 2 * c0] = decode8(p.c.x);
-        lds[b][r0 * ROW + 2 * c0 + 1] = decode8(p.c.y);
+    auto to_lds = [&](int b, const Pre& p) {
+        dec[b][r0 * ROW + 2 * c0] = decode8(p.c.x);
+        dec[b][r0 * ROW + 2 * c0 + 1] = decode8(p.c.y);
+        if (tid < 32 * G) scl[b][sr * SROW + sj] = p.s * unscale;
+    };
+    auto read_scales = [&](int b, float (&s)[G]) {
 #pragma unroll
-        for (int j = 0; j < G; ++j) s[j] = p.s[j] * unscale;
+        for (int j = 0; j < G; ++j) s[j] = scl[b][col * SROW + j];
     };
     auto group = [&](int b, int j, floatx16& acc) {
-        const uint4* rowp = &lds[b][col * ROW + half];
+        const uint4* rowp = &dec[b][col * ROW + half];
         acc = floatx16{0};
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -322,24 +336,33 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
             acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j][t], bf, acc, 0, 0, 0);
         }
     };
-    auto store_tile = [&](const floatx16& o, long long tile) {
-        const long long row0 = tile * kTileVecs;
-        const long long left = last - row0;
-        const int c = (left < col) ? (int)left : col;
-        uint4* dst = out + row0 * U + (c * U + 4 * wave + 2 * half);
-        dst[0] = make_uint4(pack_half2(o[0], o[1]), pack_half2(o[2], o[3]),
-                            pack_half2(o[4], o[5]), pack_half2(o[6], o[7]));
-        dst[1] = make_uint4(pack_half2(o[8], o[9]), pack_half2(o[10], o[11]),
-                            pack_half2(o[12], o[13]), pack_half2(o[14], o[15]));
-    };
     floatx16 o, acc0, acc1, acc_last;
     // o (+)= s * acc
     auto fold = [&](const floatx16& acc, float s, bool first) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[v] = first ? acc[v] * s : fmaf(acc[v], s, o[v]);
     };
-    // all groups of the tile in LDS buffer b; `prev` : fold in and store the previous tile first
-    auto tile_body = [&](int b, const float (&s)[G], bool prev, float s_prev_last, long long tile_prev) {
+    // the 16 finished outputs of this lane, rounded to fp16, into the staging tile b
+    auto stage_out = [&](int b) {
+        uint4* dst = &stg[b][col * ROW + 4 * wave + 2 * half];
+        dst[0] = make_uint4(pack_half2(o[0], o[1]), pack_half2(o[2], o[3]),
+                            pack_half2(o[4], o[5]), pack_half2(o[6], o[7]));
+        dst[1] = make_uint4(pack_half2(o[8], o[9]), pack_half2(o[10], o[11]),
+                            pack_half2(o[12], o[13]), pack_half2(o[14], o[15]));
+    };
+    // staging tile b -> global rows of `tile`: two fully coalesced 16-byte stores per thread
+    auto flush = [&](int b, long long tile) {
+        const long long row0 = tile * kTileVecs;
+        const long long left = last - row0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int u = tid + i * NT, r = u / U, c = u % U;
+            const long long rr = (left < r) ? left : r;                 // rows past the end alias to the last row
+            out[(row0 + rr) * U + c] = stg[b][r * ROW + c];
+        }
+    };
+    // all groups of the tile in dec[b]; `prev`: first fold in the last group of the previous tile and stage it
+    auto tile_body = [&](int b, const float (&s)[G], bool prev, float s_prev_last, int b_prev) {
 #pragma unroll
         for (int j = 0; j < G; ++j) {
             floatx16& acc = (j == G - 1) ? acc_last : ((j & 1) ? acc1 : acc0);
@@ -348,10 +371,10 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
                 if constexpr (G > 1) {
                     group(b, 0, acc);
                     fold(acc_last, s_prev_last, false);
-                    store_tile(o, tile_prev);
+                    stage_out(b_prev);
                 } else {
                     fold(acc_last, s_prev_last, true);
-                    store_tile(o, tile_prev);
+                    stage_out(b_prev);
                     group(b, 0, acc);
                 }
             } else {
@@ -368,40 +391,62 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     fetch(pa, t0);
     fetch(pb, t0 + stride);
     hold_in_registers(rhi, rlo);
-    to_lds(0, pa, sa);
+    to_lds(0, pa);
     fetch(pa, t0 + 2 * stride);
     // stage 0
     __syncthreads();
+    read_scales(0, sa);
     tile_body(0, sa, false, 0.0f, 0);
-    to_lds(1, pb, sb);
+    to_lds(1, pb);
     fetch(pb, t0 + 3 * stride);
-    long long k = 1;
-    for (; k + 1 < m; k += 2) {
-        const long long tk = t0 + k * stride;
-        const float sl_a = sa[G - 1];
-        __syncthreads();                         // stage k (odd): tile in buffer 1, scales sb
-        tile_body(1, sb, true, sl_a, tk - stride);
-        to_lds(0, pa, sa);
-        fetch(pa, tk + 3 * stride);
-        const float sl_b = sb[G - 1];
-        __syncthreads();                         // stage k + 1 (even)
-        tile_body(0, sa, true, sl_b, tk);
-        to_lds(1, pb, sb);
-        fetch(pb, tk + 4 * stride);
-    }
-    // the last tile's final group is still in acc_last
-    auto drain = [&](float s_last, long long tile) {
-        fold(acc_last, s_last, G == 1);
-        store_tile(o, tile);
-    };
-    if (k < m) {
-        const long long tk = t0 + k * stride;
-        const float sl_a = sa[G - 1];
+    // stage k: barrier; flush T_{k-2}; contract T_k (staging T_{k-1} under its first group); decode T_{k+1}
+    auto odd_stage = [&](long long tk, auto flush_first) {      // T_k in dec[1]
         __syncthreads();
-        tile_body(1, sb, true, sl_a, tk - stride);
-        drain(sb[G - 1], tk);
-    } else {
-        drain(sa[G - 1], t0 + (k - 1) * stride);
+        if constexpr (decltype(flush_first)::value) flush(1, tk - 2 * stride);
+        read_scales(1, sb);
+        tile_body(1, sb, true, sa[G - 1], 0);
+        to_lds(0, pa);
+        fetch(pa, tk + 3 * stride);
+    };
+    auto even_stage = [&](long long tk) {                       // T_k in dec[0]
+        __syncthreads();
+        flush(0, tk - 2 * stride);
+        read_scales(0, sa);
+        tile_body(0, sa, true, sb[G - 1], 1);
+        to_lds(1, pb);
+        fetch(pb, tk + 3 * stride);
+    };
+    long long k = 1;
+    if (k + 1 < m) {                             // stages 1 and 2: nothing to flush in stage 1 yet
+        odd_stage(t0 + stride, std::false_type{});
+        even_stage(t0 + 2 * stride);
+        k = 3;
+    }
+    for (; k + 1 < m; k += 2) {
+        odd_stage(t0 + k * stride, std::true_type{});
+        even_stage(t0 + (k + 1) * stride);
+    }
+    // the last group of the last tile is still in acc_last; up to two staged tiles are unflushed
+    if (k < m) {                                 // one more odd stage: T_k in dec[1]
+        const long long tk = t0 + k * stride;
+        __syncthreads();
+        if (k >= 2) flush(1, tk - 2 * stride);
+        read_scales(1, sb);
+        tile_body(1, sb, true, sa[G - 1], 0);
+        __syncthreads();                         // every thread is done reading stg[1]
+        fold(acc_last, sb[G - 1], G == 1);
+        stage_out(1);
+        flush(0, tk - stride);
+        __syncthreads();
+        flush(1, tk);
+    } else {                                     // the last stage was even (or stage 0): T_{k-1} in dec[0]
+        const long long tl = t0 + (k - 1) * stride;
+        __syncthreads();                         // every thread is done reading stg[0]
+        fold(acc_last, sa[G - 1], G == 1);
+        stage_out(0);
+        if (k >= 2) flush(1, tl - stride);
+        __syncthreads();
+        flush(0, tl);
     }
 }
 
