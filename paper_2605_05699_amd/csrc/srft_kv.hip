@@ -322,10 +322,7 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
         dec[b][r0 * ROW + 2 * c0 + 1] = decode8(p.c.y);
         if (tid < 32 * G) scl[b][sr * SROW + sj] = p.s * unscale;
     };
-    auto read_scales = [&](int b, float (&s)[G]) {
-#pragma unroll
-        for (int j = 0; j < G; ++j) s[j] = scl[b][col * SROW + j];
-    };
+    auto scale_of = [&](int b, int j) { return scl[b][col * SROW + j]; };
     auto group = [&](int b, int j, floatx16& acc) {
         const uint4* rowp = &dec[b][col * ROW + half];
         acc = floatx16{0};
@@ -336,7 +333,10 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
             acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j][t], bf, acc, 0, 0, 0);
         }
     };
-    floatx16 o, acc0, acc1, acc_last;
+    // The last group of a tile is folded in one stage later, under group 0 of the next tile (which uses
+    // acc0); with an even number of groups it can live in acc1, otherwise it needs a register set of its own.
+    floatx16 o, acc0, acc1, acc_odd;
+    floatx16& acc_last = (G % 2 == 0) ? acc1 : acc_odd;
     // o (+)= s * acc
     auto fold = [&](const floatx16& acc, float s, bool first) {
 #pragma unroll
@@ -361,8 +361,9 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
             out[(row0 + rr) * U + c] = stg[b][r * ROW + c];
         }
     };
-    // all groups of the tile in dec[b]; `prev`: first fold in the last group of the previous tile and stage it
-    auto tile_body = [&](int b, const float (&s)[G], bool prev, float s_prev_last, int b_prev) {
+    // all groups of the tile in dec[b] (scales in scl[b]); `prev`: first fold in the last group of the
+    // previous tile, whose scale is s_prev_last, and stage that tile in stg[b_prev]
+    auto tile_body = [&](int b, bool prev, float s_prev_last, int b_prev) {
 #pragma unroll
         for (int j = 0; j < G; ++j) {
             floatx16& acc = (j == G - 1) ? acc_last : ((j & 1) ? acc1 : acc0);
@@ -380,14 +381,16 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
             } else {
                 group(b, j, acc);
             }
-            if (j >= 1) fold((j - 1) & 1 ? acc1 : acc0, s[j - 1], j == 1);
+            if (j >= 1) fold((j - 1) & 1 ? acc1 : acc0, scale_of(b, j - 1), j == 1);
+            // with many groups, keep the scheduler from reading every group's fragments up front
+            if constexpr (G > 4) __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     const long long t0 = blockIdx.x, stride = gridDim.x;
     const long long m = (n_tiles - 1 - t0) / stride + 1;
     Pre pa, pb;
-    float sa[G], sb[G];
+    float s_last;                                // scale of the last group of the tile contracted last
     fetch(pa, t0);
     fetch(pb, t0 + stride);
     hold_in_registers(rhi, rlo);
@@ -395,24 +398,24 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     fetch(pa, t0 + 2 * stride);
     // stage 0
     __syncthreads();
-    read_scales(0, sa);
-    tile_body(0, sa, false, 0.0f, 0);
+    tile_body(0, false, 0.0f, 0);
+    s_last = scale_of(0, G - 1);
     to_lds(1, pb);
     fetch(pb, t0 + 3 * stride);
     // stage k: barrier; flush T_{k-2}; contract T_k (staging T_{k-1} under its first group); decode T_{k+1}
     auto odd_stage = [&](long long tk, auto flush_first) {      // T_k in dec[1]
         __syncthreads();
         if constexpr (decltype(flush_first)::value) flush(1, tk - 2 * stride);
-        read_scales(1, sb);
-        tile_body(1, sb, true, sa[G - 1], 0);
+        tile_body(1, true, s_last, 0);
+        s_last = scale_of(1, G - 1);
         to_lds(0, pa);
         fetch(pa, tk + 3 * stride);
     };
     auto even_stage = [&](long long tk) {                       // T_k in dec[0]
         __syncthreads();
         flush(0, tk - 2 * stride);
-        read_scales(0, sa);
-        tile_body(0, sa, true, sb[G - 1], 1);
+        tile_body(0, true, s_last, 1);
+        s_last = scale_of(0, G - 1);
         to_lds(1, pb);
         fetch(pb, tk + 3 * stride);
     };
@@ -431,10 +434,10 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
         const long long tk = t0 + k * stride;
         __syncthreads();
         if (k >= 2) flush(1, tk - 2 * stride);
-        read_scales(1, sb);
-        tile_body(1, sb, true, sa[G - 1], 0);
+        tile_body(1, true, s_last, 0);
+        s_last = scale_of(1, G - 1);
         __syncthreads();                         // every thread is done reading stg[1]
-        fold(acc_last, sb[G - 1], G == 1);
+        fold(acc_last, s_last, G == 1);
         stage_out(1);
         flush(0, tk - stride);
         __syncthreads();
@@ -442,7 +445,7 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     } else {                                     // the last stage was even (or stage 0): T_{k-1} in dec[0]
         const long long tl = t0 + (k - 1) * stride;
         __syncthreads();                         // every thread is done reading stg[0]
-        fold(acc_last, sa[G - 1], G == 1);
+        fold(acc_last, s_last, G == 1);
         stage_out(0);
         if (k >= 2) flush(1, tl - stride);
         __syncthreads();
