@@ -19,6 +19,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/), in bytes,
 # for launches of the default workload; None until a counter run has been recorded.
 MEASURED_TRAFFIC = {
+    # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (factors from the copy kernel of known size), KiB -> bytes, per launch
+    # of 1,048,576 vectors at d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
+    ("llama3-70b-128k", "srft_quantize_kernel"): (131436.5 * 2.0 + 81924.9) * 1024,
+    ("llama3-70b-128k", "srft_dequantize_kernel"): (41318.4 * 2.0 + 262144.0) * 1024,
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
@@ -35,6 +39,10 @@ def main() -> int:
     ap.add_argument("--plans", type=int, default=0, help="use only the first N plans (debugging; 0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-workgroups", type=int, default=0)
+    ap.add_argument("--ceiling", action="store_true",
+                    help="also time the streaming kernel that has each path's read:write byte mix (HBM ceiling)")
+    ap.add_argument("--copy-bytes", type=int, default=0,
+                    help="also run the library's plain copy kernel over this many bytes (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (vectors are independent; more GPUs would each take a share "
@@ -131,12 +139,50 @@ def main() -> int:
         "paper_context_apple_m1": PAPER_CONTEXT,
     }
 
+    if args.ceiling:
+        result["hbm_ceiling"] = mix_ceiling(B, torch, x, out, n_plans * n, d, G, stream)
+    if args.copy_bytes:
+        nb = args.copy_bytes // 16 * 16
+        src = out.view(torch.uint8).reshape(-1)[:nb]
+        dst = x.view(torch.uint8).reshape(-1)[:nb]
+        for _ in range(2):
+            B.srft_stream_copy(dst, src, stream)
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record(stream)
+        for _ in range(5):
+            B.srft_stream_copy(dst, src, stream)
+        c1.record(stream)
+        torch.cuda.synchronize()
+        result["copy_kernel"] = {"bytes_each_way": nb, "GBps_read_plus_write": 2 * nb / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, x[0], plans[0], W)
     for pl in plans:
         pl.close()
     print(json.dumps(result))
     return 0
+
+
+def mix_ceiling(B, torch, x, out, total_vec, d, G, stream):
+    """Streaming kernel with the write path's and the read path's byte mix, no arithmetic: GB/s over a few grids."""
+    big, small = 32 * 2 * d, 32 * (d // 2 + 4 * G)
+    n_tiles = min(total_vec // 32, (2 << 30) // big)         # at most 2 GiB on the large side
+    a, b = x.view(torch.uint8).reshape(-1), out.view(torch.uint8).reshape(-1)
+    res = {"tiles": n_tiles, "read_write_bytes_per_tile": {"quantize_mix": [big, small], "dequantize_mix": [small, big]}}
+    for name, (rb, wb) in (("quantize_mix", (big, small)), ("dequantize_mix", (small, big))):
+        best = {}
+        for wgs in (512, 768, 1024, 2048, 4096, 8192):
+            for _ in range(3):
+                B.srft_stream_mix(a, b, n_tiles, rb, wb, wgs, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                B.srft_stream_mix(a, b, n_tiles, rb, wb, wgs, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            best[str(wgs)] = n_tiles * (rb + wb) / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+        res[name + "_GBps_by_workgroups"] = best
+        res[name + "_GBps"] = max(best.values())
+    return res
 
 
 def cpu_baseline(w, x0, plan0, W):
@@ -148,19 +194,25 @@ def cpu_baseline(w, x0, plan0, W):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = 1
-    sample = min(x0.shape[0], 1 << 17)
-    xs = x0[:sample].cpu().numpy()
+    chunk = min(x0.shape[0], 1 << 17)
+    n_chunks = max(1, min(x0.shape[0] // chunk, 24))         # about 10-20 s of oracle time at d = 128
     _, lam, _ = W.plan_constants(w, 0)
     s = plan0.signs
-    t0 = time.perf_counter()
-    q = O.quantize(xs, s, lam, w.g)
-    t1 = time.perf_counter()
-    O.dequantize(q["codes"], q["scales"], s, lam, w.g)
-    t2 = time.perf_counter()
-    return {"value": sample / (t2 - t0), "unit": "vectors/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {sample} vectors of plan 0 of {w.name}: oracle quantize {t1 - t0:.2f} s + "
-                      f"dequantize {t2 - t1:.2f} s (numpy, float64, dense d x d form)",
-            "quantize_vectors_per_s": sample / (t1 - t0), "dequantize_vectors_per_s": sample / (t2 - t1)}
+    tq = td = 0.0
+    for i in range(n_chunks):
+        xs = x0[i * chunk:(i + 1) * chunk].cpu().numpy()
+        t0 = time.perf_counter()
+        q = O.quantize(xs, s, lam, w.g)
+        t1 = time.perf_counter()
+        O.dequantize(q["codes"], q["scales"], s, lam, w.g)
+        t2 = time.perf_counter()
+        tq += t1 - t0
+        td += t2 - t1
+    sample = chunk * n_chunks
+    return {"value": sample / (tq + td), "unit": "vectors/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {sample} vectors of plan 0 of {w.name}: oracle quantize {tq:.2f} s + "
+                      f"dequantize {td:.2f} s (numpy, float64, dense d x d form)",
+            "quantize_vectors_per_s": sample / tq, "dequantize_vectors_per_s": sample / td}
 
 
 if __name__ == "__main__":

@@ -115,6 +115,17 @@ int srft_plan_set_max_workgroups(srft_plan_t* plan, int max_workgroups);
  */
 int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* hip_stream);
 
+/*
+ * Measurement aid, not part of the method: a streaming kernel with a chosen traffic shape.  For each of
+ * n_tiles tiles it reads read_bytes_per_tile contiguous bytes from src_dev (tile t at t * read_bytes_per_tile)
+ * and writes write_bytes_per_tile contiguous bytes to dst_dev, with coalesced 16-byte accesses and no
+ * arithmetic.  With 8192 : 2560 it has the write path's byte mix at d = 128 (32 vectors per tile), with
+ * 2560 : 8192 the read path's; its rate is the ceiling the memory system offers such a kernel.
+ * Byte counts must be positive multiples of 16; workgroups = 0 picks 3 per compute unit.
+ */
+int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int read_bytes_per_tile,
+                    int write_bytes_per_tile, int workgroups, void* hip_stream);
+
 const char* srft_status_string(int status);
 int srft_last_hip_error(void);    /* the hipError_t of the most recent SRFT_ERR_HIP on this thread */
 

@@ -460,6 +460,28 @@ srft_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, long lo
         dst[i] = src[i];
 }
 
+// Streaming kernel with a given read : write byte mix per tile and no arithmetic to speak of: every
+// workgroup walks tiles, reads r_units 16-byte units and writes w_units units per tile, all coalesced.
+// Its rate is the ceiling the memory system offers a kernel with the same traffic shape.
+template <int RU>      // RU = ceil(r_units / 256): loads per thread and tile, all issued before any is used
+__global__ void __launch_bounds__(256)
+srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n_tiles, int r_units, int w_units) {
+    for (long long t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const uint4* s = src + t * r_units;
+        uint4 v[RU];
+#pragma unroll
+        for (int i = 0; i < RU; ++i) {
+            const int u = threadIdx.x + 256 * i;
+            v[i] = s[u < r_units ? u : r_units - 1];
+        }
+        uint4 acc = v[0];
+#pragma unroll
+        for (int i = 1; i < RU; ++i) { acc.x ^= v[i].x; acc.y ^= v[i].y; acc.z ^= v[i].z; acc.w ^= v[i].w; }
+        uint4* d = dst + t * w_units;
+        for (int u = threadIdx.x; u < w_units; u += 256) d[u] = acc;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
@@ -770,6 +792,36 @@ int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* 
     if (grid > (units + 255) / 256) grid = (units + 255) / 256;
     hipLaunchKernelGGL(srft_copy_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, (uint4*)dst_dev,
                        (const uint4*)src_dev, units);
+    SRFT_HIP(hipGetLastError());
+    return SRFT_OK;
+}
+
+int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int read_bytes_per_tile,
+                    int write_bytes_per_tile, int workgroups, void* hip_stream) {
+    if (n_tiles < 0 || read_bytes_per_tile <= 0 || write_bytes_per_tile <= 0 || read_bytes_per_tile % 16 ||
+        write_bytes_per_tile % 16 || workgroups < 0)
+        return SRFT_ERR_BAD_N;
+    if (n_tiles == 0) return SRFT_OK;
+    if (!src_dev || !dst_dev) return SRFT_ERR_NULL;
+    if (!aligned(src_dev, 16) || !aligned(dst_dev, 16)) return SRFT_ERR_ALIGN;
+    int dev = 0, cus = 0;
+    SRFT_HIP(hipGetDevice(&dev));
+    SRFT_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    long long grid = workgroups > 0 ? workgroups : (long long)cus * 3;
+    if (grid > n_tiles) grid = n_tiles;
+    const int r_units = read_bytes_per_tile / 16, w_units = write_bytes_per_tile / 16;
+    const int ru = (r_units + 255) / 256;
+#define SRFT_MIX_CASE(N)                                                                                          \
+    case N:                                                                                                       \
+        hipLaunchKernelGGL(srft_mix_kernel<N>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream,      \
+                           (const uint4*)src_dev, (uint4*)dst_dev, (long long)n_tiles, r_units, w_units);         \
+        break;
+    switch (ru) {
+        SRFT_MIX_CASE(1) SRFT_MIX_CASE(2) SRFT_MIX_CASE(3) SRFT_MIX_CASE(4)
+        SRFT_MIX_CASE(5) SRFT_MIX_CASE(6) SRFT_MIX_CASE(7) SRFT_MIX_CASE(8)
+        default: return SRFT_ERR_BAD_N;         // at most 32 KiB read per tile
+    }
+#undef SRFT_MIX_CASE
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
