@@ -31,6 +31,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstdint>
 #include <cstring>
 #include <new>
@@ -73,6 +74,12 @@ __device__ __forceinline__ void hold_in_registers(half8 (&a)[N][M], half8 (&b)[N
         for (int j = 0; j < M; ++j) asm volatile("" : "+v"(a[i][j]), "+v"(b[i][j]));
 }
 
+template <int N> struct Accs;          // one 32x32 accumulator tile per slab, as named registers
+template <> struct Accs<1> { floatx16 a; };
+template <> struct Accs<2> { floatx16 a, b; };
+template <class F> __device__ __forceinline__ void each_acc(Accs<1>& p, F f) { f(p.a, 0); }
+template <class F> __device__ __forceinline__ void each_acc(Accs<2>& p, F f) { f(p.a, 0); f(p.b, 1); }
+
 // Eight values already multiplied by 1/scale -> eight two's-complement nibbles in one dword.
 // Adding 1.5*2^23 + 8 rounds to nearest-even and leaves q + 8 (1..15) in the low four bits above a
 // constant bit pattern; a shift-add chain concatenates the nibbles (no borrows because q + 8 > 0),
@@ -109,20 +116,26 @@ __device__ __forceinline__ uint32_t pack8(const floatx16& acc, int base, float i
 // ------------------------------------------------------------------------------------------
 // write path
 // ------------------------------------------------------------------------------------------
-// wfrag : [D/32 waves][D/16 k-steps][hi, lo][64 lanes] 16-byte A-operand fragments of W
+// wfrag : [D/32 slabs][D/16 k-steps][hi, lo][64 lanes] 16-byte A-operand fragments of W
 // x     : [n_vec][D/8] 16-byte units of fp16 input
+// S     : slabs (= quantization groups) per wavefront; the workgroup has D / (32 S) wavefronts.  With S = 2
+//         every B fragment read from LDS feeds four MFMAs instead of two and half as many wavefronts read the
+//         tile; the price is a 2 x larger register-resident slab (at d = 256 it only fits with one wavefront
+//         per SIMD, the slab in the accumulation half of the register file).
 // RAW   : store the fp32 coefficients w instead of quantizing (srft_kv_forward_f32)
-template <int D, bool RAW>
-__global__ void __launch_bounds__(2 * D)
+template <int D, int S, bool RAW>
+__global__ void __launch_bounds__(2 * D / S)
 srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
                      uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
                      float unscale, float scale_mul) {
-    constexpr int G = D / 32;            // wavefronts per workgroup = groups per vector
+    constexpr int G = D / 32;            // quantization groups per vector = slabs of the matrix
     constexpr int T = D / 16;            // MFMA k-steps
     constexpr int U = D / 8;             // 16-byte units per input row
     constexpr int ROW = U + 1;           // padded LDS row (odd number of units: conflict-free b128 reads)
-    constexpr int NT = 64 * G;
+    constexpr int NT = 64 * G / S;       // threads per workgroup
+    constexpr int PER = 2 * S;           // 16-byte units each thread moves per tile (32 * U = PER * NT)
     constexpr int TB = (T < 8) ? T : 8;  // B fragments read from LDS ahead of their MFMAs
+    static_assert(G % S == 0, "slabs per wavefront must divide the number of groups");
     __shared__ uint4 lds[2][kTileVecs * ROW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -130,31 +143,41 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
     const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
     const long long last = n_vec - 1;
 
-    half8 ahi[T], alo[T];
+    half8 ahi[S][T], alo[S][T];
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
-        ahi[t] = __builtin_bit_cast(half8, wfrag[((wave * T + t) * 2 + 0) * 64 + lane]);
-        alo[t] = __builtin_bit_cast(half8, wfrag[((wave * T + t) * 2 + 1) * 64 + lane]);
-    }
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            ahi[s][t] = __builtin_bit_cast(half8, wfrag[(((wave * S + s) * T + t) * 2 + 0) * 64 + lane]);
+            alo[s][t] = __builtin_bit_cast(half8, wfrag[(((wave * S + s) * T + t) * 2 + 1) * 64 + lane]);
+        }
 
-    // each thread moves two 16-byte units of the 32 x D tile (32 * U = 2 * NT units)
-    const int u0 = tid, u1 = tid + NT;
-    const int r0 = u0 / U, c0 = u0 % U, r1 = u1 / U, c1 = u1 % U;
-    auto fetch = [&](uint4& pa, uint4& pb, long long tile) {
+    // The PER prefetched units of one tile live in separately named registers (PER = 2 uses a and b only).
+    auto fetch1 = [&](uint4& v, int i, long long row0) __attribute__((always_inline)) {
+        const int u = tid + i * NT, r = u / U, c = u % U;
+        const long long rr = (row0 + r < last) ? row0 + r : last;
+        v = x[rr * U + c];
+    };
+    auto fetch = [&](uint4& a, uint4& b, uint4& c, uint4& d, long long tile) __attribute__((always_inline)) {
         if (tile > n_tiles - 1) tile = n_tiles - 1;          // prefetch past the end re-reads the last tile
         const long long row0 = tile * kTileVecs;
-        const long long ra = (row0 + r0 < last) ? row0 + r0 : last;
-        const long long rb = (row0 + r1 < last) ? row0 + r1 : last;
-        pa = x[ra * U + c0];
-        pb = x[rb * U + c1];
+        fetch1(a, 0, row0);
+        fetch1(b, 1, row0);
+        if constexpr (PER > 2) { fetch1(c, 2, row0); fetch1(d, 3, row0); }
     };
-    auto to_lds = [&](int b, const uint4& pa, const uint4& pb) {
-        lds[b][r0 * ROW + c0] = pa;
-        lds[b][r1 * ROW + c1] = pb;
+    auto put1 = [&](int buf, const uint4& v, int i) __attribute__((always_inline)) {
+        const int u = tid + i * NT, r = u / U, c = u % U;
+        lds[buf][r * ROW + c] = v;
     };
-    auto contract = [&](int b, floatx16& acc) {
+    auto to_lds = [&](int buf, const uint4& a, const uint4& b, const uint4& c, const uint4& d) __attribute__((always_inline)) {
+        put1(buf, a, 0);
+        put1(buf, b, 1);
+        if constexpr (PER > 2) { put1(buf, c, 2); put1(buf, d, 3); }
+    };
+    using Acc = Accs<S>;
+    auto contract = [&](int b, Acc& accs) __attribute__((always_inline)) {
         const uint4* rowp = &lds[b][col * ROW + half];
-        acc = floatx16{0};
+        each_acc(accs, [&](floatx16& acc, int) { acc = floatx16{0}; });
 #pragma unroll
         for (int t0 = 0; t0 < T; t0 += TB) {
             half8 bf[TB];
@@ -164,65 +187,70 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
 #pragma unroll
             for (int t = 0; t < TB; ++t)
                 if (t0 + t < T) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[t0 + t], bf[t], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[t0 + t], bf[t], acc, 0, 0, 0);
+                    each_acc(accs, [&](floatx16& acc, int s) {
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[s][t0 + t], bf[t], acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[s][t0 + t], bf[t], acc, 0, 0, 0);
+                    });
                 }
         }
     };
     // vector-ALU tail of one tile: per-group abs-max, scale, int4 codes, stores
-    auto finish = [&](const floatx16& acc, long long tile) {
+    auto finish = [&](Acc& accs, long long tile) __attribute__((always_inline)) {
         const long long row0 = tile * kTileVecs;
         const long long left = last - row0;                               // uniform
         const int c = (left < col) ? (int)left : col;                     // alias rows past the end
-        if constexpr (RAW) {
-            float4* o = wout + (row0 * D) / 4 + (c * D + 32 * wave + 16 * half) / 4;
+        each_acc(accs, [&](floatx16& acc, int s) {
+            const int slab = wave * S + s;
+            if constexpr (RAW) {
+                float4* o = wout + (row0 * D) / 4 + (c * D + 32 * slab + 16 * half) / 4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                o[i] = make_float4(acc[4 * i] * unscale, acc[4 * i + 1] * unscale,
-                                   acc[4 * i + 2] * unscale, acc[4 * i + 3] * unscale);
-        } else {
-            float m = fmaxf(fabsf(acc[0]), fabsf(acc[1]));
+                for (int i = 0; i < 4; ++i)
+                    o[i] = make_float4(acc[4 * i] * unscale, acc[4 * i + 1] * unscale,
+                                       acc[4 * i + 2] * unscale, acc[4 * i + 3] * unscale);
+            } else {
+                float m = fmaxf(fabsf(acc[0]), fabsf(acc[1]));
 #pragma unroll
-            for (int v = 2; v < 16; ++v) m = fmaxf(m, fabsf(acc[v]));
-            m = other_half_max(m);
-            float scale = m * scale_mul;                 // scale_mul = fl(2^-e / 7): abs-max / 7
-            float inv = unscale * __builtin_amdgcn_rcpf(scale);
-            if (!(scale >= kMinScale)) { scale = 0.0f; inv = 0.0f; }
-            uint2 packed;
-            packed.x = pack8(acc, 0, inv);
-            packed.y = pack8(acc, 8, inv);
-            codes[row0 * (D / 16) + (c * (D / 16) + 2 * wave + half)] = packed;
-            scales[row0 * G + (c * G + wave)] = scale;   // both halves store the same value
-        }
+                for (int v = 2; v < 16; ++v) m = fmaxf(m, fabsf(acc[v]));
+                m = other_half_max(m);
+                float scale = m * scale_mul;                 // scale_mul = fl(2^-e / 7): abs-max / 7
+                float inv = unscale * __builtin_amdgcn_rcpf(scale);
+                if (!(scale >= kMinScale)) { scale = 0.0f; inv = 0.0f; }
+                uint2 packed;
+                packed.x = pack8(acc, 0, inv);
+                packed.y = pack8(acc, 8, inv);
+                codes[row0 * (D / 16) + (c * (D / 16) + 2 * slab + half)] = packed;
+                scales[row0 * G + (c * G + slab)] = scale;   // both halves store the same value
+            }
+        });
     };
 
     const long long t0 = blockIdx.x, stride = gridDim.x;
     const long long m = (n_tiles - 1 - t0) / stride + 1;     // tiles of this workgroup (the grid never exceeds n_tiles)
-    uint4 pa0, pa1, pb0, pb1;
-    floatx16 acc_a, acc_b;
-    fetch(pa0, pa1, t0);
-    fetch(pb0, pb1, t0 + stride);
+    uint4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3;
+    Acc acc_a, acc_b;
+    fetch(pa0, pa1, pa2, pa3, t0);
+    fetch(pb0, pb1, pb2, pb3, t0 + stride);
     hold_in_registers(ahi, alo);                 // the matrix slab has arrived before the pipeline starts
-    to_lds(0, pa0, pa1);
-    fetch(pa0, pa1, t0 + 2 * stride);
+    to_lds(0, pa0, pa1, pa2, pa3);
+    fetch(pa0, pa1, pa2, pa3, t0 + 2 * stride);
     // stage 0
     __syncthreads();
     contract(0, acc_a);
-    to_lds(1, pb0, pb1);
-    fetch(pb0, pb1, t0 + 3 * stride);
+    to_lds(1, pb0, pb1, pb2, pb3);
+    fetch(pb0, pb1, pb2, pb3, t0 + 3 * stride);
     long long k = 1;
     for (; k + 1 < m; k += 2) {
         const long long tk = t0 + k * stride;
         __syncthreads();                         // stage k (odd)
         contract(1, acc_b);
         finish(acc_a, tk - stride);
-        to_lds(0, pa0, pa1);
-        fetch(pa0, pa1, tk + 3 * stride);
+        to_lds(0, pa0, pa1, pa2, pa3);
+        fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
         __syncthreads();                         // stage k + 1 (even)
         contract(0, acc_a);
         finish(acc_b, tk);
-        to_lds(1, pb0, pb1);
-        fetch(pb0, pb1, tk + 4 * stride);
+        to_lds(1, pb0, pb1, pb2, pb3);
+        fetch(pb0, pb1, pb2, pb3, tk + 4 * stride);
     }
     if (k < m) {                                 // one more odd stage
         const long long tk = t0 + k * stride;
@@ -274,8 +302,9 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
 // written out one stage later by all threads as fully coalesced 16-byte-per-lane stores of the
 // contiguous 32 x 2D-byte block (stage k flushes T_{k-2}).  The per-vector scales reach the lanes through
 // LDS as well: they are loaded once per workgroup, coalesced, together with the codes.
-template <int D>
-__global__ void __launch_bounds__(2 * D)
+// S: output slabs per wavefront (the workgroup has D / (32 S) wavefronts), as on the write path.
+template <int D, int S>
+__global__ void __launch_bounds__(2 * D / S)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
                        const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                        float unscale) {
@@ -283,8 +312,12 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     constexpr int U = D / 8;             // 16-byte units per decoded row (D fp16)
     constexpr int ROW = U + 1;
     constexpr int C = D / 16;            // 8-byte code units per row
-    constexpr int NT = 64 * G;
+    constexpr int NT = 64 * G / S;
     constexpr int SROW = G + 1;          // padded row of the scale tile (floats)
+    static_assert(G % S == 0 && (S == 1 || S == 2), "one or two slabs per wavefront");
+    // Two slabs of a large matrix leave no room for alternating accumulators: one accumulator set, each group
+    // folded in as soon as it is done, the tile staged in the stage that computes it.
+    constexpr bool LEAN = (S == 2 && G > 4);
     __shared__ uint4 dec[2][kTileVecs * ROW];    // decoded codes of T_k in dec[k % 2]
     __shared__ uint4 stg[2][kTileVecs * ROW];    // finished fp16 rows of T_k in stg[k % 2]
     __shared__ float scl[2][kTileVecs * SROW];   // scales (times 2^-e) of T_k in scl[k % 2]
@@ -294,68 +327,88 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
     const long long last = n_vec - 1;
 
-    half8 rhi[G][2], rlo[G][2];
+    half8 rhi[S * G][2], rlo[S * G][2];          // [s * G + j][t]
 #pragma unroll
-    for (int j = 0; j < G; ++j)
+    for (int s = 0; s < S; ++s)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            rhi[j][t] = __builtin_bit_cast(half8, rfrag[(((wave * G + j) * 2 + t) * 2 + 0) * 64 + lane]);
-            rlo[j][t] = __builtin_bit_cast(half8, rfrag[(((wave * G + j) * 2 + t) * 2 + 1) * 64 + lane]);
-        }
+        for (int j = 0; j < G; ++j)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int slab = wave * S + s;
+                rhi[s * G + j][t] = __builtin_bit_cast(half8, rfrag[(((slab * G + j) * 2 + t) * 2 + 0) * 64 + lane]);
+                rlo[s * G + j][t] = __builtin_bit_cast(half8, rfrag[(((slab * G + j) * 2 + t) * 2 + 1) * 64 + lane]);
+            }
 
-    // each thread decodes one 8-byte unit of the 32 x D/2 code tile (32 * C = NT units) and carries one
-    // float of the 32 x G scale tile (the first 32 * G threads; the others re-read its last float)
-    const int r0 = tid / C, c0 = tid % C;
+    // each thread decodes S 8-byte units of the 32 x D/2 code tile (32 * C = S * NT units) and carries one
+    // float of the 32 x G scale tile (the first 32 * G threads; any others re-read its last float)
     const int se = (tid < 32 * G) ? tid : 32 * G - 1;
     const int sr = se / G, sj = se % G;
-    struct Pre { uint2 c; float s; };
-    auto fetch = [&](Pre& p, long long tile) {
+    auto fetch1 = [&](uint2& v, int i, long long row0) __attribute__((always_inline)) {
+        const int u = tid + i * NT, r = u / C, c = u % C;
+        const long long rr = (row0 + r < last) ? row0 + r : last;
+        v = codes[rr * C + c];
+    };
+    auto fetch = [&](uint2& c0, uint2& c1, float& sc, long long tile) __attribute__((always_inline)) {
         if (tile > n_tiles - 1) tile = n_tiles - 1;
         const long long row0 = tile * kTileVecs;
-        const long long ra = (row0 + r0 < last) ? row0 + r0 : last;
         const long long rs = (row0 + sr < last) ? row0 + sr : last;
-        p.c = codes[ra * C + c0];
-        p.s = scales[rs * G + sj];
+        fetch1(c0, 0, row0);
+        if constexpr (S > 1) fetch1(c1, 1, row0);
+        sc = scales[rs * G + sj];
     };
-    auto to_lds = [&](int b, const Pre& p) {
-        dec[b][r0 * ROW + 2 * c0] = decode8(p.c.x);
-        dec[b][r0 * ROW + 2 * c0 + 1] = decode8(p.c.y);
-        if (tid < 32 * G) scl[b][sr * SROW + sj] = p.s * unscale;
+    auto put1 = [&](int b, const uint2& v, int i) __attribute__((always_inline)) {
+        const int u = tid + i * NT, r = u / C, c = u % C;
+        dec[b][r * ROW + 2 * c] = decode8(v.x);
+        dec[b][r * ROW + 2 * c + 1] = decode8(v.y);
     };
-    auto scale_of = [&](int b, int j) { return scl[b][col * SROW + j]; };
-    auto group = [&](int b, int j, floatx16& acc) {
+    auto to_lds = [&](int b, const uint2& c0, const uint2& c1, float sc) __attribute__((always_inline)) {
+        put1(b, c0, 0);
+        if constexpr (S > 1) put1(b, c1, 1);
+        if (tid < 32 * G) scl[b][sr * SROW + sj] = sc * unscale;
+    };
+    auto scale_of = [&](int b, int j) __attribute__((always_inline)) { return scl[b][col * SROW + j]; };
+    // The last group of a tile is folded in one stage later, under group 0 of the next tile (which uses
+    // acc0); with an even number of groups it can live in acc1, otherwise it needs a register set of its own.
+    floatx16 o[S], acc0[S], acc1[S], acc_odd[S];
+    auto& acc_last = (G % 2 == 0) ? acc1 : acc_odd;
+    auto group = [&](int b, int j, floatx16 (&acc)[S]) {
         const uint4* rowp = &dec[b][col * ROW + half];
-        acc = floatx16{0};
+#pragma unroll
+        for (int s = 0; s < S; ++s) acc[s] = floatx16{0};
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const half8 bf = __builtin_bit_cast(half8, rowp[4 * j + 2 * t]);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[j][t], bf, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j][t], bf, acc, 0, 0, 0);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                acc[s] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[s * G + j][t], bf, acc[s], 0, 0, 0);
+                acc[s] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[s * G + j][t], bf, acc[s], 0, 0, 0);
+            }
         }
     };
-    // The last group of a tile is folded in one stage later, under group 0 of the next tile (which uses
-    // acc0); with an even number of groups it can live in acc1, otherwise it needs a register set of its own.
-    floatx16 o, acc0, acc1, acc_odd;
-    floatx16& acc_last = (G % 2 == 0) ? acc1 : acc_odd;
-    // o (+)= s * acc
-    auto fold = [&](const floatx16& acc, float s, bool first) {
+    // o (+)= sc * acc
+    auto fold = [&](const floatx16 (&acc)[S], float sc, bool first) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[v] = first ? acc[v] * s : fmaf(acc[v], s, o[v]);
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[s][v] = first ? acc[s][v] * sc : fmaf(acc[s][v], sc, o[s][v]);
     };
-    // the 16 finished outputs of this lane, rounded to fp16, into the staging tile b
-    auto stage_out = [&](int b) {
-        uint4* dst = &stg[b][col * ROW + 4 * wave + 2 * half];
-        dst[0] = make_uint4(pack_half2(o[0], o[1]), pack_half2(o[2], o[3]),
-                            pack_half2(o[4], o[5]), pack_half2(o[6], o[7]));
-        dst[1] = make_uint4(pack_half2(o[8], o[9]), pack_half2(o[10], o[11]),
-                            pack_half2(o[12], o[13]), pack_half2(o[14], o[15]));
+    // the finished outputs of this lane, rounded to fp16, into the staging tile b
+    auto stage_out = [&](int b) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            uint4* dst = &stg[b][col * ROW + 4 * (wave * S + s) + 2 * half];
+            dst[0] = make_uint4(pack_half2(o[s][0], o[s][1]), pack_half2(o[s][2], o[s][3]),
+                                pack_half2(o[s][4], o[s][5]), pack_half2(o[s][6], o[s][7]));
+            dst[1] = make_uint4(pack_half2(o[s][8], o[s][9]), pack_half2(o[s][10], o[s][11]),
+                                pack_half2(o[s][12], o[s][13]), pack_half2(o[s][14], o[s][15]));
+        }
     };
-    // staging tile b -> global rows of `tile`: two fully coalesced 16-byte stores per thread
-    auto flush = [&](int b, long long tile) {
+    // staging tile b -> global rows of `tile`: fully coalesced 16-byte stores, 2 S per thread
+    auto flush = [&](int b, long long tile) __attribute__((always_inline)) {
         const long long row0 = tile * kTileVecs;
         const long long left = last - row0;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 2 * S; ++i) {
             const int u = tid + i * NT, r = u / U, c = u % U;
             const long long rr = (left < r) ? left : r;                 // rows past the end alias to the last row
             out[(row0 + rr) * U + c] = stg[b][r * ROW + c];
@@ -363,10 +416,10 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     };
     // all groups of the tile in dec[b] (scales in scl[b]); `prev`: first fold in the last group of the
     // previous tile, whose scale is s_prev_last, and stage that tile in stg[b_prev]
-    auto tile_body = [&](int b, bool prev, float s_prev_last, int b_prev) {
+    auto tile_body = [&](int b, bool prev, float s_prev_last, int b_prev) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < G; ++j) {
-            floatx16& acc = (j == G - 1) ? acc_last : ((j & 1) ? acc1 : acc0);
+            auto& acc = (j == G - 1) ? acc_last : ((j & 1) ? acc1 : acc0);
             if (j == 0 && prev) {
                 // acc_last still holds the last group of the previous tile
                 if constexpr (G > 1) {
@@ -387,37 +440,69 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
         }
     };
 
+    auto lean_body = [&](int b) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            group(b, j, acc0);
+            fold(acc0, scale_of(b, j), j == 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        stage_out(b);
+    };
+
     const long long t0 = blockIdx.x, stride = gridDim.x;
     const long long m = (n_tiles - 1 - t0) / stride + 1;
-    Pre pa, pb;
+    uint2 pa0, pa1, pb0, pb1;                    // prefetched code units of the next two tiles
+    float pas, pbs;                              // and one float each of their scale tiles
     float s_last;                                // scale of the last group of the tile contracted last
-    fetch(pa, t0);
-    fetch(pb, t0 + stride);
+    fetch(pa0, pa1, pas, t0);
+    fetch(pb0, pb1, pbs, t0 + stride);
     hold_in_registers(rhi, rlo);
-    to_lds(0, pa);
-    fetch(pa, t0 + 2 * stride);
+    to_lds(0, pa0, pa1, pas);
+    fetch(pa0, pa1, pas, t0 + 2 * stride);
+    if constexpr (LEAN) {
+        // stage k: barrier; flush T_{k-1}; contract, fold and stage T_k; decode T_{k+1}
+        for (long long k = 0; k < m; ++k) {
+            const long long tk = t0 + k * stride;
+            __syncthreads();
+            if (k & 1) {
+                flush(0, tk - stride);
+                lean_body(1);
+                to_lds(0, pa0, pa1, pas);
+                fetch(pa0, pa1, pas, tk + 3 * stride);
+            } else {
+                if (k > 0) flush(1, tk - stride);
+                lean_body(0);
+                to_lds(1, pb0, pb1, pbs);
+                fetch(pb0, pb1, pbs, tk + 3 * stride);
+            }
+        }
+        __syncthreads();
+        flush((int)((m - 1) & 1), t0 + (m - 1) * stride);
+        return;
+    }
     // stage 0
     __syncthreads();
     tile_body(0, false, 0.0f, 0);
     s_last = scale_of(0, G - 1);
-    to_lds(1, pb);
-    fetch(pb, t0 + 3 * stride);
+    to_lds(1, pb0, pb1, pbs);
+    fetch(pb0, pb1, pbs, t0 + 3 * stride);
     // stage k: barrier; flush T_{k-2}; contract T_k (staging T_{k-1} under its first group); decode T_{k+1}
-    auto odd_stage = [&](long long tk, auto flush_first) {      // T_k in dec[1]
+    auto odd_stage = [&](long long tk, auto flush_first) __attribute__((always_inline)) {      // T_k in dec[1]
         __syncthreads();
         if constexpr (decltype(flush_first)::value) flush(1, tk - 2 * stride);
         tile_body(1, true, s_last, 0);
         s_last = scale_of(1, G - 1);
-        to_lds(0, pa);
-        fetch(pa, tk + 3 * stride);
+        to_lds(0, pa0, pa1, pas);
+        fetch(pa0, pa1, pas, tk + 3 * stride);
     };
-    auto even_stage = [&](long long tk) {                       // T_k in dec[0]
+    auto even_stage = [&](long long tk) __attribute__((always_inline)) {                       // T_k in dec[0]
         __syncthreads();
         flush(0, tk - 2 * stride);
         tile_body(0, true, s_last, 1);
         s_last = scale_of(0, G - 1);
-        to_lds(1, pb);
-        fetch(pb, tk + 3 * stride);
+        to_lds(1, pb0, pb1, pbs);
+        fetch(pb0, pb1, pbs, tk + 3 * stride);
     };
     long long k = 1;
     if (k + 1 < m) {                             // stages 1 and 2: nothing to flush in stage 1 yet
@@ -558,6 +643,7 @@ struct srft_plan {
     float unscale_w = 1.0f;     // 2^-e of the write matrix
     float unscale_r = 1.0f;
     int grid_q = 0, grid_dq = 0;    // default persistent grid sizes
+    int slabs_q = 1, slabs_dq = 1;  // slabs of the matrix per wavefront in the write / read kernel
     int max_wgs = 0;
 };
 
@@ -566,8 +652,18 @@ namespace {
 template <int D>
 int occupancy_grids(srft_plan* p, int cus) {
     int bq = 0, bd = 0;
-    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, srft_quantize_kernel<D, false>, 2 * D, 0));
-    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, srft_dequantize_kernel<D>, 2 * D, 0));
+    if (p->slabs_q == 2) {
+        if constexpr ((D / 32) % 2 == 0)
+            SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, srft_quantize_kernel<D, 2, false>, D, 0));
+    } else {
+        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, srft_quantize_kernel<D, 1, false>, 2 * D, 0));
+    }
+    if (p->slabs_dq == 2) {
+        if constexpr ((D / 32) % 2 == 0)
+            SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, srft_dequantize_kernel<D, 2>, D, 0));
+    } else {
+        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, srft_dequantize_kernel<D, 1>, 2 * D, 0));
+    }
     p->grid_q = cus * (bq > 0 ? bq : 1);
     p->grid_dq = cus * (bd > 0 ? bd : 1);
     return SRFT_OK;
@@ -579,12 +675,24 @@ int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* cod
     const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_q;
     if (grid > n_tiles) grid = n_tiles;
-    if (wout)
-        hipLaunchKernelGGL((srft_quantize_kernel<D, true>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
-                           (const uint4*)x, n, (uint2*)nullptr, (float*)nullptr, (float4*)wout, p->unscale_w, p->unscale_w / 7.0f);
-    else
-        hipLaunchKernelGGL((srft_quantize_kernel<D, false>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
-                           (const uint4*)x, n, (uint2*)codes, scales, (float4*)nullptr, p->unscale_w, p->unscale_w / 7.0f);
+    const float sm = p->unscale_w / 7.0f;
+    if (p->slabs_q == 2) {
+        if constexpr ((D / 32) % 2 == 0) {
+            if (wout)
+                hipLaunchKernelGGL((srft_quantize_kernel<D, 2, true>), dim3((unsigned)grid), dim3(D), 0, st, p->wfrag,
+                                   (const uint4*)x, n, (uint2*)nullptr, (float*)nullptr, (float4*)wout, p->unscale_w, sm);
+            else
+                hipLaunchKernelGGL((srft_quantize_kernel<D, 2, false>), dim3((unsigned)grid), dim3(D), 0, st, p->wfrag,
+                                   (const uint4*)x, n, (uint2*)codes, scales, (float4*)nullptr, p->unscale_w, sm);
+        }
+    } else {
+        if (wout)
+            hipLaunchKernelGGL((srft_quantize_kernel<D, 1, true>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
+                               (const uint4*)x, n, (uint2*)nullptr, (float*)nullptr, (float4*)wout, p->unscale_w, sm);
+        else
+            hipLaunchKernelGGL((srft_quantize_kernel<D, 1, false>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
+                               (const uint4*)x, n, (uint2*)codes, scales, (float4*)nullptr, p->unscale_w, sm);
+    }
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
@@ -595,8 +703,14 @@ int launch_dequantize(const srft_plan* p, const uint8_t* codes, const float* sca
     const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_dq;
     if (grid > n_tiles) grid = n_tiles;
-    hipLaunchKernelGGL((srft_dequantize_kernel<D>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->rfrag,
-                       (const uint2*)codes, scales, n, (uint4*)out, p->unscale_r);
+    if (p->slabs_dq == 2) {
+        if constexpr ((D / 32) % 2 == 0)
+            hipLaunchKernelGGL((srft_dequantize_kernel<D, 2>), dim3((unsigned)grid), dim3(D), 0, st, p->rfrag,
+                               (const uint2*)codes, scales, n, (uint4*)out, p->unscale_r);
+    } else {
+        hipLaunchKernelGGL((srft_dequantize_kernel<D, 1>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->rfrag,
+                           (const uint2*)codes, scales, n, (uint4*)out, p->unscale_r);
+    }
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
@@ -619,6 +733,15 @@ int dispatch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* c
                       hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_quantize, p, x, n, c, s, w, st) }
 int dispatch_dequantize(const srft_plan* p, const uint8_t* c, const float* s, long long n, void* o,
                         hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_dequantize, p, c, s, n, o, st) }
+
+// Slabs per wavefront: 1, or 2 where the number of groups is even and the table (or the tuning override in
+// the environment) says so.
+int default_slabs(int d, const char* env_name, int table_value) {
+    int s = table_value;
+    if (const char* e = std::getenv(env_name)) s = std::atoi(e);
+    if (s != 2 || (d / 32) % 2 != 0) s = 1;
+    return s;
+}
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
@@ -705,6 +828,8 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
                     }
         }
 
+    p->slabs_q = default_slabs(d, "SRFT_SLABS_Q", d == 64 ? 2 : 1);
+    p->slabs_dq = default_slabs(d, "SRFT_SLABS_DQ", (d == 256 || d == 64) ? 2 : 1);
     hipError_t e = hipGetDevice(&p->device);
     int cus = 0;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
