@@ -23,7 +23,8 @@
  *     All argument checks happen before the first HIP call.
  *   - Supported shapes: d a multiple of 32 with 32 <= d <= 256 (so 96 = 2^5 * 3 is covered; the
  *     transform is applied as a dense d x d contraction, which needs no power-of-two length);
- *     group_size 32.
+ *     group_size g = 32 (the deployed format, the fast path), 16, or any multiple of 32 that divides d
+ *     (g = d is the per-token quantizer of Sec. 3.2 step 3).
  */
 #ifndef SRFT_KV_H
 #define SRFT_KV_H
@@ -41,7 +42,7 @@ typedef enum srft_status {
     SRFT_OK             =  0,
     SRFT_ERR_NULL       = -1,   /* a required pointer is NULL */
     SRFT_ERR_BAD_D      = -2,   /* d not a multiple of 32 in [32, 256] */
-    SRFT_ERR_BAD_GROUP  = -3,   /* group_size not supported (must be 32) */
+    SRFT_ERR_BAD_GROUP  = -3,   /* group_size not 16 and not a multiple of 32 dividing d */
     SRFT_ERR_BAD_LAMBDA = -4,   /* a lambda is not finite, not > 0, or max/min exceeds 2^16 */
     SRFT_ERR_ALIGN      = -5,   /* a device pointer is not aligned as documented */
     SRFT_ERR_HIP        = -6,   /* a HIP call failed; see srft_last_hip_error() */

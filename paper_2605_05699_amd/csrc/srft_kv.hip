@@ -123,11 +123,16 @@ __device__ __forceinline__ uint32_t pack8(const floatx16& acc, int base, float i
 //         tile; the price is a 2 x larger register-resident slab (at d = 256 it only fits with one wavefront
 //         per SIMD, the slab in the accumulation half of the register file).
 // RAW   : store the fp32 coefficients w instead of quantizing (srft_kv_forward_f32)
-template <int D, int S, bool RAW>
+// GM    : group mode.  kGroup32: one scale per slab (g = 32, the deployed format).  kGroup16: one scale per
+//         lane (g = 16; a lane's 16 outputs are one group, no cross-lane step).  kGroupWide: g = 32 * gw with
+//         gw >= 2 slabs per group, up to the per-token case g = d; the slab maxima meet in LDS, which costs
+//         two more barriers per tile.
+enum { kGroup16 = 0, kGroup32 = 1, kGroupWide = 2 };
+template <int D, int S, bool RAW, int GM>
 __global__ void __launch_bounds__(2 * D / S)
 srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
                      uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
-                     float unscale, float scale_mul) {
+                     float unscale, float scale_mul, int gw) {
     constexpr int G = D / 32;            // quantization groups per vector = slabs of the matrix
     constexpr int T = D / 16;            // MFMA k-steps
     constexpr int U = D / 8;             // 16-byte units per input row
@@ -137,6 +142,7 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
     constexpr int TB = (T < 8) ? T : 8;  // B fragments read from LDS ahead of their MFMAs
     static_assert(G % S == 0, "slabs per wavefront must divide the number of groups");
     __shared__ uint4 lds[2][kTileVecs * ROW];
+    __shared__ float gmax[GM == kGroupWide ? kTileVecs * G : 1];     // per (vector, slab) abs-max
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -177,7 +183,7 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
     using Acc = Accs<S>;
     auto contract = [&](int b, Acc& accs) __attribute__((always_inline)) {
         const uint4* rowp = &lds[b][col * ROW + half];
-        each_acc(accs, [&](floatx16& acc, int) { acc = floatx16{0}; });
+        each_acc(accs, [&](floatx16& acc, int) __attribute__((always_inline)) { acc = floatx16{0}; });
 #pragma unroll
         for (int t0 = 0; t0 < T; t0 += TB) {
             half8 bf[TB];
@@ -187,7 +193,7 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
 #pragma unroll
             for (int t = 0; t < TB; ++t)
                 if (t0 + t < T) {
-                    each_acc(accs, [&](floatx16& acc, int s) {
+                    each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
                         acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[s][t0 + t], bf[t], acc, 0, 0, 0);
                         acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[s][t0 + t], bf[t], acc, 0, 0, 0);
                     });
@@ -199,29 +205,52 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
         const long long row0 = tile * kTileVecs;
         const long long left = last - row0;                               // uniform
         const int c = (left < col) ? (int)left : col;                     // alias rows past the end
-        each_acc(accs, [&](floatx16& acc, int s) {
-            const int slab = wave * S + s;
-            if constexpr (RAW) {
+        if constexpr (RAW) {
+            each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
+                const int slab = wave * S + s;
                 float4* o = wout + (row0 * D) / 4 + (c * D + 32 * slab + 16 * half) / 4;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     o[i] = make_float4(acc[4 * i] * unscale, acc[4 * i + 1] * unscale,
                                        acc[4 * i + 2] * unscale, acc[4 * i + 3] * unscale);
-            } else {
+            });
+        } else {
+            float mm[S];
+            each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
                 float m = fmaxf(fabsf(acc[0]), fabsf(acc[1]));
 #pragma unroll
                 for (int v = 2; v < 16; ++v) m = fmaxf(m, fabsf(acc[v]));
-                m = other_half_max(m);
-                float scale = m * scale_mul;                 // scale_mul = fl(2^-e / 7): abs-max / 7
+                if constexpr (GM != kGroup16) m = other_half_max(m);
+                mm[s] = m;
+            });
+            if constexpr (GM == kGroupWide) {
+                __syncthreads();                             // the previous tile's maxima have been read
+#pragma unroll
+                for (int s = 0; s < S; ++s) gmax[col * G + wave * S + s] = mm[s];
+                __syncthreads();
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    const int first = (wave * S + s) / gw * gw;
+                    float m = gmax[col * G + first];
+                    for (int i = 1; i < gw; ++i) m = fmaxf(m, gmax[col * G + first + i]);
+                    mm[s] = m;
+                }
+            }
+            each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
+                const int slab = wave * S + s;
+                float scale = mm[s] * scale_mul;             // scale_mul = fl(2^-e / 7): abs-max / 7
                 float inv = unscale * __builtin_amdgcn_rcpf(scale);
                 if (!(scale >= kMinScale)) { scale = 0.0f; inv = 0.0f; }
                 uint2 packed;
                 packed.x = pack8(acc, 0, inv);
                 packed.y = pack8(acc, 8, inv);
                 codes[row0 * (D / 16) + (c * (D / 16) + 2 * slab + half)] = packed;
-                scales[row0 * G + (c * G + slab)] = scale;   // both halves store the same value
-            }
-        });
+                // lanes that hold the same group store the same value to the same place
+                if constexpr (GM == kGroup16) scales[row0 * (2 * G) + (c * (2 * G) + 2 * slab + half)] = scale;
+                else if constexpr (GM == kGroup32) scales[row0 * G + (c * G + slab)] = scale;
+                else scales[row0 * (G / gw) + (c * (G / gw) + slab / gw)] = scale;
+            });
+        }
     };
 
     const long long t0 = blockIdx.x, stride = gridDim.x;
@@ -302,22 +331,27 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
 // written out one stage later by all threads as fully coalesced 16-byte-per-lane stores of the
 // contiguous 32 x 2D-byte block (stage k flushes T_{k-2}).  The per-vector scales reach the lanes through
 // LDS as well: they are loaded once per workgroup, coalesced, together with the codes.
-// S: output slabs per wavefront (the workgroup has D / (32 S) wavefronts), as on the write path.
-template <int D, int S>
+// S : output slabs per wavefront (the workgroup has D / (32 S) wavefronts), as on the write path.
+// KS: MFMA k-steps (of 16 codes) contracted under one scale: 2 for g >= 32 (g = 32 * gw, gw slabs of codes
+//     share a scale), 1 for g = 16.  "Group" below means one such run of 16 * KS codes.
+template <int D, int S, int KS>
 __global__ void __launch_bounds__(2 * D / S)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
                        const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
-                       float unscale) {
-    constexpr int G = D / 32;
+                       float unscale, int gw) {
+    constexpr int G = D / 32 * (2 / KS);  // groups per vector as contracted
+    constexpr int NSMAX = D / 16;         // most scales a vector can have (g = 16)
+    const int ns = (KS == 1) ? D / 16 : D / 32 / gw;      // scales per vector
     constexpr int U = D / 8;             // 16-byte units per decoded row (D fp16)
     constexpr int ROW = U + 1;
     constexpr int C = D / 16;            // 8-byte code units per row
-    constexpr int NT = 64 * G / S;
-    constexpr int SROW = G + 1;          // padded row of the scale tile (floats)
-    static_assert(G % S == 0 && (S == 1 || S == 2), "one or two slabs per wavefront");
+    constexpr int NT = 2 * D / S;
+    constexpr int SROW = NSMAX + 1;      // padded row of the scale tile (floats)
+    constexpr int PS = (32 * NSMAX + NT - 1) / NT;      // scale floats a thread may have to carry (1 or 2)
+    static_assert((D / 32) % S == 0 && (S == 1 || S == 2), "one or two slabs per wavefront");
     // Two slabs of a large matrix leave no room for alternating accumulators: one accumulator set, each group
     // folded in as soon as it is done, the tile staged in the stage that computes it.
-    constexpr bool LEAN = (S == 2 && G > 4);
+    constexpr bool LEAN = (S == 2 && D / 32 > 4);
     __shared__ uint4 dec[2][kTileVecs * ROW];    // decoded codes of T_k in dec[k % 2]
     __shared__ uint4 stg[2][kTileVecs * ROW];    // finished fp16 rows of T_k in stg[k % 2]
     __shared__ float scl[2][kTileVecs * SROW];   // scales (times 2^-e) of T_k in scl[k % 2]
@@ -327,46 +361,57 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
     const long long last = n_vec - 1;
 
-    half8 rhi[S * G][2], rlo[S * G][2];          // [s * G + j][t]
+    half8 rhi[S * G][KS], rlo[S * G][KS];        // [s * G + group][k-step within the group]
 #pragma unroll
     for (int s = 0; s < S; ++s)
 #pragma unroll
         for (int j = 0; j < G; ++j)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int slab = wave * S + s;
-                rhi[s * G + j][t] = __builtin_bit_cast(half8, rfrag[(((slab * G + j) * 2 + t) * 2 + 0) * 64 + lane]);
-                rlo[s * G + j][t] = __builtin_bit_cast(half8, rfrag[(((slab * G + j) * 2 + t) * 2 + 1) * 64 + lane]);
+            for (int t = 0; t < KS; ++t) {
+                const int slab = wave * S + s, kstep = j * KS + t;
+                rhi[s * G + j][t] = __builtin_bit_cast(half8, rfrag[((slab * (D / 16) + kstep) * 2 + 0) * 64 + lane]);
+                rlo[s * G + j][t] = __builtin_bit_cast(half8, rfrag[((slab * (D / 16) + kstep) * 2 + 1) * 64 + lane]);
             }
 
-    // each thread decodes S 8-byte units of the 32 x D/2 code tile (32 * C = S * NT units) and carries one
-    // float of the 32 x G scale tile (the first 32 * G threads; any others re-read its last float)
-    const int se = (tid < 32 * G) ? tid : 32 * G - 1;
-    const int sr = se / G, sj = se % G;
+    // each thread decodes S 8-byte units of the 32 x D/2 code tile (32 * C = S * NT units) and carries up to
+    // PS floats of the 32 x ns scale tile (float e = tid + i * NT; past the end it re-reads the last one)
     auto fetch1 = [&](uint2& v, int i, long long row0) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / C, c = u % C;
         const long long rr = (row0 + r < last) ? row0 + r : last;
         v = codes[rr * C + c];
     };
-    auto fetch = [&](uint2& c0, uint2& c1, float& sc, long long tile) __attribute__((always_inline)) {
+    auto fetch_scale = [&](float& sc, int i, long long row0) __attribute__((always_inline)) {
+        int e = tid + i * NT;
+        if (e > 32 * ns - 1) e = 32 * ns - 1;
+        const int r = e / ns, j = e % ns;
+        const long long rs = (row0 + r < last) ? row0 + r : last;
+        sc = scales[rs * ns + j];
+    };
+    auto fetch = [&](uint2& c0, uint2& c1, float& s0, float& s1, long long tile) __attribute__((always_inline)) {
         if (tile > n_tiles - 1) tile = n_tiles - 1;
         const long long row0 = tile * kTileVecs;
-        const long long rs = (row0 + sr < last) ? row0 + sr : last;
         fetch1(c0, 0, row0);
         if constexpr (S > 1) fetch1(c1, 1, row0);
-        sc = scales[rs * G + sj];
+        fetch_scale(s0, 0, row0);
+        if constexpr (PS > 1) fetch_scale(s1, 1, row0);
     };
     auto put1 = [&](int b, const uint2& v, int i) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / C, c = u % C;
         dec[b][r * ROW + 2 * c] = decode8(v.x);
         dec[b][r * ROW + 2 * c + 1] = decode8(v.y);
     };
-    auto to_lds = [&](int b, const uint2& c0, const uint2& c1, float sc) __attribute__((always_inline)) {
+    auto put_scale = [&](int b, float sc, int i) __attribute__((always_inline)) {
+        const int e = tid + i * NT;
+        if (e < 32 * ns) scl[b][(e / ns) * SROW + e % ns] = sc * unscale;
+    };
+    auto to_lds = [&](int b, const uint2& c0, const uint2& c1, float s0, float s1) __attribute__((always_inline)) {
         put1(b, c0, 0);
         if constexpr (S > 1) put1(b, c1, 1);
-        if (tid < 32 * G) scl[b][sr * SROW + sj] = sc * unscale;
+        put_scale(b, s0, 0);
+        if constexpr (PS > 1) put_scale(b, s1, 1);
     };
-    auto scale_of = [&](int b, int j) __attribute__((always_inline)) { return scl[b][col * SROW + j]; };
+    // scale of contracted group j: its own at g = 16 and g = 32, shared by gw groups at g = 32 * gw
+    auto scale_of = [&](int b, int j) __attribute__((always_inline)) { return scl[b][col * SROW + (KS == 1 ? j : j / gw)]; };
     // The last group of a tile is folded in one stage later, under group 0 of the next tile (which uses
     // acc0); with an even number of groups it can live in acc1, otherwise it needs a register set of its own.
     floatx16 o[S], acc0[S], acc1[S], acc_odd[S];
@@ -376,8 +421,8 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
 #pragma unroll
         for (int s = 0; s < S; ++s) acc[s] = floatx16{0};
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const half8 bf = __builtin_bit_cast(half8, rowp[4 * j + 2 * t]);
+        for (int t = 0; t < KS; ++t) {
+            const half8 bf = __builtin_bit_cast(half8, rowp[2 * (j * KS + t)]);
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 acc[s] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[s * G + j][t], bf, acc[s], 0, 0, 0);
@@ -453,13 +498,13 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     const long long t0 = blockIdx.x, stride = gridDim.x;
     const long long m = (n_tiles - 1 - t0) / stride + 1;
     uint2 pa0, pa1, pb0, pb1;                    // prefetched code units of the next two tiles
-    float pas, pbs;                              // and one float each of their scale tiles
+    float pas, pat, pbs, pbt;                    // and up to two floats each of their scale tiles
     float s_last;                                // scale of the last group of the tile contracted last
-    fetch(pa0, pa1, pas, t0);
-    fetch(pb0, pb1, pbs, t0 + stride);
+    fetch(pa0, pa1, pas, pat, t0);
+    fetch(pb0, pb1, pbs, pbt, t0 + stride);
     hold_in_registers(rhi, rlo);
-    to_lds(0, pa0, pa1, pas);
-    fetch(pa0, pa1, pas, t0 + 2 * stride);
+    to_lds(0, pa0, pa1, pas, pat);
+    fetch(pa0, pa1, pas, pat, t0 + 2 * stride);
     if constexpr (LEAN) {
         // stage k: barrier; flush T_{k-1}; contract, fold and stage T_k; decode T_{k+1}
         for (long long k = 0; k < m; ++k) {
@@ -468,13 +513,13 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
             if (k & 1) {
                 flush(0, tk - stride);
                 lean_body(1);
-                to_lds(0, pa0, pa1, pas);
-                fetch(pa0, pa1, pas, tk + 3 * stride);
+                to_lds(0, pa0, pa1, pas, pat);
+                fetch(pa0, pa1, pas, pat, tk + 3 * stride);
             } else {
                 if (k > 0) flush(1, tk - stride);
                 lean_body(0);
-                to_lds(1, pb0, pb1, pbs);
-                fetch(pb0, pb1, pbs, tk + 3 * stride);
+                to_lds(1, pb0, pb1, pbs, pbt);
+                fetch(pb0, pb1, pbs, pbt, tk + 3 * stride);
             }
         }
         __syncthreads();
@@ -485,24 +530,24 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
     __syncthreads();
     tile_body(0, false, 0.0f, 0);
     s_last = scale_of(0, G - 1);
-    to_lds(1, pb0, pb1, pbs);
-    fetch(pb0, pb1, pbs, t0 + 3 * stride);
+    to_lds(1, pb0, pb1, pbs, pbt);
+    fetch(pb0, pb1, pbs, pbt, t0 + 3 * stride);
     // stage k: barrier; flush T_{k-2}; contract T_k (staging T_{k-1} under its first group); decode T_{k+1}
     auto odd_stage = [&](long long tk, auto flush_first) __attribute__((always_inline)) {      // T_k in dec[1]
         __syncthreads();
         if constexpr (decltype(flush_first)::value) flush(1, tk - 2 * stride);
         tile_body(1, true, s_last, 0);
         s_last = scale_of(1, G - 1);
-        to_lds(0, pa0, pa1, pas);
-        fetch(pa0, pa1, pas, tk + 3 * stride);
+        to_lds(0, pa0, pa1, pas, pat);
+        fetch(pa0, pa1, pas, pat, tk + 3 * stride);
     };
     auto even_stage = [&](long long tk) __attribute__((always_inline)) {                       // T_k in dec[0]
         __syncthreads();
         flush(0, tk - 2 * stride);
         tile_body(0, true, s_last, 1);
         s_last = scale_of(0, G - 1);
-        to_lds(1, pb0, pb1, pbs);
-        fetch(pb0, pb1, pbs, tk + 3 * stride);
+        to_lds(1, pb0, pb1, pbs, pbt);
+        fetch(pb0, pb1, pbs, pbt, tk + 3 * stride);
     };
     long long k = 1;
     if (k + 1 < m) {                             // stages 1 and 2: nothing to flush in stage 1 yet
@@ -644,26 +689,47 @@ struct srft_plan {
     float unscale_r = 1.0f;
     int grid_q = 0, grid_dq = 0;    // default persistent grid sizes
     int slabs_q = 1, slabs_dq = 1;  // slabs of the matrix per wavefront in the write / read kernel
+    int gm = 1, gw = 1;             // group mode (kGroup16 / kGroup32 / kGroupWide) and slabs per group
     int max_wgs = 0;
 };
 
 namespace {
 
+typedef void (*quantize_kernel_t)(const uint4*, const uint4*, long long, uint2*, float*, float4*, float, float, int);
+typedef void (*dequantize_kernel_t)(const uint4*, const uint2*, const float*, long long, uint4*, float, int);
+
+// The kernel instance for a plan: d, slabs per wavefront, group mode.
+template <int D, int S>
+quantize_kernel_t quantize_instance(bool raw, int gm) {
+    if (raw) return srft_quantize_kernel<D, S, true, kGroup32>;
+    switch (gm) {
+        case kGroup16: return srft_quantize_kernel<D, S, false, kGroup16>;
+        case kGroupWide: return srft_quantize_kernel<D, S, false, kGroupWide>;
+        default: return srft_quantize_kernel<D, S, false, kGroup32>;
+    }
+}
+template <int D>
+quantize_kernel_t quantize_instance(int slabs, bool raw, int gm) {
+    if constexpr ((D / 32) % 2 == 0) {
+        if (slabs == 2) return quantize_instance<D, 2>(raw, gm);
+    }
+    return quantize_instance<D, 1>(raw, gm);
+}
+template <int D>
+dequantize_kernel_t dequantize_instance(int slabs, int gm) {
+    if constexpr ((D / 32) % 2 == 0) {
+        if (slabs == 2) return gm == kGroup16 ? srft_dequantize_kernel<D, 2, 1> : srft_dequantize_kernel<D, 2, 2>;
+    }
+    return gm == kGroup16 ? srft_dequantize_kernel<D, 1, 1> : srft_dequantize_kernel<D, 1, 2>;
+}
+
 template <int D>
 int occupancy_grids(srft_plan* p, int cus) {
     int bq = 0, bd = 0;
-    if (p->slabs_q == 2) {
-        if constexpr ((D / 32) % 2 == 0)
-            SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, srft_quantize_kernel<D, 2, false>, D, 0));
-    } else {
-        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, srft_quantize_kernel<D, 1, false>, 2 * D, 0));
-    }
-    if (p->slabs_dq == 2) {
-        if constexpr ((D / 32) % 2 == 0)
-            SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, srft_dequantize_kernel<D, 2>, D, 0));
-    } else {
-        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, srft_dequantize_kernel<D, 1>, 2 * D, 0));
-    }
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, quantize_instance<D>(p->slabs_q, false, p->gm),
+                                                          2 * D / p->slabs_q, 0));
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, dequantize_instance<D>(p->slabs_dq, p->gm),
+                                                          2 * D / p->slabs_dq, 0));
     p->grid_q = cus * (bq > 0 ? bq : 1);
     p->grid_dq = cus * (bd > 0 ? bd : 1);
     return SRFT_OK;
@@ -675,24 +741,9 @@ int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* cod
     const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_q;
     if (grid > n_tiles) grid = n_tiles;
-    const float sm = p->unscale_w / 7.0f;
-    if (p->slabs_q == 2) {
-        if constexpr ((D / 32) % 2 == 0) {
-            if (wout)
-                hipLaunchKernelGGL((srft_quantize_kernel<D, 2, true>), dim3((unsigned)grid), dim3(D), 0, st, p->wfrag,
-                                   (const uint4*)x, n, (uint2*)nullptr, (float*)nullptr, (float4*)wout, p->unscale_w, sm);
-            else
-                hipLaunchKernelGGL((srft_quantize_kernel<D, 2, false>), dim3((unsigned)grid), dim3(D), 0, st, p->wfrag,
-                                   (const uint4*)x, n, (uint2*)codes, scales, (float4*)nullptr, p->unscale_w, sm);
-        }
-    } else {
-        if (wout)
-            hipLaunchKernelGGL((srft_quantize_kernel<D, 1, true>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
-                               (const uint4*)x, n, (uint2*)nullptr, (float*)nullptr, (float4*)wout, p->unscale_w, sm);
-        else
-            hipLaunchKernelGGL((srft_quantize_kernel<D, 1, false>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->wfrag,
-                               (const uint4*)x, n, (uint2*)codes, scales, (float4*)nullptr, p->unscale_w, sm);
-    }
+    const quantize_kernel_t kernel = quantize_instance<D>(p->slabs_q, wout != nullptr, p->gm);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(2 * D / p->slabs_q), 0, st, p->wfrag, (const uint4*)x, n,
+                       (uint2*)codes, scales, (float4*)wout, p->unscale_w, p->unscale_w / 7.0f, p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
@@ -703,14 +754,9 @@ int launch_dequantize(const srft_plan* p, const uint8_t* codes, const float* sca
     const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_dq;
     if (grid > n_tiles) grid = n_tiles;
-    if (p->slabs_dq == 2) {
-        if constexpr ((D / 32) % 2 == 0)
-            hipLaunchKernelGGL((srft_dequantize_kernel<D, 2>), dim3((unsigned)grid), dim3(D), 0, st, p->rfrag,
-                               (const uint2*)codes, scales, n, (uint4*)out, p->unscale_r);
-    } else {
-        hipLaunchKernelGGL((srft_dequantize_kernel<D, 1>), dim3((unsigned)grid), dim3(2 * D), 0, st, p->rfrag,
-                           (const uint2*)codes, scales, n, (uint4*)out, p->unscale_r);
-    }
+    const dequantize_kernel_t kernel = dequantize_instance<D>(p->slabs_dq, p->gm);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(2 * D / p->slabs_dq), 0, st, p->rfrag, (const uint2*)codes,
+                       scales, n, (uint4*)out, p->unscale_r, p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
@@ -771,7 +817,7 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
     if (!out) return SRFT_ERR_NULL;
     *out = nullptr;
     if (d < 32 || d > kMaxD || d % 32 != 0) return SRFT_ERR_BAD_D;
-    if (group_size != 32) return SRFT_ERR_BAD_GROUP;
+    if (!(group_size == 16 || (group_size >= 32 && group_size % 32 == 0 && d % group_size == 0))) return SRFT_ERR_BAD_GROUP;
     std::vector<double> lam(d, 1.0);
     if (lambda_host) {
         double lo = INFINITY, hi = 0.0;
@@ -789,6 +835,8 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
     if (!p) return SRFT_ERR_HIP;
     p->d = d;
     p->g = group_size;
+    p->gm = group_size == 16 ? kGroup16 : (group_size == 32 ? kGroup32 : kGroupWide);
+    p->gw = group_size <= 32 ? 1 : group_size / 32;
     p->seed = sign_seed;
     p->signs.resize(d);
     uint64_t state = sign_seed;
@@ -956,7 +1004,7 @@ const char* srft_status_string(int status) {
         case SRFT_OK: return "ok";
         case SRFT_ERR_NULL: return "required pointer is NULL";
         case SRFT_ERR_BAD_D: return "unsupported head dimension (need a multiple of 32 in [32, 256])";
-        case SRFT_ERR_BAD_GROUP: return "unsupported group size (need 32)";
+        case SRFT_ERR_BAD_GROUP: return "unsupported group size (need 16, or a multiple of 32 that divides d)";
         case SRFT_ERR_BAD_LAMBDA: return "lambda must be finite, > 0 and span at most 2^16";
         case SRFT_ERR_ALIGN: return "device pointer is misaligned";
         case SRFT_ERR_HIP: return "HIP call failed (see srft_last_hip_error)";

@@ -47,7 +47,7 @@ def test_plan_create_rejects_bad_arguments_before_any_hip_call(L):
     for d in (0, 2, 16, 31, 100, 130, 288, 512, -128):
         assert L.srft_plan_create(C.byref(h), d, 32, 0, None) == -2, d
         assert h.value is None
-    for g in (0, 16, 64, 128, 33):
+    for g in (0, 8, 33, 48, 96, 256, -32):
         assert L.srft_plan_create(C.byref(h), 128, g, 0, None) == -3, g
     for bad in (0.0, -1.0, float("nan"), float("inf")):
         lam[17] = bad

@@ -74,6 +74,37 @@ def test_quantize_and_dequantize_match_oracle(B, d, n):
         assert r["bit_identical_fraction"] > 0.99
 
 
+GROUP_CASES = [(128, 16), (128, 64), (128, 128), (96, 16), (96, 96), (256, 16), (256, 64), (256, 128), (256, 256),
+               (64, 16), (64, 64), (192, 96), (32, 16), (160, 160)]
+
+
+@pytest.mark.parametrize("d,g", GROUP_CASES)
+@pytest.mark.parametrize("n", [33, 2531])
+def test_other_group_sizes_match_oracle(B, d, g, n):
+    # g = 16, multiples of 32, and the per-token quantizer g = d (Sec. 3.2 step 3)
+    x, s, lam, codes, scales, out = _run_both(B, d, n, seed=7 * d + g + n, g=g)
+    assert scales.shape == (n, d // g)
+    q = P.check_quantize(x, s, lam, g, codes, scales)
+    r = P.check_dequantize(codes, scales, s, lam, g, out)
+    if n > 1000:
+        assert q["mismatch_rate"] < 1e-3 and r["bit_identical_fraction"] > 0.99
+
+
+def test_group_sizes_do_not_depend_on_the_grid(B):
+    d, n = 128, 3000
+    x = torch.from_numpy(W.gaussian_with_outliers(n, d, seed=5)).cuda()
+    for g in (16, 64, 128):
+        plan = B.Plan(d, g, 5, W.lognormal_lambda(d, 5))
+        c0, s0 = plan.quantize(x)
+        o0 = plan.dequantize(c0, s0)
+        for cap in (1, 5):
+            B.srft_plan_set_max_workgroups(plan.handle, cap)
+            c1, s1 = plan.quantize(x)
+            o1 = plan.dequantize(c1, s1)
+            assert torch.equal(c0, c1) and torch.equal(s0, s1) and torch.equal(o0, o1)
+        plan.close()
+
+
 @pytest.mark.parametrize("d", MAIN_D)
 def test_larger_batch_spanning_many_workgroups(B, d):
     n = 70_001                     # > 2000 tiles with a ragged tail: every workgroup loops
