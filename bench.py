@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--max-workgroups", type=int, default=0)
     ap.add_argument("--ceiling", action="store_true",
                     help="also time the streaming kernel that has each path's read:write byte mix (HBM ceiling)")
+    ap.add_argument("--decode-append", action="store_true",
+                    help="also time the decode-step append of the decode-d96 workload: a launch per plan against "
+                         "one batched launch")
     ap.add_argument("--copy-bytes", type=int, default=0,
                     help="also run the library's plain copy kernel over this many bytes (counter calibration)")
     args = ap.parse_args()
@@ -141,6 +144,8 @@ def main() -> int:
 
     if args.ceiling:
         result["hbm_ceiling"] = mix_ceiling(B, torch, x, out, n_plans * n, d, G, stream)
+    if args.decode_append:
+        result["decode_append"] = decode_append(B, W, torch, dev, stream)
     if args.copy_bytes:
         nb = args.copy_bytes // 16 * 16
         src = out.view(torch.uint8).reshape(-1)[:nb]
@@ -182,6 +187,55 @@ def mix_ceiling(B, torch, x, out, total_vec, d, G, stream):
             best[str(wgs)] = n_tiles * (rb + wb) / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
         res[name + "_GBps_by_workgroups"] = best
         res[name + "_GBps"] = max(best.values())
+    return res
+
+
+def decode_append(B, W, torch, dev, stream, iters=200):
+    """One decode step of the decode-d96 workload: every plan appends batch x kv_heads new vectors (write path)
+    and, for comparison, reads the same few back.  Microseconds per step, a launch per plan against one batched
+    launch per direction."""
+    w = W.WORKLOADS["decode-d96"]
+    n, d, G, k = w.append_vectors_per_plan, w.d, w.d // w.g, w.n_plans
+    plans = [B.Plan(d, w.g, *W.plan_constants(w, p)[:2]) for p in range(k)]
+    x = torch.empty(k, n, d, dtype=torch.float16, device=dev)
+    for p in range(k):
+        W.fill_kv(x[p], w, p)
+    codes = torch.empty(k, n, d // 2, dtype=torch.uint8, device=dev)
+    scales = torch.empty(k, n, G, dtype=torch.float32, device=dev)
+    out = torch.empty(k, n, d, dtype=torch.float16, device=dev)
+    h = [pl.handle for pl in plans]
+    tq = B.BatchTable(h, list(x), list(codes), list(scales))
+    td = B.BatchTable(h, list(out), list(codes), list(scales))
+
+    def timed(fn):
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(iters):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return {"gpu_us": e0.elapsed_time(e1) / iters * 1e3, "wall_us": (time.perf_counter() - t0) / iters * 1e6}
+
+    def per_plan_q():
+        for p in range(k):
+            B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
+
+    def per_plan_d():
+        for p in range(k):
+            B.srft_kv_dequantize(h[p], codes[p], scales[p], out[p], stream)
+
+    res = {"workload": w.name, "plans": k, "vectors_per_plan": n, "d": d,
+           "bytes_per_step_each_direction": k * n * (2 * d + d // 2 + 4 * G),
+           "quantize_per_plan": timed(per_plan_q),
+           "quantize_batched": timed(lambda: B.srft_kv_quantize_batched(tq, stream)),
+           "dequantize_per_plan": timed(per_plan_d),
+           "dequantize_batched": timed(lambda: B.srft_kv_dequantize_batched(td, stream))}
+    for pl in plans:
+        pl.close()
     return res
 
 

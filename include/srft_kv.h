@@ -46,7 +46,8 @@ typedef enum srft_status {
     SRFT_ERR_BAD_LAMBDA = -4,   /* a lambda is not finite, not > 0, or max/min exceeds 2^16 */
     SRFT_ERR_ALIGN      = -5,   /* a device pointer is not aligned as documented */
     SRFT_ERR_HIP        = -6,   /* a HIP call failed; see srft_last_hip_error() */
-    SRFT_ERR_BAD_N      = -7    /* n_vec < 0 or byte count negative */
+    SRFT_ERR_BAD_N      = -7,   /* n_vec < 0, count < 0 or byte count negative */
+    SRFT_ERR_MISMATCH   = -8    /* plans of one batched call differ in d, group_size or device */
 } srft_status;
 
 /*
@@ -85,6 +86,27 @@ int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_v
  */
 int srft_kv_dequantize(const srft_plan_t* plan, const uint8_t* codes_dev, const float* scales_dev,
                        int64_t n_vec, void* out_f16_dev, void* hip_stream);
+
+/*
+ * Write path / read path over several plans in one launch.     (Sec. 7.2: one stored transform per layer and
+ * K|V; a decode step appends a few vectors to every one of them, so a launch per plan is all latency.)
+ *   plans, *_dev arrays, n_vec   HOST arrays of `count` entries; entry i describes one call of
+ *                                srft_kv_quantize / srft_kv_dequantize (same shapes, alignment and ownership;
+ *                                the *_dev entries are device addresses).  The arrays are read before the call
+ *                                returns and not kept.
+ *   count                        number of entries; 0 is a successful no-op.  Entries with n_vec[i] == 0 are
+ *                                skipped (their pointers are not looked at).
+ * All plans must share d, group_size and device (else SRFT_ERR_MISMATCH); signs and lambda may differ.
+ * Every entry is validated before anything is enqueued.  Up to 64 entries go into one kernel launch; longer
+ * lists take several launches on the same stream.  Results are bit-identical to the per-plan calls.
+ * Buffers of different entries must not overlap.
+ */
+int srft_kv_quantize_batched(const srft_plan_t* const* plans, const void* const* x_f16_dev,
+                             const int64_t* n_vec, uint8_t* const* codes_dev, float* const* scales_dev,
+                             int count, void* hip_stream);
+int srft_kv_dequantize_batched(const srft_plan_t* const* plans, const uint8_t* const* codes_dev,
+                               const float* const* scales_dev, const int64_t* n_vec,
+                               void* const* out_f16_dev, int count, void* hip_stream);
 
 /*
  * The transform alone, quantization disabled: w = lambda * pack(F (s * x)) in fp32.  (Eq. 1-2, Sec. 5.1)

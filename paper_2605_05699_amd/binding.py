@@ -22,6 +22,7 @@ EXPORTS = [
     "srft_kv_forward_f32", "srft_plan_d", "srft_plan_group_size", "srft_plan_groups",
     "srft_plan_code_bytes", "srft_plan_get_signs", "srft_plan_set_max_workgroups",
     "srft_stream_copy", "srft_stream_mix", "srft_status_string", "srft_last_hip_error",
+    "srft_kv_quantize_batched", "srft_kv_dequantize_batched",
 ]
 
 
@@ -50,6 +51,8 @@ def lib() -> C.CDLL:
     L.srft_kv_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
     L.srft_kv_dequantize.argtypes = [vp, vp, vp, i64, vp, vp]
     L.srft_kv_forward_f32.argtypes = [vp, vp, i64, vp, vp]
+    L.srft_kv_quantize_batched.argtypes = [vp, vp, vp, vp, vp, ci, vp]
+    L.srft_kv_dequantize_batched.argtypes = [vp, vp, vp, vp, vp, ci, vp]
     for name in ("srft_plan_d", "srft_plan_group_size", "srft_plan_groups", "srft_plan_code_bytes"):
         getattr(L, name).argtypes = [vp]
     L.srft_plan_get_signs.argtypes = [vp, vp]
@@ -118,6 +121,47 @@ def srft_kv_dequantize(plan: int, codes: torch.Tensor, scales: torch.Tensor, out
                                     _dev_ptr(scales, torch.float32, "scales"), n,
                                     _dev_ptr(out, torch.float16, "out"), _stream_handle(stream)),
            "srft_kv_dequantize")
+
+
+class BatchTable:
+    """Host arrays for one batched call: plan handles, device addresses, vector counts.  Marshalling only.
+
+    Built once and reused by a decode loop whose buffers do not move; ``set_counts`` changes the number of
+    vectors per entry between calls.  The tensors are kept alive by the table.
+    """
+
+    def __init__(self, plans, big, codes, scales, n_vec=None):
+        """big: the fp16 tensors (x on the write path, out on the read path), one per plan."""
+        k = len(plans)
+        if not (len(big) == len(codes) == len(scales) == k):
+            raise ValueError("one tensor of each kind per plan")
+        self.count = k
+        self._keep = (list(big), list(codes), list(scales))
+        self.plans = (C.c_void_p * k)(*[int(h) for h in plans])
+        self.big = (C.c_void_p * k)(*[_dev_ptr(t, torch.float16, "x/out") for t in big])
+        self.codes = (C.c_void_p * k)(*[_dev_ptr(t, torch.uint8, "codes") for t in codes])
+        self.scales = (C.c_void_p * k)(*[_dev_ptr(t, torch.float32, "scales") for t in scales])
+        self.n_vec = (C.c_int64 * k)()
+        self.set_counts([t.shape[0] for t in big] if n_vec is None else n_vec)
+
+    def set_counts(self, n_vec) -> None:
+        if len(n_vec) != self.count:
+            raise ValueError("one count per plan")
+        big, codes, scales = self._keep
+        for i, n in enumerate(n_vec):
+            if n > min(big[i].shape[0], codes[i].shape[0], scales[i].shape[0]):
+                raise ValueError(f"entry {i}: {n} vectors exceed the buffers")
+            self.n_vec[i] = int(n)
+
+
+def srft_kv_quantize_batched(table: BatchTable, stream=None) -> None:
+    _check(lib().srft_kv_quantize_batched(table.plans, table.big, table.n_vec, table.codes, table.scales,
+                                          table.count, _stream_handle(stream)), "srft_kv_quantize_batched")
+
+
+def srft_kv_dequantize_batched(table: BatchTable, stream=None) -> None:
+    _check(lib().srft_kv_dequantize_batched(table.plans, table.codes, table.scales, table.n_vec, table.big,
+                                            table.count, _stream_handle(stream)), "srft_kv_dequantize_batched")
 
 
 def srft_kv_forward_f32(plan: int, x: torch.Tensor, w: torch.Tensor, stream=None) -> None:

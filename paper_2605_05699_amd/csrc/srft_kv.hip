@@ -128,11 +128,12 @@ __device__ __forceinline__ uint32_t pack8(const floatx16& acc, int base, float i
 //         gw >= 2 slabs per group, up to the per-token case g = d; the slab maxima meet in LDS, which costs
 //         two more barriers per tile.
 enum { kGroup16 = 0, kGroup32 = 1, kGroupWide = 2 };
+// The work of one workgroup: tiles t0, t0 + stride, ... of one plan's n_vec vectors (t0 < number of tiles).
 template <int D, int S, bool RAW, int GM>
-__global__ void __launch_bounds__(2 * D / S)
-srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
-                     uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
-                     float unscale, float scale_mul, int gw) {
+__device__ __forceinline__ void
+srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
+                    uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
+                    float unscale, float scale_mul, int gw, const long long t0, const long long stride) {
     constexpr int G = D / 32;            // quantization groups per vector = slabs of the matrix
     constexpr int T = D / 16;            // MFMA k-steps
     constexpr int U = D / 8;             // 16-byte units per input row
@@ -253,8 +254,7 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
         }
     };
 
-    const long long t0 = blockIdx.x, stride = gridDim.x;
-    const long long m = (n_tiles - 1 - t0) / stride + 1;     // tiles of this workgroup (the grid never exceeds n_tiles)
+    const long long m = (n_tiles - 1 - t0) / stride + 1;     // tiles of this workgroup
     uint4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3;
     Acc acc_a, acc_b;
     fetch(pa0, pa1, pa2, pa3, t0);
@@ -290,6 +290,47 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
     } else {
         finish(acc_a, t0 + (k - 1) * stride);
     }
+}
+
+template <int D, int S, bool RAW, int GM>
+__global__ void __launch_bounds__(2 * D / S)
+srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
+                     uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
+                     float unscale, float scale_mul, int gw) {
+    srft_quantize_tiles<D, S, RAW, GM>(wfrag, x, n_vec, codes, scales, wout, unscale, scale_mul, gw, blockIdx.x,
+                                       gridDim.x);       // the grid never exceeds the number of tiles
+}
+
+// Several plans in one launch (a decode step appends a few hundred vectors to each of many (layer, K|V)
+// caches: one launch per plan would be all launch latency).  Segment i = plan i's constants and buffers; it
+// is served by workgroups first_block[i] .. first_block[i+1]-1, each walking that segment's tiles with
+// that many as stride.  The table travels as a kernel argument.
+constexpr int kMaxBatch = 64;       // the table is about 3.5 KiB of the 4 KiB a kernel may take as arguments
+struct srft_batch_args {
+    int count;
+    int first_block[kMaxBatch + 1];
+    const uint4* frag[kMaxBatch];
+    const void* in0[kMaxBatch];      // write path: x      read path: codes
+    const void* in1[kMaxBatch];      //                    read path: scales
+    void* out0[kMaxBatch];           // write path: codes  read path: out
+    void* out1[kMaxBatch];           // write path: scales
+    long long n_vec[kMaxBatch];
+    float unscale[kMaxBatch];
+};
+static_assert(sizeof(srft_batch_args) + sizeof(int) <= 4096, "kernel arguments are limited to 4 KiB");
+__device__ __forceinline__ int srft_segment_of_block(const srft_batch_args& a, int block) {
+    int i = 0;
+    while (i + 1 < a.count && a.first_block[i + 1] <= block) ++i;     // uniform; count is small
+    return i;
+}
+
+template <int D, int S, int GM>
+__global__ void __launch_bounds__(2 * D / S)
+srft_quantize_batched_kernel(const srft_batch_args a, int gw) {
+    const int i = srft_segment_of_block(a, blockIdx.x);
+    srft_quantize_tiles<D, S, false, GM>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
+                                         (float*)a.out1[i], nullptr, a.unscale[i], a.unscale[i] / 7.0f, gw,
+                                         blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -335,10 +376,10 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
 // KS: MFMA k-steps (of 16 codes) contracted under one scale: 2 for g >= 32 (g = 32 * gw, gw slabs of codes
 //     share a scale), 1 for g = 16.  "Group" below means one such run of 16 * KS codes.
 template <int D, int S, int KS>
-__global__ void __launch_bounds__(2 * D / S)
-srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
-                       const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
-                       float unscale, int gw) {
+__device__ __forceinline__ void
+srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
+                      const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
+                      float unscale, int gw, const long long t0, const long long stride) {
     constexpr int G = D / 32 * (2 / KS);  // groups per vector as contracted
     constexpr int NSMAX = D / 16;         // most scales a vector can have (g = 16)
     const int ns = (KS == 1) ? D / 16 : D / 32 / gw;      // scales per vector
@@ -495,7 +536,6 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
         stage_out(b);
     };
 
-    const long long t0 = blockIdx.x, stride = gridDim.x;
     const long long m = (n_tiles - 1 - t0) / stride + 1;
     uint2 pa0, pa1, pb0, pb1;                    // prefetched code units of the next two tiles
     float pas, pat, pbs, pbt;                    // and up to two floats each of their scale tiles
@@ -581,6 +621,23 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
         __syncthreads();
         flush(0, tl);
     }
+}
+
+template <int D, int S, int KS>
+__global__ void __launch_bounds__(2 * D / S)
+srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
+                       const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
+                       float unscale, int gw) {
+    srft_dequantize_tiles<D, S, KS>(rfrag, codes, scales, n_vec, out, unscale, gw, blockIdx.x, gridDim.x);
+}
+
+template <int D, int S, int KS>
+__global__ void __launch_bounds__(2 * D / S)
+srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
+    const int i = srft_segment_of_block(a, blockIdx.x);
+    srft_dequantize_tiles<D, S, KS>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
+                                    (uint4*)a.out0[i], a.unscale[i], gw, blockIdx.x - a.first_block[i],
+                                    a.first_block[i + 1] - a.first_block[i]);
 }
 
 __global__ void __launch_bounds__(256)
@@ -761,6 +818,59 @@ int launch_dequantize(const srft_plan* p, const uint8_t* codes, const float* sca
     return SRFT_OK;
 }
 
+typedef void (*quantize_batched_kernel_t)(const srft_batch_args, int);
+typedef void (*dequantize_batched_kernel_t)(const srft_batch_args, int);
+
+template <int D>
+quantize_batched_kernel_t quantize_batched_instance(int slabs, int gm) {
+    if constexpr ((D / 32) % 2 == 0) {
+        if (slabs == 2)
+            return gm == kGroup16 ? srft_quantize_batched_kernel<D, 2, kGroup16>
+                 : gm == kGroupWide ? srft_quantize_batched_kernel<D, 2, kGroupWide>
+                                    : srft_quantize_batched_kernel<D, 2, kGroup32>;
+    }
+    return gm == kGroup16 ? srft_quantize_batched_kernel<D, 1, kGroup16>
+         : gm == kGroupWide ? srft_quantize_batched_kernel<D, 1, kGroupWide>
+                            : srft_quantize_batched_kernel<D, 1, kGroup32>;
+}
+template <int D>
+dequantize_batched_kernel_t dequantize_batched_instance(int slabs, int gm) {
+    if constexpr ((D / 32) % 2 == 0) {
+        if (slabs == 2)
+            return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 2, 1> : srft_dequantize_batched_kernel<D, 2, 2>;
+    }
+    return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 1, 1> : srft_dequantize_batched_kernel<D, 1, 2>;
+}
+
+// One batched launch: the segment table is complete except for first_block, which is laid out here.
+// Every segment gets at least one workgroup and at most one per tile; when the tiles of all segments
+// exceed the persistent grid, workgroups are shared out in proportion to the tiles.
+template <int D>
+int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipStream_t st) {
+    long long budget = p->max_wgs > 0 ? p->max_wgs : (write_path ? p->grid_q : p->grid_dq);
+    long long total_tiles = 0;
+    for (int i = 0; i < a.count; ++i) total_tiles += (a.n_vec[i] + kTileVecs - 1) / kTileVecs;
+    int next = 0;
+    for (int i = 0; i < a.count; ++i) {
+        const long long tiles = (a.n_vec[i] + kTileVecs - 1) / kTileVecs;
+        long long blocks = total_tiles <= budget ? tiles : tiles * budget / total_tiles;
+        if (blocks < 1) blocks = 1;
+        if (blocks > tiles) blocks = tiles;
+        a.first_block[i] = next;
+        next += (int)blocks;
+    }
+    a.first_block[a.count] = next;
+    const int slabs = write_path ? p->slabs_q : p->slabs_dq;
+    if (write_path)
+        hipLaunchKernelGGL(quantize_batched_instance<D>(slabs, p->gm), dim3((unsigned)next), dim3(2 * D / slabs), 0, st,
+                           a, p->gw);
+    else
+        hipLaunchKernelGGL(dequantize_batched_instance<D>(slabs, p->gm), dim3((unsigned)next), dim3(2 * D / slabs), 0,
+                           st, a, p->gw);
+    SRFT_HIP(hipGetLastError());
+    return SRFT_OK;
+}
+
 #define SRFT_DISPATCH_D(d, fn, ...)                       \
     switch (d) {                                          \
         case 32:  return fn<32>(__VA_ARGS__);             \
@@ -779,6 +889,10 @@ int dispatch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* c
                       hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_quantize, p, x, n, c, s, w, st) }
 int dispatch_dequantize(const srft_plan* p, const uint8_t* c, const float* s, long long n, void* o,
                         hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_dequantize, p, c, s, n, o, st) }
+
+int dispatch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipStream_t st) {
+    SRFT_DISPATCH_D(p->d, launch_batched, p, a, write_path, st)
+}
 
 // Slabs per wavefront: 1, or 2 where the number of groups is even and the table (or the tuning override in
 // the environment) says so.
@@ -934,6 +1048,59 @@ int srft_kv_dequantize(const srft_plan_t* plan, const uint8_t* codes_dev, const 
     return dispatch_dequantize(plan, codes_dev, scales_dev, n_vec, out_f16_dev, (hipStream_t)hip_stream);
 }
 
+// Shared body of the two batched entry points.  in1 / out1 are NULL arrays where the path has no such buffer.
+static int run_batched(const srft_plan_t* const* plans, const void* const* in0, const void* const* in1,
+                       void* const* out0, void* const* out1, const int64_t* n_vec, int count, bool write_path,
+                       hipStream_t st) {
+    if (count < 0) return SRFT_ERR_BAD_N;
+    if (count == 0) return SRFT_OK;
+    if (!plans || !in0 || !out0 || !n_vec || (write_path ? !out1 : !in1)) return SRFT_ERR_NULL;
+    // validate everything before the first launch: a bad segment must not leave half a batch enqueued
+    for (int i = 0; i < count; ++i) {
+        if (!plans[i]) return SRFT_ERR_NULL;
+        if (plans[i]->d != plans[0]->d || plans[i]->g != plans[0]->g || plans[i]->device != plans[0]->device)
+            return SRFT_ERR_MISMATCH;
+        if (n_vec[i] < 0) return SRFT_ERR_BAD_N;
+        if (n_vec[i] == 0) continue;
+        const void* small = write_path ? (const void*)out1[i] : in1[i];       // the scales
+        if (!in0[i] || !out0[i] || !small) return SRFT_ERR_NULL;
+        if (!aligned(in0[i], 16) || !aligned(out0[i], 16) || !aligned(small, 4)) return SRFT_ERR_ALIGN;
+    }
+    srft_batch_args a;
+    a.count = 0;
+    for (int i = 0; i <= count; ++i) {
+        if (i < count && n_vec[i] > 0) {
+            const int k = a.count++;
+            a.frag[k] = write_path ? plans[i]->wfrag : plans[i]->rfrag;
+            a.in0[k] = in0[i];
+            a.in1[k] = write_path ? nullptr : in1[i];
+            a.out0[k] = out0[i];
+            a.out1[k] = write_path ? out1[i] : nullptr;
+            a.n_vec[k] = n_vec[i];
+            a.unscale[k] = write_path ? plans[i]->unscale_w : plans[i]->unscale_r;
+        }
+        if (a.count == kMaxBatch || (i == count && a.count > 0)) {
+            const int rc = dispatch_batched(plans[0], a, write_path, st);
+            if (rc != SRFT_OK) return rc;
+            a.count = 0;
+        }
+    }
+    return SRFT_OK;
+}
+
+int srft_kv_quantize_batched(const srft_plan_t* const* plans, const void* const* x_f16_dev, const int64_t* n_vec,
+                             uint8_t* const* codes_dev, float* const* scales_dev, int count, void* hip_stream) {
+    return run_batched(plans, x_f16_dev, nullptr, (void* const*)codes_dev, (void* const*)scales_dev, n_vec, count,
+                       true, (hipStream_t)hip_stream);
+}
+
+int srft_kv_dequantize_batched(const srft_plan_t* const* plans, const uint8_t* const* codes_dev,
+                               const float* const* scales_dev, const int64_t* n_vec, void* const* out_f16_dev,
+                               int count, void* hip_stream) {
+    return run_batched(plans, (const void* const*)codes_dev, (const void* const*)scales_dev, out_f16_dev, nullptr,
+                       n_vec, count, false, (hipStream_t)hip_stream);
+}
+
 int srft_plan_d(const srft_plan_t* plan) { return plan ? plan->d : SRFT_ERR_NULL; }
 int srft_plan_group_size(const srft_plan_t* plan) { return plan ? plan->g : SRFT_ERR_NULL; }
 int srft_plan_groups(const srft_plan_t* plan) { return plan ? plan->d / plan->g : SRFT_ERR_NULL; }
@@ -1009,6 +1176,7 @@ const char* srft_status_string(int status) {
         case SRFT_ERR_ALIGN: return "device pointer is misaligned";
         case SRFT_ERR_HIP: return "HIP call failed (see srft_last_hip_error)";
         case SRFT_ERR_BAD_N: return "negative or malformed size";
+        case SRFT_ERR_MISMATCH: return "plans of one batched call must share d, group size and device";
         default: return "unknown status";
     }
 }

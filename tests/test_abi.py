@@ -35,8 +35,10 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_status_strings(L):
-    for code in range(0, -9, -1):
+    for code in range(0, -10, -1):
         assert L.srft_status_string(code)
+    known = {L.srft_status_string(code) for code in range(0, -9, -1)}
+    assert len(known) == 9 and L.srft_status_string(-9) not in known      # -8 is the last defined status
     assert L.srft_status_string(0) == b"ok"
 
 
@@ -67,6 +69,14 @@ def test_null_plan_and_size_errors(L):
     assert L.srft_stream_copy(None, None, 24, None) == -7
     assert L.srft_stream_copy(None, None, 32, None) == -1
     assert L.srft_stream_copy(None, None, 0, None) == 0
+    # batched calls: an empty list is a no-op, a negative count or a missing array is an error
+    one = (C.c_void_p * 1)(None)
+    n1 = (C.c_int64 * 1)(5)
+    for fn in (L.srft_kv_quantize_batched, L.srft_kv_dequantize_batched):
+        assert fn(None, None, None, None, None, 0, None) == 0
+        assert fn(None, None, None, None, None, -3, None) == -7
+        assert fn(None, None, None, None, None, 1, None) == -1
+        assert fn(one, one, n1, one, one, 1, None) == -1          # entry 0 has no plan
 
 
 def test_workload_table_matches_the_stated_shapes():
