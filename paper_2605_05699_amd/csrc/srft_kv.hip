@@ -133,7 +133,7 @@ template <int D, int S, bool RAW, int GM>
 __device__ __forceinline__ void
 srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
                     uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
-                    float unscale, float scale_mul, int gw, const long long t0, const long long stride) {
+                    float unscale, float scale_mul, int gw, const int t0, const int stride) {
     constexpr int G = D / 32;            // quantization groups per vector = slabs of the matrix
     constexpr int T = D / 16;            // MFMA k-steps
     constexpr int U = D / 8;             // 16-byte units per input row
@@ -147,8 +147,9 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
-    const long long last = n_vec - 1;
+    // tile indices are 32-bit (the host bounds n_vec), so that the uniform index arithmetic stays scalar
+    const int n_tiles = (int)((n_vec + kTileVecs - 1) / kTileVecs);
+    const int last_lim = (int)(n_vec - 1 - (long long)(n_tiles - 1) * kTileVecs);   // last valid row of the last tile
 
     half8 ahi[S][T], alo[S][T];
 #pragma unroll
@@ -160,17 +161,20 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
         }
 
     // The PER prefetched units of one tile live in separately named registers (PER = 2 uses a and b only).
-    auto fetch1 = [&](uint4& v, int i, long long row0) __attribute__((always_inline)) {
+    // Addresses are a uniform tile base (scalar registers) plus a 32-bit per-lane offset; rows past the end
+    // alias to the last row through `lim`, the index of the last valid row of the tile (uniform).
+    auto fetch1 = [&](uint4& v, int i, const uint4* tile_base, int lim) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / U, c = u % U;
-        const long long rr = (row0 + r < last) ? row0 + r : last;
-        v = x[rr * U + c];
+        v = tile_base[(unsigned)(min(r, lim) * U + c)];
     };
-    auto fetch = [&](uint4& a, uint4& b, uint4& c, uint4& d, long long tile) __attribute__((always_inline)) {
+    auto fetch = [&](uint4& a, uint4& b, uint4& c, uint4& d, int tile) __attribute__((always_inline)) {
         if (tile > n_tiles - 1) tile = n_tiles - 1;          // prefetch past the end re-reads the last tile
-        const long long row0 = tile * kTileVecs;
-        fetch1(a, 0, row0);
-        fetch1(b, 1, row0);
-        if constexpr (PER > 2) { fetch1(c, 2, row0); fetch1(d, 3, row0); }
+        const long long row0 = (long long)tile * kTileVecs;
+        const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
+        const uint4* tile_base = x + row0 * U;
+        fetch1(a, 0, tile_base, lim);
+        fetch1(b, 1, tile_base, lim);
+        if constexpr (PER > 2) { fetch1(c, 2, tile_base, lim); fetch1(d, 3, tile_base, lim); }
     };
     auto put1 = [&](int buf, const uint4& v, int i) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / U, c = u % U;
@@ -202,14 +206,14 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
         }
     };
     // vector-ALU tail of one tile: per-group abs-max, scale, int4 codes, stores
-    auto finish = [&](Acc& accs, long long tile) __attribute__((always_inline)) {
-        const long long row0 = tile * kTileVecs;
-        const long long left = last - row0;                               // uniform
-        const int c = (left < col) ? (int)left : col;                     // alias rows past the end
+    auto finish = [&](Acc& accs, int tile) __attribute__((always_inline)) {
+        const long long row0 = (long long)tile * kTileVecs;
+        const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;     // uniform
+        const int c = min(col, lim);                                      // alias rows past the end
         if constexpr (RAW) {
             each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
                 const int slab = wave * S + s;
-                float4* o = wout + (row0 * D) / 4 + (c * D + 32 * slab + 16 * half) / 4;
+                float4* o = wout + (row0 * D) / 4 + (unsigned)((c * D + 32 * slab + 16 * half) / 4);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     o[i] = make_float4(acc[4 * i] * unscale, acc[4 * i + 1] * unscale,
@@ -245,16 +249,16 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
                 uint2 packed;
                 packed.x = pack8(acc, 0, inv);
                 packed.y = pack8(acc, 8, inv);
-                codes[row0 * (D / 16) + (c * (D / 16) + 2 * slab + half)] = packed;
+                (codes + row0 * (D / 16))[(unsigned)(c * (D / 16) + 2 * slab + half)] = packed;
                 // lanes that hold the same group store the same value to the same place
-                if constexpr (GM == kGroup16) scales[row0 * (2 * G) + (c * (2 * G) + 2 * slab + half)] = scale;
-                else if constexpr (GM == kGroup32) scales[row0 * G + (c * G + slab)] = scale;
-                else scales[row0 * (G / gw) + (c * (G / gw) + slab / gw)] = scale;
+                if constexpr (GM == kGroup16) (scales + row0 * (2 * G))[(unsigned)(c * (2 * G) + 2 * slab + half)] = scale;
+                else if constexpr (GM == kGroup32) (scales + row0 * G)[(unsigned)(c * G + slab)] = scale;
+                else (scales + row0 * (G / gw))[(unsigned)(c * (G / gw) + slab / gw)] = scale;
             });
         }
     };
 
-    const long long m = (n_tiles - 1 - t0) / stride + 1;     // tiles of this workgroup
+    const int m = (n_tiles - 1 - t0) / stride + 1;           // tiles of this workgroup
     uint4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3;
     Acc acc_a, acc_b;
     fetch(pa0, pa1, pa2, pa3, t0);
@@ -267,9 +271,9 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
     contract(0, acc_a);
     to_lds(1, pb0, pb1, pb2, pb3);
     fetch(pb0, pb1, pb2, pb3, t0 + 3 * stride);
-    long long k = 1;
+    int k = 1;
     for (; k + 1 < m; k += 2) {
-        const long long tk = t0 + k * stride;
+        const int tk = t0 + k * stride;
         __syncthreads();                         // stage k (odd)
         contract(1, acc_b);
         finish(acc_a, tk - stride);
@@ -282,7 +286,7 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
         fetch(pb0, pb1, pb2, pb3, tk + 4 * stride);
     }
     if (k < m) {                                 // one more odd stage
-        const long long tk = t0 + k * stride;
+        const int tk = t0 + k * stride;
         __syncthreads();
         contract(1, acc_b);
         finish(acc_a, tk - stride);
@@ -375,14 +379,25 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
 // S : output slabs per wavefront (the workgroup has D / (32 S) wavefronts), as on the write path.
 // KS: MFMA k-steps (of 16 codes) contracted under one scale: 2 for g >= 32 (g = 32 * gw, gw slabs of codes
 //     share a scale), 1 for g = 16.  "Group" below means one such run of 16 * KS codes.
-template <int D, int S, int KS>
+// FOLD: half the matrix work, for d a multiple of 64 and g >= 32.  Every row of Q satisfies
+//     Q[p][n + d/2] = (-1)^p Q[p][n]   (DC and Nyquist rows: +1; cos and sin rows of bin k: (-1)^k, and the
+//     packed index p has the parity of k), so with  A_n = sum over even p,  B_n = sum over odd p  of
+//     Q[p][n] z_p  the outputs are  x_n = s_n (A_n + B_n)  and  x_{n+d/2} = s_{n+d/2} (A_n - B_n),  n < d/2.
+//     A byte holds an even p in its low and an odd p in its high nibble, so the two operands are the low and
+//     the high nibbles.  Wavefront w owns n = 32w .. 32w+31: slab 0 is A, slab 1 is B (S = 2, KS = 1: per
+//     group of 32 codes one k-step of 16 even and one of 16 odd codes), rows scaled by s_n on the host;
+//     the relative sign s_n s_{n+d/2} is applied to the packed fp16 bits.  rfrag is then
+//     [D/64 waves][A, B][D/32 groups][hi, lo][64 lanes], followed by [D/64 waves][64 lanes][2] sign masks.
+template <int D, int S, int KS, bool FOLD>
 __device__ __forceinline__ void
 srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
                       const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
-                      float unscale, int gw, const long long t0, const long long stride) {
-    constexpr int G = D / 32 * (2 / KS);  // groups per vector as contracted
+                      float unscale, int gw, const int t0, const int stride) {
+    constexpr int G = FOLD ? D / 32 : D / 32 * (2 / KS);  // groups per vector as contracted
     constexpr int NSMAX = D / 16;         // most scales a vector can have (g = 16)
-    const int ns = (KS == 1) ? D / 16 : D / 32 / gw;      // scales per vector
+    constexpr bool kPerStep = (KS == 1 && !FOLD);         // g = 16: a scale per k-step of the full matrix
+    const int ns = kPerStep ? D / 16 : D / 32 / gw;       // scales per vector
+    static_assert(!FOLD || (S == 2 && KS == 1 && D % 64 == 0), "the folded form pairs an A and a B slab");
     constexpr int U = D / 8;             // 16-byte units per decoded row (D fp16)
     constexpr int ROW = U + 1;
     constexpr int C = D / 16;            // 8-byte code units per row
@@ -392,15 +407,16 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     static_assert((D / 32) % S == 0 && (S == 1 || S == 2), "one or two slabs per wavefront");
     // Two slabs of a large matrix leave no room for alternating accumulators: one accumulator set, each group
     // folded in as soon as it is done, the tile staged in the stage that computes it.
-    constexpr bool LEAN = (S == 2 && D / 32 > 4);
+    constexpr bool LEAN = (S == 2 && (D / 32 > 4 || FOLD));
     __shared__ uint4 dec[2][kTileVecs * ROW];    // decoded codes of T_k in dec[k % 2]
     __shared__ uint4 stg[2][kTileVecs * ROW];    // finished fp16 rows of T_k in stg[k % 2]
     __shared__ float scl[2][kTileVecs * SROW];   // scales (times 2^-e) of T_k in scl[k % 2]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const long long n_tiles = (n_vec + kTileVecs - 1) / kTileVecs;
-    const long long last = n_vec - 1;
+    // tile indices are 32-bit (the host bounds n_vec), so that the uniform index arithmetic stays scalar
+    const int n_tiles = (int)((n_vec + kTileVecs - 1) / kTileVecs);
+    const int last_lim = (int)(n_vec - 1 - (long long)(n_tiles - 1) * kTileVecs);   // last valid row of the last tile
 
     half8 rhi[S * G][KS], rlo[S * G][KS];        // [s * G + group][k-step within the group]
 #pragma unroll
@@ -410,36 +426,54 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
 #pragma unroll
             for (int t = 0; t < KS; ++t) {
                 const int slab = wave * S + s, kstep = j * KS + t;
-                rhi[s * G + j][t] = __builtin_bit_cast(half8, rfrag[((slab * (D / 16) + kstep) * 2 + 0) * 64 + lane]);
-                rlo[s * G + j][t] = __builtin_bit_cast(half8, rfrag[((slab * (D / 16) + kstep) * 2 + 1) * 64 + lane]);
+                const int f = FOLD ? slab * G + j : slab * (D / 16) + kstep;
+                rhi[s * G + j][t] = __builtin_bit_cast(half8, rfrag[(f * 2 + 0) * 64 + lane]);
+                rlo[s * G + j][t] = __builtin_bit_cast(half8, rfrag[(f * 2 + 1) * 64 + lane]);
             }
+    uint4 flip0 = {}, flip1 = {};                // sign-bit masks of this lane's 16 outputs n + d/2 (FOLD)
+    if constexpr (FOLD) {
+        const uint4* masks = rfrag + (D / 32) * G * 2 * 64;
+        flip0 = masks[(wave * 64 + lane) * 2];
+        flip1 = masks[(wave * 64 + lane) * 2 + 1];
+        asm volatile("" : "+v"(flip0.x), "+v"(flip0.y), "+v"(flip0.z), "+v"(flip0.w));
+        asm volatile("" : "+v"(flip1.x), "+v"(flip1.y), "+v"(flip1.z), "+v"(flip1.w));
+    }
 
     // each thread decodes S 8-byte units of the 32 x D/2 code tile (32 * C = S * NT units) and carries up to
     // PS floats of the 32 x ns scale tile (float e = tid + i * NT; past the end it re-reads the last one)
-    auto fetch1 = [&](uint2& v, int i, long long row0) __attribute__((always_inline)) {
+    // Addresses are a uniform tile base (scalar registers) plus a 32-bit per-lane offset; rows past the end
+    // alias to the last row through `lim`, the index of the last valid row of the tile (uniform).
+    auto fetch1 = [&](uint2& v, int i, const uint2* tile_base, int lim) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / C, c = u % C;
-        const long long rr = (row0 + r < last) ? row0 + r : last;
-        v = codes[rr * C + c];
+        v = tile_base[(unsigned)(min(r, lim) * C + c)];
     };
-    auto fetch_scale = [&](float& sc, int i, long long row0) __attribute__((always_inline)) {
+    auto fetch_scale = [&](float& sc, int i, const float* tile_base, int lim) __attribute__((always_inline)) {
         int e = tid + i * NT;
         if (e > 32 * ns - 1) e = 32 * ns - 1;
         const int r = e / ns, j = e % ns;
-        const long long rs = (row0 + r < last) ? row0 + r : last;
-        sc = scales[rs * ns + j];
+        sc = tile_base[(unsigned)(min(r, lim) * ns + j)];
     };
-    auto fetch = [&](uint2& c0, uint2& c1, float& s0, float& s1, long long tile) __attribute__((always_inline)) {
+    auto fetch = [&](uint2& c0, uint2& c1, float& s0, float& s1, int tile) __attribute__((always_inline)) {
         if (tile > n_tiles - 1) tile = n_tiles - 1;
-        const long long row0 = tile * kTileVecs;
-        fetch1(c0, 0, row0);
-        if constexpr (S > 1) fetch1(c1, 1, row0);
-        fetch_scale(s0, 0, row0);
-        if constexpr (PS > 1) fetch_scale(s1, 1, row0);
+        const long long row0 = (long long)tile * kTileVecs;
+        const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
+        const uint2* code_base = codes + row0 * C;
+        const float* scale_base = scales + row0 * ns;
+        fetch1(c0, 0, code_base, lim);
+        if constexpr (S > 1) fetch1(c1, 1, code_base, lim);
+        fetch_scale(s0, 0, scale_base, lim);
+        if constexpr (PS > 1) fetch_scale(s1, 1, scale_base, lim);
     };
     auto put1 = [&](int b, const uint2& v, int i) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / C, c = u % C;
-        dec[b][r * ROW + 2 * c] = decode8(v.x);
-        dec[b][r * ROW + 2 * c + 1] = decode8(v.y);
+        const uint4 lo = decode8(v.x), hi = decode8(v.y);
+        if constexpr (FOLD) {                    // .x .z hold the even, .y .w the odd nibbles of a dword
+            dec[b][r * ROW + 2 * c] = make_uint4(lo.x, lo.z, hi.x, hi.z);
+            dec[b][r * ROW + 2 * c + 1] = make_uint4(lo.y, lo.w, hi.y, hi.w);
+        } else {
+            dec[b][r * ROW + 2 * c] = lo;
+            dec[b][r * ROW + 2 * c + 1] = hi;
+        }
     };
     auto put_scale = [&](int b, float sc, int i) __attribute__((always_inline)) {
         const int e = tid + i * NT;
@@ -452,7 +486,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         if constexpr (PS > 1) put_scale(b, s1, 1);
     };
     // scale of contracted group j: its own at g = 16 and g = 32, shared by gw groups at g = 32 * gw
-    auto scale_of = [&](int b, int j) __attribute__((always_inline)) { return scl[b][col * SROW + (KS == 1 ? j : j / gw)]; };
+    auto scale_of = [&](int b, int j) __attribute__((always_inline)) { return scl[b][col * SROW + (kPerStep ? j : j / gw)]; };
     // The last group of a tile is folded in one stage later, under group 0 of the next tile (which uses
     // acc0); with an even number of groups it can live in acc1, otherwise it needs a register set of its own.
     floatx16 o[S], acc0[S], acc1[S], acc_odd[S];
@@ -461,6 +495,15 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         const uint4* rowp = &dec[b][col * ROW + half];
 #pragma unroll
         for (int s = 0; s < S; ++s) acc[s] = floatx16{0};
+        if constexpr (FOLD) {                    // unit 2j + half of the row: [even codes][odd codes]
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const half8 bf = __builtin_bit_cast(half8, rowp[4 * j + half + s]);
+                acc[s] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[s * G + j][0], bf, acc[s], 0, 0, 0);
+                acc[s] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[s * G + j][0], bf, acc[s], 0, 0, 0);
+            }
+            return;
+        }
 #pragma unroll
         for (int t = 0; t < KS; ++t) {
             const half8 bf = __builtin_bit_cast(half8, rowp[2 * (j * KS + t)]);
@@ -480,6 +523,20 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     };
     // the finished outputs of this lane, rounded to fp16, into the staging tile b
     auto stage_out = [&](int b) __attribute__((always_inline)) {
+        if constexpr (FOLD) {
+            uint4* dst = &stg[b][col * ROW + 4 * wave + 2 * half];
+            uint32_t lo[8], hi[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                lo[i] = pack_half2(o[0][2 * i] + o[1][2 * i], o[0][2 * i + 1] + o[1][2 * i + 1]);
+                hi[i] = pack_half2(o[0][2 * i] - o[1][2 * i], o[0][2 * i + 1] - o[1][2 * i + 1]);
+            }
+            dst[0] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+            dst[1] = make_uint4(lo[4], lo[5], lo[6], lo[7]);
+            dst[U / 2] = make_uint4(hi[0] ^ flip0.x, hi[1] ^ flip0.y, hi[2] ^ flip0.z, hi[3] ^ flip0.w);
+            dst[U / 2 + 1] = make_uint4(hi[4] ^ flip1.x, hi[5] ^ flip1.y, hi[6] ^ flip1.z, hi[7] ^ flip1.w);
+            return;
+        }
 #pragma unroll
         for (int s = 0; s < S; ++s) {
             uint4* dst = &stg[b][col * ROW + 4 * (wave * S + s) + 2 * half];
@@ -490,14 +547,14 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         }
     };
     // staging tile b -> global rows of `tile`: fully coalesced 16-byte stores, 2 S per thread
-    auto flush = [&](int b, long long tile) __attribute__((always_inline)) {
-        const long long row0 = tile * kTileVecs;
-        const long long left = last - row0;
+    auto flush = [&](int b, int tile) __attribute__((always_inline)) {
+        const long long row0 = (long long)tile * kTileVecs;
+        const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
+        uint4* tile_base = out + row0 * U;
 #pragma unroll
         for (int i = 0; i < 2 * S; ++i) {
             const int u = tid + i * NT, r = u / U, c = u % U;
-            const long long rr = (left < r) ? left : r;                 // rows past the end alias to the last row
-            out[(row0 + rr) * U + c] = stg[b][r * ROW + c];
+            tile_base[(unsigned)(min(r, lim) * U + c)] = stg[b][r * ROW + c];    // rows past the end alias to the last row
         }
     };
     // all groups of the tile in dec[b] (scales in scl[b]); `prev`: first fold in the last group of the
@@ -536,7 +593,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         stage_out(b);
     };
 
-    const long long m = (n_tiles - 1 - t0) / stride + 1;
+    const int m = (n_tiles - 1 - t0) / stride + 1;
     uint2 pa0, pa1, pb0, pb1;                    // prefetched code units of the next two tiles
     float pas, pat, pbs, pbt;                    // and up to two floats each of their scale tiles
     float s_last;                                // scale of the last group of the tile contracted last
@@ -547,8 +604,8 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     fetch(pa0, pa1, pas, pat, t0 + 2 * stride);
     if constexpr (LEAN) {
         // stage k: barrier; flush T_{k-1}; contract, fold and stage T_k; decode T_{k+1}
-        for (long long k = 0; k < m; ++k) {
-            const long long tk = t0 + k * stride;
+        for (int k = 0; k < m; ++k) {
+            const int tk = t0 + k * stride;
             __syncthreads();
             if (k & 1) {
                 flush(0, tk - stride);
@@ -573,7 +630,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     to_lds(1, pb0, pb1, pbs, pbt);
     fetch(pb0, pb1, pbs, pbt, t0 + 3 * stride);
     // stage k: barrier; flush T_{k-2}; contract T_k (staging T_{k-1} under its first group); decode T_{k+1}
-    auto odd_stage = [&](long long tk, auto flush_first) __attribute__((always_inline)) {      // T_k in dec[1]
+    auto odd_stage = [&](int tk, auto flush_first) __attribute__((always_inline)) {      // T_k in dec[1]
         __syncthreads();
         if constexpr (decltype(flush_first)::value) flush(1, tk - 2 * stride);
         tile_body(1, true, s_last, 0);
@@ -581,7 +638,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         to_lds(0, pa0, pa1, pas, pat);
         fetch(pa0, pa1, pas, pat, tk + 3 * stride);
     };
-    auto even_stage = [&](long long tk) __attribute__((always_inline)) {                       // T_k in dec[0]
+    auto even_stage = [&](int tk) __attribute__((always_inline)) {                       // T_k in dec[0]
         __syncthreads();
         flush(0, tk - 2 * stride);
         tile_body(0, true, s_last, 1);
@@ -589,7 +646,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         to_lds(1, pb0, pb1, pbs, pbt);
         fetch(pb0, pb1, pbs, pbt, tk + 3 * stride);
     };
-    long long k = 1;
+    int k = 1;
     if (k + 1 < m) {                             // stages 1 and 2: nothing to flush in stage 1 yet
         odd_stage(t0 + stride, std::false_type{});
         even_stage(t0 + 2 * stride);
@@ -601,7 +658,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     }
     // the last group of the last tile is still in acc_last; up to two staged tiles are unflushed
     if (k < m) {                                 // one more odd stage: T_k in dec[1]
-        const long long tk = t0 + k * stride;
+        const int tk = t0 + k * stride;
         __syncthreads();
         if (k >= 2) flush(1, tk - 2 * stride);
         tile_body(1, true, s_last, 0);
@@ -613,7 +670,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         __syncthreads();
         flush(1, tk);
     } else {                                     // the last stage was even (or stage 0): T_{k-1} in dec[0]
-        const long long tl = t0 + (k - 1) * stride;
+        const int tl = t0 + (k - 1) * stride;
         __syncthreads();                         // every thread is done reading stg[0]
         fold(acc_last, s_last, G == 1);
         stage_out(0);
@@ -623,19 +680,19 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     }
 }
 
-template <int D, int S, int KS>
+template <int D, int S, int KS, bool FOLD>
 __global__ void __launch_bounds__(2 * D / S)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
                        const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                        float unscale, int gw) {
-    srft_dequantize_tiles<D, S, KS>(rfrag, codes, scales, n_vec, out, unscale, gw, blockIdx.x, gridDim.x);
+    srft_dequantize_tiles<D, S, KS, FOLD>(rfrag, codes, scales, n_vec, out, unscale, gw, blockIdx.x, gridDim.x);
 }
 
-template <int D, int S, int KS>
+template <int D, int S, int KS, bool FOLD>
 __global__ void __launch_bounds__(2 * D / S)
 srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
-    srft_dequantize_tiles<D, S, KS>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
+    srft_dequantize_tiles<D, S, KS, FOLD>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
                                     (uint4*)a.out0[i], a.unscale[i], gw, blockIdx.x - a.first_block[i],
                                     a.first_block[i + 1] - a.first_block[i]);
 }
@@ -742,6 +799,8 @@ struct srft_plan {
     std::vector<int8_t> signs;
     uint4* wfrag = nullptr;     // write-path matrix fragments (device)
     uint4* rfrag = nullptr;     // read-path matrix fragments (device)
+    uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
+    bool fold_dq = false;       // read path contracts even and odd codes separately (half the matrix work)
     float unscale_w = 1.0f;     // 2^-e of the write matrix
     float unscale_r = 1.0f;
     int grid_q = 0, grid_dq = 0;    // default persistent grid sizes
@@ -773,11 +832,13 @@ quantize_kernel_t quantize_instance(int slabs, bool raw, int gm) {
     return quantize_instance<D, 1>(raw, gm);
 }
 template <int D>
-dequantize_kernel_t dequantize_instance(int slabs, int gm) {
+dequantize_kernel_t dequantize_instance(int slabs, int gm, bool fold) {
     if constexpr ((D / 32) % 2 == 0) {
-        if (slabs == 2) return gm == kGroup16 ? srft_dequantize_kernel<D, 2, 1> : srft_dequantize_kernel<D, 2, 2>;
+        if (fold && gm != kGroup16) return srft_dequantize_kernel<D, 2, 1, true>;
+        if (slabs == 2)
+            return gm == kGroup16 ? srft_dequantize_kernel<D, 2, 1, false> : srft_dequantize_kernel<D, 2, 2, false>;
     }
-    return gm == kGroup16 ? srft_dequantize_kernel<D, 1, 1> : srft_dequantize_kernel<D, 1, 2>;
+    return gm == kGroup16 ? srft_dequantize_kernel<D, 1, 1, false> : srft_dequantize_kernel<D, 1, 2, false>;
 }
 
 template <int D>
@@ -785,7 +846,7 @@ int occupancy_grids(srft_plan* p, int cus) {
     int bq = 0, bd = 0;
     SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, quantize_instance<D>(p->slabs_q, false, p->gm),
                                                           2 * D / p->slabs_q, 0));
-    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, dequantize_instance<D>(p->slabs_dq, p->gm),
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, dequantize_instance<D>(p->slabs_dq, p->gm, p->fold_dq),
                                                           2 * D / p->slabs_dq, 0));
     p->grid_q = cus * (bq > 0 ? bq : 1);
     p->grid_dq = cus * (bd > 0 ? bd : 1);
@@ -811,8 +872,9 @@ int launch_dequantize(const srft_plan* p, const uint8_t* codes, const float* sca
     const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_dq;
     if (grid > n_tiles) grid = n_tiles;
-    const dequantize_kernel_t kernel = dequantize_instance<D>(p->slabs_dq, p->gm);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(2 * D / p->slabs_dq), 0, st, p->rfrag, (const uint2*)codes,
+    const dequantize_kernel_t kernel = dequantize_instance<D>(p->slabs_dq, p->gm, p->fold_dq);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(2 * D / p->slabs_dq), 0, st,
+                       p->fold_dq ? p->rfold : p->rfrag, (const uint2*)codes,
                        scales, n, (uint4*)out, p->unscale_r, p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
@@ -834,12 +896,14 @@ quantize_batched_kernel_t quantize_batched_instance(int slabs, int gm) {
                             : srft_quantize_batched_kernel<D, 1, kGroup32>;
 }
 template <int D>
-dequantize_batched_kernel_t dequantize_batched_instance(int slabs, int gm) {
+dequantize_batched_kernel_t dequantize_batched_instance(int slabs, int gm, bool fold) {
     if constexpr ((D / 32) % 2 == 0) {
+        if (fold && gm != kGroup16) return srft_dequantize_batched_kernel<D, 2, 1, true>;
         if (slabs == 2)
-            return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 2, 1> : srft_dequantize_batched_kernel<D, 2, 2>;
+            return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 2, 1, false>
+                                  : srft_dequantize_batched_kernel<D, 2, 2, false>;
     }
-    return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 1, 1> : srft_dequantize_batched_kernel<D, 1, 2>;
+    return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 1, 1, false> : srft_dequantize_batched_kernel<D, 1, 2, false>;
 }
 
 // One batched launch: the segment table is complete except for first_block, which is laid out here.
@@ -865,8 +929,8 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
         hipLaunchKernelGGL(quantize_batched_instance<D>(slabs, p->gm), dim3((unsigned)next), dim3(2 * D / slabs), 0, st,
                            a, p->gw);
     else
-        hipLaunchKernelGGL(dequantize_batched_instance<D>(slabs, p->gm), dim3((unsigned)next), dim3(2 * D / slabs), 0,
-                           st, a, p->gw);
+        hipLaunchKernelGGL(dequantize_batched_instance<D>(slabs, p->gm, p->fold_dq), dim3((unsigned)next),
+                           dim3(2 * D / slabs), 0, st, a, p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
@@ -904,6 +968,9 @@ int default_slabs(int d, const char* env_name, int table_value) {
 }
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// The kernels index tiles of 32 vectors with 32-bit integers and look a few grid strides ahead.
+constexpr int64_t kMaxVectors = (int64_t)1 << 33;
 
 // Scale a matrix by the power of two that puts its largest magnitude in [2^13, 2^14) and split every
 // entry into fp16 hi + fp16 lo.  Returns the exponent e (entries were multiplied by 2^e).
@@ -992,6 +1059,38 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
 
     p->slabs_q = default_slabs(d, "SRFT_SLABS_Q", d == 64 ? 2 : 1);
     p->slabs_dq = default_slabs(d, "SRFT_SLABS_DQ", (d == 256 || d == 64) ? 2 : 1);
+    // Folded read path where it applies and pays (d = 128, 192, 256; g >= 32); SRFT_FOLD_DQ=0 turns it off (tuning).
+    p->fold_dq = (d % 64 == 0) && d >= 128 && p->gm != kGroup16;      // at d = 64 it gains nothing
+    if (const char* e = std::getenv("SRFT_FOLD_DQ")) p->fold_dq = p->fold_dq && std::atoi(e) != 0;
+    std::vector<uint16_t> rfold;
+    if (p->fold_dq) {
+        p->slabs_dq = 2;
+        // A (even p) and B (odd p) fragments of wavefront w: row n = 32w + (output of MFMA row l % 32); group j,
+        // lane half kh, element e <-> packed index 32j + 16 kh + off[e] (+ 1 for B), off[] being the order in
+        // which the kernel lays out the decoded low nibbles of an 8-byte unit: (n0, n4, n2, n6) of each dword.
+        static const int off[8] = {0, 4, 2, 6, 8, 12, 10, 14};
+        const int waves = d / 64;
+        const size_t frag_halves = (size_t)waves * 2 * G * 2 * 64 * 8;
+        rfold.assign(frag_halves + (size_t)waves * 64 * 16, 0);
+        for (int w = 0; w < waves; ++w)
+            for (int l = 0; l < 64; ++l) {
+                const int n = 32 * w + slab_output_of_row(l % 32), kh = l / 32;
+                for (int ab = 0; ab < 2; ++ab)
+                    for (int j = 0; j < G; ++j)
+                        for (int e = 0; e < 8; ++e) {
+                            const size_t src = (size_t)n * d + (32 * j + 16 * kh + off[e] + ab);
+                            const size_t dst = (((size_t)(w * 2 + ab) * G + j) * 2) * 64;
+                            rfold[((dst + 0) + l) * 8 + e] = rhi[src];
+                            rfold[((dst + 64) + l) * 8 + e] = rlo[src];
+                        }
+                // sign-bit masks for this lane's outputs n + d/2, n = 32w + 16 kh + v: s_n s_{n+d/2} < 0
+                for (int v = 0; v < 16; ++v) {
+                    const int nn = 32 * w + 16 * kh + v;
+                    rfold[frag_halves + ((size_t)w * 64 + l) * 16 + v] =
+                        (p->signs[nn] * p->signs[nn + d / 2] < 0) ? 0x8000u : 0u;
+                }
+            }
+    }
     hipError_t e = hipGetDevice(&p->device);
     int cus = 0;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
@@ -999,6 +1098,8 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
     if (e == hipSuccess) e = hipMalloc((void**)&p->rfrag, rf.size() * 2);
     if (e == hipSuccess) e = hipMemcpy(p->wfrag, wf.data(), wf.size() * 2, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(p->rfrag, rf.data(), rf.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess && p->fold_dq) e = hipMalloc((void**)&p->rfold, rfold.size() * 2);
+    if (e == hipSuccess && p->fold_dq) e = hipMemcpy(p->rfold, rfold.data(), rfold.size() * 2, hipMemcpyHostToDevice);
     int rc = (e == hipSuccess) ? dispatch_occupancy(p, cus) : hip_fail(e);
     if (rc != SRFT_OK) {
         srft_plan_destroy(p);
@@ -1012,16 +1113,18 @@ int srft_plan_destroy(srft_plan_t* plan) {
     if (!plan) return SRFT_OK;
     hipError_t e1 = plan->wfrag ? hipFree(plan->wfrag) : hipSuccess;
     hipError_t e2 = plan->rfrag ? hipFree(plan->rfrag) : hipSuccess;
+    hipError_t e3 = plan->rfold ? hipFree(plan->rfold) : hipSuccess;
     delete plan;
     if (e1 != hipSuccess) return hip_fail(e1);
     if (e2 != hipSuccess) return hip_fail(e2);
+    if (e3 != hipSuccess) return hip_fail(e3);
     return SRFT_OK;
 }
 
 int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, uint8_t* codes_dev,
                      float* scales_dev, void* hip_stream) {
     if (!plan) return SRFT_ERR_NULL;
-    if (n_vec < 0) return SRFT_ERR_BAD_N;
+    if (n_vec < 0 || n_vec > kMaxVectors) return SRFT_ERR_BAD_N;
     if (n_vec == 0) return SRFT_OK;
     if (!x_f16_dev || !codes_dev || !scales_dev) return SRFT_ERR_NULL;
     if (!aligned(x_f16_dev, 16) || !aligned(codes_dev, 16) || !aligned(scales_dev, 4)) return SRFT_ERR_ALIGN;
@@ -1031,7 +1134,7 @@ int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_v
 int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, float* w_f32_dev,
                         void* hip_stream) {
     if (!plan) return SRFT_ERR_NULL;
-    if (n_vec < 0) return SRFT_ERR_BAD_N;
+    if (n_vec < 0 || n_vec > kMaxVectors) return SRFT_ERR_BAD_N;
     if (n_vec == 0) return SRFT_OK;
     if (!x_f16_dev || !w_f32_dev) return SRFT_ERR_NULL;
     if (!aligned(x_f16_dev, 16) || !aligned(w_f32_dev, 16)) return SRFT_ERR_ALIGN;
@@ -1041,7 +1144,7 @@ int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t 
 int srft_kv_dequantize(const srft_plan_t* plan, const uint8_t* codes_dev, const float* scales_dev, int64_t n_vec,
                        void* out_f16_dev, void* hip_stream) {
     if (!plan) return SRFT_ERR_NULL;
-    if (n_vec < 0) return SRFT_ERR_BAD_N;
+    if (n_vec < 0 || n_vec > kMaxVectors) return SRFT_ERR_BAD_N;
     if (n_vec == 0) return SRFT_OK;
     if (!codes_dev || !scales_dev || !out_f16_dev) return SRFT_ERR_NULL;
     if (!aligned(codes_dev, 16) || !aligned(scales_dev, 4) || !aligned(out_f16_dev, 16)) return SRFT_ERR_ALIGN;
@@ -1060,7 +1163,7 @@ static int run_batched(const srft_plan_t* const* plans, const void* const* in0, 
         if (!plans[i]) return SRFT_ERR_NULL;
         if (plans[i]->d != plans[0]->d || plans[i]->g != plans[0]->g || plans[i]->device != plans[0]->device)
             return SRFT_ERR_MISMATCH;
-        if (n_vec[i] < 0) return SRFT_ERR_BAD_N;
+        if (n_vec[i] < 0 || n_vec[i] > kMaxVectors) return SRFT_ERR_BAD_N;
         if (n_vec[i] == 0) continue;
         const void* small = write_path ? (const void*)out1[i] : in1[i];       // the scales
         if (!in0[i] || !out0[i] || !small) return SRFT_ERR_NULL;
@@ -1071,7 +1174,7 @@ static int run_batched(const srft_plan_t* const* plans, const void* const* in0, 
     for (int i = 0; i <= count; ++i) {
         if (i < count && n_vec[i] > 0) {
             const int k = a.count++;
-            a.frag[k] = write_path ? plans[i]->wfrag : plans[i]->rfrag;
+            a.frag[k] = write_path ? plans[i]->wfrag : (plans[i]->fold_dq ? plans[i]->rfold : plans[i]->rfrag);
             a.in0[k] = in0[i];
             a.in1[k] = write_path ? nullptr : in1[i];
             a.out0[k] = out0[i];
