@@ -305,6 +305,246 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
                                        gridDim.x);       // the grid never exceeds the number of tiles
 }
 
+// ------------------------------------------------------------------------------------------
+// write path, folded form: half the matrix work, for d a multiple of 128 and g = 32
+// ------------------------------------------------------------------------------------------
+// Rows k and d/2 - k of the cosine block of Q differ only by the factor (-1)^n, and so do (up to a sign)
+// rows k and d/2 - k of the sine block.  With  E_k = sum over even n,  O_k = sum over odd n  of Q[k][n] u_n:
+//     z_k       = E_k + O_k        z_{d/2-k}     =   E_k - O_k          (cosine block, packed index p = k)
+//     z_{d/2+k} = E'_k + O'_k      z_{d-k}       = -(E'_k - O'_k)       (sine block)
+// so only the rows k < d/4 are contracted, each over half of the inputs.  A workgroup has d/64 wavefronts: the
+// first half owns the cosine block, the second half the sine block, 32 values of k each; a wavefront keeps an
+// E slab (contracted with the even-n inputs) and an O slab (odd-n inputs), each 32 rows x d/2.  The inputs
+// are split into even and odd positions when the tile is staged in LDS.  A lane holds k = 16 h + v (v < 16)
+// and produces a "direct" run of 16 packed indices (ascending with v) and a "mirror" run (descending).
+// lambda of the direct index is folded into the rows; the mirror value is rho_k (E - O) with
+// rho = +-lambda_mirror / lambda_direct.
+//
+// The mirror run of a lane is p_top - 16h - v: one index above a 16-aligned block.  Each lane therefore takes
+// the bottom element of its block from its neighbour: the h = 0 lane from the h = 1 lane of the same vector (one
+// v_permlane32_swap), the h = 1 lane from another wavefront, through LDS (`xch`, one slot per group: the value of
+// packed index 32 * slot).  The four indices without a partner go the same way: k = 0 gives DC (direct) and
+// Nyquist (mirror top of the first cosine wavefront, slot d/64); the first sine wavefront has no k = 0 of its own
+// and uses that row pair for the quarter bins, E = row d/4 and O = row 3d/4 (slots d/128 and 3d/128), and takes
+// Nyquist as its direct element 0.  Values are exchanged already multiplied by their lambda.
+// A tile's exchange values are written at the end of the stage that contracts it and read after the next
+// barrier, in the stage that quantizes it.
+//
+// wfold : [d/64 waves][E, O][d/32 k-steps][hi, lo][64 lanes] fragments, then [d/64 waves][64 lanes][4] x 4 floats rho
+template <int D>
+__device__ __forceinline__ void
+srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
+                         uint2* __restrict__ codes, float* __restrict__ scales, float unscale, float scale_mul,
+                         const int t0, const int stride) {
+    constexpr int M = D / 64;            // wavefronts per workgroup
+    constexpr int G = D / 32;            // groups per vector
+    constexpr int T = D / 32;            // k-steps per slab (K = D / 2)
+    constexpr int U = D / 8;             // 16-byte units per input row
+    constexpr int ROW = U + 1;
+    constexpr int NT = 64 * M;
+    constexpr int DUMMY = 2 * M + 1;     // exchange slot for values nobody reads
+    static_assert(M % 2 == 0, "the cosine and the sine block each need whole wavefronts");
+    __shared__ uint4 lds[2][kTileVecs * ROW];
+    __shared__ float xch[2][(DUMMY + 1) * kTileVecs];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const int n_tiles = (int)((n_vec + kTileVecs - 1) / kTileVecs);
+    const int last_lim = (int)(n_vec - 1 - (long long)(n_tiles - 1) * kTileVecs);
+    const bool sine = wave >= M / 2;
+    const int wk = sine ? wave - M / 2 : wave;               // which 32 values of k
+    const bool quarter = (wave == M / 2);                    // the wavefront that carries the quarter bins
+    const int base_d = (sine ? D / 2 : 0) + 32 * wk;         // first packed index of the direct group
+    const int p_top = (sine ? D : D / 2) - 32 * wk;          // packed index of mirror element v = 0, h = 0
+    const int slot_out = (half || quarter) ? DUMMY : p_top / 32;
+    const int slot_e = (quarter && !half) ? M / 2 : DUMMY;   // where this lane's E[0] and O[0] go as they are:
+    const int slot_o = (quarter && !half) ? 3 * M / 2 : DUMMY;       // the quarter bins, or nowhere
+    const int slot_in = p_top / 32 - 1;                      // bottom of the mirror group
+
+    half8 ehi[T], elo[T], ohi[T], olo[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        ehi[t] = __builtin_bit_cast(half8, wfold[(((wave * 2 + 0) * T + t) * 2 + 0) * 64 + lane]);
+        elo[t] = __builtin_bit_cast(half8, wfold[(((wave * 2 + 0) * T + t) * 2 + 1) * 64 + lane]);
+        ohi[t] = __builtin_bit_cast(half8, wfold[(((wave * 2 + 1) * T + t) * 2 + 0) * 64 + lane]);
+        olo[t] = __builtin_bit_cast(half8, wfold[(((wave * 2 + 1) * T + t) * 2 + 1) * 64 + lane]);
+    }
+    float rho[16];
+    {
+        const uint4* rp = wfold + M * 2 * T * 2 * 64 + (wave * 64 + lane) * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 r = rp[i];
+            rho[4 * i] = __uint_as_float(r.x); rho[4 * i + 1] = __uint_as_float(r.y);
+            rho[4 * i + 2] = __uint_as_float(r.z); rho[4 * i + 3] = __uint_as_float(r.w);
+        }
+    }
+
+    // each thread moves two pairs of adjacent units (32 contiguous bytes each) per tile: pair q = tid + i NT
+    auto fetch2 = [&](uint4& a, uint4& b, int i, const uint4* tile_base, int lim) __attribute__((always_inline)) {
+        const int q = tid + i * NT, r = q / (U / 2), c = q % (U / 2);
+        const uint4* src = tile_base + (unsigned)(min(r, lim) * U + 2 * c);
+        a = src[0];
+        b = src[1];
+    };
+    auto fetch = [&](uint4& a, uint4& b, uint4& c, uint4& d, int tile) __attribute__((always_inline)) {
+        if (tile > n_tiles - 1) tile = n_tiles - 1;
+        const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
+        const uint4* tile_base = x + (long long)tile * kTileVecs * U;
+        fetch2(a, b, 0, tile_base, lim);
+        fetch2(c, d, 1, tile_base, lim);
+    };
+    // 16 consecutive inputs -> the 8 at even and the 8 at odd positions
+    auto put2 = [&](int buf, const uint4& a, const uint4& b, int i) __attribute__((always_inline)) {
+        const int q = tid + i * NT, r = q / (U / 2), c = q % (U / 2);
+        constexpr uint32_t kLo = 0x05040100u, kHi = 0x07060302u;
+        lds[buf][r * ROW + 2 * c] = make_uint4(__builtin_amdgcn_perm(a.y, a.x, kLo), __builtin_amdgcn_perm(a.w, a.z, kLo),
+                                               __builtin_amdgcn_perm(b.y, b.x, kLo), __builtin_amdgcn_perm(b.w, b.z, kLo));
+        lds[buf][r * ROW + 2 * c + 1] = make_uint4(__builtin_amdgcn_perm(a.y, a.x, kHi), __builtin_amdgcn_perm(a.w, a.z, kHi),
+                                                   __builtin_amdgcn_perm(b.y, b.x, kHi), __builtin_amdgcn_perm(b.w, b.z, kHi));
+    };
+    auto to_lds = [&](int buf, const uint4& a, const uint4& b, const uint4& c, const uint4& d) __attribute__((always_inline)) {
+        put2(buf, a, b, 0);
+        put2(buf, c, d, 1);
+    };
+    auto contract = [&](int b, floatx16& e, floatx16& o) __attribute__((always_inline)) {
+        const uint4* rowp = &lds[b][col * ROW + 2 * half];      // unit pair 2t + half: [even][odd]
+        e = floatx16{0};
+        o = floatx16{0};
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const half8 be = __builtin_bit_cast(half8, rowp[4 * t]);
+            const half8 bo = __builtin_bit_cast(half8, rowp[4 * t + 1]);
+            e = __builtin_amdgcn_mfma_f32_32x32x16_f16(ehi[t], be, e, 0, 0, 0);
+            o = __builtin_amdgcn_mfma_f32_32x32x16_f16(ohi[t], bo, o, 0, 0, 0);
+            e = __builtin_amdgcn_mfma_f32_32x32x16_f16(elo[t], be, e, 0, 0, 0);
+            o = __builtin_amdgcn_mfma_f32_32x32x16_f16(olo[t], bo, o, 0, 0, 0);
+        }
+    };
+    // what other wavefronts need of the tile just contracted
+    auto publish = [&](int b, const floatx16& e, const floatx16& o) __attribute__((always_inline)) {
+        float* slots = &xch[b][col];
+        slots[slot_out * kTileVecs] = rho[0] * (e[0] - o[0]);
+        slots[slot_e * kTileVecs] = e[0];                    // straight-line code: no branch splits the stage
+        slots[slot_o * kTileVecs] = o[0];
+    };
+    auto pack8v = [&](float f0, float f1, float f2, float f3, float f4, float f5, float f6, float f7, float inv)
+                      __attribute__((always_inline)) {
+        constexpr float kMagic = 12582912.0f + 8.0f;
+        constexpr uint32_t kMagicBits = 0x4B400000u;
+        uint32_t p = __float_as_uint(fmaf(f7, inv, kMagic));
+        p = (p << 4) + __float_as_uint(fmaf(f6, inv, kMagic));
+        p = (p << 4) + __float_as_uint(fmaf(f5, inv, kMagic));
+        p = (p << 4) + __float_as_uint(fmaf(f4, inv, kMagic));
+        p = (p << 4) + __float_as_uint(fmaf(f3, inv, kMagic));
+        p = (p << 4) + __float_as_uint(fmaf(f2, inv, kMagic));
+        p = (p << 4) + __float_as_uint(fmaf(f1, inv, kMagic));
+        p = (p << 4) + __float_as_uint(fmaf(f0, inv, kMagic));
+        uint32_t k = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) k += kMagicBits << (4 * i);
+        return (p - k) ^ 0x88888888u;
+    };
+    auto scale_of = [&](float m, float& scale, float& inv) __attribute__((always_inline)) {
+        scale = m * scale_mul;
+        inv = unscale * __builtin_amdgcn_rcpf(scale);
+        if (!(scale >= kMinScale)) { scale = 0.0f; inv = 0.0f; }
+    };
+    // vector-ALU tail of one tile, whose exchange values are in xch[b]
+    auto finish = [&](int b, floatx16& e, floatx16& o, int tile) __attribute__((always_inline)) {
+        const long long row0 = (long long)tile * kTileVecs;
+        const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
+        const int c = min(col, lim);
+        float below = xch[b][slot_in * kTileVecs + col];                 // packed index 32 * slot_in
+        float nyquist = xch[b][M * kTileVecs + col];
+        asm volatile("" : "+v"(below), "+v"(nyquist));       // read by every lane: no branch around the loads
+        float dv[16], mv[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            dv[v] = e[v] + o[v];
+            mv[v] = rho[v] * (e[v] - o[v]);
+        }
+        dv[0] = (quarter && !half) ? nyquist : dv[0];
+        // bottom element of this lane's aligned mirror block
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mv[0]), __float_as_uint(mv[0]), false, false);
+        const float bottom = half ? below : __uint_as_float(sw[1]);      // [1]: the upper lanes' value, in all lanes
+        float md = fmaxf(fabsf(dv[0]), fabsf(dv[1])), mm = fmaxf(fabsf(bottom), fabsf(mv[1]));
+#pragma unroll
+        for (int v = 2; v < 16; ++v) {
+            md = fmaxf(md, fabsf(dv[v]));
+            mm = fmaxf(mm, fabsf(mv[v]));
+        }
+        md = other_half_max(md);
+        mm = other_half_max(mm);
+        float sd, id, sm, im;
+        scale_of(md, sd, id);
+        scale_of(mm, sm, im);
+        uint2 pd, pm;
+        pd.x = pack8v(dv[0], dv[1], dv[2], dv[3], dv[4], dv[5], dv[6], dv[7], id);
+        pd.y = pack8v(dv[8], dv[9], dv[10], dv[11], dv[12], dv[13], dv[14], dv[15], id);
+        pm.x = pack8v(bottom, mv[15], mv[14], mv[13], mv[12], mv[11], mv[10], mv[9], im);
+        pm.y = pack8v(mv[8], mv[7], mv[6], mv[5], mv[4], mv[3], mv[2], mv[1], im);
+        uint2* crow = codes + row0 * (D / 16);
+        crow[(unsigned)(c * (D / 16) + base_d / 16 + half)] = pd;
+        crow[(unsigned)(c * (D / 16) + p_top / 16 - 1 - half)] = pm;
+        float* srow = scales + row0 * G;
+        srow[(unsigned)(c * G + base_d / 32)] = sd;          // both halves store the same value
+        srow[(unsigned)(c * G + slot_in)] = sm;
+    };
+
+    const int m = (n_tiles - 1 - t0) / stride + 1;
+    uint4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3;
+    floatx16 ea, oa, eb, ob;
+    fetch(pa0, pa1, pa2, pa3, t0);
+    fetch(pb0, pb1, pb2, pb3, t0 + stride);
+    hold_in_registers(ehi, elo);
+    hold_in_registers(ohi, olo);
+    to_lds(0, pa0, pa1, pa2, pa3);
+    fetch(pa0, pa1, pa2, pa3, t0 + 2 * stride);
+    // stage 0
+    __syncthreads();
+    contract(0, ea, oa);
+    to_lds(1, pb0, pb1, pb2, pb3);
+    fetch(pb0, pb1, pb2, pb3, t0 + 3 * stride);
+    publish(0, ea, oa);
+    int k = 1;
+    for (; k + 1 < m; k += 2) {
+        const int tk = t0 + k * stride;
+        __syncthreads();                         // stage k (odd)
+        contract(1, eb, ob);
+        finish(0, ea, oa, tk - stride);
+        to_lds(0, pa0, pa1, pa2, pa3);
+        fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
+        publish(1, eb, ob);
+        __syncthreads();                         // stage k + 1 (even)
+        contract(0, ea, oa);
+        finish(1, eb, ob, tk);
+        to_lds(1, pb0, pb1, pb2, pb3);
+        fetch(pb0, pb1, pb2, pb3, tk + 4 * stride);
+        publish(0, ea, oa);
+    }
+    if (k < m) {                                 // one more odd stage
+        const int tk = t0 + k * stride;
+        __syncthreads();
+        contract(1, eb, ob);
+        finish(0, ea, oa, tk - stride);
+        publish(1, eb, ob);
+        __syncthreads();
+        finish(1, eb, ob, tk);
+    } else {
+        __syncthreads();
+        finish(0, ea, oa, t0 + (k - 1) * stride);
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(D)
+srft_quantize_fold_kernel(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
+                          uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__,
+                          float unscale, float scale_mul, int) {
+    srft_quantize_fold_tiles<D>(wfold, x, n_vec, codes, scales, unscale, scale_mul, blockIdx.x, gridDim.x);
+}
+
 // Several plans in one launch (a decode step appends a few hundred vectors to each of many (layer, K|V)
 // caches: one launch per plan would be all launch latency).  Segment i = plan i's constants and buffers; it
 // is served by workgroups first_block[i] .. first_block[i+1]-1, each walking that segment's tiles with
@@ -335,6 +575,15 @@ srft_quantize_batched_kernel(const srft_batch_args a, int gw) {
     srft_quantize_tiles<D, S, false, GM>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
                                          (float*)a.out1[i], nullptr, a.unscale[i], a.unscale[i] / 7.0f, gw,
                                          blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i]);
+}
+
+template <int D>
+__global__ void __launch_bounds__(D)
+srft_quantize_fold_batched_kernel(const srft_batch_args a, int) {
+    const int i = srft_segment_of_block(a, blockIdx.x);
+    srft_quantize_fold_tiles<D>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i], (float*)a.out1[i],
+                                a.unscale[i], a.unscale[i] / 7.0f, blockIdx.x - a.first_block[i],
+                                a.first_block[i + 1] - a.first_block[i]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -800,7 +1049,9 @@ struct srft_plan {
     uint4* wfrag = nullptr;     // write-path matrix fragments (device)
     uint4* rfrag = nullptr;     // read-path matrix fragments (device)
     uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
+    uint4* wfold = nullptr;     // write-path fragments of the folded form (device), when fold_q
     bool fold_dq = false;       // read path contracts even and odd codes separately (half the matrix work)
+    bool fold_q = false;        // write path contracts even and odd inputs separately (half the matrix work)
     float unscale_w = 1.0f;     // 2^-e of the write matrix
     float unscale_r = 1.0f;
     int grid_q = 0, grid_dq = 0;    // default persistent grid sizes
@@ -825,7 +1076,10 @@ quantize_kernel_t quantize_instance(bool raw, int gm) {
     }
 }
 template <int D>
-quantize_kernel_t quantize_instance(int slabs, bool raw, int gm) {
+quantize_kernel_t quantize_instance(int slabs, bool raw, int gm, bool fold = false) {
+    if constexpr (D % 128 == 0) {
+        if (fold && !raw && gm == kGroup32) return srft_quantize_fold_kernel<D>;
+    }
     if constexpr ((D / 32) % 2 == 0) {
         if (slabs == 2) return quantize_instance<D, 2>(raw, gm);
     }
@@ -844,8 +1098,8 @@ dequantize_kernel_t dequantize_instance(int slabs, int gm, bool fold) {
 template <int D>
 int occupancy_grids(srft_plan* p, int cus) {
     int bq = 0, bd = 0;
-    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, quantize_instance<D>(p->slabs_q, false, p->gm),
-                                                          2 * D / p->slabs_q, 0));
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, quantize_instance<D>(p->slabs_q, false, p->gm, p->fold_q),
+                                                          p->fold_q ? D : 2 * D / p->slabs_q, 0));
     SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, dequantize_instance<D>(p->slabs_dq, p->gm, p->fold_dq),
                                                           2 * D / p->slabs_dq, 0));
     p->grid_q = cus * (bq > 0 ? bq : 1);
@@ -859,8 +1113,10 @@ int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* cod
     const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_q;
     if (grid > n_tiles) grid = n_tiles;
-    const quantize_kernel_t kernel = quantize_instance<D>(p->slabs_q, wout != nullptr, p->gm);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(2 * D / p->slabs_q), 0, st, p->wfrag, (const uint4*)x, n,
+    const bool fold = p->fold_q && wout == nullptr;
+    const quantize_kernel_t kernel = quantize_instance<D>(p->slabs_q, wout != nullptr, p->gm, fold);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(fold ? D : 2 * D / p->slabs_q), 0, st,
+                       fold ? p->wfold : p->wfrag, (const uint4*)x, n,
                        (uint2*)codes, scales, (float4*)wout, p->unscale_w, p->unscale_w / 7.0f, p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
@@ -884,7 +1140,10 @@ typedef void (*quantize_batched_kernel_t)(const srft_batch_args, int);
 typedef void (*dequantize_batched_kernel_t)(const srft_batch_args, int);
 
 template <int D>
-quantize_batched_kernel_t quantize_batched_instance(int slabs, int gm) {
+quantize_batched_kernel_t quantize_batched_instance(int slabs, int gm, bool fold) {
+    if constexpr (D % 128 == 0) {
+        if (fold && gm == kGroup32) return srft_quantize_fold_batched_kernel<D>;
+    }
     if constexpr ((D / 32) % 2 == 0) {
         if (slabs == 2)
             return gm == kGroup16 ? srft_quantize_batched_kernel<D, 2, kGroup16>
@@ -926,8 +1185,8 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
     a.first_block[a.count] = next;
     const int slabs = write_path ? p->slabs_q : p->slabs_dq;
     if (write_path)
-        hipLaunchKernelGGL(quantize_batched_instance<D>(slabs, p->gm), dim3((unsigned)next), dim3(2 * D / slabs), 0, st,
-                           a, p->gw);
+        hipLaunchKernelGGL(quantize_batched_instance<D>(slabs, p->gm, p->fold_q), dim3((unsigned)next),
+                           dim3(p->fold_q ? D : 2 * D / slabs), 0, st, a, p->gw);
     else
         hipLaunchKernelGGL(dequantize_batched_instance<D>(slabs, p->gm, p->fold_dq), dim3((unsigned)next),
                            dim3(2 * D / slabs), 0, st, a, p->gw);
@@ -1091,6 +1350,49 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
                 }
             }
     }
+    // Folded write path where it applies (d a multiple of 128, g = 32); SRFT_FOLD_Q=0 turns it off (tuning).
+    p->fold_q = (d % 128 == 0) && p->gm == kGroup32;
+    if (const char* e = std::getenv("SRFT_FOLD_Q")) p->fold_q = p->fold_q && std::atoi(e) != 0;
+    std::vector<uint16_t> wfold;
+    if (p->fold_q) {
+        // Wavefront w < M/2 owns cosine rows k = 32w + i, the others sine rows; row i of its E (O) slab is row
+        // p = k (cosine) or d/2 + k (sine) of W restricted to even (odd) n.  The first sine wavefront has no k = 0:
+        // there E is row d/4 and O is row 3d/4.  k-step t, lane half kh, element e <-> n = 32t + 16kh + 2e (+ 1).
+        const int M = d / 64, TF = d / 32;
+        const size_t frag_halves = (size_t)M * 2 * TF * 2 * 64 * 8;
+        wfold.assign(frag_halves + (size_t)M * 64 * 16 * 2, 0);          // rho: 16 floats = 32 halves per lane
+        for (int w = 0; w < M; ++w) {
+            const bool sine = w >= M / 2;
+            const int wk = sine ? w - M / 2 : w;
+            for (int l = 0; l < 64; ++l) {
+                const int kh = l / 32, k = 32 * wk + slab_output_of_row(l % 32);
+                for (int eo = 0; eo < 2; ++eo) {
+                    int prow = sine ? d / 2 + k : k;
+                    if (sine && k == 0) prow = eo == 0 ? d / 4 : 3 * d / 4;
+                    for (int t = 0; t < TF; ++t)
+                        for (int e = 0; e < 8; ++e) {
+                            const size_t src = (size_t)prow * d + (32 * t + 16 * kh + 2 * e + eo);
+                            const size_t dst = (((size_t)(w * 2 + eo) * TF + t) * 2) * 64;
+                            wfold[((dst + 0) + l) * 8 + e] = whi[src];
+                            wfold[((dst + 64) + l) * 8 + e] = wlo[src];
+                        }
+                }
+                // rho of this lane's 16 values k = 32 wk + 16 kh + v: lambda_mirror / lambda_direct, negated in the
+                // sine block; 0 where there is no mirror value (k = 0 of the sine block)
+                for (int v = 0; v < 16; ++v) {
+                    const int kk = 32 * wk + 16 * kh + v;
+                    const int pd = sine ? d / 2 + kk : kk, pm = sine ? d - kk : d / 2 - kk;
+                    float r = 0.0f;
+                    if (!(sine && kk == 0)) r = (float)((sine ? -1.0 : 1.0) * lam[pm] / lam[pd]);
+                    uint32_t bits;
+                    std::memcpy(&bits, &r, 4);
+                    const size_t at = frag_halves + (((size_t)w * 64 + l) * 16 + v) * 2;
+                    wfold[at] = (uint16_t)(bits & 0xFFFFu);
+                    wfold[at + 1] = (uint16_t)(bits >> 16);
+                }
+            }
+        }
+    }
     hipError_t e = hipGetDevice(&p->device);
     int cus = 0;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
@@ -1098,6 +1400,8 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
     if (e == hipSuccess) e = hipMalloc((void**)&p->rfrag, rf.size() * 2);
     if (e == hipSuccess) e = hipMemcpy(p->wfrag, wf.data(), wf.size() * 2, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(p->rfrag, rf.data(), rf.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess && p->fold_q) e = hipMalloc((void**)&p->wfold, wfold.size() * 2);
+    if (e == hipSuccess && p->fold_q) e = hipMemcpy(p->wfold, wfold.data(), wfold.size() * 2, hipMemcpyHostToDevice);
     if (e == hipSuccess && p->fold_dq) e = hipMalloc((void**)&p->rfold, rfold.size() * 2);
     if (e == hipSuccess && p->fold_dq) e = hipMemcpy(p->rfold, rfold.data(), rfold.size() * 2, hipMemcpyHostToDevice);
     int rc = (e == hipSuccess) ? dispatch_occupancy(p, cus) : hip_fail(e);
@@ -1114,6 +1418,10 @@ int srft_plan_destroy(srft_plan_t* plan) {
     hipError_t e1 = plan->wfrag ? hipFree(plan->wfrag) : hipSuccess;
     hipError_t e2 = plan->rfrag ? hipFree(plan->rfrag) : hipSuccess;
     hipError_t e3 = plan->rfold ? hipFree(plan->rfold) : hipSuccess;
+    if (plan->wfold) {
+        const hipError_t e4 = hipFree(plan->wfold);
+        if (e3 == hipSuccess) e3 = e4;
+    }
     delete plan;
     if (e1 != hipSuccess) return hip_fail(e1);
     if (e2 != hipSuccess) return hip_fail(e2);
@@ -1174,7 +1482,8 @@ static int run_batched(const srft_plan_t* const* plans, const void* const* in0, 
     for (int i = 0; i <= count; ++i) {
         if (i < count && n_vec[i] > 0) {
             const int k = a.count++;
-            a.frag[k] = write_path ? plans[i]->wfrag : (plans[i]->fold_dq ? plans[i]->rfold : plans[i]->rfrag);
+            a.frag[k] = write_path ? (plans[i]->fold_q ? plans[i]->wfold : plans[i]->wfrag)
+                                   : (plans[i]->fold_dq ? plans[i]->rfold : plans[i]->rfrag);
             a.in0[k] = in0[i];
             a.in1[k] = write_path ? nullptr : in1[i];
             a.out0[k] = out0[i];
