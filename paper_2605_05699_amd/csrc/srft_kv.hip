@@ -343,6 +343,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     constexpr int ROW = U + 1;
     constexpr int NT = 64 * M;
     constexpr int DUMMY = 2 * M + 1;     // exchange slot for values nobody reads
+    constexpr bool LEAN = (D >= 256);    // registers for one accumulator set only
     static_assert(M % 2 == 0, "the cosine and the sine block each need whole wavefronts");
     __shared__ uint4 lds[2][kTileVecs * ROW];
     __shared__ float xch[2][(DUMMY + 1) * kTileVecs];
@@ -369,16 +370,30 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         ohi[t] = __builtin_bit_cast(half8, wfold[(((wave * 2 + 1) * T + t) * 2 + 0) * 64 + lane]);
         olo[t] = __builtin_bit_cast(half8, wfold[(((wave * 2 + 1) * T + t) * 2 + 1) * 64 + lane]);
     }
+    // rho: in registers, or (large d, where registers are short) in LDS, re-read for every tile
+    constexpr bool RHO_LDS = (D >= 256);
+    __shared__ uint4 rho_s[RHO_LDS ? 4 * NT : 1];
     float rho[16];
     {
         const uint4* rp = wfold + M * 2 * T * 2 * 64 + (wave * 64 + lane) * 4;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint4 r = rp[i];
+            if constexpr (RHO_LDS) rho_s[i * NT + tid] = r;
             rho[4 * i] = __uint_as_float(r.x); rho[4 * i + 1] = __uint_as_float(r.y);
             rho[4 * i + 2] = __uint_as_float(r.z); rho[4 * i + 3] = __uint_as_float(r.w);
         }
     }
+    auto load_rho = [&]() __attribute__((always_inline)) {
+        if constexpr (RHO_LDS) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint4 r = rho_s[i * NT + tid];
+                rho[4 * i] = __uint_as_float(r.x); rho[4 * i + 1] = __uint_as_float(r.y);
+                rho[4 * i + 2] = __uint_as_float(r.z); rho[4 * i + 3] = __uint_as_float(r.w);
+            }
+        }
+    };
 
     // each thread moves two pairs of adjacent units (32 contiguous bytes each) per tile: pair q = tid + i NT
     auto fetch2 = [&](uint4& a, uint4& b, int i, const uint4* tile_base, int lim) __attribute__((always_inline)) {
@@ -424,7 +439,9 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     // what other wavefronts need of the tile just contracted
     auto publish = [&](int b, const floatx16& e, const floatx16& o) __attribute__((always_inline)) {
         float* slots = &xch[b][col];
-        slots[slot_out * kTileVecs] = rho[0] * (e[0] - o[0]);
+        float rho0 = rho[0];
+        if constexpr (RHO_LDS) rho0 = __uint_as_float(rho_s[tid].x);
+        slots[slot_out * kTileVecs] = rho0 * (e[0] - o[0]);
         slots[slot_e * kTileVecs] = e[0];                    // straight-line code: no branch splits the stage
         slots[slot_o * kTileVecs] = o[0];
     };
@@ -459,6 +476,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         float nyquist = xch[b][M * kTileVecs + col];
         asm volatile("" : "+v"(below), "+v"(nyquist));       // read by every lane: no branch around the loads
         float dv[16], mv[16];
+        load_rho();
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             dv[v] = e[v] + o[v];
@@ -501,6 +519,26 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     hold_in_registers(ohi, olo);
     to_lds(0, pa0, pa1, pa2, pa3);
     fetch(pa0, pa1, pa2, pa3, t0 + 2 * stride);
+    if constexpr (LEAN) {
+        // One accumulator set: a tile is contracted and quantized in the same stage, with a second barrier
+        // between the two for the exchange values; two workgroups per compute unit overlap each other.
+        for (int k = 0; k < m; ++k) {
+            const int tk = t0 + k * stride;
+            __syncthreads();                     // T_k is in lds[k % 2]; everyone is done with xch
+            contract(k & 1, ea, oa);
+            if (k & 1) {
+                to_lds(0, pa0, pa1, pa2, pa3);
+                fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
+            } else {
+                to_lds(1, pb0, pb1, pb2, pb3);
+                fetch(pb0, pb1, pb2, pb3, tk + 3 * stride);
+            }
+            publish(0, ea, oa);
+            __syncthreads();
+            finish(0, ea, oa, tk);
+        }
+        return;
+    }
     // stage 0
     __syncthreads();
     contract(0, ea, oa);
@@ -537,8 +575,9 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     }
 }
 
+// two wavefronts per SIMD (8 per compute unit): the register allocator is told to stay within 256 VGPRs
 template <int D>
-__global__ void __launch_bounds__(D)
+__global__ void __launch_bounds__(D, 2)
 srft_quantize_fold_kernel(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
                           uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__,
                           float unscale, float scale_mul, int) {
@@ -578,7 +617,7 @@ srft_quantize_batched_kernel(const srft_batch_args a, int gw) {
 }
 
 template <int D>
-__global__ void __launch_bounds__(D)
+__global__ void __launch_bounds__(D, 2)
 srft_quantize_fold_batched_kernel(const srft_batch_args a, int) {
     const int i = srft_segment_of_block(a, blockIdx.x);
     srft_quantize_fold_tiles<D>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i], (float*)a.out1[i],
