@@ -2,7 +2,8 @@
 """Benchmark of the SRFT int4 KV-cache write + read path on one MI355X.
 
 A step is one pass of the whole hot path over the workload's cache: every plan's fp16 K/V tensor is
-quantized (one launch per plan), then every plan's int4 record is dequantized (one launch per plan).
+quantized, then every plan's int4 record is dequantized.  Plans with at least 65,536 vectors get a launch
+each; smaller ones go through the batched entry points, up to 64 plans per launch (--batched on|off overrides).
 Inputs are synthetic, seeded, and resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
@@ -21,8 +22,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 MEASURED_TRAFFIC = {
     # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (factors from the copy kernel of known size), KiB -> bytes, per launch
     # of 1,048,576 vectors at d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
-    ("llama3-70b-128k", "srft_quantize_kernel"): (131436.5 * 2.0 + 81924.9) * 1024,
-    ("llama3-70b-128k", "srft_dequantize_kernel"): (41318.4 * 2.0 + 262144.0) * 1024,
+    ("llama3-70b-128k", "srft_quantize_kernel"): (131342.9 * 2.0 + 82098.2) * 1024,
+    ("llama3-70b-128k", "srft_dequantize_kernel"): (41172.1 * 2.0 + 262144.0) * 1024,
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
@@ -39,6 +40,8 @@ def main() -> int:
     ap.add_argument("--plans", type=int, default=0, help="use only the first N plans (debugging; 0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-workgroups", type=int, default=0)
+    ap.add_argument("--batched", choices=["auto", "on", "off"], default="auto",
+                    help="several plans per launch (auto: when a plan has fewer than 65,536 vectors)")
     ap.add_argument("--ceiling", action="store_true",
                     help="also time the streaming kernel that has each path's read:write byte mix (HBM ceiling)")
     ap.add_argument("--decode-append", action="store_true",
@@ -84,16 +87,27 @@ def main() -> int:
 
     stream = torch.cuda.current_stream()
     h = [pl.handle for pl in plans]
+    batched = args.batched == "on" or (args.batched == "auto" and n < 65536)
+    launches = -(-n_plans // 64) if batched else n_plans          # per direction and step
+    if batched:
+        table_q = B.BatchTable(h, list(x), list(codes), list(scales))
+        table_d = B.BatchTable(h, list(out), list(codes), list(scales))
 
     def step(ev=None):
         if ev:
             ev[0].record(stream)
-        for p in range(n_plans):
-            B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
+        if batched:
+            B.srft_kv_quantize_batched(table_q, stream)
+        else:
+            for p in range(n_plans):
+                B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
         if ev:
             ev[1].record(stream)
-        for p in range(n_plans):
-            B.srft_kv_dequantize(h[p], codes[p], scales[p], out[p], stream)
+        if batched:
+            B.srft_kv_dequantize_batched(table_d, stream)
+        else:
+            for p in range(n_plans):
+                B.srft_kv_dequantize(h[p], codes[p], scales[p], out[p], stream)
         if ev:
             ev[2].record(stream)
 
@@ -112,8 +126,8 @@ def main() -> int:
     ms_per_step = wall / args.steps * 1e3
 
     def roof(t_phase):
-        per_launch_s = t_phase / n_plans
-        achieved = n * bytes_per_vec / per_launch_s / 1e9
+        per_launch_s = t_phase / launches
+        achieved = total_vec * bytes_per_vec / t_phase / 1e9
         return per_launch_s, achieved
 
     ql, qa = roof(tq)
@@ -131,14 +145,15 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
                    "total_vectors": total_vec, "bytes_per_vector_each_direction": bytes_per_vec,
-                   "launches_per_step": 2 * n_plans},
+                   "launches_per_step": 2 * launches, "batched": batched},
         "quantize": {"vectors_per_s": total_vec / tq, "ns_per_vec": tq / total_vec * 1e9, "GBps": qa,
                      "hbm_frac": qa / HBM_PEAK_GBPS, "avg_launch_ms": ql * 1e3},
         "dequantize": {"vectors_per_s": total_vec / td, "ns_per_vec": td / total_vec * 1e9, "GBps": da,
                        "hbm_frac": da / HBM_PEAK_GBPS, "avg_launch_ms": dl * 1e3},
         "roofline": {"kernel": dominant, "bound": "hbm", "achieved": dom_a, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dom_a / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get((w.name, dominant)),
-                     "algorithmic_bytes_per_launch": n * bytes_per_vec, "avg_launch_ms": dom_l * 1e3},
+                     "algorithmic_bytes_per_launch": total_vec * bytes_per_vec // launches,
+                     "avg_launch_ms": dom_l * 1e3},
         "paper_context_apple_m1": PAPER_CONTEXT,
     }
 
@@ -160,7 +175,7 @@ def main() -> int:
         torch.cuda.synchronize()
         result["copy_kernel"] = {"bytes_each_way": nb, "GBps_read_plus_write": 2 * nb / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, x[0], plans[0], W)
+        result["cpu_baseline"] = cpu_baseline(w, x, plans, W)
     for pl in plans:
         pl.close()
     print(json.dumps(result))
@@ -239,8 +254,9 @@ def decode_append(B, W, torch, dev, stream, iters=200):
     return res
 
 
-def cpu_baseline(w, x0, plan0, W):
-    """The oracle as it stands, timed on this host over a bounded sample of plan 0 (write + read path)."""
+def cpu_baseline(w, x, plans, W, budget_s=12.0, max_vectors=1 << 23):
+    """The oracle as it stands, timed on this host over a bounded sample of the workload (write + read path):
+    chunks of 131,072 vectors, plan after plan, until about `budget_s` seconds of oracle time are spent."""
     import numpy as np
     from oracle import srft_oracle as O
     try:
@@ -248,23 +264,29 @@ def cpu_baseline(w, x0, plan0, W):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = 1
-    chunk = min(x0.shape[0], 1 << 17)
-    n_chunks = max(1, min(x0.shape[0] // chunk, 24))         # about 10-20 s of oracle time at d = 128
-    _, lam, _ = W.plan_constants(w, 0)
-    s = plan0.signs
     tq = td = 0.0
-    for i in range(n_chunks):
-        xs = x0[i * chunk:(i + 1) * chunk].cpu().numpy()
-        t0 = time.perf_counter()
-        q = O.quantize(xs, s, lam, w.g)
-        t1 = time.perf_counter()
-        O.dequantize(q["codes"], q["scales"], s, lam, w.g)
-        t2 = time.perf_counter()
-        tq += t1 - t0
-        td += t2 - t1
-    sample = chunk * n_chunks
+    sample = 0
+    used_plans = 0
+    for p in range(len(plans)):
+        _, lam, _ = W.plan_constants(w, p)
+        s = plans[p].signs
+        used_plans += 1
+        for lo in range(0, x[p].shape[0], 1 << 17):
+            xs = x[p][lo:lo + (1 << 17)].cpu().numpy()
+            t0 = time.perf_counter()
+            q = O.quantize(xs, s, lam, w.g)
+            t1 = time.perf_counter()
+            O.dequantize(q["codes"], q["scales"], s, lam, w.g)
+            t2 = time.perf_counter()
+            tq += t1 - t0
+            td += t2 - t1
+            sample += xs.shape[0]
+            if tq + td > budget_s or sample >= max_vectors:
+                break
+        if tq + td > budget_s or sample >= max_vectors:
+            break
     return {"value": sample / (tq + td), "unit": "vectors/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {sample} vectors of plan 0 of {w.name}: oracle quantize {tq:.2f} s + "
+            "sample": f"the first {sample} vectors of {w.name} (plans 0..{used_plans - 1}): oracle quantize {tq:.2f} s + "
                       f"dequantize {td:.2f} s (numpy, float64, dense d x d form)",
             "quantize_vectors_per_s": sample / tq, "dequantize_vectors_per_s": sample / td}
 
