@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--decode-append", action="store_true",
                     help="also time the decode-step append of the decode-d96 workload: a launch per plan against "
                          "one batched launch")
+    ap.add_argument("--power", action="store_true",
+                    help="also run each path, and the streaming kernel with its byte mix, for about 3 s each while "
+                         "sampling socket power and shader clock with amd-smi")
     ap.add_argument("--copy-bytes", type=int, default=0,
                     help="also run the library's plain copy kernel over this many bytes (counter calibration)")
     args = ap.parse_args()
@@ -159,6 +162,25 @@ def main() -> int:
 
     if args.ceiling:
         result["hbm_ceiling"] = mix_ceiling(B, torch, x, out, n_plans * n, d, G, stream)
+    if args.power:
+        def q_pass():
+            for p in range(n_plans):
+                B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
+
+        def d_pass():
+            for p in range(n_plans):
+                B.srft_kv_dequantize(h[p], codes[p], scales[p], out[p], stream)
+        big, small = 32 * 2 * d, 32 * (d // 2 + 4 * G)
+        tiles = min(n_plans * n // 32, (2 << 30) // big)
+        xa, xb = x.view(torch.uint8).reshape(-1), out.view(torch.uint8).reshape(-1)
+        result["power"] = {
+            "quantize": sampled_phase(torch, q_pass, n_plans * n * bytes_per_vec),
+            "dequantize": sampled_phase(torch, d_pass, n_plans * n * bytes_per_vec),
+            "stream_quantize_mix": sampled_phase(
+                torch, lambda: B.srft_stream_mix(xa, xb, tiles, big, small, 768, stream), tiles * (big + small)),
+            "stream_dequantize_mix": sampled_phase(
+                torch, lambda: B.srft_stream_mix(xa, xb, tiles, small, big, 768, stream), tiles * (big + small)),
+        }
     if args.decode_append:
         result["decode_append"] = decode_append(B, W, torch, dev, stream)
     if args.copy_bytes:
@@ -203,6 +225,47 @@ def mix_ceiling(B, torch, x, out, total_vec, d, G, stream):
         res[name + "_GBps_by_workgroups"] = best
         res[name + "_GBps"] = max(best.values())
     return res
+
+
+def sampled_phase(torch, fn, bytes_per_call, seconds=3.0):
+    """Run fn back to back for `seconds`; a thread samples `amd-smi metric --power --clock` meanwhile.
+    Returns the sustained GB/s and the mean socket power / shader clock over the samples (the first is dropped)."""
+    import subprocess
+    import threading
+    samples, stop = [], threading.Event()
+
+    def sampler():
+        while not stop.is_set():
+            try:
+                js = json.loads(subprocess.run(["amd-smi", "metric", "--power", "--clock", "--json"],
+                                               capture_output=True, text=True, timeout=10).stdout)
+                g = js["gpu_data"][0] if isinstance(js, dict) else js[0]
+                clk = [v["clk"]["value"] for k, v in g["clock"].items() if k.startswith("gfx_") and
+                       isinstance(v.get("clk"), dict)]
+                samples.append((g["power"]["socket_power"]["value"], sum(clk) / max(1, len(clk))))
+            except Exception:
+                pass
+            stop.wait(0.2)
+
+    fn()
+    torch.cuda.synchronize()
+    th = threading.Thread(target=sampler, daemon=True)
+    th.start()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0, calls = time.perf_counter(), 0
+    e0.record()
+    while time.perf_counter() - t0 < seconds:
+        fn()
+        calls += 1
+        torch.cuda.synchronize()
+    e1.record()
+    torch.cuda.synchronize()
+    stop.set()
+    th.join()
+    use = samples[1:] if len(samples) > 2 else samples
+    return {"GBps": calls * bytes_per_call / (e0.elapsed_time(e1) * 1e-3) / 1e9, "samples": len(use),
+            "socket_power_W": sum(a for a, _ in use) / max(1, len(use)),
+            "shader_clock_MHz": sum(b for _, b in use) / max(1, len(use))}
 
 
 def decode_append(B, W, torch, dev, stream, iters=200):

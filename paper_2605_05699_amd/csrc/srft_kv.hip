@@ -48,6 +48,9 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTileVecs = 32;          // vectors per tile = N of the 32x32x16 MFMA
 constexpr int kMaxD = 256;
+#ifndef SRFT_LEAN_ALT_MAX
+#define SRFT_LEAN_ALT_MAX 8              // read path: slabs x groups up to which two accumulator sets alternate
+#endif
 constexpr float kMinScale = 7.888609052210118e-31f;   // 2^-100: below this a group is stored as zero
 
 // ------------------------------------------------------------------------------------------
@@ -885,12 +888,24 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         }
     };
 
+    // With few groups two accumulator sets fit: group j + 1 is on the matrix cores while group j is folded in.
+    constexpr bool LEAN_ALT = LEAN && (S * G <= SRFT_LEAN_ALT_MAX);
     auto lean_body = [&](int b) __attribute__((always_inline)) {
+        if constexpr (LEAN_ALT) {
+            group(b, 0, acc0);
 #pragma unroll
-        for (int j = 0; j < G; ++j) {
-            group(b, j, acc0);
-            fold(acc0, scale_of(b, j), j == 0);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int j = 1; j < G; ++j) {
+                group(b, j, (j & 1) ? acc1 : acc0);
+                fold((j & 1) ? acc0 : acc1, scale_of(b, j - 1), j == 1);
+            }
+            fold(((G - 1) & 1) ? acc1 : acc0, scale_of(b, G - 1), G == 1);
+        } else {
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                group(b, j, acc0);
+                fold(acc0, scale_of(b, j), j == 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         stage_out(b);
     };
