@@ -32,6 +32,10 @@ What each function follows:
 * ``pack_nibbles`` /
   ``unpack_nibbles``       -- Sec. 3.2 detail (ii):
                               byte = (q[2i+1] << 4) | (q[2i] & 0xF).
+* ``channel_absmax`` /
+  ``lambda_from_absmax``   -- Sec. 7.1: lambda_d = 1 / per_channel_max(SRFT
+                              output)_d, the maximum taken over a calibration
+                              batch (Sec. 7.2: over whole windows).
 * ``record_bytes``         -- Sec. 3.2 step 4, Sec. 4.5 and Sec. 7.2 item (i):
                               d/2 code bytes plus one fp32 scale per group.
 
@@ -278,3 +282,34 @@ def dequantize_f64(codes, scales, s, lam, g: int, form: str = "dense") -> np.nda
 def dequantize(codes, scales, s, lam, g: int, form: str = "dense") -> np.ndarray:
     """Read path: unpack, times scale, / max(lambda, 1e-6), inverse SRFT, unsign, fp16 (RNE)."""
     return dequantize_f64(codes, scales, s, lam, g, form=form).astype(np.float16)
+
+
+def channel_absmax(x_f16, s, lam=None, running=None) -> np.ndarray:
+    """Per-channel abs-max of w = lambda * pack(F (s * x)) over the rows of x_f16 ([n, d]); float64 [d].
+
+    Sec. 7.1 names this statistic ("per_channel_max(SRFT-output)"); Sec. 7.2 takes it over whole calibration
+    windows, batch after batch, hence ``running``: the maxima so far (element-wise maximum with them).
+    """
+    x = np.asarray(x_f16, dtype=np.float64)
+    d = x.shape[-1]
+    w = srft_forward(x, s)
+    if lam is not None:
+        w = w * np.asarray(lam, dtype=np.float64)
+    amax = np.abs(w).max(axis=0) if x.shape[0] else np.zeros(d)
+    if running is not None:
+        amax = np.maximum(amax, np.asarray(running, dtype=np.float64))
+    return amax
+
+
+def lambda_from_absmax(amax) -> np.ndarray:
+    """lambda_k = 1 / amax_k (Sec. 7.1), float64.
+
+    The paper does not say what a channel that never moved gets; reading taken here: channels below 2^-16 of
+    the largest abs-max are treated as if they were at that floor, and an all-zero statistic gives lambda = 1.
+    """
+    a = np.asarray(amax, dtype=np.float64)
+    top = a.max(initial=0.0)
+    if top <= 0.0:
+        return np.ones_like(a)
+    return 1.0 / np.maximum(a, top * 2.0 ** -16)
+

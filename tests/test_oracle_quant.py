@@ -208,3 +208,71 @@ def test_pins_would_catch_a_transposed_or_conjugated_matrix():
     assert not np.allclose(z, x @ Q)                 # transposed operand differs on an impulse
     Qc = Q.copy(); Qc[d // 2 + 1:] *= -1             # conjugate convention differs on the Im rows
     assert not np.allclose(z, x @ Qc.T)
+
+
+# ----------------------------------------------------------------------------- calibration statistic (Sec. 7.1)
+def test_channel_absmax_against_a_loop_and_closed_forms():
+    d, n = 24, 37
+    rng = np.random.RandomState(3)
+    x = rng.standard_normal((n, d)).astype(np.float16)
+    s = O.signs_from_seed(11, d)
+    lam = np.exp(0.3 * rng.standard_normal(d))
+    got = O.channel_absmax(x, s, lam)
+    # brute force: every vector through numpy's rfft, packed by hand per Eq. 2, maximum taken in a loop
+    want = np.zeros(d)
+    for r in range(n):
+        Y = np.fft.rfft(s * x[r].astype(np.float64), norm="ortho")
+        z = np.empty(d)
+        z[0], z[d // 2] = Y[0].real, Y[d // 2].real
+        z[1:d // 2] = np.sqrt(2) * Y[1:d // 2].real
+        z[d // 2 + 1:] = np.sqrt(2) * Y[1:d // 2].imag
+        want = np.maximum(want, np.abs(lam * z))
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-14)
+    # constant vectors c * s: only the DC channel moves, by |c| sqrt(d)
+    c = np.array([0.5, -3.0, 2.0])
+    amax = O.channel_absmax(np.outer(c, s).astype(np.float16), s)
+    assert abs(amax[0] - 3.0 * np.sqrt(d)) < 1e-12 and np.all(amax[1:] < 1e-12)
+    # a pure cosine at bin m, amplitude a: channel m moves by a sqrt(d/2), nothing else
+    m, a = 5, 1.5
+    v = (a * np.cos(2 * np.pi * m * np.arange(d) / d)).astype(np.float16).astype(np.float64)
+    z = O.srft_forward(s * v, s)
+    amax = O.channel_absmax((s * v)[None, :], s)
+    assert np.argmax(amax) == m and abs(amax[m] - abs(z[m])) < 1e-12 and abs(amax[m] - a * np.sqrt(d / 2)) < 2e-3
+
+
+def test_channel_absmax_properties_and_running_maximum():
+    d = 32
+    rng = np.random.RandomState(4)
+    x = rng.standard_normal((50, d)).astype(np.float16)
+    s = O.signs_from_seed(2, d)
+    full = O.channel_absmax(x, s)
+    # order of the rows does not matter; batches combine through the running maximum
+    # (compared to a few ulp: the matrix product may sum in another order for another batch shape)
+    assert np.allclose(full, O.channel_absmax(x[::-1], s), rtol=1e-13, atol=0)
+    part = O.channel_absmax(x[:20], s)
+    assert np.allclose(full, O.channel_absmax(x[20:], s, running=part), rtol=1e-13, atol=0)
+    assert np.all(full >= part * (1 - 1e-13))
+    # homogeneous of degree one (a power of two keeps fp16 exact)
+    assert np.allclose(O.channel_absmax(x * np.float16(4.0), s), 4.0 * full, rtol=1e-14)
+    # empty batch: zeros, or the running value
+    assert np.array_equal(O.channel_absmax(x[:0], s), np.zeros(d))
+    assert np.array_equal(O.channel_absmax(x[:0], s, running=part), part)
+
+
+def test_lambda_from_absmax_normalises_every_channel_to_one():
+    d = 64
+    rng = np.random.RandomState(5)
+    gain = np.exp(rng.standard_normal(d))
+    x = (rng.standard_normal((200, d)) * gain).astype(np.float16)
+    s = O.signs_from_seed(9, d)
+    amax = O.channel_absmax(x, s)
+    lam = O.lambda_from_absmax(amax)
+    assert np.allclose(lam * amax, 1.0, rtol=1e-14)
+    # with that lambda the rescaled coefficients of the calibration batch fill [-1, 1] exactly, channel by channel
+    w = O.srft_forward(x.astype(np.float64), s) * lam
+    assert np.allclose(np.abs(w).max(axis=0), 1.0, rtol=1e-12)
+    assert np.allclose(O.channel_absmax(x, s, lam), np.abs(w).max(axis=0), rtol=1e-13, atol=0)
+    # readings: dead channels sit at the 2^-16 floor, an all-zero statistic gives ones
+    a = np.array([2.0, 0.0, 1e-9, 0.5])
+    assert np.allclose(O.lambda_from_absmax(a), [0.5, 2.0 ** 15, 2.0 ** 15, 2.0])
+    assert np.array_equal(O.lambda_from_absmax(np.zeros(8)), np.ones(8))
