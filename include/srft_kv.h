@@ -117,6 +117,27 @@ int srft_kv_dequantize_batched(const srft_plan_t* const* plans, const uint8_t* c
 int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec,
                         float* w_f32_dev, void* hip_stream);
 
+/*
+ * Calibration statistic for lambda: per-channel abs-max of the transform output over a batch.  (Sec. 7.1: "lambda_d =
+ * 1 / per_channel_max(SRFT output)_d"; Sec. 7.2, the static "window-uniform" calibration over whole windows.)
+ *   x_f16_dev  [n_vec, d] fp16, 16-byte aligned.                                         read only
+ *   amax_dev   d fp32 on the device, 4-byte aligned, all >= 0: a RUNNING maximum.  On return amax_dev[k] =
+ *              max(old amax_dev[k], max over the n_vec vectors of |w_k|), w = lambda * pack(F (s * x)) with the
+ *              plan's lambda.  Zero it before the first batch; call once per batch of the calibration window.
+ *              With a plan created with lambda_host = NULL, w is the plain SRFT output.
+ * Updated with atomic maxima: calls on the same amax_dev may overlap.
+ */
+int srft_kv_channel_absmax(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, float* amax_dev,
+                           void* hip_stream);
+
+/*
+ * lambda from that statistic, on the host: lambda_k = 1 / amax_k (Sec. 7.1).  Two cases the paper does not cover:
+ * a channel whose amax is below 2^-16 of the largest is treated as if it were at that floor (srft_plan_create
+ * accepts max/min lambda up to 2^16), and an all-zero statistic gives lambda = 1.  amax_host: d finite floats >= 0
+ * (else SRFT_ERR_BAD_LAMBDA); lambda_host: d floats, written.  No HIP calls.
+ */
+int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host);
+
 /* Plan introspection (host side, no HIP calls). */
 int srft_plan_d(const srft_plan_t* plan);             /* d, or a negative status */
 int srft_plan_group_size(const srft_plan_t* plan);    /* g */

@@ -23,6 +23,7 @@ EXPORTS = [
     "srft_plan_code_bytes", "srft_plan_get_signs", "srft_plan_set_max_workgroups",
     "srft_stream_copy", "srft_stream_mix", "srft_status_string", "srft_last_hip_error",
     "srft_kv_quantize_batched", "srft_kv_dequantize_batched",
+    "srft_kv_channel_absmax", "srft_lambda_from_absmax",
 ]
 
 
@@ -51,6 +52,8 @@ def lib() -> C.CDLL:
     L.srft_kv_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
     L.srft_kv_dequantize.argtypes = [vp, vp, vp, i64, vp, vp]
     L.srft_kv_forward_f32.argtypes = [vp, vp, i64, vp, vp]
+    L.srft_kv_channel_absmax.argtypes = [vp, vp, i64, vp, vp]
+    L.srft_lambda_from_absmax.argtypes = [vp, ci, vp]
     L.srft_kv_quantize_batched.argtypes = [vp, vp, vp, vp, vp, ci, vp]
     L.srft_kv_dequantize_batched.argtypes = [vp, vp, vp, vp, vp, ci, vp]
     for name in ("srft_plan_d", "srft_plan_group_size", "srft_plan_groups", "srft_plan_code_bytes"):
@@ -170,6 +173,23 @@ def srft_kv_forward_f32(plan: int, x: torch.Tensor, w: torch.Tensor, stream=None
            "srft_kv_forward_f32")
 
 
+def srft_kv_channel_absmax(plan: int, x: torch.Tensor, amax: torch.Tensor, stream=None) -> None:
+    """amax (d fp32 on the device, >= 0) becomes max(amax, per-channel abs-max of the transform of x)."""
+    if amax.numel() != lib().srft_plan_d(plan):
+        raise ValueError("amax must have d entries")
+    _check(lib().srft_kv_channel_absmax(plan, _dev_ptr(x, torch.float16, "x"), x.shape[0],
+                                        _dev_ptr(amax, torch.float32, "amax"), _stream_handle(stream)),
+           "srft_kv_channel_absmax")
+
+
+def srft_lambda_from_absmax(amax) -> np.ndarray:
+    a = np.ascontiguousarray(np.asarray(amax, dtype=np.float32))
+    lam = np.empty_like(a)
+    _check(lib().srft_lambda_from_absmax(a.ctypes.data_as(C.c_void_p), a.size, lam.ctypes.data_as(C.c_void_p)),
+           "srft_lambda_from_absmax")
+    return lam
+
+
 def srft_plan_get_signs(plan: int) -> np.ndarray:
     d = lib().srft_plan_d(plan)
     out = np.empty(d, dtype=np.int8)
@@ -236,6 +256,12 @@ class Plan:
             out = torch.empty(codes.shape[0], self.d, dtype=torch.float16, device=codes.device)
         srft_kv_dequantize(self.handle, codes, scales, out, stream)
         return out
+
+    def channel_absmax(self, x, amax=None, stream=None):
+        if amax is None:
+            amax = torch.zeros(self.d, dtype=torch.float32, device=x.device)
+        srft_kv_channel_absmax(self.handle, x, amax, stream)
+        return amax
 
     def forward_f32(self, x, w=None, stream=None):
         if w is None:

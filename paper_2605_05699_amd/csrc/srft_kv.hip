@@ -130,14 +130,18 @@ __device__ __forceinline__ uint32_t pack8(const floatx16& acc, int base, float i
 //         every B fragment read from LDS feeds four MFMAs instead of two and half as many wavefronts read the
 //         tile; the price is a 2 x larger register-resident slab (at d = 256 it only fits with one wavefront
 //         per SIMD, the slab in the accumulation half of the register file).
-// RAW   : store the fp32 coefficients w instead of quantizing (srft_kv_forward_f32)
+// OUT   : kOutCodes: the quantizer.  kOutRaw: store the fp32 coefficients w instead (srft_kv_forward_f32).
+//         kOutAmax: no per-vector output; every lane keeps the running maximum of |w| of its 16 channels over the
+//         tiles it sees, lanes are reduced once at the end and one atomic max per channel and workgroup goes
+//         to wout, read as float[d] (srft_kv_channel_absmax: the statistic lambda is calibrated from, Sec. 7.1).
 // GM    : group mode.  kGroup32: one scale per slab (g = 32, the deployed format).  kGroup16: one scale per
 //         lane (g = 16; a lane's 16 outputs are one group, no cross-lane step).  kGroupWide: g = 32 * gw with
 //         gw >= 2 slabs per group, up to the per-token case g = d; the slab maxima meet in LDS, which costs
 //         two more barriers per tile.
 enum { kGroup16 = 0, kGroup32 = 1, kGroupWide = 2 };
+enum { kOutCodes = 0, kOutRaw = 1, kOutAmax = 2 };
 // The work of one workgroup: tiles t0, t0 + stride, ... of one plan's n_vec vectors (t0 < number of tiles).
-template <int D, int S, bool RAW, int GM>
+template <int D, int S, int OUT, int GM>
 __device__ __forceinline__ void
 srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
                     uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
@@ -193,6 +197,7 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
         put1(buf, b, 1);
         if constexpr (PER > 2) { put1(buf, c, 2); put1(buf, d, 3); }
     };
+    float cmax[OUT == kOutAmax ? S : 1][16] = {};            // running per-channel maxima (kOutAmax)
     using Acc = Accs<S>;
     auto contract = [&](int b, Acc& accs) __attribute__((always_inline)) {
         const uint4* rowp = &lds[b][col * ROW + half];
@@ -218,7 +223,13 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
         const long long row0 = (long long)tile * kTileVecs;
         const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;     // uniform
         const int c = min(col, lim);                                      // alias rows past the end
-        if constexpr (RAW) {
+        if constexpr (OUT == kOutAmax) {
+            // rows past the end repeat the last row, which changes no maximum
+            each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) cmax[s][v] = fmaxf(cmax[s][v], fabsf(acc[v]));
+            });
+        } else if constexpr (OUT == kOutRaw) {
             each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
                 const int slab = wave * S + s;
                 float4* o = wout + (row0 * D) / 4 + (unsigned)((c * D + 32 * slab + 16 * half) / 4);
@@ -302,14 +313,28 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
     } else {
         finish(acc_a, t0 + (k - 1) * stride);
     }
+    if constexpr (OUT == kOutAmax) {
+        // lanes of one half hold the same 16 channels for 32 different vectors: butterfly over the 32, then one
+        // atomic per channel (non-negative floats order like their bit patterns)
+        unsigned int* amax = reinterpret_cast<unsigned int*>(wout);
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float mx = cmax[s][v];
+#pragma unroll
+                for (int step = 1; step < 32; step *= 2) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
+                if (col == 0) atomicMax(&amax[32 * (wave * S + s) + 16 * half + v], __float_as_uint(mx * unscale));
+            }
+    }
 }
 
-template <int D, int S, bool RAW, int GM>
+template <int D, int S, int OUT, int GM>
 __global__ void __launch_bounds__(2 * D / S)
 srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
                      uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
                      float unscale, float scale_mul, int gw) {
-    srft_quantize_tiles<D, S, RAW, GM>(wfrag, x, n_vec, codes, scales, wout, unscale, scale_mul, gw, blockIdx.x,
+    srft_quantize_tiles<D, S, OUT, GM>(wfrag, x, n_vec, codes, scales, wout, unscale, scale_mul, gw, blockIdx.x,
                                        gridDim.x);       // the grid never exceeds the number of tiles
 }
 
@@ -619,7 +644,7 @@ template <int D, int S, int GM>
 __global__ void __launch_bounds__(2 * D / S)
 srft_quantize_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
-    srft_quantize_tiles<D, S, false, GM>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
+    srft_quantize_tiles<D, S, kOutCodes, GM>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
                                          (float*)a.out1[i], nullptr, a.unscale[i], a.unscale[i] / 7.0f, gw,
                                          blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i]);
 }
@@ -1135,23 +1160,24 @@ typedef void (*dequantize_kernel_t)(const uint4*, const uint2*, const float*, lo
 
 // The kernel instance for a plan: d, slabs per wavefront, group mode.
 template <int D, int S>
-quantize_kernel_t quantize_instance(bool raw, int gm) {
-    if (raw) return srft_quantize_kernel<D, S, true, kGroup32>;
+quantize_kernel_t quantize_instance(int out, int gm) {
+    if (out == kOutRaw) return srft_quantize_kernel<D, S, kOutRaw, kGroup32>;
+    if (out == kOutAmax) return srft_quantize_kernel<D, S, kOutAmax, kGroup32>;
     switch (gm) {
-        case kGroup16: return srft_quantize_kernel<D, S, false, kGroup16>;
-        case kGroupWide: return srft_quantize_kernel<D, S, false, kGroupWide>;
-        default: return srft_quantize_kernel<D, S, false, kGroup32>;
+        case kGroup16: return srft_quantize_kernel<D, S, kOutCodes, kGroup16>;
+        case kGroupWide: return srft_quantize_kernel<D, S, kOutCodes, kGroupWide>;
+        default: return srft_quantize_kernel<D, S, kOutCodes, kGroup32>;
     }
 }
 template <int D>
-quantize_kernel_t quantize_instance(int slabs, bool raw, int gm, bool fold = false) {
+quantize_kernel_t quantize_instance(int slabs, int out, int gm, bool fold = false) {
     if constexpr (D % 128 == 0) {
-        if (fold && !raw && gm == kGroup32) return srft_quantize_fold_kernel<D>;
+        if (fold && out == kOutCodes && gm == kGroup32) return srft_quantize_fold_kernel<D>;
     }
     if constexpr ((D / 32) % 2 == 0) {
-        if (slabs == 2) return quantize_instance<D, 2>(raw, gm);
+        if (slabs == 2) return quantize_instance<D, 2>(out, gm);
     }
-    return quantize_instance<D, 1>(raw, gm);
+    return quantize_instance<D, 1>(out, gm);
 }
 template <int D>
 dequantize_kernel_t dequantize_instance(int slabs, int gm, bool fold) {
@@ -1166,7 +1192,7 @@ dequantize_kernel_t dequantize_instance(int slabs, int gm, bool fold) {
 template <int D>
 int occupancy_grids(srft_plan* p, int cus) {
     int bq = 0, bd = 0;
-    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, quantize_instance<D>(p->slabs_q, false, p->gm, p->fold_q),
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, quantize_instance<D>(p->slabs_q, kOutCodes, p->gm, p->fold_q),
                                                           p->fold_q ? D : 2 * D / p->slabs_q, 0));
     SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, dequantize_instance<D>(p->slabs_dq, p->gm, p->fold_dq),
                                                           2 * D / p->slabs_dq, 0));
@@ -1177,12 +1203,12 @@ int occupancy_grids(srft_plan* p, int cus) {
 
 template <int D>
 int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* codes, float* scales,
-                    float* wout, hipStream_t st) {
+                    float* wout, int out, hipStream_t st) {
     const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_q;
     if (grid > n_tiles) grid = n_tiles;
-    const bool fold = p->fold_q && wout == nullptr;
-    const quantize_kernel_t kernel = quantize_instance<D>(p->slabs_q, wout != nullptr, p->gm, fold);
+    const bool fold = p->fold_q && out == kOutCodes;
+    const quantize_kernel_t kernel = quantize_instance<D>(p->slabs_q, out, p->gm, fold);
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(fold ? D : 2 * D / p->slabs_q), 0, st,
                        fold ? p->wfold : p->wfrag, (const uint4*)x, n,
                        (uint2*)codes, scales, (float4*)wout, p->unscale_w, p->unscale_w / 7.0f, p->gw);
@@ -1276,8 +1302,8 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
     }
 
 int dispatch_occupancy(srft_plan* p, int cus) { SRFT_DISPATCH_D(p->d, occupancy_grids, p, cus) }
-int dispatch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* c, float* s, float* w,
-                      hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_quantize, p, x, n, c, s, w, st) }
+int dispatch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* c, float* s, float* w, int out,
+                      hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_quantize, p, x, n, c, s, w, out, st) }
 int dispatch_dequantize(const srft_plan* p, const uint8_t* c, const float* s, long long n, void* o,
                         hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_dequantize, p, c, s, n, o, st) }
 
@@ -1504,7 +1530,7 @@ int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_v
     if (n_vec == 0) return SRFT_OK;
     if (!x_f16_dev || !codes_dev || !scales_dev) return SRFT_ERR_NULL;
     if (!aligned(x_f16_dev, 16) || !aligned(codes_dev, 16) || !aligned(scales_dev, 4)) return SRFT_ERR_ALIGN;
-    return dispatch_quantize(plan, x_f16_dev, n_vec, codes_dev, scales_dev, nullptr, (hipStream_t)hip_stream);
+    return dispatch_quantize(plan, x_f16_dev, n_vec, codes_dev, scales_dev, nullptr, kOutCodes, (hipStream_t)hip_stream);
 }
 
 int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, float* w_f32_dev,
@@ -1514,7 +1540,32 @@ int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t 
     if (n_vec == 0) return SRFT_OK;
     if (!x_f16_dev || !w_f32_dev) return SRFT_ERR_NULL;
     if (!aligned(x_f16_dev, 16) || !aligned(w_f32_dev, 16)) return SRFT_ERR_ALIGN;
-    return dispatch_quantize(plan, x_f16_dev, n_vec, nullptr, nullptr, w_f32_dev, (hipStream_t)hip_stream);
+    return dispatch_quantize(plan, x_f16_dev, n_vec, nullptr, nullptr, w_f32_dev, kOutRaw, (hipStream_t)hip_stream);
+}
+
+int srft_kv_channel_absmax(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, float* amax_dev,
+                           void* hip_stream) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (n_vec < 0 || n_vec > kMaxVectors) return SRFT_ERR_BAD_N;
+    if (n_vec == 0) return SRFT_OK;
+    if (!x_f16_dev || !amax_dev) return SRFT_ERR_NULL;
+    if (!aligned(x_f16_dev, 16) || !aligned(amax_dev, 4)) return SRFT_ERR_ALIGN;
+    return dispatch_quantize(plan, x_f16_dev, n_vec, nullptr, nullptr, amax_dev, kOutAmax, (hipStream_t)hip_stream);
+}
+
+int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host) {
+    if (!amax_host || !lambda_host) return SRFT_ERR_NULL;
+    if (d < 1) return SRFT_ERR_BAD_D;
+    float top = 0.0f;
+    for (int k = 0; k < d; ++k) {
+        if (!std::isfinite(amax_host[k]) || amax_host[k] < 0.0f) return SRFT_ERR_BAD_LAMBDA;
+        top = std::fmax(top, amax_host[k]);
+    }
+    // lambda_k = 1 / amax_k; channels below 2^-16 of the largest are held there, which keeps max/min of lambda
+    // within what srft_plan_create accepts; an all-zero batch gives all ones
+    const float floor_ = std::ldexp(top, -16);
+    for (int k = 0; k < d; ++k) lambda_host[k] = top > 0.0f ? 1.0f / std::fmax(amax_host[k], floor_) : 1.0f;
+    return SRFT_OK;
 }
 
 int srft_kv_dequantize(const srft_plan_t* plan, const uint8_t* codes_dev, const float* scales_dev, int64_t n_vec,

@@ -69,6 +69,19 @@ def test_null_plan_and_size_errors(L):
     assert L.srft_stream_copy(None, None, 24, None) == -7
     assert L.srft_stream_copy(None, None, 32, None) == -1
     assert L.srft_stream_copy(None, None, 0, None) == 0
+    # lambda from the calibration statistic: host only
+    amax = (C.c_float * 4)(2.0, 0.0, 1e-9, 0.5)
+    lam = (C.c_float * 4)()
+    assert L.srft_lambda_from_absmax(amax, 4, lam) == 0
+    assert list(lam) == [0.5, 2.0 ** 15, 2.0 ** 15, 2.0]
+    zero = (C.c_float * 4)()
+    assert L.srft_lambda_from_absmax(zero, 4, lam) == 0 and list(lam) == [1.0] * 4
+    assert L.srft_lambda_from_absmax(None, 4, lam) == -1 and L.srft_lambda_from_absmax(amax, 0, lam) == -2
+    amax[1] = -1.0
+    assert L.srft_lambda_from_absmax(amax, 4, lam) == -4
+    amax[1] = float("nan")
+    assert L.srft_lambda_from_absmax(amax, 4, lam) == -4
+    assert L.srft_kv_channel_absmax(None, None, 1, None, None) == -1
     # batched calls: an empty list is a no-op, a negative count or a missing array is an error
     one = (C.c_void_p * 1)(None)
     n1 = (C.c_int64 * 1)(5)
