@@ -312,6 +312,25 @@ def decode_append(B, W, torch, dev, stream, iters=200):
            "quantize_batched": timed(lambda: B.srft_kv_quantize_batched(tq, stream)),
            "dequantize_per_plan": timed(per_plan_d),
            "dequantize_batched": timed(lambda: B.srft_kv_dequantize_batched(td, stream))}
+    # the same step through the cache manager: 15 steps of 16 only copy the token into the window, the 16th also
+    # quantizes the full page of every plan and writes its reconstruction into the view (three launches)
+    R, steps = 16, 320
+    cache = B.Cache(plans, n, steps, R, device=dev)
+    new = [x[p].view(n, 1, d) for p in range(k)]
+    prepared = cache.prepare(new)                            # static buffers: the pointer table is built once
+    cache.append_prepared(prepared, stream)                  # first call outside the timed region
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps - 1):
+        cache.append_prepared(prepared, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    res["cache_manager_step"] = {"residual_tokens": R, "steps": steps - 1, "flushes": (steps // R),
+                                 "gpu_us": e0.elapsed_time(e1) / (steps - 1) * 1e3,
+                                 "wall_us": (time.perf_counter() - t0) / (steps - 1) * 1e6}
+    cache.close()
     for pl in plans:
         pl.close()
     return res

@@ -118,6 +118,42 @@ int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t 
                         float* w_f32_dev, void* hip_stream);
 
 /*
+ * Cache manager: int4 store + fp16 residual window + dequantized-prefix cache.   (Sec. 7.2: the cache class,
+ * items (i)-(iv); the "Residual window" paragraph: 16 tokens.)
+ *
+ * One cache holds n_plans (layer, K|V) plans of one shape, each with n_seq sequences (batch x kv_heads) that grow
+ * in lock-step.  All device buffers belong to the caller, one per plan, in a paged layout whose page is the
+ * residual window of R tokens:
+ *     codes_dev[p]     [capacity/R][n_seq][R][d/2]  bytes      the int4 store            (16-byte aligned)
+ *     scales_dev[p]    [capacity/R][n_seq][R][d/g]  fp32                                  (4-byte aligned)
+ *     view_f16_dev[p]  [capacity/R][n_seq][R][d]    fp16       what attention reads       (16-byte aligned)
+ * Token j of sequence q is at page j / R, slot j % R.  In the view, tokens below srft_cache_quantized_tokens() hold
+ * what the store decodes to (the dequantized prefix, written once when their page is flushed, never again: an
+ * update costs O(1) in the prefix length); tokens from there up to srft_cache_tokens() are the residual window,
+ * exact fp16 copies of what was appended.  The store holds the quantized tokens only.
+ *
+ * srft_cache_create   records the geometry and the pointers (host arrays of n_plans entries, copied); no HIP
+ *                     calls.  capacity_tokens must be a positive multiple of residual_tokens (>= 1).
+ * srft_cache_append   new_f16_dev: host array of n_plans device pointers, each [n_seq, t, d] fp16 (16-byte
+ *                     aligned): t new tokens per sequence.  Enqueues: a copy of the tokens into the view; then, if
+ *                     one or more pages became full, ONE batched quantize of those pages over all plans and one
+ *                     batched dequantize of them back into the view.  Exceeding the capacity is SRFT_ERR_BAD_N
+ *                     (nothing is enqueued).  The result does not depend on how the tokens are split into calls.
+ * srft_cache_rebuild_view  dequantizes the whole store into the view again (for a caller that dropped or
+ *                     overwrote the view); O(prefix).  The window part of the view is not touched.
+ * Calls on one cache must be made from one thread at a time and enqueued on one stream (or ordered by the caller).
+ */
+typedef struct srft_cache srft_cache_t;
+int srft_cache_create(srft_cache_t** out, const srft_plan_t* const* plans, int n_plans, int n_seq,
+                      int64_t capacity_tokens, int residual_tokens, uint8_t* const* codes_dev,
+                      float* const* scales_dev, void* const* view_f16_dev);
+int srft_cache_destroy(srft_cache_t* cache);     /* NULL is accepted; the buffers stay the caller's */
+int srft_cache_append(srft_cache_t* cache, const void* const* new_f16_dev, int t, void* hip_stream);
+int srft_cache_rebuild_view(srft_cache_t* cache, void* hip_stream);
+int64_t srft_cache_tokens(const srft_cache_t* cache);              /* tokens per sequence, or a negative status */
+int64_t srft_cache_quantized_tokens(const srft_cache_t* cache);    /* of which in the int4 store */
+
+/*
  * Calibration statistic for lambda: per-channel abs-max of the transform output over a batch.  (Sec. 7.1: "lambda_d =
  * 1 / per_channel_max(SRFT output)_d"; Sec. 7.2, the static "window-uniform" calibration over whole windows.)
  *   x_f16_dev  [n_vec, d] fp16, 16-byte aligned.                                         read only

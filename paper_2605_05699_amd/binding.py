@@ -24,6 +24,8 @@ EXPORTS = [
     "srft_stream_copy", "srft_stream_mix", "srft_status_string", "srft_last_hip_error",
     "srft_kv_quantize_batched", "srft_kv_dequantize_batched",
     "srft_kv_channel_absmax", "srft_lambda_from_absmax",
+    "srft_cache_create", "srft_cache_destroy", "srft_cache_append", "srft_cache_rebuild_view",
+    "srft_cache_tokens", "srft_cache_quantized_tokens",
 ]
 
 
@@ -52,6 +54,12 @@ def lib() -> C.CDLL:
     L.srft_kv_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
     L.srft_kv_dequantize.argtypes = [vp, vp, vp, i64, vp, vp]
     L.srft_kv_forward_f32.argtypes = [vp, vp, i64, vp, vp]
+    L.srft_cache_create.argtypes = [C.POINTER(vp), vp, ci, ci, i64, ci, vp, vp, vp]
+    L.srft_cache_destroy.argtypes = [vp]
+    L.srft_cache_append.argtypes = [vp, vp, ci, vp]
+    L.srft_cache_rebuild_view.argtypes = [vp, vp]
+    L.srft_cache_tokens.argtypes = [vp]
+    L.srft_cache_quantized_tokens.argtypes = [vp]
     L.srft_kv_channel_absmax.argtypes = [vp, vp, i64, vp, vp]
     L.srft_lambda_from_absmax.argtypes = [vp, ci, vp]
     L.srft_kv_quantize_batched.argtypes = [vp, vp, vp, vp, vp, ci, vp]
@@ -68,6 +76,8 @@ def lib() -> C.CDLL:
     for name in EXPORTS:
         if name != "srft_status_string":
             getattr(L, name).restype = ci
+    L.srft_cache_tokens.restype = i64
+    L.srft_cache_quantized_tokens.restype = i64
     _lib = L
     return L
 
@@ -215,6 +225,77 @@ def srft_stream_mix(src: torch.Tensor, dst: torch.Tensor, n_tiles: int, read_byt
     assert dst.numel() * dst.element_size() >= n_tiles * write_bytes
     _check(lib().srft_stream_mix(src.data_ptr(), dst.data_ptr(), n_tiles, read_bytes, write_bytes, workgroups,
                                  _stream_handle(stream)), "srft_stream_mix")
+
+
+class Cache:
+    """The library's cache manager over torch-owned buffers (marshalling only): per plan an int4 store, its scales
+    and the fp16 view, each paged as [capacity / R][n_seq][R][...]."""
+
+    def __init__(self, plans, n_seq: int, capacity_tokens: int, residual_tokens: int = 16, device="cuda"):
+        self.plans = list(plans)
+        d, G = self.plans[0].d, self.plans[0].groups
+        self.n_seq, self.R, self.capacity, self.d = n_seq, residual_tokens, capacity_tokens, d
+        if capacity_tokens < 1 or residual_tokens < 1 or capacity_tokens % residual_tokens:
+            raise ValueError("capacity must be a positive multiple of the residual window")
+        pages = capacity_tokens // residual_tokens
+        k = len(self.plans)
+        self.codes = [torch.zeros(pages, n_seq, residual_tokens, d // 2, dtype=torch.uint8, device=device) for _ in range(k)]
+        self.scales = [torch.zeros(pages, n_seq, residual_tokens, G, dtype=torch.float32, device=device) for _ in range(k)]
+        self.view = [torch.zeros(pages, n_seq, residual_tokens, d, dtype=torch.float16, device=device) for _ in range(k)]
+        handle = C.c_void_p()
+        _check(lib().srft_cache_create(
+            C.byref(handle), (C.c_void_p * k)(*[int(p.handle) for p in self.plans]), k, n_seq, capacity_tokens,
+            residual_tokens, (C.c_void_p * k)(*[t.data_ptr() for t in self.codes]),
+            (C.c_void_p * k)(*[t.data_ptr() for t in self.scales]),
+            (C.c_void_p * k)(*[t.data_ptr() for t in self.view])), "srft_cache_create")
+        self.handle = handle.value
+
+    def append(self, new, stream=None) -> None:
+        """new: one [n_seq, t, d] fp16 device tensor per plan (all with the same t)."""
+        k = len(self.plans)
+        if len(new) != k:
+            raise ValueError("one tensor of new tokens per plan")
+        t = new[0].shape[1]
+        for x in new:
+            if x.shape != (self.n_seq, t, self.d):
+                raise ValueError("new tokens must be [n_seq, t, d]")
+        ptrs = (C.c_void_p * k)(*[_dev_ptr(x, torch.float16, "new") if t else 0 for x in new])
+        _check(lib().srft_cache_append(self.handle, ptrs, t, _stream_handle(stream)), "srft_cache_append")
+
+    def prepare(self, new):
+        """Pointer table for tensors that will be appended again and again from the same addresses (a decode
+        loop with static buffers): pass it to ``append_prepared``."""
+        t = new[0].shape[1]
+        for x in new:
+            if x.shape != (self.n_seq, t, self.d):
+                raise ValueError("new tokens must be [n_seq, t, d]")
+        return (C.c_void_p * len(new))(*[_dev_ptr(x, torch.float16, "new") for x in new]), t, list(new)
+
+    def append_prepared(self, prepared, stream=None) -> None:
+        _check(lib().srft_cache_append(self.handle, prepared[0], prepared[1], _stream_handle(stream)),
+               "srft_cache_append")
+
+    def rebuild_view(self, stream=None) -> None:
+        _check(lib().srft_cache_rebuild_view(self.handle, _stream_handle(stream)), "srft_cache_rebuild_view")
+
+    @property
+    def tokens(self) -> int:
+        return lib().srft_cache_tokens(self.handle)
+
+    @property
+    def quantized_tokens(self) -> int:
+        return lib().srft_cache_quantized_tokens(self.handle)
+
+    def close(self) -> None:
+        if self.handle:
+            _check(lib().srft_cache_destroy(self.handle), "srft_cache_destroy")
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 # ---------------------------------------------------------------------------- convenience wrapper

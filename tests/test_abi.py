@@ -82,6 +82,17 @@ def test_null_plan_and_size_errors(L):
     amax[1] = float("nan")
     assert L.srft_lambda_from_absmax(amax, 4, lam) == -4
     assert L.srft_kv_channel_absmax(None, None, 1, None, None) == -1
+    # cache manager: argument checks need no GPU (and no plan: a NULL plan entry is caught first)
+    h = C.c_void_p()
+    one = (C.c_void_p * 1)(None)
+    assert L.srft_cache_create(None, one, 1, 1, 16, 16, one, one, one) == -1
+    assert L.srft_cache_create(C.byref(h), None, 1, 1, 16, 16, one, one, one) == -1
+    for bad in ((0, 1, 16, 16), (1, 0, 16, 16), (1, 1, 16, 0), (1, 1, 8, 16), (1, 1, 24, 16), (1, 1, 0, 16)):
+        assert L.srft_cache_create(C.byref(h), one, bad[0], bad[1], bad[2], bad[3], one, one, one) == -7, bad
+    assert L.srft_cache_create(C.byref(h), one, 1, 1, 16, 16, one, one, one) == -1 and h.value is None
+    assert L.srft_cache_destroy(None) == 0
+    assert L.srft_cache_append(None, None, 1, None) == -1 and L.srft_cache_rebuild_view(None, None) == -1
+    assert L.srft_cache_tokens(None) == -1 and L.srft_cache_quantized_tokens(None) == -1
     # batched calls: an empty list is a no-op, a negative count or a missing array is an error
     one = (C.c_void_p * 1)(None)
     n1 = (C.c_int64 * 1)(5)
