@@ -219,17 +219,17 @@ def unpack_nibbles(b: np.ndarray) -> np.ndarray:
     return q
 
 
-def record_bytes(d: int, g: int) -> int:
-    """Stored bytes per vector: d/2 code bytes + one fp32 scale per group of g."""
+def record_bytes(d: int, g: int, bits: int = 4) -> int:
+    """Stored bytes per vector: d/2 code bytes (d at 8 bits) + one fp32 scale per group of g."""
     if d % 2 or d % g:
         raise ValueError("d must be even and divisible by g")
-    return d // 2 + 4 * (d // g)
+    return d * bits // 8 + 4 * (d // g)
 
 
 # --------------------------------------------------------------------------
 # write path / read path
 # --------------------------------------------------------------------------
-def quantize(x_f16, s, lam, g: int, form: str = "dense") -> dict:
+def quantize(x_f16, s, lam, g: int, form: str = "dense", bits: int = 4) -> dict:
     """Write path for x_f16 of shape [n, d] (fp16 values).
 
     1. u = s * x                      (Sec. 3.2 step 1)
@@ -243,7 +243,13 @@ def quantize(x_f16, s, lam, g: int, form: str = "dense") -> dict:
 
     Returns codes [n, d/2] uint8, scales [n, d/g] float32, and for the parity
     tests q [n, d] int8, the pre-rounding ratios r [n, d] and w [n, d].
+
+    bits = 8 is the paper's other output width (Sec. 3.2 steps 3-4 with b = 8): scale = a / 127, codes in
+    [-127, 127], "one byte per value" (two's complement), codes [n, d] uint8.
     """
+    if bits not in (4, 8):
+        raise ValueError("bits must be 4 or 8")
+    qmax = 2 ** (bits - 1) - 1
     x = np.asarray(x_f16).astype(np.float64)
     n, d = x.shape
     if d % g:
@@ -253,14 +259,14 @@ def quantize(x_f16, s, lam, g: int, form: str = "dense") -> dict:
     w = z * lam
     wg = w.reshape(n, d // g, g)
     a = np.abs(wg).max(axis=-1)
-    scales = (a / QMAX).astype(np.float32)
+    scales = (a / qmax).astype(np.float32)
     sc = scales.astype(np.float64)[..., None]
     safe = np.where(sc > 0, sc, 1.0)
     r = np.where(sc > 0, wg / safe, 0.0)
-    q = np.clip(np.rint(r), -QMAX, QMAX).astype(np.int8)
+    q = np.clip(np.rint(r), -qmax, qmax).astype(np.int8)
     q = q.reshape(n, d)
     return {
-        "codes": pack_nibbles(q),
+        "codes": pack_nibbles(q) if bits == 4 else q.view(np.uint8).copy(),
         "scales": scales,
         "q": q,
         "r": r.reshape(n, d),
@@ -268,9 +274,12 @@ def quantize(x_f16, s, lam, g: int, form: str = "dense") -> dict:
     }
 
 
-def dequantize_f64(codes, scales, s, lam, g: int, form: str = "dense") -> np.ndarray:
+def dequantize_f64(codes, scales, s, lam, g: int, form: str = "dense", bits: int = 4) -> np.ndarray:
     """Read path up to, not including, the final fp16 rounding.  Returns [n, d] float64."""
-    q = unpack_nibbles(codes).astype(np.float64)
+    if bits == 4:
+        q = unpack_nibbles(codes).astype(np.float64)
+    else:                                        # one byte per value, two's complement
+        q = np.asarray(codes, dtype=np.uint8).view(np.int8).astype(np.float64)
     n, d = q.shape
     sc = np.asarray(scales, dtype=np.float32).astype(np.float64)
     w = (q.reshape(n, d // g, g) * sc[..., None]).reshape(n, d)
@@ -279,9 +288,9 @@ def dequantize_f64(codes, scales, s, lam, g: int, form: str = "dense") -> np.nda
     return srft_inverse(z, s, form=form)
 
 
-def dequantize(codes, scales, s, lam, g: int, form: str = "dense") -> np.ndarray:
+def dequantize(codes, scales, s, lam, g: int, form: str = "dense", bits: int = 4) -> np.ndarray:
     """Read path: unpack, times scale, / max(lambda, 1e-6), inverse SRFT, unsign, fp16 (RNE)."""
-    return dequantize_f64(codes, scales, s, lam, g, form=form).astype(np.float16)
+    return dequantize_f64(codes, scales, s, lam, g, form=form, bits=bits).astype(np.float16)
 
 
 def channel_absmax(x_f16, s, lam=None, running=None) -> np.ndarray:

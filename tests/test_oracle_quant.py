@@ -276,3 +276,63 @@ def test_lambda_from_absmax_normalises_every_channel_to_one():
     a = np.array([2.0, 0.0, 1e-9, 0.5])
     assert np.allclose(O.lambda_from_absmax(a), [0.5, 2.0 ** 15, 2.0 ** 15, 2.0])
     assert np.array_equal(O.lambda_from_absmax(np.zeros(8)), np.ones(8))
+
+
+# ----------------------------------------------------------------------------- 8-bit output (Sec. 3.2, b = 8)
+def test_int8_quantizer_properties_and_record():
+    d, g, n = 64, 32, 300
+    rng = np.random.RandomState(8)
+    x = rng.standard_normal((n, d)).astype(np.float16)
+    s = O.signs_from_seed(4, d)
+    lam = np.exp(0.3 * rng.standard_normal(d)).astype(np.float32)
+    q8 = O.quantize(x, s, lam, g, bits=8)
+    q4 = O.quantize(x, s, lam, g, bits=4)
+    assert q8["codes"].shape == (n, d) and q8["codes"].dtype == np.uint8      # one byte per value
+    assert np.array_equal(q8["codes"].view(np.int8), q8["q"])                 # two's complement
+    assert q8["q"].min() >= -127 and q8["q"].max() <= 127
+    assert np.array_equal(q8["w"], q4["w"])                                   # same transform, other quantizer
+    # scale = abs-max / (2^(b-1) - 1): the 4-bit and 8-bit scales differ by 127 / 7
+    assert np.allclose(q8["scales"].astype(np.float64) * 127, q4["scales"].astype(np.float64) * 7, rtol=3e-7)
+    sc = np.repeat(q8["scales"].astype(np.float64), g, axis=1)
+    assert np.all(np.abs(q8["q"] * sc - q8["w"]) <= 0.5 * sc * (1 + 1e-12))
+    assert np.all(np.abs(q8["q"]).reshape(n, d // g, g).max(axis=-1) == 127)  # the abs-max element hits the top code
+    # read path: reconstruction error is the 4-bit one shrunk by about 127 / 7
+    e8 = np.linalg.norm(O.dequantize_f64(q8["codes"], q8["scales"], s, lam, g, bits=8) - x.astype(np.float64))
+    e4 = np.linalg.norm(O.dequantize_f64(q4["codes"], q4["scales"], s, lam, g) - x.astype(np.float64))
+    assert 12 < e4 / e8 < 25
+    # stored bytes: d + 4 d / g; per token (g = d): (2d) / (d + 4) against fp16
+    assert O.record_bytes(128, 32, bits=8) == 144 and O.record_bytes(64, 64, bits=8) == 68
+    with pytest.raises(ValueError):
+        O.quantize(x, s, lam, g, bits=5)
+
+
+def test_int8_near_ties_and_per_token_case():
+    # coefficients chosen directly (x = Q^T w, lambda = 1, one group): abs-max 127 -> scale 1; values a hair either
+    # side of a tie must round away from / towards it (exact ties cannot be produced through the transform)
+    d = 32
+    s = np.ones(d, dtype=np.int8)
+    lam = np.ones(d, dtype=np.float32)
+    Q = O.srft_matrix(d)
+    w = np.zeros(d)
+    w[:7] = [127, 0.5, 1.5, 2.5, -0.5, -1.5, 126.5]
+    up, down = w.copy(), w.copy()
+    up[1:7] += 1e-9 * np.sign(w[1:7])
+    down[1:7] -= 1e-9 * np.sign(w[1:7])
+    q_up = O.quantize((Q.T @ up)[None, :], s, lam, d, bits=8)
+    q_down = O.quantize((Q.T @ down)[None, :], s, lam, d, bits=8)
+    assert q_up["scales"][0, 0] == np.float32(1.0)
+    assert list(q_up["q"][0, :7]) == [127, 1, 2, 3, -1, -2, 127]
+    assert list(q_down["q"][0, :7]) == [127, 0, 1, 2, 0, -1, 126]
+    # per-token special case against numpy's rfft written out (Sec. 3.2 steps 3-4 with b = 8)
+    x = W.gaussian_with_outliers(40, d, seed=3)
+    s = O.signs_from_seed(6, d)
+    out = O.quantize(x, s, lam, d, bits=8)
+    z = np.fft.rfft(x.astype(np.float64) * s, norm="ortho", axis=-1)
+    h = d // 2
+    zz = np.concatenate([z[:, :1].real, math.sqrt(2) * z[:, 1:h].real, z[:, h:h + 1].real,
+                         math.sqrt(2) * z[:, 1:h].imag], axis=1)
+    scale = (np.abs(zz).max(1) / (2 ** 7 - 1)).astype(np.float32)
+    assert np.array_equal(out["scales"][:, 0], scale)
+    ratio = zz / scale.astype(np.float64)[:, None]
+    near_tie = np.abs(np.abs(ratio % 1.0) - 0.5) < 1e-9
+    assert np.array_equal(out["q"][~near_tie], np.rint(ratio)[~near_tie].astype(np.int8))
