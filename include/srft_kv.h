@@ -47,7 +47,8 @@ typedef enum srft_status {
     SRFT_ERR_ALIGN      = -5,   /* a device pointer is not aligned as documented */
     SRFT_ERR_HIP        = -6,   /* a HIP call failed; see srft_last_hip_error() */
     SRFT_ERR_BAD_N      = -7,   /* n_vec < 0, count < 0 or byte count negative */
-    SRFT_ERR_MISMATCH   = -8    /* plans of one batched call differ in d, group_size or device */
+    SRFT_ERR_MISMATCH   = -8,   /* plans of one call differ in d, group_size, code width or device */
+    SRFT_ERR_BAD_BITS   = -9    /* code width not 4 or 8 */
 } srft_status;
 
 /*
@@ -63,13 +64,23 @@ typedef enum srft_status {
 int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_seed,
                      const float* lambda_host);
 
+/*
+ * The same with a chosen code width.                                   (Sec. 3.2 steps 3-4: b in {4, 8})
+ *   bits = 4   the format above (srft_plan_create is this case).
+ *   bits = 8   scale_j = max |w_k| / 127, q_k = rint(w_k / scale_j) in [-127, 127], one two's-complement byte per
+ *              value: codes are [n_vec, d] bytes, byte k = q_k; the record is d + 4 d/g bytes.  Every entry point
+ *              that takes codes then takes this layout (srft_plan_code_bytes tells the row size).
+ */
+int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, uint64_t sign_seed,
+                          const float* lambda_host);
+
 /* Free the plan and its device tables.  NULL is accepted.  Work already enqueued must have finished. */
 int srft_plan_destroy(srft_plan_t* plan);
 
 /*
  * Write path over n_vec vectors.                                        (Sec. 3.2 steps 1-4, Sec. 7.1)
  *   x_f16_dev   [n_vec, d] row-major IEEE fp16, 16-byte aligned.        read only
- *   codes_dev   [n_vec, d/2] bytes, 16-byte aligned.                    written
+ *   codes_dev   [n_vec, d/2] bytes ([n_vec, d] for an 8-bit plan), 16-byte aligned.   written
  *   scales_dev  [n_vec, d/g] fp32, 4-byte aligned.                      written
  * n_vec == 0 is a successful no-op.  Inputs must be finite.  A group whose abs-max / 7 is below
  * 2^-100 is stored as scale 0 with all-zero codes.
@@ -79,10 +90,10 @@ int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_v
 
 /*
  * Read path over n_vec vectors: the inverse of srft_kv_quantize.        (Sec. 7.1; sentence after Eq. 2)
- *   codes_dev   [n_vec, d/2] bytes, 16-byte aligned.                    read only
+ *   codes_dev   [n_vec, d/2] bytes ([n_vec, d] for an 8-bit plan), 16-byte aligned.   read only
  *   scales_dev  [n_vec, d/g] fp32, 4-byte aligned.                      read only
  *   out_f16_dev [n_vec, d] fp16 (round to nearest even), 16-byte aligned.  written
- * Nibble 0x8 decodes as -8.
+ * Nibble 0x8 decodes as -8 (byte 0x80 as -128 at 8 bits).
  */
 int srft_kv_dequantize(const srft_plan_t* plan, const uint8_t* codes_dev, const float* scales_dev,
                        int64_t n_vec, void* out_f16_dev, void* hip_stream);
@@ -124,7 +135,7 @@ int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t 
  * One cache holds n_plans (layer, K|V) plans of one shape, each with n_seq sequences (batch x kv_heads) that grow
  * in lock-step.  All device buffers belong to the caller, one per plan, in a paged layout whose page is the
  * residual window of R tokens:
- *     codes_dev[p]     [capacity/R][n_seq][R][d/2]  bytes      the int4 store            (16-byte aligned)
+ *     codes_dev[p]     [capacity/R][n_seq][R][d/2]  bytes      the int4 store ([..][d] at 8 bits)  (16-byte aligned)
  *     scales_dev[p]    [capacity/R][n_seq][R][d/g]  fp32                                  (4-byte aligned)
  *     view_f16_dev[p]  [capacity/R][n_seq][R][d]    fp16       what attention reads       (16-byte aligned)
  * Token j of sequence q is at page j / R, slot j % R.  In the view, tokens below srft_cache_quantized_tokens() hold
@@ -178,7 +189,8 @@ int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host);
 int srft_plan_d(const srft_plan_t* plan);             /* d, or a negative status */
 int srft_plan_group_size(const srft_plan_t* plan);    /* g */
 int srft_plan_groups(const srft_plan_t* plan);        /* d / g: scales per vector */
-int srft_plan_code_bytes(const srft_plan_t* plan);    /* d / 2: code bytes per vector */
+int srft_plan_code_bytes(const srft_plan_t* plan);    /* code bytes per vector: d / 2 at 4 bits, d at 8 */
+int srft_plan_bits(const srft_plan_t* plan);          /* 4 or 8 */
 int srft_plan_get_signs(const srft_plan_t* plan, int8_t* out_host /* d entries, each -1 or +1 */);
 
 /*

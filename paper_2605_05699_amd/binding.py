@@ -26,6 +26,7 @@ EXPORTS = [
     "srft_kv_channel_absmax", "srft_lambda_from_absmax",
     "srft_cache_create", "srft_cache_destroy", "srft_cache_append", "srft_cache_rebuild_view",
     "srft_cache_tokens", "srft_cache_quantized_tokens",
+    "srft_plan_create_bits", "srft_plan_bits",
 ]
 
 
@@ -50,6 +51,8 @@ def lib() -> C.CDLL:
     L = C.CDLL(LIB_PATH)
     vp, i64, u64, ci = C.c_void_p, C.c_int64, C.c_uint64, C.c_int
     L.srft_plan_create.argtypes = [C.POINTER(vp), ci, ci, u64, vp]
+    L.srft_plan_create_bits.argtypes = [C.POINTER(vp), ci, ci, ci, u64, vp]
+    L.srft_plan_bits.argtypes = [vp]
     L.srft_plan_destroy.argtypes = [vp]
     L.srft_kv_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
     L.srft_kv_dequantize.argtypes = [vp, vp, vp, i64, vp, vp]
@@ -102,7 +105,7 @@ def _dev_ptr(t: torch.Tensor, dtype, name: str) -> int:
 
 
 # ---------------------------------------------------------------------------- C entry points
-def srft_plan_create(d: int, group_size: int, sign_seed: int, lam=None) -> int:
+def srft_plan_create(d: int, group_size: int, sign_seed: int, lam=None, bits: int = 4) -> int:
     """Returns the opaque plan handle.  ``lam``: d positive floats (host) or None for all ones."""
     handle = C.c_void_p()
     lam_ptr = None
@@ -111,8 +114,12 @@ def srft_plan_create(d: int, group_size: int, sign_seed: int, lam=None) -> int:
         if lam_arr.shape != (d,):
             raise ValueError("lambda must have d entries")
         lam_ptr = lam_arr.ctypes.data_as(C.c_void_p)
-    _check(lib().srft_plan_create(C.byref(handle), d, group_size, sign_seed & (2 ** 64 - 1), lam_ptr),
-           "srft_plan_create")
+    if bits == 4:
+        _check(lib().srft_plan_create(C.byref(handle), d, group_size, sign_seed & (2 ** 64 - 1), lam_ptr),
+               "srft_plan_create")
+    else:
+        _check(lib().srft_plan_create_bits(C.byref(handle), d, group_size, bits, sign_seed & (2 ** 64 - 1), lam_ptr),
+               "srft_plan_create_bits")
     return handle.value
 
 
@@ -239,7 +246,8 @@ class Cache:
             raise ValueError("capacity must be a positive multiple of the residual window")
         pages = capacity_tokens // residual_tokens
         k = len(self.plans)
-        self.codes = [torch.zeros(pages, n_seq, residual_tokens, d // 2, dtype=torch.uint8, device=device) for _ in range(k)]
+        cb = self.plans[0].code_bytes
+        self.codes = [torch.zeros(pages, n_seq, residual_tokens, cb, dtype=torch.uint8, device=device) for _ in range(k)]
         self.scales = [torch.zeros(pages, n_seq, residual_tokens, G, dtype=torch.float32, device=device) for _ in range(k)]
         self.view = [torch.zeros(pages, n_seq, residual_tokens, d, dtype=torch.float16, device=device) for _ in range(k)]
         handle = C.c_void_p()
@@ -302,9 +310,9 @@ class Cache:
 class Plan:
     """One (layer, K|V) plan.  Allocates outputs with torch when none are passed; computes nothing itself."""
 
-    def __init__(self, d: int, group_size: int = 32, sign_seed: int = 0, lam=None):
-        self.handle = srft_plan_create(d, group_size, sign_seed, lam)
-        self.d, self.g = d, group_size
+    def __init__(self, d: int, group_size: int = 32, sign_seed: int = 0, lam=None, bits: int = 4):
+        self.handle = srft_plan_create(d, group_size, sign_seed, lam, bits)
+        self.d, self.g, self.bits = d, group_size, bits
         self.groups = lib().srft_plan_groups(self.handle)
         self.code_bytes = lib().srft_plan_code_bytes(self.handle)
 

@@ -105,6 +105,17 @@ __device__ __forceinline__ uint32_t pack8(const floatx16& acc, int base, float i
     return (p - k) ^ 0x88888888u;
 }
 
+// Four values already multiplied by 1/scale -> four two's-complement bytes in one dword (8-bit output).
+// Adding 1.5 * 2^23 rounds to nearest-even and leaves q mod 256 in the low byte of the bit pattern.
+__device__ __forceinline__ uint32_t pack4_bytes(const floatx16& acc, int base, float inv) {
+    constexpr float kMagic = 12582912.0f;
+    const uint32_t a = __float_as_uint(fmaf(acc[base], inv, kMagic)), b = __float_as_uint(fmaf(acc[base + 1], inv, kMagic));
+    const uint32_t c = __float_as_uint(fmaf(acc[base + 2], inv, kMagic)), d = __float_as_uint(fmaf(acc[base + 3], inv, kMagic));
+    const uint32_t lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);       // byte 0 of a, byte 0 of b, 0, 0
+    const uint32_t hi = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+    return (hi << 16) | lo;
+}
+
 // ------------------------------------------------------------------------------------------
 // Both kernels are software pipelines over the tiles T_0, T_1, ... of a workgroup (T_k = blockIdx +
 // k * gridDim).  Stage k starts with the only barrier of the stage and then, in ONE straight-line
@@ -142,7 +153,8 @@ __device__ __forceinline__ uint32_t pack8(const floatx16& acc, int base, float i
 enum { kGroup16 = 0, kGroup32 = 1, kGroupWide = 2 };
 enum { kOutCodes = 0, kOutRaw = 1, kOutAmax = 2 };
 // The work of one workgroup: tiles t0, t0 + stride, ... of one plan's n_vec vectors (t0 < number of tiles).
-template <int D, int S, int OUT, int GM>
+// BITS  : 4 (two nibbles per byte) or 8 (one byte per value, scale = abs-max / 127; Sec. 3.2 steps 3-4)
+template <int D, int S, int OUT, int GM, int BITS>
 __device__ __forceinline__ void
 srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
                     uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
@@ -266,10 +278,16 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
                 float scale = mm[s] * scale_mul;             // scale_mul = fl(2^-e / 7): abs-max / 7
                 float inv = unscale * __builtin_amdgcn_rcpf(scale);
                 if (!(scale >= kMinScale)) { scale = 0.0f; inv = 0.0f; }
-                uint2 packed;
-                packed.x = pack8(acc, 0, inv);
-                packed.y = pack8(acc, 8, inv);
-                (codes + row0 * (D / 16))[(unsigned)(c * (D / 16) + 2 * slab + half)] = packed;
+                if constexpr (BITS == 8) {       // 16 bytes per lane; a row is D / 16 such units
+                    const uint4 packed = make_uint4(pack4_bytes(acc, 0, inv), pack4_bytes(acc, 4, inv),
+                                                    pack4_bytes(acc, 8, inv), pack4_bytes(acc, 12, inv));
+                    (reinterpret_cast<uint4*>(codes) + row0 * (D / 16))[(unsigned)(c * (D / 16) + 2 * slab + half)] = packed;
+                } else {
+                    uint2 packed;
+                    packed.x = pack8(acc, 0, inv);
+                    packed.y = pack8(acc, 8, inv);
+                    (codes + row0 * (D / 16))[(unsigned)(c * (D / 16) + 2 * slab + half)] = packed;
+                }
                 // lanes that hold the same group store the same value to the same place
                 if constexpr (GM == kGroup16) (scales + row0 * (2 * G))[(unsigned)(c * (2 * G) + 2 * slab + half)] = scale;
                 else if constexpr (GM == kGroup32) (scales + row0 * G)[(unsigned)(c * G + slab)] = scale;
@@ -330,12 +348,12 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
     }
 }
 
-template <int D, int S, int OUT, int GM>
+template <int D, int S, int OUT, int GM, int BITS>
 __global__ void __launch_bounds__(2 * D / S)
 srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ x, long long n_vec,
                      uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__ wout,
                      float unscale, float scale_mul, int gw) {
-    srft_quantize_tiles<D, S, OUT, GM>(wfrag, x, n_vec, codes, scales, wout, unscale, scale_mul, gw, blockIdx.x,
+    srft_quantize_tiles<D, S, OUT, GM, BITS>(wfrag, x, n_vec, codes, scales, wout, unscale, scale_mul, gw, blockIdx.x,
                                        gridDim.x);       // the grid never exceeds the number of tiles
 }
 
@@ -641,12 +659,13 @@ __device__ __forceinline__ int srft_segment_of_block(const srft_batch_args& a, i
     return i;
 }
 
-template <int D, int S, int GM>
+template <int D, int S, int GM, int BITS>
 __global__ void __launch_bounds__(2 * D / S)
 srft_quantize_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
-    srft_quantize_tiles<D, S, kOutCodes, GM>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
-                                         (float*)a.out1[i], nullptr, a.unscale[i], a.unscale[i] / 7.0f, gw,
+    srft_quantize_tiles<D, S, kOutCodes, GM, BITS>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
+                                         (float*)a.out1[i], nullptr, a.unscale[i],
+                                         a.unscale[i] / (BITS == 8 ? 127.0f : 7.0f), gw,
                                          blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i]);
 }
 
@@ -681,6 +700,18 @@ __device__ __forceinline__ uint4 decode8(uint32_t v) {
     o.y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, and_or(v, 0x00F000F0u, one_k)) * sixteenth - bias16);
     o.z = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, and_or(w, 0x000F000Fu, one_k)) - bias);
     o.w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, and_or(w, 0x00F000F0u, one_k)) * sixteenth - bias16);
+    return o;
+}
+
+// One dword of four two's-complement bytes -> four exact fp16 codes as the packed pairs (b0, b2) and (b1, b3):
+// flipping bit 7 gives u = q + 128 in 0..255, 0x6400 | u is 1024 + u, minus 1152 is q.
+__device__ __forceinline__ uint2 decode4_bytes(uint32_t v) {
+    v ^= 0x80808080u;
+    const half2v bias = {(_Float16)1152.0f, (_Float16)1152.0f};
+    const uint32_t one_k = 0x64006400u;
+    uint2 o;
+    o.x = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, and_or(v, 0x00FF00FFu, one_k)) - bias);
+    o.y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, and_or(v >> 8, 0x00FF00FFu, one_k)) - bias);
     return o;
 }
 
@@ -719,9 +750,11 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
 //     group of 32 codes one k-step of 16 even and one of 16 odd codes), rows scaled by s_n on the host;
 //     the relative sign s_n s_{n+d/2} is applied to the packed fp16 bits.  rfrag is then
 //     [D/64 waves][A, B][D/32 groups][hi, lo][64 lanes], followed by [D/64 waves][64 lanes][2] sign masks.
-template <int D, int S, int KS, bool FOLD>
+// BITS: 4, or 8 (one two's-complement byte per code).  A "code unit" is 16 codes: 8 bytes at 4 bits, 16 at 8.
+//     At 8 bits a dword gives the pairs (b0, b2) and (b1, b3): again even and odd p apart, so FOLD applies as is.
+template <int D, int S, int KS, bool FOLD, int BITS>
 __device__ __forceinline__ void
-srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
+srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes_raw,
                       const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                       float unscale, int gw, const int t0, const int stride) {
     constexpr int G = FOLD ? D / 32 : D / 32 * (2 / KS);  // groups per vector as contracted
@@ -731,7 +764,9 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     static_assert(!FOLD || (S == 2 && KS == 1 && D % 64 == 0), "the folded form pairs an A and a B slab");
     constexpr int U = D / 8;             // 16-byte units per decoded row (D fp16)
     constexpr int ROW = U + 1;
-    constexpr int C = D / 16;            // 8-byte code units per row
+    constexpr int C = D / 16;            // code units (16 codes) per row
+    using CodeUnit = std::conditional_t<BITS == 8, uint4, uint2>;
+    const CodeUnit* __restrict__ codes = reinterpret_cast<const CodeUnit*>(codes_raw);
     constexpr int NT = 2 * D / S;
     constexpr int SROW = NSMAX + 1;      // padded row of the scale tile (floats)
     constexpr int PS = (32 * NSMAX + NT - 1) / NT;      // scale floats a thread may have to carry (1 or 2)
@@ -774,7 +809,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     // PS floats of the 32 x ns scale tile (float e = tid + i * NT; past the end it re-reads the last one)
     // Addresses are a uniform tile base (scalar registers) plus a 32-bit per-lane offset; rows past the end
     // alias to the last row through `lim`, the index of the last valid row of the tile (uniform).
-    auto fetch1 = [&](uint2& v, int i, const uint2* tile_base, int lim) __attribute__((always_inline)) {
+    auto fetch1 = [&](CodeUnit& v, int i, const CodeUnit* tile_base, int lim) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / C, c = u % C;
         v = tile_base[(unsigned)(min(r, lim) * C + c)];
     };
@@ -784,33 +819,44 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         const int r = e / ns, j = e % ns;
         sc = tile_base[(unsigned)(min(r, lim) * ns + j)];
     };
-    auto fetch = [&](uint2& c0, uint2& c1, float& s0, float& s1, int tile) __attribute__((always_inline)) {
+    auto fetch = [&](CodeUnit& c0, CodeUnit& c1, float& s0, float& s1, int tile) __attribute__((always_inline)) {
         if (tile > n_tiles - 1) tile = n_tiles - 1;
         const long long row0 = (long long)tile * kTileVecs;
         const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
-        const uint2* code_base = codes + row0 * C;
+        const CodeUnit* code_base = codes + row0 * C;
         const float* scale_base = scales + row0 * ns;
         fetch1(c0, 0, code_base, lim);
         if constexpr (S > 1) fetch1(c1, 1, code_base, lim);
         fetch_scale(s0, 0, scale_base, lim);
         if constexpr (PS > 1) fetch_scale(s1, 1, scale_base, lim);
     };
-    auto put1 = [&](int b, const uint2& v, int i) __attribute__((always_inline)) {
+    auto put1 = [&](int b, const CodeUnit& v, int i) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / C, c = u % C;
-        const uint4 lo = decode8(v.x), hi = decode8(v.y);
-        if constexpr (FOLD) {                    // .x .z hold the even, .y .w the odd nibbles of a dword
-            dec[b][r * ROW + 2 * c] = make_uint4(lo.x, lo.z, hi.x, hi.z);
-            dec[b][r * ROW + 2 * c + 1] = make_uint4(lo.y, lo.w, hi.y, hi.w);
+        if constexpr (BITS == 8) {               // .x: bytes 0 and 2 (even p), .y: bytes 1 and 3 (odd p) of a dword
+            const uint2 a = decode4_bytes(v.x), b2 = decode4_bytes(v.y), c2 = decode4_bytes(v.z), d2 = decode4_bytes(v.w);
+            if constexpr (FOLD) {
+                dec[b][r * ROW + 2 * c] = make_uint4(a.x, b2.x, c2.x, d2.x);
+                dec[b][r * ROW + 2 * c + 1] = make_uint4(a.y, b2.y, c2.y, d2.y);
+            } else {
+                dec[b][r * ROW + 2 * c] = make_uint4(a.x, a.y, b2.x, b2.y);
+                dec[b][r * ROW + 2 * c + 1] = make_uint4(c2.x, c2.y, d2.x, d2.y);
+            }
         } else {
-            dec[b][r * ROW + 2 * c] = lo;
-            dec[b][r * ROW + 2 * c + 1] = hi;
+            const uint4 lo = decode8(v.x), hi = decode8(v.y);
+            if constexpr (FOLD) {                // .x .z hold the even, .y .w the odd nibbles of a dword
+                dec[b][r * ROW + 2 * c] = make_uint4(lo.x, lo.z, hi.x, hi.z);
+                dec[b][r * ROW + 2 * c + 1] = make_uint4(lo.y, lo.w, hi.y, hi.w);
+            } else {
+                dec[b][r * ROW + 2 * c] = lo;
+                dec[b][r * ROW + 2 * c + 1] = hi;
+            }
         }
     };
     auto put_scale = [&](int b, float sc, int i) __attribute__((always_inline)) {
         const int e = tid + i * NT;
         if (e < 32 * ns) scl[b][(e / ns) * SROW + e % ns] = sc * unscale;
     };
-    auto to_lds = [&](int b, const uint2& c0, const uint2& c1, float s0, float s1) __attribute__((always_inline)) {
+    auto to_lds = [&](int b, const CodeUnit& c0, const CodeUnit& c1, float s0, float s1) __attribute__((always_inline)) {
         put1(b, c0, 0);
         if constexpr (S > 1) put1(b, c1, 1);
         put_scale(b, s0, 0);
@@ -937,7 +983,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     };
 
     const int m = (n_tiles - 1 - t0) / stride + 1;
-    uint2 pa0, pa1, pb0, pb1;                    // prefetched code units of the next two tiles
+    CodeUnit pa0, pa1, pb0, pb1;                 // prefetched code units of the next two tiles
     float pas, pat, pbs, pbt;                    // and up to two floats each of their scale tiles
     float s_last;                                // scale of the last group of the tile contracted last
     fetch(pa0, pa1, pas, pat, t0);
@@ -1023,19 +1069,19 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     }
 }
 
-template <int D, int S, int KS, bool FOLD>
+template <int D, int S, int KS, bool FOLD, int BITS>
 __global__ void __launch_bounds__(2 * D / S)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
                        const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                        float unscale, int gw) {
-    srft_dequantize_tiles<D, S, KS, FOLD>(rfrag, codes, scales, n_vec, out, unscale, gw, blockIdx.x, gridDim.x);
+    srft_dequantize_tiles<D, S, KS, FOLD, BITS>(rfrag, codes, scales, n_vec, out, unscale, gw, blockIdx.x, gridDim.x);
 }
 
-template <int D, int S, int KS, bool FOLD>
+template <int D, int S, int KS, bool FOLD, int BITS>
 __global__ void __launch_bounds__(2 * D / S)
 srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
-    srft_dequantize_tiles<D, S, KS, FOLD>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
+    srft_dequantize_tiles<D, S, KS, FOLD, BITS>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
                                     (uint4*)a.out0[i], a.unscale[i], gw, blockIdx.x - a.first_block[i],
                                     a.first_block[i + 1] - a.first_block[i]);
 }
@@ -1156,7 +1202,7 @@ int slab_output_of_row(int i) {
 }  // namespace
 
 struct srft_plan {
-    int d = 0, g = 0, device = 0;
+    int d = 0, g = 0, bits = 4, device = 0;
     uint64_t seed = 0;
     std::vector<int8_t> signs;
     uint4* wfrag = nullptr;     // write-path matrix fragments (device)
@@ -1188,42 +1234,51 @@ typedef void (*quantize_kernel_t)(const uint4*, const uint4*, long long, uint2*,
 typedef void (*dequantize_kernel_t)(const uint4*, const uint2*, const float*, long long, uint4*, float, int);
 
 // The kernel instance for a plan: d, slabs per wavefront, group mode.
-template <int D, int S>
-quantize_kernel_t quantize_instance(int out, int gm) {
-    if (out == kOutRaw) return srft_quantize_kernel<D, S, kOutRaw, kGroup32>;
-    if (out == kOutAmax) return srft_quantize_kernel<D, S, kOutAmax, kGroup32>;
+template <int D, int S, int BITS>
+quantize_kernel_t quantize_codes_instance(int gm) {
     switch (gm) {
-        case kGroup16: return srft_quantize_kernel<D, S, kOutCodes, kGroup16>;
-        case kGroupWide: return srft_quantize_kernel<D, S, kOutCodes, kGroupWide>;
-        default: return srft_quantize_kernel<D, S, kOutCodes, kGroup32>;
+        case kGroup16: return srft_quantize_kernel<D, S, kOutCodes, kGroup16, BITS>;
+        case kGroupWide: return srft_quantize_kernel<D, S, kOutCodes, kGroupWide, BITS>;
+        default: return srft_quantize_kernel<D, S, kOutCodes, kGroup32, BITS>;
     }
 }
+template <int D, int S>
+quantize_kernel_t quantize_instance(int out, int gm, int bits) {
+    if (out == kOutRaw) return srft_quantize_kernel<D, S, kOutRaw, kGroup32, 4>;
+    if (out == kOutAmax) return srft_quantize_kernel<D, S, kOutAmax, kGroup32, 4>;
+    return bits == 8 ? quantize_codes_instance<D, S, 8>(gm) : quantize_codes_instance<D, S, 4>(gm);
+}
 template <int D>
-quantize_kernel_t quantize_instance(int slabs, int out, int gm, bool fold = false) {
+quantize_kernel_t quantize_instance(int slabs, int out, int gm, bool fold, int bits) {
     if constexpr (D % 128 == 0) {
-        if (fold && out == kOutCodes && gm == kGroup32) return srft_quantize_fold_kernel<D>;
+        if (fold && out == kOutCodes && gm == kGroup32 && bits == 4) return srft_quantize_fold_kernel<D>;
     }
     if constexpr ((D / 32) % 2 == 0) {
-        if (slabs == 2) return quantize_instance<D, 2>(out, gm);
+        if (slabs == 2) return quantize_instance<D, 2>(out, gm, bits);
     }
-    return quantize_instance<D, 1>(out, gm);
+    return quantize_instance<D, 1>(out, gm, bits);
+}
+template <int D, int BITS>
+dequantize_kernel_t dequantize_instance_bits(int slabs, int gm, bool fold) {
+    if constexpr ((D / 32) % 2 == 0) {
+        if (fold && gm != kGroup16) return srft_dequantize_kernel<D, 2, 1, true, BITS>;
+        if (slabs == 2)
+            return gm == kGroup16 ? srft_dequantize_kernel<D, 2, 1, false, BITS>
+                                  : srft_dequantize_kernel<D, 2, 2, false, BITS>;
+    }
+    return gm == kGroup16 ? srft_dequantize_kernel<D, 1, 1, false, BITS> : srft_dequantize_kernel<D, 1, 2, false, BITS>;
 }
 template <int D>
-dequantize_kernel_t dequantize_instance(int slabs, int gm, bool fold) {
-    if constexpr ((D / 32) % 2 == 0) {
-        if (fold && gm != kGroup16) return srft_dequantize_kernel<D, 2, 1, true>;
-        if (slabs == 2)
-            return gm == kGroup16 ? srft_dequantize_kernel<D, 2, 1, false> : srft_dequantize_kernel<D, 2, 2, false>;
-    }
-    return gm == kGroup16 ? srft_dequantize_kernel<D, 1, 1, false> : srft_dequantize_kernel<D, 1, 2, false>;
+dequantize_kernel_t dequantize_instance(int slabs, int gm, bool fold, int bits) {
+    return bits == 8 ? dequantize_instance_bits<D, 8>(slabs, gm, fold) : dequantize_instance_bits<D, 4>(slabs, gm, fold);
 }
 
 template <int D>
 int occupancy_grids(srft_plan* p, int cus) {
     int bq = 0, bd = 0;
-    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, quantize_instance<D>(p->slabs_q, kOutCodes, p->gm, p->fold_q),
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bq, quantize_instance<D>(p->slabs_q, kOutCodes, p->gm, p->fold_q, p->bits),
                                                           p->fold_q ? D : 2 * D / p->slabs_q, 0));
-    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, dequantize_instance<D>(p->slabs_dq, p->gm, p->fold_dq),
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bd, dequantize_instance<D>(p->slabs_dq, p->gm, p->fold_dq, p->bits),
                                                           2 * D / p->slabs_dq, 0));
     p->grid_q = cus * (bq > 0 ? bq : 1);
     p->grid_dq = cus * (bd > 0 ? bd : 1);
@@ -1237,10 +1292,11 @@ int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* cod
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_q;
     if (grid > n_tiles) grid = n_tiles;
     const bool fold = p->fold_q && out == kOutCodes;
-    const quantize_kernel_t kernel = quantize_instance<D>(p->slabs_q, out, p->gm, fold);
+    const quantize_kernel_t kernel = quantize_instance<D>(p->slabs_q, out, p->gm, fold, p->bits);
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(fold ? D : 2 * D / p->slabs_q), 0, st,
                        fold ? p->wfold : p->wfrag, (const uint4*)x, n,
-                       (uint2*)codes, scales, (float4*)wout, p->unscale_w, p->unscale_w / 7.0f, p->gw);
+                       (uint2*)codes, scales, (float4*)wout, p->unscale_w, p->unscale_w / (p->bits == 8 ? 127.0f : 7.0f),
+                       p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
@@ -1251,7 +1307,7 @@ int launch_dequantize(const srft_plan* p, const uint8_t* codes, const float* sca
     const long long n_tiles = (n + kTileVecs - 1) / kTileVecs;
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_dq;
     if (grid > n_tiles) grid = n_tiles;
-    const dequantize_kernel_t kernel = dequantize_instance<D>(p->slabs_dq, p->gm, p->fold_dq);
+    const dequantize_kernel_t kernel = dequantize_instance<D>(p->slabs_dq, p->gm, p->fold_dq, p->bits);
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(2 * D / p->slabs_dq), 0, st,
                        p->fold_dq ? p->rfold : p->rfrag, (const uint2*)codes,
                        scales, n, (uint4*)out, p->unscale_r, p->gw);
@@ -1262,30 +1318,38 @@ int launch_dequantize(const srft_plan* p, const uint8_t* codes, const float* sca
 typedef void (*quantize_batched_kernel_t)(const srft_batch_args, int);
 typedef void (*dequantize_batched_kernel_t)(const srft_batch_args, int);
 
-template <int D>
-quantize_batched_kernel_t quantize_batched_instance(int slabs, int gm, bool fold) {
-    if constexpr (D % 128 == 0) {
-        if (fold && gm == kGroup32) return srft_quantize_fold_batched_kernel<D>;
-    }
-    if constexpr ((D / 32) % 2 == 0) {
-        if (slabs == 2)
-            return gm == kGroup16 ? srft_quantize_batched_kernel<D, 2, kGroup16>
-                 : gm == kGroupWide ? srft_quantize_batched_kernel<D, 2, kGroupWide>
-                                    : srft_quantize_batched_kernel<D, 2, kGroup32>;
-    }
-    return gm == kGroup16 ? srft_quantize_batched_kernel<D, 1, kGroup16>
-         : gm == kGroupWide ? srft_quantize_batched_kernel<D, 1, kGroupWide>
-                            : srft_quantize_batched_kernel<D, 1, kGroup32>;
+template <int D, int S, int BITS>
+quantize_batched_kernel_t quantize_batched_instance_gm(int gm) {
+    return gm == kGroup16 ? srft_quantize_batched_kernel<D, S, kGroup16, BITS>
+         : gm == kGroupWide ? srft_quantize_batched_kernel<D, S, kGroupWide, BITS>
+                            : srft_quantize_batched_kernel<D, S, kGroup32, BITS>;
 }
 template <int D>
-dequantize_batched_kernel_t dequantize_batched_instance(int slabs, int gm, bool fold) {
-    if constexpr ((D / 32) % 2 == 0) {
-        if (fold && gm != kGroup16) return srft_dequantize_batched_kernel<D, 2, 1, true>;
-        if (slabs == 2)
-            return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 2, 1, false>
-                                  : srft_dequantize_batched_kernel<D, 2, 2, false>;
+quantize_batched_kernel_t quantize_batched_instance(int slabs, int gm, bool fold, int bits) {
+    if constexpr (D % 128 == 0) {
+        if (fold && gm == kGroup32 && bits == 4) return srft_quantize_fold_batched_kernel<D>;
     }
-    return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 1, 1, false> : srft_dequantize_batched_kernel<D, 1, 2, false>;
+    if constexpr ((D / 32) % 2 == 0) {
+        if (slabs == 2)
+            return bits == 8 ? quantize_batched_instance_gm<D, 2, 8>(gm) : quantize_batched_instance_gm<D, 2, 4>(gm);
+    }
+    return bits == 8 ? quantize_batched_instance_gm<D, 1, 8>(gm) : quantize_batched_instance_gm<D, 1, 4>(gm);
+}
+template <int D, int BITS>
+dequantize_batched_kernel_t dequantize_batched_instance_bits(int slabs, int gm, bool fold) {
+    if constexpr ((D / 32) % 2 == 0) {
+        if (fold && gm != kGroup16) return srft_dequantize_batched_kernel<D, 2, 1, true, BITS>;
+        if (slabs == 2)
+            return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 2, 1, false, BITS>
+                                  : srft_dequantize_batched_kernel<D, 2, 2, false, BITS>;
+    }
+    return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 1, 1, false, BITS>
+                          : srft_dequantize_batched_kernel<D, 1, 2, false, BITS>;
+}
+template <int D>
+dequantize_batched_kernel_t dequantize_batched_instance(int slabs, int gm, bool fold, int bits) {
+    return bits == 8 ? dequantize_batched_instance_bits<D, 8>(slabs, gm, fold)
+                     : dequantize_batched_instance_bits<D, 4>(slabs, gm, fold);
 }
 
 // One batched launch: the segment table is complete except for first_block, which is laid out here.
@@ -1308,10 +1372,10 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
     a.first_block[a.count] = next;
     const int slabs = write_path ? p->slabs_q : p->slabs_dq;
     if (write_path)
-        hipLaunchKernelGGL(quantize_batched_instance<D>(slabs, p->gm, p->fold_q), dim3((unsigned)next),
+        hipLaunchKernelGGL(quantize_batched_instance<D>(slabs, p->gm, p->fold_q, p->bits), dim3((unsigned)next),
                            dim3(p->fold_q ? D : 2 * D / slabs), 0, st, a, p->gw);
     else
-        hipLaunchKernelGGL(dequantize_batched_instance<D>(slabs, p->gm, p->fold_dq), dim3((unsigned)next),
+        hipLaunchKernelGGL(dequantize_batched_instance<D>(slabs, p->gm, p->fold_dq, p->bits), dim3((unsigned)next),
                            dim3(2 * D / slabs), 0, st, a, p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
@@ -1377,8 +1441,14 @@ int split_hi_lo(const std::vector<double>& m, std::vector<uint16_t>& hi, std::ve
 extern "C" {
 
 int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_seed, const float* lambda_host) {
+    return srft_plan_create_bits(out, d, group_size, 4, sign_seed, lambda_host);
+}
+
+int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, uint64_t sign_seed,
+                          const float* lambda_host) {
     if (!out) return SRFT_ERR_NULL;
     *out = nullptr;
+    if (bits != 4 && bits != 8) return SRFT_ERR_BAD_BITS;
     if (d < 32 || d > kMaxD || d % 32 != 0) return SRFT_ERR_BAD_D;
     if (!(group_size == 16 || (group_size >= 32 && group_size % 32 == 0 && d % group_size == 0))) return SRFT_ERR_BAD_GROUP;
     std::vector<double> lam(d, 1.0);
@@ -1398,6 +1468,7 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
     if (!p) return SRFT_ERR_HIP;
     p->d = d;
     p->g = group_size;
+    p->bits = bits;
     p->gm = group_size == 16 ? kGroup16 : (group_size == 32 ? kGroup32 : kGroupWide);
     p->gw = group_size <= 32 ? 1 : group_size / 32;
     p->seed = sign_seed;
@@ -1429,10 +1500,14 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
                     wf[((((size_t)w * T + t) * 2 + 0) * 64 + l) * 8 + e] = whi[src];
                     wf[((((size_t)w * T + t) * 2 + 1) * 64 + l) * 8 + e] = wlo[src];
                 }
-            for (int j = 0; j < G; ++j)           // read path: group j, code dword 4j + 2t + kh,
-                for (int t = 0; t < 2; ++t)       // element e <-> nibble e/2 + 4 (e % 2) of that dword
+            // read path: group j, run of 8 codes 4j + 2t + kh; element e <-> code e/2 + 4 (e % 2) of the run at
+            // 4 bits (nibble pairs (n0, n4), (n1, n5), ...), code {0, 2, 1, 3, 4, 6, 5, 7}[e] at 8 bits (byte pairs
+            // (b0, b2), (b1, b3) of each dword): the orders in which the kernel's decode lays the codes out
+            static const int byte_order[8] = {0, 2, 1, 3, 4, 6, 5, 7};
+            for (int j = 0; j < G; ++j)
+                for (int t = 0; t < 2; ++t)
                     for (int e = 0; e < 8; ++e) {
-                        const int k = 8 * (4 * j + 2 * t + kh) + (e / 2) + 4 * (e % 2);
+                        const int k = 8 * (4 * j + 2 * t + kh) + (bits == 8 ? byte_order[e] : (e / 2) + 4 * (e % 2));
                         const size_t src = (size_t)row * d + k;
                         rf[(((((size_t)w * G + j) * 2 + t) * 2 + 0) * 64 + l) * 8 + e] = rhi[src];
                         rf[(((((size_t)w * G + j) * 2 + t) * 2 + 1) * 64 + l) * 8 + e] = rlo[src];
@@ -1450,7 +1525,9 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
         // A (even p) and B (odd p) fragments of wavefront w: row n = 32w + (output of MFMA row l % 32); group j,
         // lane half kh, element e <-> packed index 32j + 16 kh + off[e] (+ 1 for B), off[] being the order in
         // which the kernel lays out the decoded low nibbles of an 8-byte unit: (n0, n4, n2, n6) of each dword.
-        static const int off[8] = {0, 4, 2, 6, 8, 12, 10, 14};
+        // (at 8 bits: bytes 0 and 2 of each of the four dwords)
+        static const int off4[8] = {0, 4, 2, 6, 8, 12, 10, 14}, off8[8] = {0, 2, 4, 6, 8, 10, 12, 14};
+        const int* off = bits == 8 ? off8 : off4;
         const int waves = d / 64;
         const size_t frag_halves = (size_t)waves * 2 * G * 2 * 64 * 8;
         rfold.assign(frag_halves + (size_t)waves * 64 * 16, 0);
@@ -1474,7 +1551,7 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
             }
     }
     // Folded write path where it applies (d a multiple of 128, g = 32); SRFT_FOLD_Q=0 turns it off (tuning).
-    p->fold_q = (d % 128 == 0) && p->gm == kGroup32;
+    p->fold_q = (d % 128 == 0) && p->gm == kGroup32 && bits == 4;
     if (const char* e = std::getenv("SRFT_FOLD_Q")) p->fold_q = p->fold_q && std::atoi(e) != 0;
     std::vector<uint16_t> wfold;
     if (p->fold_q) {
@@ -1617,7 +1694,8 @@ static int run_batched(const srft_plan_t* const* plans, const void* const* in0, 
     // validate everything before the first launch: a bad segment must not leave half a batch enqueued
     for (int i = 0; i < count; ++i) {
         if (!plans[i]) return SRFT_ERR_NULL;
-        if (plans[i]->d != plans[0]->d || plans[i]->g != plans[0]->g || plans[i]->device != plans[0]->device)
+        if (plans[i]->d != plans[0]->d || plans[i]->g != plans[0]->g || plans[i]->bits != plans[0]->bits ||
+            plans[i]->device != plans[0]->device)
             return SRFT_ERR_MISMATCH;
         if (n_vec[i] < 0 || n_vec[i] > kMaxVectors) return SRFT_ERR_BAD_N;
         if (n_vec[i] == 0) continue;
@@ -1675,7 +1753,8 @@ int srft_cache_create(srft_cache_t** out, const srft_plan_t* const* plans, int n
         return SRFT_ERR_BAD_N;
     for (int i = 0; i < n_plans; ++i) {
         if (!plans[i] || !codes_dev[i] || !scales_dev[i] || !view_f16_dev[i]) return SRFT_ERR_NULL;
-        if (plans[i]->d != plans[0]->d || plans[i]->g != plans[0]->g || plans[i]->device != plans[0]->device)
+        if (plans[i]->d != plans[0]->d || plans[i]->g != plans[0]->g || plans[i]->bits != plans[0]->bits ||
+            plans[i]->device != plans[0]->device)
             return SRFT_ERR_MISMATCH;
         if (!aligned(codes_dev[i], 16) || !aligned(scales_dev[i], 4) || !aligned(view_f16_dev[i], 16))
             return SRFT_ERR_ALIGN;
@@ -1712,7 +1791,7 @@ static int cache_convert(const srft_cache* c, int64_t first, int64_t count, bool
     std::vector<int64_t> n(np, nv);
     for (size_t i = 0; i < np; ++i) {
         xo[i] = (char*)c->view[i] + v0 * d * 2;
-        cdo[i] = c->codes[i] + v0 * (d / 2);
+        cdo[i] = c->codes[i] + v0 * (d * c->plans[0]->bits / 8);
         sco[i] = c->scales[i] + v0 * G;
         x[i] = xo[i];
         cd[i] = cdo[i];
@@ -1773,7 +1852,8 @@ int srft_cache_rebuild_view(srft_cache_t* cache, void* hip_stream) {
 int srft_plan_d(const srft_plan_t* plan) { return plan ? plan->d : SRFT_ERR_NULL; }
 int srft_plan_group_size(const srft_plan_t* plan) { return plan ? plan->g : SRFT_ERR_NULL; }
 int srft_plan_groups(const srft_plan_t* plan) { return plan ? plan->d / plan->g : SRFT_ERR_NULL; }
-int srft_plan_code_bytes(const srft_plan_t* plan) { return plan ? plan->d / 2 : SRFT_ERR_NULL; }
+int srft_plan_code_bytes(const srft_plan_t* plan) { return plan ? plan->d * plan->bits / 8 : SRFT_ERR_NULL; }
+int srft_plan_bits(const srft_plan_t* plan) { return plan ? plan->bits : SRFT_ERR_NULL; }
 
 int srft_plan_get_signs(const srft_plan_t* plan, int8_t* out_host) {
     if (!plan || !out_host) return SRFT_ERR_NULL;
@@ -1845,7 +1925,8 @@ const char* srft_status_string(int status) {
         case SRFT_ERR_ALIGN: return "device pointer is misaligned";
         case SRFT_ERR_HIP: return "HIP call failed (see srft_last_hip_error)";
         case SRFT_ERR_BAD_N: return "negative or malformed size";
-        case SRFT_ERR_MISMATCH: return "plans of one batched call must share d, group size and device";
+        case SRFT_ERR_MISMATCH: return "plans of one call must share d, group size, code width and device";
+        case SRFT_ERR_BAD_BITS: return "unsupported code width (need 4 or 8 bits)";
         default: return "unknown status";
     }
 }

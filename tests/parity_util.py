@@ -14,7 +14,10 @@ import numpy as np
 
 from oracle import srft_oracle as O
 
-BOUNDARY_WINDOW = 1e-4     # in units of the group's scale
+BOUNDARY_WINDOW = 1e-4     # in units of the group's scale, at 4 bits
+# At 8 bits one code step is 7/127 of the 4-bit step for the same accuracy of w, so the same relative error of w
+# moves r = w / scale by 127/7 as much: the window is the 4-bit one scaled by that ratio (1.8e-3).
+BOUNDARY_WINDOW_8 = BOUNDARY_WINDOW * 127.0 / 7.0
 SCALE_RTOL = 2e-3          # stated bar; the measured error is reported alongside
 SCALE_RTOL_TIGHT = 2e-6    # what fp32 arithmetic on the abs-max actually delivers
 W_ABS_ERR = 1e-6           # bound on |w_gpu - w| in units of lambda_k * ||x||_2 (fp32 accumulation of d terms)
@@ -24,7 +27,7 @@ OUT_FLOOR = 8e-6           # times max |ref| of the vector: fp32 accumulation ov
 FP16_TINY = 1.2e-7         # two fp16 subnormal quanta
 
 
-def check_quantize(x_f16: np.ndarray, s, lam, g, codes_gpu: np.ndarray, scales_gpu: np.ndarray) -> dict:
+def check_quantize(x_f16: np.ndarray, s, lam, g, codes_gpu: np.ndarray, scales_gpu: np.ndarray, bits: int = 4) -> dict:
     """x_f16 [n, d] float16; GPU outputs as numpy.  Raises AssertionError on any violation.
 
     A group is "cancellation-dominated" when its abs-max is below COND_MIN of what its lambdas and the
@@ -32,10 +35,12 @@ def check_quantize(x_f16: np.ndarray, s, lam, g, codes_gpu: np.ndarray, scales_g
     coefficients are rounding noise of the fp32 transform, relative agreement is not defined, and the
     group is held to the absolute checks only.  Random data has no such groups; the count is reported.
     """
-    ref = O.quantize(x_f16, s, lam, g)
+    ref = O.quantize(x_f16, s, lam, g, bits=bits)
     n, d = x_f16.shape
     G = d // g
-    assert codes_gpu.shape == (n, d // 2) and codes_gpu.dtype == np.uint8
+    qmax = 2 ** (bits - 1) - 1
+    window = BOUNDARY_WINDOW if bits == 4 else BOUNDARY_WINDOW_8
+    assert codes_gpu.shape == (n, d * bits // 8) and codes_gpu.dtype == np.uint8
     assert scales_gpu.shape == (n, G) and scales_gpu.dtype == np.float32
     lam64 = np.asarray(lam, dtype=np.float64)
     xn = np.linalg.norm(x_f16.astype(np.float64), axis=1)                       # [n]
@@ -43,11 +48,11 @@ def check_quantize(x_f16: np.ndarray, s, lam, g, codes_gpu: np.ndarray, scales_g
     sr = ref["scales"].astype(np.float64)
     sg = scales_gpu.astype(np.float64)
     well = sr > COND_MIN * typical / np.sqrt(d)
-    q_gpu = O.unpack_nibbles(codes_gpu)
+    q_gpu = O.unpack_nibbles(codes_gpu) if bits == 4 else codes_gpu.view(np.int8)
     q_ref = ref["q"]
-    assert q_gpu.min(initial=0) >= -7 and q_gpu.max(initial=0) <= 7, "code outside [-7, 7]"
+    assert q_gpu.min(initial=0) >= -qmax and q_gpu.max(initial=0) <= qmax, "code outside the symmetric range"
     # every group, absolute: scale within the fp32 error of the transform; codes are a nearest rounding of w
-    assert np.all(np.abs(sg - sr) <= SCALE_RTOL_TIGHT * sr + W_ABS_ERR * typical / 7), "scale abs err"
+    assert np.all(np.abs(sg - sr) <= SCALE_RTOL_TIGHT * sr + W_ABS_ERR * typical / qmax), "scale abs err"
     sg_k = np.repeat(sg, g, axis=1)
     e_k = W_ABS_ERR * lam64[None, :] * xn[:, None]
     assert np.all(np.abs(q_gpu * sg_k - ref["w"]) <= 0.5 * sg_k * (1 + 1e-5) + e_k), "codes are not a nearest rounding"
@@ -64,11 +69,12 @@ def check_quantize(x_f16: np.ndarray, s, lam, g, codes_gpu: np.ndarray, scales_g
         dist = np.abs(np.abs(r - np.floor(r)) - 0.5)        # distance to the nearest half-integer
         step = np.abs(q_gpu[mism].astype(np.int32) - q_ref[mism].astype(np.int32))
         assert np.all(step == 1), "code mismatch larger than one step"
-        assert np.all(dist < BOUNDARY_WINDOW), f"code mismatch {dist.max():.3e} away from a rounding boundary"
+        assert np.all(dist < window), f"code mismatch {dist.max():.3e} away from a rounding boundary"
     # (a) bytes: rows whose codes all agree must agree byte for byte; and re-packing the GPU codes is the identity
     rows_equal = ~(q_gpu != q_ref).any(axis=1)
     assert np.array_equal(codes_gpu[rows_equal], ref["codes"][rows_equal])
-    assert np.array_equal(O.pack_nibbles(q_gpu), codes_gpu)
+    if bits == 4:
+        assert np.array_equal(O.pack_nibbles(q_gpu), codes_gpu)
     return {
         "n": n, "mismatches": n_mism, "mismatch_rate": n_mism / max(1, n * d),
         "scale_max_rel": float(rel.max(initial=0.0)), "ill_conditioned_groups": int((~well & (sr > 0)).sum()),
@@ -81,9 +87,9 @@ def out_tolerance(ref64: np.ndarray) -> np.ndarray:
     return OUT_RTOL * np.abs(ref64) + OUT_FLOOR * vmax + FP16_TINY
 
 
-def check_dequantize(codes: np.ndarray, scales: np.ndarray, s, lam, g, out_gpu: np.ndarray) -> dict:
+def check_dequantize(codes: np.ndarray, scales: np.ndarray, s, lam, g, out_gpu: np.ndarray, bits: int = 4) -> dict:
     """GPU read path on (codes, scales) against the oracle's read path on the same bytes."""
-    ref64 = O.dequantize_f64(codes, scales, s, lam, g)
+    ref64 = O.dequantize_f64(codes, scales, s, lam, g, bits=bits)
     ref16 = ref64.astype(np.float16)
     assert out_gpu.dtype == np.float16 and out_gpu.shape == ref16.shape
     assert np.isfinite(out_gpu.astype(np.float32)).all()
