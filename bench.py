@@ -22,8 +22,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 MEASURED_TRAFFIC = {
     # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (factors from the copy kernel of known size), KiB -> bytes, per launch
     # of 1,048,576 vectors at d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
-    ("llama3-70b-128k", "srft_quantize_kernel"): (131342.9 * 2.0 + 82098.2) * 1024,
-    ("llama3-70b-128k", "srft_dequantize_kernel"): (41172.1 * 2.0 + 262144.0) * 1024,
+    ("llama3-70b-128k", "srft_quantize_kernel"): (131341.5 * 2.0 + 82097.3) * 1024,
+    ("llama3-70b-128k", "srft_dequantize_kernel"): (41173.2 * 2.0 + 262144.0) * 1024,
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
