@@ -210,7 +210,10 @@ def mix_ceiling(B, torch, x, out, total_vec, d, G, stream):
     n_tiles = min(total_vec // 32, (2 << 30) // big)         # at most 2 GiB on the large side
     a, b = x.view(torch.uint8).reshape(-1), out.view(torch.uint8).reshape(-1)
     res = {"tiles": n_tiles, "read_write_bytes_per_tile": {"quantize_mix": [big, small], "dequantize_mix": [small, big]}}
-    for name, (rb, wb) in (("quantize_mix", (big, small)), ("dequantize_mix", (small, big))):
+    import os
+    for name, (rb, wb), stream_env in (("quantize_mix", (big, small), "0"), ("dequantize_mix", (small, big), "0"),
+                                       ("dequantize_mix_streaming_accesses", (small, big), "1")):
+        os.environ["SRFT_MIX_STREAM"] = stream_env           # the library reads it at every call
         best = {}
         for wgs in (512, 768, 1024, 2048, 4096, 8192):
             for _ in range(3):

@@ -1130,7 +1130,8 @@ srft_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, long lo
 // Streaming kernel with a given read : write byte mix per tile and no arithmetic to speak of: every
 // workgroup walks tiles, reads r_units 16-byte units and writes w_units units per tile, all coalesced.
 // Its rate is the ceiling the memory system offers a kernel with the same traffic shape.
-template <int RU>      // RU = ceil(r_units / 256): loads per thread and tile, all issued before any is used
+// STREAM: non-temporal loads and stores (what the read path uses)
+template <int RU, bool STREAM>   // RU = ceil(r_units / 256): loads per thread and tile, all issued before any is used
 __global__ void __launch_bounds__(256)
 srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n_tiles, int r_units, int w_units) {
     for (long long t = blockIdx.x; t < n_tiles; t += gridDim.x) {
@@ -1139,13 +1140,16 @@ srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long lon
 #pragma unroll
         for (int i = 0; i < RU; ++i) {
             const int u = threadIdx.x + 256 * i;
-            v[i] = s[u < r_units ? u : r_units - 1];
+            v[i] = STREAM ? stream_load(&s[u < r_units ? u : r_units - 1]) : s[u < r_units ? u : r_units - 1];
         }
         uint4 acc = v[0];
 #pragma unroll
         for (int i = 1; i < RU; ++i) { acc.x ^= v[i].x; acc.y ^= v[i].y; acc.z ^= v[i].z; acc.w ^= v[i].w; }
         uint4* d = dst + t * w_units;
-        for (int u = threadIdx.x; u < w_units; u += 256) d[u] = acc;
+        for (int u = threadIdx.x; u < w_units; u += 256) {
+            if (STREAM) stream_store(&d[u], acc);
+            else d[u] = acc;
+        }
     }
 }
 
@@ -1915,10 +1919,12 @@ int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int rea
     if (grid > n_tiles) grid = n_tiles;
     const int r_units = read_bytes_per_tile / 16, w_units = write_bytes_per_tile / 16;
     const int ru = (r_units + 255) / 256;
+    const char* env = std::getenv("SRFT_MIX_STREAM");          // 1: non-temporal accesses (read on every call)
+    const bool stream = env && std::atoi(env) != 0;
+    void (*kernel)(const uint4*, uint4*, long long, int, int) = nullptr;
 #define SRFT_MIX_CASE(N)                                                                                          \
     case N:                                                                                                       \
-        hipLaunchKernelGGL(srft_mix_kernel<N>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream,      \
-                           (const uint4*)src_dev, (uint4*)dst_dev, (long long)n_tiles, r_units, w_units);         \
+        kernel = stream ? srft_mix_kernel<N, true> : srft_mix_kernel<N, false>;                                  \
         break;
     switch (ru) {
         SRFT_MIX_CASE(1) SRFT_MIX_CASE(2) SRFT_MIX_CASE(3) SRFT_MIX_CASE(4)
@@ -1926,6 +1932,8 @@ int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int rea
         default: return SRFT_ERR_BAD_N;         // at most 32 KiB read per tile
     }
 #undef SRFT_MIX_CASE
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, (const uint4*)src_dev,
+                       (uint4*)dst_dev, (long long)n_tiles, r_units, w_units);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
