@@ -19,7 +19,7 @@
 // scale cannot enter the matrix, so each group's 32 codes are contracted separately (K = 32) and
 // the partial results are combined as  x = sum_j scale_j * P_j  on the vector ALU in fp32.
 //
-// Work decomposition: a workgroup has d/32 wavefronts and walks over tiles of 32 vectors
+// Work decomposition (plain forms): a workgroup has d/32 wavefronts and walks over tiles of 32 vectors
 // (persistent grid).  Wavefront w owns the 32 output rows 32w..32w+31 -- on the write path that is
 // exactly quantization group w, so the abs-max needs a single cross-lane step -- and keeps its
 // 32 x d slab of the matrix (hi and lo) in registers for the whole launch.  The 32 x d operand tile
@@ -28,6 +28,15 @@
 // The MFMA row order inside a slab is permuted on the host so that a lane ends up holding 16
 // CONSECUTIVE outputs: 16 nibbles = one 8-byte store on the write path, 16 fp16 = two 16-byte
 // stores on the read path, with no cross-lane shuffles.
+//
+// Folded forms (d = 128 and 256 on the write path, 128 / 192 / 256 on the read path): two symmetries of Q
+// let every output pair share two half-length partial sums, which halves the matrix work; they are
+// described at srft_quantize_fold_tiles and at the FOLD parameter of srft_dequantize_tiles.
+//
+// Around the two paths: the same kernels serving several plans in one launch (a segment table passed as a
+// kernel argument), the per-channel abs-max statistic lambda is calibrated from, an 8-bit code width, and
+// a host-side cache manager (int4 store, fp16 residual window, dequantized view) built on the batched
+// launches.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
