@@ -2,8 +2,10 @@
 """Benchmark of the SRFT int4 KV-cache write + read path on one MI355X.
 
 A step is one pass of the whole hot path over the workload's cache: every plan's fp16 K/V tensor is
-quantized, then every plan's int4 record is dequantized.  Plans with at least 65,536 vectors get a launch
-each; smaller ones go through the batched entry points, up to 64 plans per launch (--batched on|off overrides).
+quantized, then every plan's int4 record is dequantized.  By default (--batched auto) the read path goes through the
+batched entry point, up to 64 plans per launch (measured faster than a launch per plan: fewer pipeline prologues),
+and the write path does so only for plans with fewer than 65,536 vectors (for large plans a launch each is faster);
+--batched on|off forces one way for both.
 Inputs are synthetic, seeded, and resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
@@ -17,13 +19,13 @@ import time
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 
-# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/), in bytes,
-# for launches of the default workload; None until a counter run has been recorded.
-MEASURED_TRAFFIC = {
-    # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (factors from the copy kernel of known size), KiB -> bytes, per launch
-    # of 1,048,576 vectors at d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
-    ("llama3-70b-128k", "srft_quantize_kernel"): (131341.5 * 2.0 + 82097.3) * 1024,
-    ("llama3-70b-128k", "srft_dequantize_kernel"): (41173.2 * 2.0 + 262144.0) * 1024,
+# HBM traffic measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/), in bytes per vector, for the
+# default workload; scaled below by the vectors one launch processes.  None until a counter run has been recorded.
+MEASURED_TRAFFIC_PER_VECTOR = {
+    # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch (factors from the copy kernel of known size) x 1024 /
+    # vectors per dispatch, d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
+    ("llama3-70b-128k", "srft_quantize_kernel"): (131339.2 * 2.0 + 82109.5) * 1024 / 1048576,
+    ("llama3-70b-128k", "srft_dequantize_kernel"): (164593.3 * 2.0 + 1048576.0) * 1024 / (4 * 1048576),
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
@@ -90,23 +92,26 @@ def main() -> int:
 
     stream = torch.cuda.current_stream()
     h = [pl.handle for pl in plans]
-    batched = args.batched == "on" or (args.batched == "auto" and n < 65536)
-    launches = -(-n_plans // 64) if batched else n_plans          # per direction and step
-    if batched:
+    batched_q = args.batched == "on" or (args.batched == "auto" and n < 65536)
+    batched_d = args.batched == "on" or (args.batched == "auto" and n_plans > 1)
+    launches_q = -(-n_plans // 64) if batched_q else n_plans      # per step
+    launches_d = -(-n_plans // 64) if batched_d else n_plans
+    if batched_q:
         table_q = B.BatchTable(h, list(x), list(codes), list(scales))
+    if batched_d:
         table_d = B.BatchTable(h, list(out), list(codes), list(scales))
 
     def step(ev=None):
         if ev:
             ev[0].record(stream)
-        if batched:
+        if batched_q:
             B.srft_kv_quantize_batched(table_q, stream)
         else:
             for p in range(n_plans):
                 B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
         if ev:
             ev[1].record(stream)
-        if batched:
+        if batched_d:
             B.srft_kv_dequantize_batched(table_d, stream)
         else:
             for p in range(n_plans):
@@ -128,13 +133,14 @@ def main() -> int:
     total_vec = n_plans * n
     ms_per_step = wall / args.steps * 1e3
 
-    def roof(t_phase):
+    def roof(t_phase, launches):
         per_launch_s = t_phase / launches
         achieved = total_vec * bytes_per_vec / t_phase / 1e9
         return per_launch_s, achieved
 
-    ql, qa = roof(tq)
-    dl, da = roof(td)
+    ql, qa = roof(tq, launches_q)
+    dl, da = roof(td, launches_d)
+    launches = launches_q if tq >= td else launches_d
     dominant = "srft_quantize_kernel" if tq >= td else "srft_dequantize_kernel"
     dom_l, dom_a = (ql, qa) if tq >= td else (dl, da)
     result = {
@@ -148,13 +154,16 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
                    "total_vectors": total_vec, "bytes_per_vector_each_direction": bytes_per_vec,
-                   "launches_per_step": 2 * launches, "batched": batched},
+                   "launches_per_step": launches_q + launches_d,
+                   "batched": {"quantize": batched_q, "dequantize": batched_d}},
         "quantize": {"vectors_per_s": total_vec / tq, "ns_per_vec": tq / total_vec * 1e9, "GBps": qa,
                      "hbm_frac": qa / HBM_PEAK_GBPS, "avg_launch_ms": ql * 1e3},
         "dequantize": {"vectors_per_s": total_vec / td, "ns_per_vec": td / total_vec * 1e9, "GBps": da,
                        "hbm_frac": da / HBM_PEAK_GBPS, "avg_launch_ms": dl * 1e3},
         "roofline": {"kernel": dominant, "bound": "hbm", "achieved": dom_a, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": dom_a / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get((w.name, dominant)),
+                     "frac": dom_a / HBM_PEAK_GBPS,
+                     "traffic": (MEASURED_TRAFFIC_PER_VECTOR[(w.name, dominant)] * total_vec / launches
+                                 if (w.name, dominant) in MEASURED_TRAFFIC_PER_VECTOR else None),
                      "algorithmic_bytes_per_launch": total_vec * bytes_per_vec // launches,
                      "avg_launch_ms": dom_l * 1e3},
         "paper_context_apple_m1": PAPER_CONTEXT,
