@@ -2,6 +2,7 @@
 and checked against the oracle on the decode-step append of the d = 96 workload."""
 import ctypes as C
 
+import numpy as np
 import pytest
 import torch
 
@@ -162,4 +163,34 @@ def test_batched_argument_errors(B):
     with pytest.raises(B.SrftError):
         B.srft_kv_quantize_batched(B.BatchTable([p96.handle, p128.handle], [x, x], [c, c], [s, s]))
     for p in (p96, p128, p96g):
+        p.close()
+
+
+def test_full_size_plans_in_the_launch_shape_the_benchmark_times(B):
+    """Three plans of the Llama-70B-shaped workload at their full 1,048,576 vectors: the batched read path (what
+    bench.py launches) gives the bytes of the per-plan calls, which the parity tests check against the oracle on a
+    sample; the batched write path likewise."""
+    w = W.WORKLOADS["llama3-70b-128k"]
+    n = w.vectors_per_plan
+    plans, xs = [], []
+    for pi in (0, 1, 159):
+        seed, lam, _ = W.plan_constants(w, pi)
+        plans.append(B.Plan(w.d, w.g, seed, lam))
+        xs.append(W.make_kv(w, pi, n_vec=n, device="cuda"))
+    ref = []
+    for p, x in zip(plans, xs):
+        c, s = p.quantize(x)
+        ref.append((c, s, p.dequantize(c, s)))
+    got = _batched(B, plans, xs, w.d, w.g)
+    _assert_same(ref, got)
+    # oracle on a sample of the batched output (first and last tile of every plan included)
+    rng = np.random.RandomState(0)
+    for i, p in enumerate(plans):
+        idx = np.unique(np.concatenate([np.arange(32), np.arange(n - 32, n), rng.randint(0, n, size=4096)]))
+        it = torch.from_numpy(idx).cuda()
+        _, lam, _ = W.plan_constants(w, (0, 1, 159)[i])
+        c, s, o = (t[it].cpu().numpy() for t in got[0][i:i + 1] + got[1][i:i + 1] + got[2][i:i + 1])
+        P.check_quantize(xs[i][it].cpu().numpy(), p.signs, lam, w.g, c, s)
+        P.check_dequantize(c, s, p.signs, lam, w.g, o)
+    for p in plans:
         p.close()
