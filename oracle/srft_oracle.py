@@ -32,6 +32,9 @@ What each function follows:
 * ``pack_nibbles`` /
   ``unpack_nibbles``       -- Sec. 3.2 detail (ii):
                               byte = (q[2i+1] << 4) | (q[2i] & 0xF).
+* ``hadamard_matrix``      -- the SRHT the paper compares against (Sec. 1,
+                              Sec. 3.1): ``form="hadamard"`` swaps it in for Q
+                              everywhere.
 * ``channel_absmax`` /
   ``lambda_from_absmax``   -- Sec. 7.1: lambda_d = 1 / per_channel_max(SRFT
                               output)_d, the maximum taken over a calibration
@@ -103,6 +106,20 @@ def srft_matrix(d: int) -> np.ndarray:
         else:
             Q[k] = -np.sqrt(2.0 / d) * np.sin(2.0 * np.pi * (k - h) * n / d)
     return Q
+
+
+def hadamard_matrix(d: int) -> np.ndarray:
+    """The orthonormal Walsh-Hadamard matrix in natural (Sylvester) order, H_{2m} = [[H_m, H_m], [H_m, -H_m]] / sqrt 2.
+
+    With it in place of Q the pipeline is the SRHT the paper compares the SRFT against (Sec. 1 contribution list,
+    Sec. 3.1): same sign diagonal, same quantizer, another orthogonal mixing matrix.  d must be a power of two.
+    """
+    if d < 1 or d & (d - 1):
+        raise ValueError("the Hadamard comparator needs a power-of-two d")
+    H = np.ones((1, 1), dtype=np.float64)
+    while H.shape[0] < d:
+        H = np.block([[H, H], [H, -H]])
+    return H / np.sqrt(d)
 
 
 def _smallest_factor(n: int) -> int:
@@ -177,6 +194,8 @@ def srft_forward(x, s, form: str = "dense", dtype=np.float64) -> np.ndarray:
     if form == "fft":
         Y = fft_mixed_radix(u.astype(np.float64)) / np.sqrt(d)
         return pack_spectrum(Y[..., :d // 2 + 1], d)
+    if form == "hadamard":                       # the SRHT comparator: H in place of Q
+        return u @ hadamard_matrix(d).astype(dtype).T
     raise ValueError(form)
 
 
@@ -190,6 +209,8 @@ def srft_inverse(z, s, form: str = "dense", dtype=np.float64) -> np.ndarray:
         Y = unpack_spectrum(z.astype(np.float64))
         # inverse unitary DFT through the forward routine: ifft(Y) = conj(fft(conj Y)) / d
         u = np.conj(fft_mixed_radix(np.conj(Y))).real / np.sqrt(d)
+    elif form == "hadamard":
+        u = z.astype(dtype) @ hadamard_matrix(d).astype(dtype)
     else:
         raise ValueError(form)
     return u * np.asarray(s).astype(u.dtype)

@@ -220,3 +220,75 @@ def test_signs_are_pm1_and_balanced():
     assert not np.array_equal(O.signs_from_seed(43, 128), s[:128])
     v = O.splitmix64_stream(42, 8)
     assert [(-1 if x >> 63 else 1) for x in v] == list(s[:8])
+
+
+# ----------------------------------------------------------------------------- the SRHT comparator
+def test_hadamard_matrix_against_scipy_the_entry_formula_and_a_butterfly():
+    import scipy.linalg
+    for d in (1, 2, 4, 32, 64, 128, 256):
+        H = O.hadamard_matrix(d)
+        assert np.allclose(H, scipy.linalg.hadamard(d) / np.sqrt(d), atol=1e-15)
+        assert np.allclose(H @ H.T, np.eye(d), atol=1e-12) and np.array_equal(H, H.T)
+    d = 64
+    H = O.hadamard_matrix(d)
+    p, n = np.meshgrid(np.arange(d), np.arange(d), indexing="ij")
+    parity = np.array([[bin(a & b).count("1") & 1 for b in range(d)] for a in range(d)])
+    assert np.allclose(H * np.sqrt(d), 1 - 2 * parity)                    # (-1)^popcount(p & n)
+    # in-place butterflies (the fast Walsh-Hadamard transform) give the same product
+    rng = np.random.RandomState(0)
+    u = rng.standard_normal(d)
+    a = u.copy()
+    h = 1
+    while h < d:
+        for i in range(0, d, 2 * h):
+            for j in range(i, i + h):
+                a[j], a[j + h] = a[j] + a[j + h], a[j] - a[j + h]
+        h *= 2
+    assert np.allclose(a / np.sqrt(d), H @ u, atol=1e-12)
+    with pytest.raises(ValueError):
+        O.hadamard_matrix(96)
+
+
+def test_srht_form_round_trips_and_keeps_norms():
+    d = 128
+    rng = np.random.RandomState(1)
+    x = rng.standard_normal((20, d))
+    s = O.signs_from_seed(3, d)
+    z = O.srft_forward(x, s, form="hadamard")
+    assert np.allclose(np.linalg.norm(z, axis=1), np.linalg.norm(x, axis=1), rtol=1e-12)
+    assert np.allclose(O.srft_inverse(z, s, form="hadamard"), x, atol=1e-12)
+    # s * ones -> all energy in coefficient 0
+    z1 = O.srft_forward((s * 2.0)[None, :], s, form="hadamard")
+    assert abs(z1[0, 0] - 2.0 * np.sqrt(d)) < 1e-12 and np.all(np.abs(z1[0, 1:]) < 1e-12)
+
+
+def test_srft_and_srht_gaussianize_alike():
+    """Sec. 3.1: heavy-tailed channels give large excess kurtosis; after either transform the coefficients are
+    near-Gaussian (the paper reports about -0.5 after SRFT, "matching SRHT's behavior"), and the 4-bit
+    reconstruction errors agree (Sec. 1: "statistically indistinguishable").  Synthetic stand-in for the paper's
+    activations: N(0,1) times per-channel gains ~ lognormal(0, 1)."""
+    d, n = 128, 4000
+    rng = np.random.RandomState(2)
+    x = (rng.standard_normal((n, d)) * np.exp(rng.standard_normal(d))).astype(np.float16)
+    s = O.signs_from_seed(5, d)
+
+    def excess_kurtosis(v):
+        v = v - v.mean(axis=1, keepdims=True)
+        return ((v ** 4).mean(axis=1) / (v ** 2).mean(axis=1) ** 2 - 3.0).mean()
+
+    assert excess_kurtosis(x.astype(np.float64)) > 10
+    lam = np.ones(d, dtype=np.float32)
+    mse, kurt = {}, {}
+    for form in ("dense", "hadamard"):
+        kurt[form] = excess_kurtosis(O.srft_forward(x, s, form=form))
+        q = O.quantize(x, s, lam, 32, form=form)
+        back = O.dequantize_f64(q["codes"], q["scales"], s, lam, 32, form=form)
+        mse[form] = np.mean((back - x.astype(np.float64)) ** 2)
+    assert -1.0 < kurt["dense"] < 0.5 and -1.0 < kurt["hadamard"] < 0.5
+    assert abs(mse["dense"] - mse["hadamard"]) / mse["dense"] < 0.1
+    # and both beat quantizing the raw vectors (identity in place of the transform would keep the loud channels)
+    g = 32
+    xr = x.astype(np.float64).reshape(n, d // g, g)
+    sc = np.abs(xr).max(axis=-1, keepdims=True) / 7
+    raw_mse = np.mean((np.rint(xr / sc) * sc - xr) ** 2)
+    assert mse["dense"] < raw_mse and mse["hadamard"] < raw_mse
