@@ -48,7 +48,8 @@ typedef enum srft_status {
     SRFT_ERR_HIP        = -6,   /* a HIP call failed; see srft_last_hip_error() */
     SRFT_ERR_BAD_N      = -7,   /* n_vec < 0, count < 0 or byte count negative */
     SRFT_ERR_MISMATCH   = -8,   /* plans of one call differ in d, group_size, code width or device */
-    SRFT_ERR_BAD_BITS   = -9    /* code width not 4 or 8 */
+    SRFT_ERR_BAD_BITS   = -9,   /* code width not 4 or 8 */
+    SRFT_ERR_BAD_TRANSFORM = -10 /* transform not one of srft_transform */
 } srft_status;
 
 /*
@@ -73,6 +74,18 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
  */
 int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, uint64_t sign_seed,
                           const float* lambda_host);
+
+/*
+ * The same with a chosen mixing matrix: the comparator of Sec. 1 / Sec. 3.1.
+ *   SRFT_TRANSFORM_DFT       the real-packed unitary DFT of Eq. 1-2 (every other create call is this case).
+ *   SRFT_TRANSFORM_HADAMARD  the orthonormal Walsh-Hadamard matrix in natural order, H[k][n] = (-1)^popcount(k & n)
+ *                            / sqrt(d): sign diagonal, lambda, quantizer and record are unchanged, which makes the
+ *                            pipeline the SRHT the paper compares against.  d must be a power of two (else
+ *                            SRFT_ERR_BAD_D).  Runs on the plain kernels (the folded forms use DFT symmetries).
+ */
+typedef enum srft_transform { SRFT_TRANSFORM_DFT = 0, SRFT_TRANSFORM_HADAMARD = 1 } srft_transform;
+int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int transform, uint64_t sign_seed,
+                        const float* lambda_host);
 
 /* Free the plan and its device tables.  NULL is accepted.  Work already enqueued must have finished. */
 int srft_plan_destroy(srft_plan_t* plan);

@@ -26,7 +26,7 @@ EXPORTS = [
     "srft_kv_channel_absmax", "srft_lambda_from_absmax",
     "srft_cache_create", "srft_cache_destroy", "srft_cache_append", "srft_cache_rebuild_view",
     "srft_cache_tokens", "srft_cache_quantized_tokens",
-    "srft_plan_create_bits", "srft_plan_bits",
+    "srft_plan_create_bits", "srft_plan_bits", "srft_plan_create_ex",
 ]
 
 
@@ -52,6 +52,7 @@ def lib() -> C.CDLL:
     vp, i64, u64, ci = C.c_void_p, C.c_int64, C.c_uint64, C.c_int
     L.srft_plan_create.argtypes = [C.POINTER(vp), ci, ci, u64, vp]
     L.srft_plan_create_bits.argtypes = [C.POINTER(vp), ci, ci, ci, u64, vp]
+    L.srft_plan_create_ex.argtypes = [C.POINTER(vp), ci, ci, ci, ci, u64, vp]
     L.srft_plan_bits.argtypes = [vp]
     L.srft_plan_destroy.argtypes = [vp]
     L.srft_kv_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
@@ -105,7 +106,10 @@ def _dev_ptr(t: torch.Tensor, dtype, name: str) -> int:
 
 
 # ---------------------------------------------------------------------------- C entry points
-def srft_plan_create(d: int, group_size: int, sign_seed: int, lam=None, bits: int = 4) -> int:
+TRANSFORMS = {"dft": 0, "hadamard": 1}
+
+
+def srft_plan_create(d: int, group_size: int, sign_seed: int, lam=None, bits: int = 4, transform: str = "dft") -> int:
     """Returns the opaque plan handle.  ``lam``: d positive floats (host) or None for all ones."""
     handle = C.c_void_p()
     lam_ptr = None
@@ -114,7 +118,10 @@ def srft_plan_create(d: int, group_size: int, sign_seed: int, lam=None, bits: in
         if lam_arr.shape != (d,):
             raise ValueError("lambda must have d entries")
         lam_ptr = lam_arr.ctypes.data_as(C.c_void_p)
-    if bits == 4:
+    if transform != "dft":
+        _check(lib().srft_plan_create_ex(C.byref(handle), d, group_size, bits, TRANSFORMS[transform],
+                                         sign_seed & (2 ** 64 - 1), lam_ptr), "srft_plan_create_ex")
+    elif bits == 4:
         _check(lib().srft_plan_create(C.byref(handle), d, group_size, sign_seed & (2 ** 64 - 1), lam_ptr),
                "srft_plan_create")
     else:
@@ -310,8 +317,9 @@ class Cache:
 class Plan:
     """One (layer, K|V) plan.  Allocates outputs with torch when none are passed; computes nothing itself."""
 
-    def __init__(self, d: int, group_size: int = 32, sign_seed: int = 0, lam=None, bits: int = 4):
-        self.handle = srft_plan_create(d, group_size, sign_seed, lam, bits)
+    def __init__(self, d: int, group_size: int = 32, sign_seed: int = 0, lam=None, bits: int = 4,
+                 transform: str = "dft"):
+        self.handle = srft_plan_create(d, group_size, sign_seed, lam, bits, transform)
         self.d, self.g, self.bits = d, group_size, bits
         self.groups = lib().srft_plan_groups(self.handle)
         self.code_bytes = lib().srft_plan_code_bytes(self.handle)

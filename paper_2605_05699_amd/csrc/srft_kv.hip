@@ -1210,6 +1210,11 @@ uint64_t splitmix64_next(uint64_t& state) {
 }
 
 // Q[k][n] of the packed unitary real DFT (Eq. 1-2), rfft sign convention.
+// Entry of the orthonormal Walsh-Hadamard matrix in natural order: (-1)^popcount(k & n) / sqrt(d).
+double hadamard_entry(int d, int k, int n) {
+    return (__builtin_popcount((unsigned)(k & n)) & 1 ? -1.0 : 1.0) / std::sqrt((double)d);
+}
+
 double q_entry(int d, int k, int n) {
     const int h = d / 2;
     const double pi = 3.14159265358979323846;
@@ -1230,7 +1235,7 @@ int slab_output_of_row(int i) {
 }  // namespace
 
 struct srft_plan {
-    int d = 0, g = 0, bits = 4, device = 0;
+    int d = 0, g = 0, bits = 4, transform = 0, device = 0;
     uint64_t seed = 0;
     std::vector<int8_t> signs;
     uint4* wfrag = nullptr;     // write-path matrix fragments (device)
@@ -1474,10 +1479,17 @@ int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_see
 
 int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, uint64_t sign_seed,
                           const float* lambda_host) {
+    return srft_plan_create_ex(out, d, group_size, bits, SRFT_TRANSFORM_DFT, sign_seed, lambda_host);
+}
+
+int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int transform, uint64_t sign_seed,
+                        const float* lambda_host) {
     if (!out) return SRFT_ERR_NULL;
     *out = nullptr;
     if (bits != 4 && bits != 8) return SRFT_ERR_BAD_BITS;
+    if (transform != SRFT_TRANSFORM_DFT && transform != SRFT_TRANSFORM_HADAMARD) return SRFT_ERR_BAD_TRANSFORM;
     if (d < 32 || d > kMaxD || d % 32 != 0) return SRFT_ERR_BAD_D;
+    if (transform == SRFT_TRANSFORM_HADAMARD && (d & (d - 1)) != 0) return SRFT_ERR_BAD_D;
     if (!(group_size == 16 || (group_size >= 32 && group_size % 32 == 0 && d % group_size == 0))) return SRFT_ERR_BAD_GROUP;
     std::vector<double> lam(d, 1.0);
     if (lambda_host) {
@@ -1497,6 +1509,7 @@ int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, ui
     p->d = d;
     p->g = group_size;
     p->bits = bits;
+    p->transform = transform;
     p->gm = group_size == 16 ? kGroup16 : (group_size == 32 ? kGroup32 : kGroupWide);
     p->gw = group_size <= 32 ? 1 : group_size / 32;
     p->seed = sign_seed;
@@ -1508,7 +1521,8 @@ int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, ui
     std::vector<double> W((size_t)d * d), R((size_t)d * d);
     for (int k = 0; k < d; ++k)
         for (int n = 0; n < d; ++n) {
-            const double q = q_entry(d, k, n) * (double)p->signs[n];
+            const double q = (transform == SRFT_TRANSFORM_HADAMARD ? hadamard_entry(d, k, n) : q_entry(d, k, n)) *
+                             (double)p->signs[n];
             W[(size_t)k * d + n] = lam[k] * q;
             R[(size_t)n * d + k] = q / std::fmax(lam[k], 1e-6);
         }
@@ -1545,7 +1559,8 @@ int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, ui
     p->slabs_q = default_slabs(d, "SRFT_SLABS_Q", d == 64 ? 2 : 1);
     p->slabs_dq = default_slabs(d, "SRFT_SLABS_DQ", (d == 256 || d == 64) ? 2 : 1);
     // Folded read path where it applies and pays (d = 128, 192, 256; g >= 32); SRFT_FOLD_DQ=0 turns it off (tuning).
-    p->fold_dq = (d % 64 == 0) && d >= 128 && p->gm != kGroup16;      // at d = 64 it gains nothing
+    p->fold_dq = (d % 64 == 0) && d >= 128 && p->gm != kGroup16 &&    // at d = 64 it gains nothing
+                 transform == SRFT_TRANSFORM_DFT;                      // (the symmetries are the DFT's)
     if (const char* e = std::getenv("SRFT_FOLD_DQ")) p->fold_dq = p->fold_dq && std::atoi(e) != 0;
     std::vector<uint16_t> rfold;
     if (p->fold_dq) {
@@ -1579,7 +1594,7 @@ int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, ui
             }
     }
     // Folded write path where it applies (d a multiple of 128, g = 32); SRFT_FOLD_Q=0 turns it off (tuning).
-    p->fold_q = (d % 128 == 0) && p->gm == kGroup32 && bits == 4;
+    p->fold_q = (d % 128 == 0) && p->gm == kGroup32 && bits == 4 && transform == SRFT_TRANSFORM_DFT;
     if (const char* e = std::getenv("SRFT_FOLD_Q")) p->fold_q = p->fold_q && std::atoi(e) != 0;
     std::vector<uint16_t> wfold;
     if (p->fold_q) {
@@ -1723,7 +1738,7 @@ static int run_batched(const srft_plan_t* const* plans, const void* const* in0, 
     for (int i = 0; i < count; ++i) {
         if (!plans[i]) return SRFT_ERR_NULL;
         if (plans[i]->d != plans[0]->d || plans[i]->g != plans[0]->g || plans[i]->bits != plans[0]->bits ||
-            plans[i]->device != plans[0]->device)
+            plans[i]->transform != plans[0]->transform || plans[i]->device != plans[0]->device)
             return SRFT_ERR_MISMATCH;
         if (n_vec[i] < 0 || n_vec[i] > kMaxVectors) return SRFT_ERR_BAD_N;
         if (n_vec[i] == 0) continue;
@@ -1782,7 +1797,7 @@ int srft_cache_create(srft_cache_t** out, const srft_plan_t* const* plans, int n
     for (int i = 0; i < n_plans; ++i) {
         if (!plans[i] || !codes_dev[i] || !scales_dev[i] || !view_f16_dev[i]) return SRFT_ERR_NULL;
         if (plans[i]->d != plans[0]->d || plans[i]->g != plans[0]->g || plans[i]->bits != plans[0]->bits ||
-            plans[i]->device != plans[0]->device)
+            plans[i]->transform != plans[0]->transform || plans[i]->device != plans[0]->device)
             return SRFT_ERR_MISMATCH;
         if (!aligned(codes_dev[i], 16) || !aligned(scales_dev[i], 4) || !aligned(view_f16_dev[i], 16))
             return SRFT_ERR_ALIGN;
@@ -1959,6 +1974,7 @@ const char* srft_status_string(int status) {
         case SRFT_ERR_BAD_N: return "negative or malformed size";
         case SRFT_ERR_MISMATCH: return "plans of one call must share d, group size, code width and device";
         case SRFT_ERR_BAD_BITS: return "unsupported code width (need 4 or 8 bits)";
+        case SRFT_ERR_BAD_TRANSFORM: return "unknown transform";
         default: return "unknown status";
     }
 }

@@ -27,7 +27,8 @@ OUT_FLOOR = 8e-6           # times max |ref| of the vector: fp32 accumulation ov
 FP16_TINY = 1.2e-7         # two fp16 subnormal quanta
 
 
-def check_quantize(x_f16: np.ndarray, s, lam, g, codes_gpu: np.ndarray, scales_gpu: np.ndarray, bits: int = 4) -> dict:
+def check_quantize(x_f16: np.ndarray, s, lam, g, codes_gpu: np.ndarray, scales_gpu: np.ndarray, bits: int = 4,
+                   form: str = "dense") -> dict:
     """x_f16 [n, d] float16; GPU outputs as numpy.  Raises AssertionError on any violation.
 
     A group is "cancellation-dominated" when its abs-max is below COND_MIN of what its lambdas and the
@@ -35,7 +36,7 @@ def check_quantize(x_f16: np.ndarray, s, lam, g, codes_gpu: np.ndarray, scales_g
     coefficients are rounding noise of the fp32 transform, relative agreement is not defined, and the
     group is held to the absolute checks only.  Random data has no such groups; the count is reported.
     """
-    ref = O.quantize(x_f16, s, lam, g, bits=bits)
+    ref = O.quantize(x_f16, s, lam, g, bits=bits, form=form)
     n, d = x_f16.shape
     G = d // g
     qmax = 2 ** (bits - 1) - 1
@@ -87,9 +88,10 @@ def out_tolerance(ref64: np.ndarray) -> np.ndarray:
     return OUT_RTOL * np.abs(ref64) + OUT_FLOOR * vmax + FP16_TINY
 
 
-def check_dequantize(codes: np.ndarray, scales: np.ndarray, s, lam, g, out_gpu: np.ndarray, bits: int = 4) -> dict:
+def check_dequantize(codes: np.ndarray, scales: np.ndarray, s, lam, g, out_gpu: np.ndarray, bits: int = 4,
+                     form: str = "dense") -> dict:
     """GPU read path on (codes, scales) against the oracle's read path on the same bytes."""
-    ref64 = O.dequantize_f64(codes, scales, s, lam, g, bits=bits)
+    ref64 = O.dequantize_f64(codes, scales, s, lam, g, bits=bits, form=form)
     ref16 = ref64.astype(np.float16)
     assert out_gpu.dtype == np.float16 and out_gpu.shape == ref16.shape
     assert np.isfinite(out_gpu.astype(np.float32)).all()

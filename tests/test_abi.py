@@ -35,10 +35,10 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_status_strings(L):
-    for code in range(0, -11, -1):
+    for code in range(0, -12, -1):
         assert L.srft_status_string(code)
-    known = {L.srft_status_string(code) for code in range(0, -10, -1)}
-    assert len(known) == 10 and L.srft_status_string(-10) not in known     # -9 is the last defined status
+    known = {L.srft_status_string(code) for code in range(0, -11, -1)}
+    assert len(known) == 11 and L.srft_status_string(-11) not in known     # -10 is the last defined status
     assert L.srft_status_string(0) == b"ok"
 
 
@@ -55,6 +55,8 @@ def test_plan_create_rejects_bad_arguments_before_any_hip_call(L):
         assert L.srft_plan_create_bits(C.byref(h), 128, 32, bits, 0, None) == -9, bits
     assert L.srft_plan_create_bits(C.byref(h), 100, 32, 8, 0, None) == -2
     assert L.srft_plan_bits(None) == -1
+    assert L.srft_plan_create_ex(C.byref(h), 128, 32, 4, 7, 0, None) == -10
+    assert L.srft_plan_create_ex(C.byref(h), 96, 32, 4, 1, 0, None) == -2      # Hadamard needs a power of two
     for bad in (0.0, -1.0, float("nan"), float("inf")):
         lam[17] = bad
         assert L.srft_plan_create(C.byref(h), 128, 32, 0, lam) == -4, bad
