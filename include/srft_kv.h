@@ -95,7 +95,7 @@ int srft_plan_destroy(srft_plan_t* plan);
  *   x_f16_dev   [n_vec, d] row-major IEEE fp16, 16-byte aligned.        read only
  *   codes_dev   [n_vec, d/2] bytes ([n_vec, d] for an 8-bit plan), 16-byte aligned.   written
  *   scales_dev  [n_vec, d/g] fp32, 4-byte aligned.                      written
- * n_vec == 0 is a successful no-op.  Inputs must be finite.  A group whose abs-max / 7 is below
+ * n_vec == 0 is a successful no-op; n_vec > 2^33 is SRFT_ERR_BAD_N (tile indices are 32-bit).  Inputs must be finite.  A group whose abs-max / 7 is below
  * 2^-100 is stored as scale 0 with all-zero codes.
  */
 int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec,

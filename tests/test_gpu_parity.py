@@ -242,6 +242,12 @@ def test_argument_errors_on_device_pointers(B):
     assert L.srft_kv_quantize(plan.handle, x.data_ptr(), -1, codes.data_ptr(), scales.data_ptr(), None) == -7
     assert L.srft_kv_dequantize(plan.handle, codes.data_ptr(), scales.data_ptr(), 8, x.data_ptr() + 2, None) == -5
     assert L.srft_kv_dequantize(None, codes.data_ptr(), scales.data_ptr(), 8, x.data_ptr(), None) == -1
+    # more vectors than the kernels' 32-bit tile indices cover (2^33) are refused before anything is launched
+    too_many = 2 ** 33 + 1
+    assert L.srft_kv_quantize(plan.handle, x.data_ptr(), too_many, codes.data_ptr(), scales.data_ptr(), None) == -7
+    assert L.srft_kv_dequantize(plan.handle, codes.data_ptr(), scales.data_ptr(), too_many, x.data_ptr(), None) == -7
+    assert L.srft_kv_forward_f32(plan.handle, x.data_ptr(), too_many, scales.data_ptr(), None) == -7
+    torch.cuda.synchronize()
     plan.close()
 
 
