@@ -596,11 +596,20 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     to_lds(0, pa0, pa1, pa2, pa3);
     fetch(pa0, pa1, pa2, pa3, t0 + 2 * stride);
     if constexpr (LEAN) {
-        // One accumulator set: a tile is contracted and quantized in the same stage, with a second barrier
-        // between the two for the exchange values; two workgroups per compute unit overlap each other.
-        for (int k = 0; k < m; ++k) {
+        // One accumulator set.  Stage k: barrier; quantize T_{k-1} out of the accumulators (its exchange values,
+        // in xch[(k-1) & 1], became visible with the barrier); contract T_k into them; fill LDS for T_{k+1};
+        // publish T_k's exchange values into xch[k & 1].  Within a wavefront the two halves do not overlap; two
+        // workgroups per compute unit overlap each other.
+        __syncthreads();                         // stage 0: nothing to quantize yet
+        contract(0, ea, oa);
+        to_lds(1, pb0, pb1, pb2, pb3);
+        fetch(pb0, pb1, pb2, pb3, t0 + 3 * stride);
+        publish(0, ea, oa);
+        for (int k = 1; k < m; ++k) {
             const int tk = t0 + k * stride;
-            __syncthreads();                     // T_k is in lds[k % 2]; everyone is done with xch
+            __syncthreads();
+            finish((k - 1) & 1, ea, oa, tk - stride);
+            __builtin_amdgcn_sched_barrier(0);   // no second accumulator set: the tail ends before the MFMAs begin
             contract(k & 1, ea, oa);
             if (k & 1) {
                 to_lds(0, pa0, pa1, pa2, pa3);
@@ -609,10 +618,10 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
                 to_lds(1, pb0, pb1, pb2, pb3);
                 fetch(pb0, pb1, pb2, pb3, tk + 3 * stride);
             }
-            publish(0, ea, oa);
-            __syncthreads();
-            finish(0, ea, oa, tk);
+            publish(k & 1, ea, oa);
         }
+        __syncthreads();
+        finish((m - 1) & 1, ea, oa, t0 + (m - 1) * stride);
         return;
     }
     // stage 0
