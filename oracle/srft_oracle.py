@@ -35,6 +35,10 @@ What each function follows:
 * ``hadamard_matrix``      -- the SRHT the paper compares against (Sec. 1,
                               Sec. 3.1): ``form="hadamard"`` swaps it in for Q
                               everywhere.
+* ``attention_scores``     -- the consumer of the stored keys (Sec. 1, "each decode
+                              step streams the stored prefix ... before attention
+                              can read it"): inner products of queries with the
+                              reconstructed keys, written as exactly that.
 * ``channel_absmax`` /
   ``lambda_from_absmax``   -- Sec. 7.1: lambda_d = 1 / per_channel_max(SRFT
                               output)_d, the maximum taken over a calibration
@@ -342,4 +346,14 @@ def lambda_from_absmax(amax) -> np.ndarray:
     if top <= 0.0:
         return np.ones_like(a)
     return 1.0 / np.maximum(a, top * 2.0 ** -16)
+
+
+def attention_scores(q_f16, codes, scales, s, lam, g: int, form: str = "dense", bits: int = 4) -> np.ndarray:
+    """scores[i, t] = <q_i, k_t>, k_t the read path's reconstruction of key t before its fp16 rounding; float64
+    [n_q, n_keys].  The plain definition: reconstruct every key, take the inner products.  (A kernel may use the
+    orthogonality of the transform and contract in the rotated domain instead; the result is the same number.)
+    """
+    q = np.asarray(q_f16).astype(np.float64)
+    keys = dequantize_f64(codes, scales, s, lam, g, form=form, bits=bits)
+    return q @ keys.T
 

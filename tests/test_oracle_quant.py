@@ -336,3 +336,34 @@ def test_int8_near_ties_and_per_token_case():
     ratio = zz / scale.astype(np.float64)[:, None]
     near_tie = np.abs(np.abs(ratio % 1.0) - 0.5) < 1e-9
     assert np.array_equal(out["q"][~near_tie], np.rint(ratio)[~near_tie].astype(np.int8))
+
+
+# ----------------------------------------------------------------------------- scores against the stored keys
+def test_attention_scores_by_loops_and_in_the_rotated_domain():
+    d, g, n_q, n_k = 32, 16, 3, 17
+    rng = np.random.RandomState(12)
+    keys = rng.standard_normal((n_k, d)).astype(np.float16)
+    q = rng.standard_normal((n_q, d)).astype(np.float16)
+    s = O.signs_from_seed(8, d)
+    lam = np.exp(0.4 * rng.standard_normal(d)).astype(np.float32)
+    rec = O.quantize(keys, s, lam, g)
+    got = O.attention_scores(q, rec["codes"], rec["scales"], s, lam, g)
+    assert got.shape == (n_q, n_k)
+    # (a) element by element from the reconstruction, in plain loops
+    back = O.dequantize_f64(rec["codes"], rec["scales"], s, lam, g)
+    for i in range(n_q):
+        for t in range(n_k):
+            assert abs(got[i, t] - sum(float(q[i, n]) * back[t, n] for n in range(d))) < 1e-12
+    # (b) orthogonality: the same numbers from the rotated domain, without ever forming the keys:
+    #     <q, s * Q^T z> = <Q (s * q), z>,  z_p = code_p * scale / max(lambda_p, 1e-6)
+    zq = O.srft_forward(q, s)
+    z = (rec["q"].astype(np.float64).reshape(n_k, d // g, g) * rec["scales"].astype(np.float64)[..., None]).reshape(n_k, d)
+    z = z / np.maximum(lam.astype(np.float64), 1e-6)
+    assert np.allclose(got, zq @ z.T, rtol=1e-12, atol=1e-12)
+    # (c) and they approximate the exact scores as well as 4 bits allow; 8 bits do better
+    exact = q.astype(np.float64) @ keys.astype(np.float64).T
+    bound = 0.25 * np.linalg.norm(q.astype(np.float64), axis=1).max() * np.linalg.norm(keys.astype(np.float64), axis=1).max()
+    assert np.abs(got - exact).max() < bound
+    rec8 = O.quantize(keys, s, lam, g, bits=8)
+    got8 = O.attention_scores(q, rec8["codes"], rec8["scales"], s, lam, g, bits=8)
+    assert np.abs(got8 - exact).max() < np.abs(got - exact).max()
