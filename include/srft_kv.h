@@ -142,6 +142,23 @@ int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t 
                         float* w_f32_dev, void* hip_stream);
 
 /*
+ * Scores of queries against stored keys, without reconstructing the keys.    (Sec. 1: the decode step streams the
+ * stored prefix before attention reads it; Eq. 1 and the sentence after Eq. 2: the transform is orthogonal.)
+ *     scores[i][t] = < q_i , k_t >,   k_t the read path's reconstruction of key t (before its fp16 rounding)
+ * computed as < Q (s * q_i) / max(lambda, 1e-6) , code_t * scale_t >: only the record of the keys is read.
+ *   q_f16_dev      [n_q, d] fp16, 16-byte aligned, 1 <= n_q <= 32 (e.g. the query heads sharing one KV head).
+ *   codes_dev      [n_keys, d/2] bytes, 16-byte aligned;  scales_dev [n_keys, d/g] fp32: the plan's record.
+ *   scores_dev     [n_q, n_keys] fp32, row-major, written.
+ *   workspace_dev  srft_scores_workspace_bytes(plan) bytes of device memory, 16-byte aligned, overwritten.
+ * For plans with d a multiple of 64, 4-bit codes and g >= 32 (else SRFT_ERR_BAD_D / _BAD_BITS / _BAD_GROUP).
+ * Enqueues three small-to-large kernels on the stream: transform of the queries, operand set-up, the scan.
+ */
+int64_t srft_scores_workspace_bytes(const srft_plan_t* plan);
+int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
+                   const float* scales_dev, int64_t n_keys, float* scores_dev, void* workspace_dev,
+                   void* hip_stream);
+
+/*
  * Cache manager: int4 store + fp16 residual window + dequantized-prefix cache.   (Sec. 7.2: the cache class,
  * items (i)-(iv); the "Residual window" paragraph: 16 tokens.)
  *

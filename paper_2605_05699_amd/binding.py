@@ -27,6 +27,7 @@ EXPORTS = [
     "srft_cache_create", "srft_cache_destroy", "srft_cache_append", "srft_cache_rebuild_view",
     "srft_cache_tokens", "srft_cache_quantized_tokens",
     "srft_plan_create_bits", "srft_plan_bits", "srft_plan_create_ex",
+    "srft_scores_workspace_bytes", "srft_kv_scores",
 ]
 
 
@@ -64,6 +65,8 @@ def lib() -> C.CDLL:
     L.srft_cache_rebuild_view.argtypes = [vp, vp]
     L.srft_cache_tokens.argtypes = [vp]
     L.srft_cache_quantized_tokens.argtypes = [vp]
+    L.srft_scores_workspace_bytes.argtypes = [vp]
+    L.srft_kv_scores.argtypes = [vp, vp, ci, vp, vp, i64, vp, vp, vp]
     L.srft_kv_channel_absmax.argtypes = [vp, vp, i64, vp, vp]
     L.srft_lambda_from_absmax.argtypes = [vp, ci, vp]
     L.srft_kv_quantize_batched.argtypes = [vp, vp, vp, vp, vp, ci, vp]
@@ -80,6 +83,7 @@ def lib() -> C.CDLL:
     for name in EXPORTS:
         if name != "srft_status_string":
             getattr(L, name).restype = ci
+    L.srft_scores_workspace_bytes.restype = i64
     L.srft_cache_tokens.restype = i64
     L.srft_cache_quantized_tokens.restype = i64
     _lib = L
@@ -195,6 +199,19 @@ def srft_kv_forward_f32(plan: int, x: torch.Tensor, w: torch.Tensor, stream=None
     _check(lib().srft_kv_forward_f32(plan, _dev_ptr(x, torch.float16, "x"), x.shape[0],
                                      _dev_ptr(w, torch.float32, "w"), _stream_handle(stream)),
            "srft_kv_forward_f32")
+
+
+def srft_kv_scores(plan: int, q: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, scores: torch.Tensor,
+                   workspace: torch.Tensor, stream=None) -> None:
+    """scores [n_q, n_keys] fp32 <- inner products of q [n_q, d] with the keys stored as (codes, scales)."""
+    if workspace.numel() * workspace.element_size() < lib().srft_scores_workspace_bytes(plan):
+        raise ValueError("workspace too small")
+    if scores.shape != (q.shape[0], codes.shape[0]):
+        raise ValueError("scores must be [n_q, n_keys]")
+    _check(lib().srft_kv_scores(plan, _dev_ptr(q, torch.float16, "q"), q.shape[0], _dev_ptr(codes, torch.uint8, "codes"),
+                                _dev_ptr(scales, torch.float32, "scales"), codes.shape[0],
+                                _dev_ptr(scores, torch.float32, "scores"), workspace.data_ptr(),
+                                _stream_handle(stream)), "srft_kv_scores")
 
 
 def srft_kv_channel_absmax(plan: int, x: torch.Tensor, amax: torch.Tensor, stream=None) -> None:
@@ -352,6 +369,14 @@ class Plan:
         if out is None:
             out = torch.empty(codes.shape[0], self.d, dtype=torch.float16, device=codes.device)
         srft_kv_dequantize(self.handle, codes, scales, out, stream)
+        return out
+
+    def scores(self, q, codes, scales, out=None, workspace=None, stream=None):
+        if out is None:
+            out = torch.empty(q.shape[0], codes.shape[0], dtype=torch.float32, device=q.device)
+        if workspace is None:
+            workspace = torch.empty(lib().srft_scores_workspace_bytes(self.handle), dtype=torch.uint8, device=q.device)
+        srft_kv_scores(self.handle, q, codes, scales, out, workspace, stream)
         return out
 
     def channel_absmax(self, x, amax=None, stream=None):

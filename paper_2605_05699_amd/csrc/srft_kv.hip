@@ -1119,6 +1119,131 @@ srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
                                     a.first_block[i + 1] - a.first_block[i]);
 }
 
+// ------------------------------------------------------------------------------------------
+// scores against the stored keys, in the rotated domain
+// ------------------------------------------------------------------------------------------
+// <q, k_t> with k_t = s * Q^T (code * scale / lambda) equals <q', code * scale> with q' = Q (s * q) / lambda:
+// the transform is orthogonal, so the keys never have to be reconstructed; the kernel reads the 4-bit record
+// only (d/2 + 4 d/g bytes per key instead of the 2d of a dequantized prefix) and writes n_q floats per key.
+//
+// Up to 32 queries are the 32 rows of the MFMA A operand (hi + lo fp16 of q', in registers for the whole
+// launch), the keys are the columns: the read path with the queries in place of the matrix.  One wavefront
+// per workgroup, each walking its own tiles of 32 keys: codes are loaded coalesced, decoded into LDS (which
+// transposes them into B fragments), contracted group by group and folded with the group scales.
+//
+// Step 1 (srft_scores_prepare_kernel): q' from w = lambda * Q (s * q), which the write path's kernel computes
+// in its raw mode: q' = w / (lambda * max(lambda, 1e-6)), split into fp16 hi + lo, laid out as A fragments
+// [d/32 groups][2 k-steps][hi, lo][64 lanes]; MFMA row i carries query slab_output(i), so that lane half h,
+// register v holds query 16h + v.
+template <int D>
+__global__ void __launch_bounds__(64)
+srft_scores_prepare_kernel(const float* __restrict__ wq, const float* __restrict__ inv_lam2, int n_q,
+                           uint4* __restrict__ qfrag) {
+    constexpr int G = D / 32;
+    const int lane = threadIdx.x, i = lane & 31, kh = lane >> 5;
+    const int qi = 16 * ((i / 4) % 2) + 4 * (i / 8) + i % 4;             // query carried by MFMA row i
+#pragma unroll 1
+    for (int f = 0; f < 2 * G; ++f) {                                    // k-step f = 2 j + t: codes 16 f .. 16 f + 15
+        half8 hi, lo;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int p = 8 * (2 * f + kh) + (e / 2) + 4 * (e % 2);      // the 4-bit decode order of the read path
+            const float v = qi < n_q ? wq[qi * D + p] * inv_lam2[p] : 0.0f;
+            hi[e] = (_Float16)v;
+            lo[e] = (_Float16)(v - (float)hi[e]);
+        }
+        qfrag[(f * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
+        qfrag[(f * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
+    }
+}
+
+// Step 2.  codes [n_keys][D/16] 8-byte units, scales [n_keys][ns], out [n_q][n_keys] fp32.
+template <int D>
+__global__ void __launch_bounds__(64)
+srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ codes, const float* __restrict__ scales,
+                   long long n_keys, float* __restrict__ out, int n_q, int gw) {
+    constexpr int G = D / 32, U = D / 8, ROW = U + 1, C = D / 16;
+    constexpr int PER = C / 2;           // 8-byte code units per lane and tile (32 C units, 64 lanes)
+    constexpr int SROW = G + 1;
+    constexpr int PS = (32 * G + 63) / 64;
+    static_assert(D % 64 == 0, "whole code units per lane");
+    __shared__ uint4 dec[2][kTileVecs * ROW];
+    __shared__ float scl[2][kTileVecs * SROW];
+    const int lane = threadIdx.x, col = lane & 31, half = lane >> 5;
+    const int ns = G / gw;
+    const int n_tiles = (int)((n_keys + kTileVecs - 1) / kTileVecs);
+    const int last_lim = (int)(n_keys - 1 - (long long)(n_tiles - 1) * kTileVecs);
+
+    half8 qhi[2 * G], qlo[2 * G];
+#pragma unroll
+    for (int f = 0; f < 2 * G; ++f) {
+        qhi[f] = __builtin_bit_cast(half8, qfrag[(f * 2 + 0) * 64 + lane]);
+        qlo[f] = __builtin_bit_cast(half8, qfrag[(f * 2 + 1) * 64 + lane]);
+    }
+    uint2 pc[PER];
+    float ps[PS];
+    auto fetch = [&](int tile) __attribute__((always_inline)) {
+        if (tile > n_tiles - 1) tile = n_tiles - 1;
+        const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
+        const uint2* cb = codes + (long long)tile * kTileVecs * C;
+        const float* sb = scales + (long long)tile * kTileVecs * ns;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int u = lane + 64 * i, r = u / C, c = u % C;
+            pc[i] = stream_load(&cb[(unsigned)(min(r, lim) * C + c)]);
+        }
+#pragma unroll
+        for (int i = 0; i < PS; ++i) {
+            int e = lane + 64 * i;
+            if (e > 32 * ns - 1) e = 32 * ns - 1;
+            ps[i] = sb[(unsigned)(min(e / ns, lim) * ns + e % ns)];
+        }
+    };
+    auto to_lds = [&](int b) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int u = lane + 64 * i, r = u / C, c = u % C;
+            dec[b][r * ROW + 2 * c] = decode8(pc[i].x);
+            dec[b][r * ROW + 2 * c + 1] = decode8(pc[i].y);
+        }
+#pragma unroll
+        for (int i = 0; i < PS; ++i) {
+            const int e = lane + 64 * i;
+            if (e < 32 * ns) scl[b][(e / ns) * SROW + e % ns] = ps[i];
+        }
+    };
+    const int m = (n_tiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1;   // the grid never exceeds the tiles
+    fetch(blockIdx.x);
+    hold_in_registers(qhi, qlo);
+    for (int k = 0; k < m; ++k) {
+        const int tile = blockIdx.x + k * gridDim.x, b = k & 1;
+        to_lds(b);
+        fetch(tile + gridDim.x);
+        __syncthreads();                         // one wavefront: orders the LDS writes before the reads
+        floatx16 o = {0};
+        const uint4* rowp = &dec[b][col * ROW + half];
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            floatx16 acc = {0};
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const half8 bf = __builtin_bit_cast(half8, rowp[2 * (2 * j + t)]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(qhi[2 * j + t], bf, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(qlo[2 * j + t], bf, acc, 0, 0, 0);
+            }
+            const float sc = scl[b][col * SROW + j / gw];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[v] = fmaf(acc[v], sc, o[v]);
+        }
+        const long long key = (long long)tile * kTileVecs + col;
+        if (key < n_keys) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (16 * half + v < n_q) out[(long long)(16 * half + v) * n_keys + key] = o[v];
+        }
+    }
+}
+
 // Cache append: the new tokens of every plan, [n_seq][t][units] 16-byte units each, go to their place in the paged
 // fp16 view [block][n_seq][R][units]: token pos0 + j of sequence q lands in block (pos0 + j) / R, slot (pos0 + j) % R.
 // a.in0[p] / a.out0[p] are plan p's new tokens and view.  A few kilobytes per step: one thread per unit.
@@ -1251,6 +1376,8 @@ struct srft_plan {
     uint4* rfrag = nullptr;     // read-path matrix fragments (device)
     uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
     uint4* wfold = nullptr;     // write-path fragments of the folded form (device), when fold_q
+    float* inv_lam2 = nullptr;  // 1 / (lambda * max(lambda, 1e-6)) per channel (device): scores in the rotated domain
+    int grid_scores = 0;        // persistent grid of the scores kernel
     bool fold_dq = false;       // read path contracts even and odd codes separately (half the matrix work)
     bool fold_q = false;        // write path contracts even and odd inputs separately (half the matrix work)
     float unscale_w = 1.0f;     // 2^-e of the write matrix
@@ -1324,6 +1451,11 @@ int occupancy_grids(srft_plan* p, int cus) {
                                                           2 * D / p->slabs_dq, 0));
     p->grid_q = cus * (bq > 0 ? bq : 1);
     p->grid_dq = cus * (bd > 0 ? bd : 1);
+    if constexpr (D % 64 == 0) {
+        int bs = 0;
+        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bs, srft_scores_kernel<D>, 64, 0));
+        p->grid_scores = cus * (bs > 0 ? bs : 1);
+    }
     return SRFT_OK;
 }
 
@@ -1436,7 +1568,29 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
         default:  return SRFT_ERR_BAD_D;                  \
     }
 
+template <int D>
+int launch_scores(const srft_plan* p, const float* wq, uint4* qfrag, int n_q, const uint8_t* codes, const float* scales,
+                  long long n_keys, float* out, hipStream_t st) {
+    if constexpr (D % 64 == 0) {
+        hipLaunchKernelGGL(srft_scores_prepare_kernel<D>, dim3(1), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
+        SRFT_HIP(hipGetLastError());
+        const long long n_tiles = (n_keys + kTileVecs - 1) / kTileVecs;
+        long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_scores;
+        if (grid > n_tiles) grid = n_tiles;
+        hipLaunchKernelGGL(srft_scores_kernel<D>, dim3((unsigned)grid), dim3(64), 0, st, (const uint4*)qfrag,
+                           (const uint2*)codes, scales, n_keys, out, n_q, p->gw);
+        SRFT_HIP(hipGetLastError());
+        return SRFT_OK;
+    } else {
+        return SRFT_ERR_BAD_D;
+    }
+}
+
 int dispatch_occupancy(srft_plan* p, int cus) { SRFT_DISPATCH_D(p->d, occupancy_grids, p, cus) }
+int dispatch_scores(const srft_plan* p, const float* wq, uint4* qfrag, int n_q, const uint8_t* c, const float* s,
+                    long long n, float* o, hipStream_t st) {
+    SRFT_DISPATCH_D(p->d, launch_scores, p, wq, qfrag, n_q, c, s, n, o, st)
+}
 int dispatch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* c, float* s, float* w, int out,
                       hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_quantize, p, x, n, c, s, w, out, st) }
 int dispatch_dequantize(const srft_plan* p, const uint8_t* c, const float* s, long long n, void* o,
@@ -1652,6 +1806,10 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     if (e == hipSuccess) e = hipMalloc((void**)&p->rfrag, rf.size() * 2);
     if (e == hipSuccess) e = hipMemcpy(p->wfrag, wf.data(), wf.size() * 2, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(p->rfrag, rf.data(), rf.size() * 2, hipMemcpyHostToDevice);
+    std::vector<float> il2(d);
+    for (int k = 0; k < d; ++k) il2[k] = (float)(1.0 / (lam[k] * std::fmax(lam[k], 1e-6)));
+    if (e == hipSuccess) e = hipMalloc((void**)&p->inv_lam2, d * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(p->inv_lam2, il2.data(), d * sizeof(float), hipMemcpyHostToDevice);
     if (e == hipSuccess && p->fold_q) e = hipMalloc((void**)&p->wfold, wfold.size() * 2);
     if (e == hipSuccess && p->fold_q) e = hipMemcpy(p->wfold, wfold.data(), wfold.size() * 2, hipMemcpyHostToDevice);
     if (e == hipSuccess && p->fold_dq) e = hipMalloc((void**)&p->rfold, rfold.size() * 2);
@@ -1673,6 +1831,10 @@ int srft_plan_destroy(srft_plan_t* plan) {
     if (plan->wfold) {
         const hipError_t e4 = hipFree(plan->wfold);
         if (e3 == hipSuccess) e3 = e4;
+    }
+    if (plan->inv_lam2) {
+        const hipError_t e5 = hipFree(plan->inv_lam2);
+        if (e3 == hipSuccess) e3 = e5;
     }
     delete plan;
     if (e1 != hipSuccess) return hip_fail(e1);
@@ -1709,6 +1871,32 @@ int srft_kv_channel_absmax(const srft_plan_t* plan, const void* x_f16_dev, int64
     if (!x_f16_dev || !amax_dev) return SRFT_ERR_NULL;
     if (!aligned(x_f16_dev, 16) || !aligned(amax_dev, 4)) return SRFT_ERR_ALIGN;
     return dispatch_quantize(plan, x_f16_dev, n_vec, nullptr, nullptr, amax_dev, kOutAmax, (hipStream_t)hip_stream);
+}
+
+int64_t srft_scores_workspace_bytes(const srft_plan_t* plan) {
+    if (!plan) return SRFT_ERR_NULL;
+    // w of up to 32 queries (fp32), then their A fragments: d/16 k-steps x (hi, lo) x 64 lanes x 16 bytes
+    return (int64_t)32 * plan->d * 4 + (int64_t)(plan->d / 16) * 2 * 64 * 16;
+}
+
+int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
+                   const float* scales_dev, int64_t n_keys, float* scores_dev, void* workspace_dev, void* hip_stream) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (plan->d % 64 != 0) return SRFT_ERR_BAD_D;
+    if (plan->bits != 4) return SRFT_ERR_BAD_BITS;
+    if (plan->gm == kGroup16) return SRFT_ERR_BAD_GROUP;
+    if (n_q < 1 || n_q > 32 || n_keys < 0 || n_keys > kMaxVectors) return SRFT_ERR_BAD_N;
+    if (n_keys == 0) return SRFT_OK;
+    if (!q_f16_dev || !codes_dev || !scales_dev || !scores_dev || !workspace_dev) return SRFT_ERR_NULL;
+    if (!aligned(q_f16_dev, 16) || !aligned(codes_dev, 16) || !aligned(scales_dev, 4) || !aligned(scores_dev, 4) ||
+        !aligned(workspace_dev, 16))
+        return SRFT_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    float* wq = (float*)workspace_dev;
+    uint4* qfrag = (uint4*)((char*)workspace_dev + (size_t)32 * plan->d * 4);
+    const int rc = dispatch_quantize(plan, q_f16_dev, n_q, nullptr, nullptr, wq, kOutRaw, st);
+    if (rc != SRFT_OK) return rc;
+    return dispatch_scores(plan, wq, qfrag, n_q, codes_dev, scales_dev, n_keys, scores_dev, st);
 }
 
 int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host) {

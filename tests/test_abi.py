@@ -88,6 +88,8 @@ def test_null_plan_and_size_errors(L):
     amax[1] = float("nan")
     assert L.srft_lambda_from_absmax(amax, 4, lam) == -4
     assert L.srft_kv_channel_absmax(None, None, 1, None, None) == -1
+    assert L.srft_kv_scores(None, None, 1, None, None, 1, None, None, None) == -1
+    assert L.srft_scores_workspace_bytes(None) == -1
     # cache manager: argument checks need no GPU (and no plan: a NULL plan entry is caught first)
     h = C.c_void_p()
     one = (C.c_void_p * 1)(None)
