@@ -49,6 +49,9 @@ def main() -> int:
     ap.add_argument("--decode-append", action="store_true",
                     help="also time the decode-step append of the decode-d96 workload: a launch per plan against "
                          "one batched launch")
+    ap.add_argument("--scores", action="store_true",
+                    help="also time srft_kv_scores (8 queries against plan 0's stored keys, read from the int4 record) "
+                         "beside dequantizing those keys")
     ap.add_argument("--power", action="store_true",
                     help="also run each path, and the streaming kernel with its byte mix, for about 3 s each while "
                          "sampling socket power and shader clock with amd-smi")
@@ -190,6 +193,29 @@ def main() -> int:
             "stream_dequantize_mix": sampled_phase(
                 torch, lambda: B.srft_stream_mix(xa, xb, tiles, small, big, 768, stream), tiles * (big + small)),
         }
+    if args.scores:
+        n_q = 8
+        q = W.make_kv(w, 1, n_vec=n_q, device=dev)
+        sc_out = torch.empty(n_q, n, dtype=torch.float32, device=dev)
+        ws = torch.empty(B.lib().srft_scores_workspace_bytes(h[0]), dtype=torch.uint8, device=dev)
+        B.srft_kv_quantize(h[0], x[0], codes[0], scales[0], stream)
+
+        def timed(fn, iters=20):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(iters):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / iters * 1e-3
+        ts = timed(lambda: B.srft_kv_scores(h[0], q, codes[0], scales[0], sc_out, ws, stream))
+        tdq = timed(lambda: B.srft_kv_dequantize(h[0], codes[0], scales[0], out[0], stream))
+        rec_bytes = d // 2 + 4 * G
+        result["scores"] = {"queries": n_q, "keys": n, "us": ts * 1e6, "keys_per_s": n / ts,
+                            "GBps_record_plus_scores": n * (rec_bytes + 4 * n_q) / ts / 1e9,
+                            "dequantize_same_keys_us": tdq * 1e6}
     if args.decode_append:
         result["decode_append"] = decode_append(B, W, torch, dev, stream)
     if args.copy_bytes:
