@@ -406,12 +406,15 @@ srft_quantize_kernel(const uint4* __restrict__ wfrag, const uint4* __restrict__ 
 // A tile's exchange values are written at the end of the stage that contracts it and read after the next
 // barrier, in the stage that quantizes it.
 //
+// BITS: 4 or 8, as on the plain path.  WIDE: g = 32 gw with gw >= 2, up to the per-token case g = d: the maxima
+// of the 32-runs meet in LDS (gmax), which costs one more barrier per tile, in the middle of the stage.
+//
 // wfold : [d/64 waves][E, O][d/32 k-steps][hi, lo][64 lanes] fragments, then [d/64 waves][64 lanes][4] x 4 floats rho
-template <int D>
+template <int D, int BITS, bool WIDE>
 __device__ __forceinline__ void
 srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
                          uint2* __restrict__ codes, float* __restrict__ scales, float unscale, float scale_mul,
-                         const int t0, const int stride) {
+                         int gw, const int t0, const int stride) {
     constexpr int M = D / 64;            // wavefronts per workgroup
     constexpr int G = D / 32;            // groups per vector
     constexpr int T = D / 32;            // k-steps per slab (K = D / 2)
@@ -423,6 +426,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     static_assert(M % 2 == 0, "the cosine and the sine block each need whole wavefronts");
     __shared__ uint4 lds[2][kTileVecs * ROW];
     __shared__ float xch[2][(DUMMY + 1) * kTileVecs];
+    __shared__ float gmax[WIDE ? 2 : 1][WIDE ? kTileVecs * G : 1];     // maxima of the 32-runs of a tile (WIDE)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -538,6 +542,12 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         for (int i = 0; i < 8; ++i) k += kMagicBits << (4 * i);
         return (p - k) ^ 0x88888888u;
     };
+    auto pack4v = [&](float f0, float f1, float f2, float f3, float inv) __attribute__((always_inline)) {
+        constexpr float kMagic = 12582912.0f;    // q mod 256 in the low byte of the bit pattern
+        const uint32_t a = __float_as_uint(fmaf(f0, inv, kMagic)), b2 = __float_as_uint(fmaf(f1, inv, kMagic));
+        const uint32_t c2 = __float_as_uint(fmaf(f2, inv, kMagic)), d2 = __float_as_uint(fmaf(f3, inv, kMagic));
+        return (__builtin_amdgcn_perm(d2, c2, 0x0c0c0400u) << 16) | __builtin_amdgcn_perm(b2, a, 0x0c0c0400u);
+    };
     auto scale_of = [&](float m, float& scale, float& inv) __attribute__((always_inline)) {
         scale = m * scale_mul;
         inv = unscale * __builtin_amdgcn_rcpf(scale);
@@ -570,20 +580,49 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         }
         md = other_half_max(md);
         mm = other_half_max(mm);
+        if constexpr (WIDE) {                    // the runs of one group meet in LDS (buffer b: free since stage k - 2)
+            gmax[b][col * G + base_d / 32] = md;
+            gmax[b][col * G + slot_in] = mm;
+            __syncthreads();
+            const int jd = base_d / 32 / gw * gw, jm = slot_in / gw * gw;
+            md = gmax[b][col * G + jd];
+            mm = gmax[b][col * G + jm];
+            for (int i = 1; i < gw; ++i) {
+                md = fmaxf(md, gmax[b][col * G + jd + i]);
+                mm = fmaxf(mm, gmax[b][col * G + jm + i]);
+            }
+        }
         float sd, id, sm, im;
         scale_of(md, sd, id);
         scale_of(mm, sm, im);
-        uint2 pd, pm;
-        pd.x = pack8v(dv[0], dv[1], dv[2], dv[3], dv[4], dv[5], dv[6], dv[7], id);
-        pd.y = pack8v(dv[8], dv[9], dv[10], dv[11], dv[12], dv[13], dv[14], dv[15], id);
-        pm.x = pack8v(bottom, mv[15], mv[14], mv[13], mv[12], mv[11], mv[10], mv[9], im);
-        pm.y = pack8v(mv[8], mv[7], mv[6], mv[5], mv[4], mv[3], mv[2], mv[1], im);
-        uint2* crow = codes + row0 * (D / 16);
-        crow[(unsigned)(c * (D / 16) + base_d / 16 + half)] = pd;
-        crow[(unsigned)(c * (D / 16) + p_top / 16 - 1 - half)] = pm;
-        float* srow = scales + row0 * G;
-        srow[(unsigned)(c * G + base_d / 32)] = sd;          // both halves store the same value
-        srow[(unsigned)(c * G + slot_in)] = sm;
+        if constexpr (BITS == 8) {               // 16 values = 16 bytes: the same unit indices, in 16-byte units
+            const uint4 pd = make_uint4(pack4v(dv[0], dv[1], dv[2], dv[3], id), pack4v(dv[4], dv[5], dv[6], dv[7], id),
+                                        pack4v(dv[8], dv[9], dv[10], dv[11], id), pack4v(dv[12], dv[13], dv[14], dv[15], id));
+            const uint4 pm = make_uint4(pack4v(bottom, mv[15], mv[14], mv[13], im), pack4v(mv[12], mv[11], mv[10], mv[9], im),
+                                        pack4v(mv[8], mv[7], mv[6], mv[5], im), pack4v(mv[4], mv[3], mv[2], mv[1], im));
+            uint4* crow = reinterpret_cast<uint4*>(codes) + row0 * (D / 16);
+            crow[(unsigned)(c * (D / 16) + base_d / 16 + half)] = pd;
+            crow[(unsigned)(c * (D / 16) + p_top / 16 - 1 - half)] = pm;
+        } else {
+            uint2 pd, pm;
+            pd.x = pack8v(dv[0], dv[1], dv[2], dv[3], dv[4], dv[5], dv[6], dv[7], id);
+            pd.y = pack8v(dv[8], dv[9], dv[10], dv[11], dv[12], dv[13], dv[14], dv[15], id);
+            pm.x = pack8v(bottom, mv[15], mv[14], mv[13], mv[12], mv[11], mv[10], mv[9], im);
+            pm.y = pack8v(mv[8], mv[7], mv[6], mv[5], mv[4], mv[3], mv[2], mv[1], im);
+            uint2* crow = codes + row0 * (D / 16);
+            crow[(unsigned)(c * (D / 16) + base_d / 16 + half)] = pd;
+            crow[(unsigned)(c * (D / 16) + p_top / 16 - 1 - half)] = pm;
+        }
+        // both halves store the same values
+        if constexpr (WIDE) {
+            float* srow = scales + row0 * (G / gw);
+            srow[(unsigned)(c * (G / gw) + base_d / 32 / gw)] = sd;
+            srow[(unsigned)(c * (G / gw) + slot_in / gw)] = sm;
+        } else {
+            float* srow = scales + row0 * G;
+            srow[(unsigned)(c * G + base_d / 32)] = sd;
+            srow[(unsigned)(c * G + slot_in)] = sm;
+        }
     };
 
     const int m = (n_tiles - 1 - t0) / stride + 1;
@@ -661,12 +700,13 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
 }
 
 // two wavefronts per SIMD (8 per compute unit): the register allocator is told to stay within 256 VGPRs
-template <int D>
+template <int D, int BITS, bool WIDE>
 __global__ void __launch_bounds__(D, 2)
 srft_quantize_fold_kernel(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
                           uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__,
-                          float unscale, float scale_mul, int) {
-    srft_quantize_fold_tiles<D>(wfold, x, n_vec, codes, scales, unscale, scale_mul, blockIdx.x, gridDim.x);
+                          float unscale, float scale_mul, int gw) {
+    srft_quantize_fold_tiles<D, BITS, WIDE>(wfold, x, n_vec, codes, scales, unscale, scale_mul, gw, blockIdx.x,
+                                            gridDim.x);
 }
 
 // Several plans in one launch (a decode step appends a few hundred vectors to each of many (layer, K|V)
@@ -702,13 +742,13 @@ srft_quantize_batched_kernel(const srft_batch_args a, int gw) {
                                          blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i]);
 }
 
-template <int D>
+template <int D, int BITS, bool WIDE>
 __global__ void __launch_bounds__(D, 2)
-srft_quantize_fold_batched_kernel(const srft_batch_args a, int) {
+srft_quantize_fold_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
-    srft_quantize_fold_tiles<D>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i], (float*)a.out1[i],
-                                a.unscale[i], a.unscale[i] / 7.0f, blockIdx.x - a.first_block[i],
-                                a.first_block[i + 1] - a.first_block[i]);
+    srft_quantize_fold_tiles<D, BITS, WIDE>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
+                                            (float*)a.out1[i], a.unscale[i], a.unscale[i] / (BITS == 8 ? 127.0f : 7.0f),
+                                            gw, blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1420,7 +1460,11 @@ quantize_kernel_t quantize_instance(int out, int gm, int bits) {
 template <int D>
 quantize_kernel_t quantize_instance(int slabs, int out, int gm, bool fold, int bits) {
     if constexpr (D % 128 == 0) {
-        if (fold && out == kOutCodes && gm == kGroup32 && bits == 4) return srft_quantize_fold_kernel<D>;
+        if (fold && out == kOutCodes && gm != kGroup16) {
+            if (gm == kGroupWide)
+                return bits == 8 ? srft_quantize_fold_kernel<D, 8, true> : srft_quantize_fold_kernel<D, 4, true>;
+            return bits == 8 ? srft_quantize_fold_kernel<D, 8, false> : srft_quantize_fold_kernel<D, 4, false>;
+        }
     }
     if constexpr ((D / 32) % 2 == 0) {
         if (slabs == 2) return quantize_instance<D, 2>(out, gm, bits);
@@ -1501,7 +1545,13 @@ quantize_batched_kernel_t quantize_batched_instance_gm(int gm) {
 template <int D>
 quantize_batched_kernel_t quantize_batched_instance(int slabs, int gm, bool fold, int bits) {
     if constexpr (D % 128 == 0) {
-        if (fold && gm == kGroup32 && bits == 4) return srft_quantize_fold_batched_kernel<D>;
+        if (fold && gm != kGroup16) {
+            if (gm == kGroupWide)
+                return bits == 8 ? srft_quantize_fold_batched_kernel<D, 8, true>
+                                 : srft_quantize_fold_batched_kernel<D, 4, true>;
+            return bits == 8 ? srft_quantize_fold_batched_kernel<D, 8, false>
+                             : srft_quantize_fold_batched_kernel<D, 4, false>;
+        }
     }
     if constexpr ((D / 32) % 2 == 0) {
         if (slabs == 2)
@@ -1756,8 +1806,8 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
                 }
             }
     }
-    // Folded write path where it applies (d a multiple of 128, g = 32); SRFT_FOLD_Q=0 turns it off (tuning).
-    p->fold_q = (d % 128 == 0) && p->gm == kGroup32 && bits == 4 && transform == SRFT_TRANSFORM_DFT;
+    // Folded write path where it applies (d a multiple of 128, g >= 32); SRFT_FOLD_Q=0 turns it off (tuning).
+    p->fold_q = (d % 128 == 0) && p->gm != kGroup16 && transform == SRFT_TRANSFORM_DFT;
     if (const char* e = std::getenv("SRFT_FOLD_Q")) p->fold_q = p->fold_q && std::atoi(e) != 0;
     std::vector<uint16_t> wfold;
     if (p->fold_q) {
