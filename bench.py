@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 MEASURED_TRAFFIC_PER_VECTOR = {
     # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch (factors from the copy kernel of known size) x 1024 /
     # vectors per dispatch, d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
-    ("llama3-70b-128k", "srft_quantize_kernel"): (131339.2 * 2.0 + 82109.5) * 1024 / 1048576,
-    ("llama3-70b-128k", "srft_dequantize_kernel"): (164593.3 * 2.0 + 1048576.0) * 1024 / (4 * 1048576),
+    ("llama3-70b-128k", "srft_quantize_kernel"): (131347.3 * 2.0 + 81965.7) * 1024 / 1048576,
+    ("llama3-70b-128k", "srft_dequantize_kernel"): (164638.2 * 2.0 + 1048578.4) * 1024 / (4 * 1048576),
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target

@@ -499,6 +499,10 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
                                                    __builtin_amdgcn_perm(b.y, b.x, kHi), __builtin_amdgcn_perm(b.w, b.z, kHi));
     };
     auto to_lds = [&](int buf, const uint4& a, const uint4& b, const uint4& c, const uint4& d) __attribute__((always_inline)) {
+        // The first use of the prefetched registers stays here, behind the tail's stores.  The scheduler otherwise
+        // moves the (cheap) byte permutes to the top of the stage or above its barrier, and the wait for the
+        // loads with them, where it also drains the younger loads and the stores.
+        __builtin_amdgcn_sched_barrier(0);
         put2(buf, a, b, 0);
         put2(buf, c, d, 1);
     };
@@ -644,23 +648,40 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         to_lds(1, pb0, pb1, pb2, pb3);
         fetch(pb0, pb1, pb2, pb3, t0 + 3 * stride);
         publish(0, ea, oa);
-        for (int k = 1; k < m; ++k) {
+        // two stages per trip, so that the two prefetch register sets keep their names: selecting them by a
+        // branch makes the compiler copy the loaded registers at the end of the stage, behind a wait for
+        // every load and store in flight
+        int k = 1;
+        for (; k + 1 < m; k += 2) {
+            const int tk = t0 + k * stride;
+            __syncthreads();                     // stage k (odd)
+            finish(0, ea, oa, tk - stride);
+            __builtin_amdgcn_sched_barrier(0);   // no second accumulator set: the tail ends before the MFMAs begin
+            contract(1, ea, oa);
+            to_lds(0, pa0, pa1, pa2, pa3);
+            fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
+            publish(1, ea, oa);
+            __syncthreads();                     // stage k + 1 (even)
+            finish(1, ea, oa, tk);
+            __builtin_amdgcn_sched_barrier(0);
+            contract(0, ea, oa);
+            to_lds(1, pb0, pb1, pb2, pb3);
+            fetch(pb0, pb1, pb2, pb3, tk + 4 * stride);
+            publish(0, ea, oa);
+        }
+        if (k < m) {                             // one more odd stage
             const int tk = t0 + k * stride;
             __syncthreads();
-            finish((k - 1) & 1, ea, oa, tk - stride);
-            __builtin_amdgcn_sched_barrier(0);   // no second accumulator set: the tail ends before the MFMAs begin
-            contract(k & 1, ea, oa);
-            if (k & 1) {
-                to_lds(0, pa0, pa1, pa2, pa3);
-                fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
-            } else {
-                to_lds(1, pb0, pb1, pb2, pb3);
-                fetch(pb0, pb1, pb2, pb3, tk + 3 * stride);
-            }
-            publish(k & 1, ea, oa);
+            finish(0, ea, oa, tk - stride);
+            __builtin_amdgcn_sched_barrier(0);
+            contract(1, ea, oa);
+            publish(1, ea, oa);
+            __syncthreads();
+            finish(1, ea, oa, tk);
+        } else {
+            __syncthreads();
+            finish(0, ea, oa, t0 + (k - 1) * stride);
         }
-        __syncthreads();
-        finish((m - 1) & 1, ea, oa, t0 + (m - 1) * stride);
         return;
     }
     // stage 0
@@ -1065,24 +1086,38 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     to_lds(0, pa0, pa1, pas, pat);
     fetch(pa0, pa1, pas, pat, t0 + 2 * stride);
     if constexpr (LEAN) {
-        // stage k: barrier; flush T_{k-1}; contract, fold and stage T_k; decode T_{k+1}
-        for (int k = 0; k < m; ++k) {
+        // stage k: barrier; flush T_{k-1}; contract, fold and stage T_k; decode T_{k+1}.  Two stages per trip,
+        // so that the two prefetch register sets keep their names (selecting them by a branch makes the compiler
+        // copy the loaded registers at the end of the stage, behind a wait for every load and store in flight).
+        __syncthreads();                         // stage 0: nothing to flush yet
+        lean_body(0);
+        to_lds(1, pb0, pb1, pbs, pbt);
+        fetch(pb0, pb1, pbs, pbt, t0 + 3 * stride);
+        int k = 1;
+        for (; k + 1 < m; k += 2) {
+            const int tk = t0 + k * stride;
+            __syncthreads();                     // stage k (odd)
+            flush(0, tk - stride);
+            lean_body(1);
+            to_lds(0, pa0, pa1, pas, pat);
+            fetch(pa0, pa1, pas, pat, tk + 3 * stride);
+            __syncthreads();                     // stage k + 1 (even)
+            flush(1, tk);
+            lean_body(0);
+            to_lds(1, pb0, pb1, pbs, pbt);
+            fetch(pb0, pb1, pbs, pbt, tk + 4 * stride);
+        }
+        if (k < m) {                             // one more odd stage
             const int tk = t0 + k * stride;
             __syncthreads();
-            if (k & 1) {
-                flush(0, tk - stride);
-                lean_body(1);
-                to_lds(0, pa0, pa1, pas, pat);
-                fetch(pa0, pa1, pas, pat, tk + 3 * stride);
-            } else {
-                if (k > 0) flush(1, tk - stride);
-                lean_body(0);
-                to_lds(1, pb0, pb1, pbs, pbt);
-                fetch(pb0, pb1, pbs, pbt, tk + 3 * stride);
-            }
+            flush(0, tk - stride);
+            lean_body(1);
+            __syncthreads();
+            flush(1, tk);
+        } else {
+            __syncthreads();
+            flush(0, t0 + (k - 1) * stride);
         }
-        __syncthreads();
-        flush((int)((m - 1) & 1), t0 + (m - 1) * stride);
         return;
     }
     // stage 0
