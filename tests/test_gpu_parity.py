@@ -228,6 +228,29 @@ def test_grid_cap_and_side_stream_give_identical_bytes(B):
     plan.close()
 
 
+@pytest.mark.parametrize("d,g,bits", [(128, 32, 4), (256, 32, 4), (192, 32, 4), (96, 32, 4), (64, 32, 4),
+                                      (128, 128, 4), (256, 64, 8), (128, 16, 4)])
+def test_every_pipeline_length_of_one_workgroup(B, d, g, bits):
+    # One workgroup walks m tiles, m = 1..7 (odd and even numbers of stages, with and without a ragged last
+    # tile): prologue, steady state and every epilogue of the software pipelines.  The reference is the same
+    # input on the full grid (one tile per workgroup), which the other tests hold against the oracle.
+    lam = W.lognormal_lambda(d, d + g)
+    plan = B.Plan(d, g, 3, lam, bits=bits)
+    for m in range(1, 8):
+        for n in (32 * m, 32 * m - 13):
+            x = torch.from_numpy(W.gaussian_with_outliers(n, d, seed=100 * m + n % 7, outliers=1, gain=25.0)).cuda()
+            B.srft_plan_set_max_workgroups(plan.handle, 0)
+            c0, s0 = plan.quantize(x)
+            o0 = plan.dequantize(c0, s0)
+            B.srft_plan_set_max_workgroups(plan.handle, 1)
+            c1, s1 = plan.quantize(x)
+            o1 = plan.dequantize(c1, s1)
+            assert torch.equal(c0, c1) and torch.equal(s0, s1) and torch.equal(o0, o1), (m, n)
+            if m in (1, 2, 5):
+                P.check_quantize(x.cpu().numpy(), plan.signs, lam, g, c1.cpu().numpy(), s1.cpu().numpy(), bits=bits)
+    plan.close()
+
+
 def test_argument_errors_on_device_pointers(B):
     d = 128
     plan = B.Plan(d, 32, 1)
