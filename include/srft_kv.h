@@ -149,7 +149,8 @@ int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t 
  *   q_f16_dev      [n_q, d] fp16, 16-byte aligned, 1 <= n_q <= 32 (e.g. the query heads sharing one KV head).
  *   codes_dev      [n_keys, d/2] bytes, 16-byte aligned;  scales_dev [n_keys, d/g] fp32: the plan's record.
  *   scores_dev     [n_q, n_keys] fp32, row-major, written.
- *   workspace_dev  srft_scores_workspace_bytes(plan) bytes of device memory, 16-byte aligned, overwritten.
+ *   workspace_dev  srft_scores_workspace_bytes(plan) bytes of device memory (about 1 MiB), 16-byte aligned,
+ *                  overwritten; two calls that may run at the same time need a workspace each.
  * For plans with d a multiple of 64, 4-bit codes and g >= 32 (else SRFT_ERR_BAD_D / _BAD_BITS / _BAD_GROUP).
  * Enqueues three small-to-large kernels on the stream: transform of the queries, operand set-up, the scan.
  */

@@ -72,6 +72,7 @@ __device__ __forceinline__ uint2 stream_load(const uint2* p) {
 }
 
 constexpr int kTileVecs = 32;          // vectors per tile = N of the 32x32x16 MFMA
+constexpr int kMaxScoreWorkgroups = 4096;   // scores kernel: largest grid (each workgroup owns 256 bytes of workspace)
 constexpr int kMaxD = 256;
 #ifndef SRFT_LEAN_ALT_MAX
 #define SRFT_LEAN_ALT_MAX 8              // read path: slabs x groups up to which two accumulator sets alternate
@@ -1208,15 +1209,16 @@ srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
 //
 // Step 1 (srft_scores_prepare_kernel): q' from w = lambda * Q (s * q), which the write path's kernel computes
 // in its raw mode: q' = w / (lambda * max(lambda, 1e-6)), split into fp16 hi + lo, laid out as A fragments
-// [d/32 groups][2 k-steps][hi, lo][64 lanes]; MFMA row i carries query slab_output(i), so that lane half h,
-// register v holds query 16h + v.
+// [d/32 groups][2 k-steps][hi, lo][64 lanes]; MFMA row i (lane half h = (i / 4) % 2, register v = 4 (i / 8) + i % 4 of
+// the result) carries query 2 v + h: the first n_q / 2 registers of both halves hold all the queries, so that a
+// small group of queries costs few stores.
 template <int D>
 __global__ void __launch_bounds__(64)
 srft_scores_prepare_kernel(const float* __restrict__ wq, const float* __restrict__ inv_lam2, int n_q,
                            uint4* __restrict__ qfrag) {
     constexpr int G = D / 32;
     const int lane = threadIdx.x, i = lane & 31, kh = lane >> 5;
-    const int qi = 16 * ((i / 4) % 2) + 4 * (i / 8) + i % 4;             // query carried by MFMA row i
+    const int qi = 2 * (4 * (i / 8) + i % 4) + (i / 4) % 2;              // query carried by MFMA row i
 #pragma unroll 1
     for (int f = 0; f < 2 * G; ++f) {                                    // k-step f = 2 j + t: codes 16 f .. 16 f + 15
         half8 hi, lo;
@@ -1233,10 +1235,15 @@ srft_scores_prepare_kernel(const float* __restrict__ wq, const float* __restrict
 }
 
 // Step 2.  codes [n_keys][D/16] 8-byte units, scales [n_keys][ns], out [n_q][n_keys] fp32.
-template <int D>
-__global__ void __launch_bounds__(64)
+// NV: registers of the result a lane stores per tile (queries 2 v + h for v < NV; NV >= ceil(n_q / 2), a power of two).
+// Every lane stores NV times per tile whatever n_q and the tile are: a lane without a valid (query, key) writes
+// to its own slot of `dump` (64 floats per workgroup, never read).  So the number of memory operations per stage
+// is fixed, the wait counters are exact, and the codes are prefetched two tiles ahead in two named register
+// sets (two stages per trip), as on the read path.
+template <int D, int NV>
+__global__ void __launch_bounds__(64, D <= 128 ? 2 : 1)
 srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ codes, const float* __restrict__ scales,
-                   long long n_keys, float* __restrict__ out, int n_q, int gw) {
+                   long long n_keys, float* __restrict__ out, int n_q, int gw, float* __restrict__ dump) {
     constexpr int G = D / 32, U = D / 8, ROW = U + 1, C = D / 16;
     constexpr int PER = C / 2;           // 8-byte code units per lane and tile (32 C units, 64 lanes)
     constexpr int SROW = G + 1;
@@ -1248,6 +1255,8 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
     const int ns = G / gw;
     const int n_tiles = (int)((n_keys + kTileVecs - 1) / kTileVecs);
     const int last_lim = (int)(n_keys - 1 - (long long)(n_tiles - 1) * kTileVecs);
+    const int t0 = blockIdx.x, stride = gridDim.x;
+    float* const my_dump = dump + (size_t)blockIdx.x * 64 + lane;
 
     half8 qhi[2 * G], qlo[2 * G];
 #pragma unroll
@@ -1255,67 +1264,109 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
         qhi[f] = __builtin_bit_cast(half8, qfrag[(f * 2 + 0) * 64 + lane]);
         qlo[f] = __builtin_bit_cast(half8, qfrag[(f * 2 + 1) * 64 + lane]);
     }
-    uint2 pc[PER];
-    float ps[PS];
-    auto fetch = [&](int tile) __attribute__((always_inline)) {
+    struct Set { uint2 pc[PER]; float ps[PS]; };
+    auto fetch = [&](Set& r, int tile) __attribute__((always_inline)) {
         if (tile > n_tiles - 1) tile = n_tiles - 1;
         const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
         const uint2* cb = codes + (long long)tile * kTileVecs * C;
         const float* sb = scales + (long long)tile * kTileVecs * ns;
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int u = lane + 64 * i, r = u / C, c = u % C;
-            pc[i] = stream_load(&cb[(unsigned)(min(r, lim) * C + c)]);
+            const int u = lane + 64 * i, rr = u / C, c = u % C;
+            r.pc[i] = stream_load(&cb[(unsigned)(min(rr, lim) * C + c)]);
         }
 #pragma unroll
         for (int i = 0; i < PS; ++i) {
             int e = lane + 64 * i;
             if (e > 32 * ns - 1) e = 32 * ns - 1;
-            ps[i] = sb[(unsigned)(min(e / ns, lim) * ns + e % ns)];
+            r.ps[i] = sb[(unsigned)(min(e / ns, lim) * ns + e % ns)];
         }
     };
-    auto to_lds = [&](int b) __attribute__((always_inline)) {
+    auto to_lds = [&](int b, const Set& r) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int u = lane + 64 * i, r = u / C, c = u % C;
-            dec[b][r * ROW + 2 * c] = decode8(pc[i].x);
-            dec[b][r * ROW + 2 * c + 1] = decode8(pc[i].y);
+            const int u = lane + 64 * i, rr = u / C, c = u % C;
+            dec[b][rr * ROW + 2 * c] = decode8(r.pc[i].x);
+            dec[b][rr * ROW + 2 * c + 1] = decode8(r.pc[i].y);
         }
 #pragma unroll
         for (int i = 0; i < PS; ++i) {
-            const int e = lane + 64 * i;
-            if (e < 32 * ns) scl[b][(e / ns) * SROW + e % ns] = ps[i];
+            int e = lane + 64 * i;
+            if (e > 32 * ns - 1) e = 32 * ns - 1;        // surplus lanes rewrite the last scale: no branch
+            scl[b][(e / ns) * SROW + e % ns] = r.ps[i];
         }
     };
-    const int m = (n_tiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1;   // the grid never exceeds the tiles
-    fetch(blockIdx.x);
-    hold_in_registers(qhi, qlo);
-    for (int k = 0; k < m; ++k) {
-        const int tile = blockIdx.x + k * gridDim.x, b = k & 1;
-        to_lds(b);
-        fetch(tile + gridDim.x);
-        __syncthreads();                         // one wavefront: orders the LDS writes before the reads
-        floatx16 o = {0};
+    // scores of the tile in dec[b] / scl[b]
+    auto tile_scores = [&](int b, int tile) __attribute__((always_inline)) {
+        floatx16 o, acc0, acc1;
         const uint4* rowp = &dec[b][col * ROW + half];
-#pragma unroll
-        for (int j = 0; j < G; ++j) {
-            floatx16 acc = {0};
+        auto group = [&](int j, floatx16& acc) __attribute__((always_inline)) {
+            acc = floatx16{0};
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const half8 bf = __builtin_bit_cast(half8, rowp[2 * (2 * j + t)]);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(qhi[2 * j + t], bf, acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(qlo[2 * j + t], bf, acc, 0, 0, 0);
             }
+        };
+        auto fold = [&](int j, const floatx16& acc) __attribute__((always_inline)) {
             const float sc = scl[b][col * SROW + j / gw];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) o[v] = fmaf(acc[v], sc, o[v]);
-        }
-        const long long key = (long long)tile * kTileVecs + col;
-        if (key < n_keys) {
+            for (int v = 0; v < 16; ++v) o[v] = j == 0 ? acc[v] * sc : fmaf(acc[v], sc, o[v]);
+        };
+        // group j + 1 is on the matrix cores while group j is folded in; the scheduling barrier keeps the
+        // compiler from reading every group's fragments up front (registers)
+        group(0, acc0);
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                if (16 * half + v < n_q) out[(long long)(16 * half + v) * n_keys + key] = o[v];
+        for (int j = 1; j < G; ++j) {
+            group(j, (j & 1) ? acc1 : acc0);
+            fold(j - 1, (j & 1) ? acc0 : acc1);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        fold(G - 1, ((G - 1) & 1) ? acc1 : acc0);
+        // lane (key, h) stores o[v] to row 2 v + h of out for v < nv_lane, elsewhere to its dump slot
+        const long long key = (long long)tile * kTileVecs + col;
+        const int nv_lane = key < n_keys ? (n_q - half + 1) >> 1 : 0;
+        float* p = out + ((long long)half * n_keys + key);
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            float* dst = v < nv_lane ? p : my_dump;
+            *dst = o[v];
+            p += 2 * n_keys;
+        }
+        // With many queries the kernel mostly writes; letting a tile's stores complete before the next stage
+        // measured 3-5 % faster than keeping them in flight (s_waitcnt vmcnt(0); the other counters at their maximum).
+        if constexpr (NV >= 8) __builtin_amdgcn_s_waitcnt(0x0F70);
+    };
+
+    const int m = (n_tiles - 1 - t0) / stride + 1;       // the grid never exceeds the tiles
+    Set ra, rb;
+    fetch(ra, t0);
+    fetch(rb, t0 + stride);
+    hold_in_registers(qhi, qlo);
+    to_lds(0, ra);
+    // stage k: barrier (one wavefront: it orders the LDS writes before the reads); prefetch T_{k+2} into the set
+    // that the previous stage decoded (the loads go out ahead of this stage's burst of stores); scores of T_k;
+    // decode T_{k+1}
+    __syncthreads();
+    fetch(ra, t0 + 2 * stride);
+    tile_scores(0, t0);
+    to_lds(1, rb);
+    int k = 1;
+    for (; k + 1 < m; k += 2) {
+        const int tk = t0 + k * stride;
+        __syncthreads();                         // stage k (odd)
+        fetch(rb, tk + 2 * stride);
+        tile_scores(1, tk);
+        to_lds(0, ra);
+        __syncthreads();                         // stage k + 1 (even)
+        fetch(ra, tk + 3 * stride);
+        tile_scores(0, tk + stride);
+        to_lds(1, rb);
+    }
+    if (k < m) {
+        __syncthreads();
+        tile_scores(1, t0 + k * stride);
     }
 }
 
@@ -1532,7 +1583,7 @@ int occupancy_grids(srft_plan* p, int cus) {
     p->grid_dq = cus * (bd > 0 ? bd : 1);
     if constexpr (D % 64 == 0) {
         int bs = 0;
-        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bs, srft_scores_kernel<D>, 64, 0));
+        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bs, srft_scores_kernel<D, 16>, 64, 0));
         p->grid_scores = cus * (bs > 0 ? bs : 1);
     }
     return SRFT_OK;
@@ -1654,16 +1705,21 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
     }
 
 template <int D>
-int launch_scores(const srft_plan* p, const float* wq, uint4* qfrag, int n_q, const uint8_t* codes, const float* scales,
-                  long long n_keys, float* out, hipStream_t st) {
+int launch_scores(const srft_plan* p, const float* wq, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
+                  const float* scales, long long n_keys, float* out, hipStream_t st) {
     if constexpr (D % 64 == 0) {
         hipLaunchKernelGGL(srft_scores_prepare_kernel<D>, dim3(1), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
         SRFT_HIP(hipGetLastError());
         const long long n_tiles = (n_keys + kTileVecs - 1) / kTileVecs;
         long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_scores;
         if (grid > n_tiles) grid = n_tiles;
-        hipLaunchKernelGGL(srft_scores_kernel<D>, dim3((unsigned)grid), dim3(64), 0, st, (const uint4*)qfrag,
-                           (const uint2*)codes, scales, n_keys, out, n_q, p->gw);
+        if (grid > kMaxScoreWorkgroups) grid = kMaxScoreWorkgroups;      // each has its 64 floats of `dump`
+        const int nv = (n_q + 1) / 2;            // result registers a lane has to store
+        auto kernel = nv <= 1 ? srft_scores_kernel<D, 1> : nv <= 2 ? srft_scores_kernel<D, 2>
+                    : nv <= 4 ? srft_scores_kernel<D, 4> : nv <= 8 ? srft_scores_kernel<D, 8>
+                                                                   : srft_scores_kernel<D, 16>;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(64), 0, st, (const uint4*)qfrag,
+                           (const uint2*)codes, scales, n_keys, out, n_q, p->gw, dump);
         SRFT_HIP(hipGetLastError());
         return SRFT_OK;
     } else {
@@ -1672,9 +1728,9 @@ int launch_scores(const srft_plan* p, const float* wq, uint4* qfrag, int n_q, co
 }
 
 int dispatch_occupancy(srft_plan* p, int cus) { SRFT_DISPATCH_D(p->d, occupancy_grids, p, cus) }
-int dispatch_scores(const srft_plan* p, const float* wq, uint4* qfrag, int n_q, const uint8_t* c, const float* s,
-                    long long n, float* o, hipStream_t st) {
-    SRFT_DISPATCH_D(p->d, launch_scores, p, wq, qfrag, n_q, c, s, n, o, st)
+int dispatch_scores(const srft_plan* p, const float* wq, uint4* qfrag, float* dump, int n_q, const uint8_t* c,
+                    const float* s, long long n, float* o, hipStream_t st) {
+    SRFT_DISPATCH_D(p->d, launch_scores, p, wq, qfrag, dump, n_q, c, s, n, o, st)
 }
 int dispatch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* c, float* s, float* w, int out,
                       hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_quantize, p, x, n, c, s, w, out, st) }
@@ -1960,8 +2016,9 @@ int srft_kv_channel_absmax(const srft_plan_t* plan, const void* x_f16_dev, int64
 
 int64_t srft_scores_workspace_bytes(const srft_plan_t* plan) {
     if (!plan) return SRFT_ERR_NULL;
-    // w of up to 32 queries (fp32), then their A fragments: d/16 k-steps x (hi, lo) x 64 lanes x 16 bytes
-    return (int64_t)32 * plan->d * 4 + (int64_t)(plan->d / 16) * 2 * 64 * 16;
+    // w of up to 32 queries (fp32), then their A fragments: d/16 k-steps x (hi, lo) x 64 lanes x 16 bytes, then
+    // 64 floats per workgroup that absorb the stores of lanes without a valid (query, key)
+    return (int64_t)32 * plan->d * 4 + (int64_t)(plan->d / 16) * 2 * 64 * 16 + (int64_t)kMaxScoreWorkgroups * 64 * 4;
 }
 
 int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
@@ -1979,9 +2036,10 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
     hipStream_t st = (hipStream_t)hip_stream;
     float* wq = (float*)workspace_dev;
     uint4* qfrag = (uint4*)((char*)workspace_dev + (size_t)32 * plan->d * 4);
+    float* dump = (float*)((char*)qfrag + (size_t)(plan->d / 16) * 2 * 64 * 16);
     const int rc = dispatch_quantize(plan, q_f16_dev, n_q, nullptr, nullptr, wq, kOutRaw, st);
     if (rc != SRFT_OK) return rc;
-    return dispatch_scores(plan, wq, qfrag, n_q, codes_dev, scales_dev, n_keys, scores_dev, st);
+    return dispatch_scores(plan, wq, qfrag, dump, n_q, codes_dev, scales_dev, n_keys, scores_dev, st);
 }
 
 int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host) {
