@@ -55,6 +55,7 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // Streaming (non-temporal) accesses for data touched once.  Measured: they help the read path (codes in, fp16
 // rows out: +3 %) and hurt the write path (its 16-byte code pieces and 4-byte scales combine worse), so only the
@@ -1208,16 +1209,39 @@ srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
 // transposes them into B fragments), contracted group by group and folded with the group scales.
 //
 // Step 1 (srft_scores_prepare_kernel): q' from w = lambda * Q (s * q), which the write path's kernel computes
-// in its raw mode: q' = w / (lambda * max(lambda, 1e-6)), split into fp16 hi + lo, laid out as A fragments
-// [d/32 groups][2 k-steps][hi, lo][64 lanes]; MFMA row i (lane half h = (i / 4) % 2, register v = 4 (i / 8) + i % 4 of
-// the result) carries query 2 v + h: the first n_q / 2 registers of both halves hold all the queries, so that a
-// small group of queries costs few stores.
-template <int D>
+// in its raw mode: q' = w / (lambda * max(lambda, 1e-6)), split into fp16 hi + lo, laid out as A fragments.
+// Two layouts, both chosen so that the first ceil(n_q / 2) result registers of the lanes hold all the queries
+// (a small group of queries costs few stores):
+//   32 rows (n_q > 16; v_mfma_f32_32x32x16_f16): [d/32 groups][2 k-steps][hi, lo][64 lanes]; MFMA row i (lane half
+//     h = (i / 4) % 2, register v = 4 (i / 8) + i % 4 of the result) carries query 2 v + h.
+//   16 rows (R16, n_q <= 16; v_mfma_f32_16x16x32_f16, half the matrix-core time): [d/32 groups][hi, lo][64 lanes];
+//     lane l holds row l % 16 and the 8 codes of unit 4 j + l / 16 of group j.  MFMA row r = 4 a + i (result register i
+//     of the lanes 16 a .. 16 a + 15) carries query 2 i + a for a < 2 and 8 + 2 i + (a - 2) for a >= 2.
+template <int D, bool R16>
 __global__ void __launch_bounds__(64)
 srft_scores_prepare_kernel(const float* __restrict__ wq, const float* __restrict__ inv_lam2, int n_q,
                            uint4* __restrict__ qfrag) {
     constexpr int G = D / 32;
-    const int lane = threadIdx.x, i = lane & 31, kh = lane >> 5;
+    const int lane = threadIdx.x;
+    if constexpr (R16) {
+        const int r = lane & 15, kg = lane >> 4, a = r / 4, i = r % 4;
+        const int qi = a < 2 ? 2 * i + a : 8 + 2 * i + (a - 2);          // query carried by MFMA row r
+#pragma unroll 1
+        for (int j = 0; j < G; ++j) {
+            half8 hi, lo;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int p = 8 * (4 * j + kg) + (e / 2) + 4 * (e % 2);  // the 4-bit decode order of the read path
+                const float v = qi < n_q ? wq[qi * D + p] * inv_lam2[p] : 0.0f;
+                hi[e] = (_Float16)v;
+                lo[e] = (_Float16)(v - (float)hi[e]);
+            }
+            qfrag[(j * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
+            qfrag[(j * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
+        }
+        return;
+    }
+    const int i = lane & 31, kh = lane >> 5;
     const int qi = 2 * (4 * (i / 8) + i % 4) + (i / 4) % 2;              // query carried by MFMA row i
 #pragma unroll 1
     for (int f = 0; f < 2 * G; ++f) {                                    // k-step f = 2 j + t: codes 16 f .. 16 f + 15
@@ -1235,20 +1259,22 @@ srft_scores_prepare_kernel(const float* __restrict__ wq, const float* __restrict
 }
 
 // Step 2.  codes [n_keys][D/16] 8-byte units, scales [n_keys][ns], out [n_q][n_keys] fp32.
-// NV: registers of the result a lane stores per tile (queries 2 v + h for v < NV; NV >= ceil(n_q / 2), a power of two).
+// NV: result registers a lane stores per tile (NV >= ceil(n_q / 2), a power of two; 16 with 32 rows, <= 8 with 16).
 // Every lane stores NV times per tile whatever n_q and the tile are: a lane without a valid (query, key) writes
 // to its own slot of `dump` (64 floats per workgroup, never read).  So the number of memory operations per stage
 // is fixed, the wait counters are exact, and the codes are prefetched two tiles ahead in two named register
 // sets (two stages per trip), as on the read path.
-template <int D, int NV>
-__global__ void __launch_bounds__(64, D <= 128 ? 2 : 1)
+template <int D, int NV, bool R16>
+__global__ void __launch_bounds__(64, (D <= 128 || R16) ? 2 : 1)
 srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ codes, const float* __restrict__ scales,
                    long long n_keys, float* __restrict__ out, int n_q, int gw, float* __restrict__ dump) {
     constexpr int G = D / 32, U = D / 8, ROW = U + 1, C = D / 16;
     constexpr int PER = C / 2;           // 8-byte code units per lane and tile (32 C units, 64 lanes)
     constexpr int SROW = G + 1;
     constexpr int PS = (32 * G + 63) / 64;
+    constexpr int NF = R16 ? G : 2 * G;  // A fragments (hi, lo each)
     static_assert(D % 64 == 0, "whole code units per lane");
+    static_assert(R16 ? NV <= 8 : NV == 16, "16 rows hold up to 16 queries");
     __shared__ uint4 dec[2][kTileVecs * ROW];
     __shared__ float scl[2][kTileVecs * SROW];
     const int lane = threadIdx.x, col = lane & 31, half = lane >> 5;
@@ -1258,9 +1284,9 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
     const int t0 = blockIdx.x, stride = gridDim.x;
     float* const my_dump = dump + (size_t)blockIdx.x * 64 + lane;
 
-    half8 qhi[2 * G], qlo[2 * G];
+    half8 qhi[NF], qlo[NF];
 #pragma unroll
-    for (int f = 0; f < 2 * G; ++f) {
+    for (int f = 0; f < NF; ++f) {
         qhi[f] = __builtin_bit_cast(half8, qfrag[(f * 2 + 0) * 64 + lane]);
         qlo[f] = __builtin_bit_cast(half8, qfrag[(f * 2 + 1) * 64 + lane]);
     }
@@ -1296,47 +1322,97 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
             scl[b][(e / ns) * SROW + e % ns] = r.ps[i];
         }
     };
-    // scores of the tile in dec[b] / scl[b]
-    auto tile_scores = [&](int b, int tile) __attribute__((always_inline)) {
-        floatx16 o, acc0, acc1;
-        const uint4* rowp = &dec[b][col * ROW + half];
-        auto group = [&](int j, floatx16& acc) __attribute__((always_inline)) {
-            acc = floatx16{0};
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const half8 bf = __builtin_bit_cast(half8, rowp[2 * (2 * j + t)]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(qhi[2 * j + t], bf, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(qlo[2 * j + t], bf, acc, 0, 0, 0);
-            }
-        };
-        auto fold = [&](int j, const floatx16& acc) __attribute__((always_inline)) {
-            const float sc = scl[b][col * SROW + j / gw];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[v] = j == 0 ? acc[v] * sc : fmaf(acc[v], sc, o[v]);
-        };
-        // group j + 1 is on the matrix cores while group j is folded in; the scheduling barrier keeps the
-        // compiler from reading every group's fragments up front (registers)
-        group(0, acc0);
-#pragma unroll
-        for (int j = 1; j < G; ++j) {
-            group(j, (j & 1) ? acc1 : acc0);
-            fold(j - 1, (j & 1) ? acc0 : acc1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        fold(G - 1, ((G - 1) & 1) ? acc1 : acc0);
-        // lane (key, h) stores o[v] to row 2 v + h of out for v < nv_lane, elsewhere to its dump slot
-        const long long key = (long long)tile * kTileVecs + col;
-        const int nv_lane = key < n_keys ? (n_q - half + 1) >> 1 : 0;
-        float* p = out + ((long long)half * n_keys + key);
+    // lane (key, a) stores val[v] to row 2 v + a of out for v < its number of valid rows, elsewhere to its dump slot
+    auto store_rows = [&](const float (&val)[NV], long long key, int a) __attribute__((always_inline)) {
+        const int nv_lane = key < n_keys ? (n_q - a + 1) >> 1 : 0;
+        float* p = out + ((long long)a * n_keys + key);
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             float* dst = v < nv_lane ? p : my_dump;
-            *dst = o[v];
+            *dst = val[v];
             p += 2 * n_keys;
         }
         // With many queries the kernel mostly writes; letting a tile's stores complete before the next stage
         // measured 3-5 % faster than keeping them in flight (s_waitcnt vmcnt(0); the other counters at their maximum).
         if constexpr (NV >= 8) __builtin_amdgcn_s_waitcnt(0x0F70);
+    };
+    // scores of the tile in dec[b] / scl[b]
+    auto tile_scores = [&](int b, int tile) __attribute__((always_inline)) {
+        if constexpr (R16) {
+            // two MFMAs of 16 keys each per group (K = 32 codes = the whole group); lane l: key l % 16 (+ 16 c),
+            // code unit 4 j + l / 16; result register i of lane l: MFMA row 4 (l / 16) + i
+            const int key16 = lane & 15, a4 = lane >> 4;
+            floatx4 o[2], acc0[2], acc1[2];
+            auto group = [&](int j, floatx4 (&acc)[2]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const half8 bf = __builtin_bit_cast(half8, dec[b][(16 * c + key16) * ROW + 4 * j + a4]);
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qhi[j], bf, floatx4{0, 0, 0, 0}, 0, 0, 0);
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qlo[j], bf, acc[c], 0, 0, 0);
+                }
+            };
+            auto fold = [&](int j, const floatx4 (&acc)[2]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const float sc = scl[b][(16 * c + key16) * SROW + j / gw];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[c][i] = j == 0 ? acc[c][i] * sc : fmaf(acc[c][i], sc, o[c][i]);
+                }
+            };
+            group(0, acc0);
+#pragma unroll
+            for (int j = 1; j < G; ++j) {
+                group(j, (j & 1) ? acc1 : acc0);
+                fold(j - 1, (j & 1) ? acc0 : acc1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            fold(G - 1, ((G - 1) & 1) ? acc1 : acc0);
+            // One swap per register puts the 32 keys of a row into one register: afterwards lane l holds key
+            // 16 (l / 32) + l % 16; x[i] is MFMA row 4 a + i with a = (l % 32) / 16 (queries 2 i + a), y[i] is row
+            // 4 (a + 2) + i (queries 8 + 2 i + a): val[v] = query 2 v + a.
+            float x[4], y[4], val[NV];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(o[0][i]), __float_as_uint(o[1][i]),
+                                                                 false, false);
+                x[i] = __uint_as_float(sw[0]);
+                y[i] = __uint_as_float(sw[1]);
+            }
+#pragma unroll
+            for (int v = 0; v < NV; ++v) val[v] = v < 4 ? x[v] : y[v < 4 ? 0 : v - 4];
+            store_rows(val, (long long)tile * kTileVecs + 16 * half + key16, (lane & 31) >> 4);
+        } else {
+            floatx16 o, acc0, acc1;
+            const uint4* rowp = &dec[b][col * ROW + half];
+            auto group = [&](int j, floatx16& acc) __attribute__((always_inline)) {
+                acc = floatx16{0};
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const half8 bf = __builtin_bit_cast(half8, rowp[2 * (2 * j + t)]);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(qhi[2 * j + t], bf, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(qlo[2 * j + t], bf, acc, 0, 0, 0);
+                }
+            };
+            auto fold = [&](int j, const floatx16& acc) __attribute__((always_inline)) {
+                const float sc = scl[b][col * SROW + j / gw];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[v] = j == 0 ? acc[v] * sc : fmaf(acc[v], sc, o[v]);
+            };
+            // group j + 1 is on the matrix cores while group j is folded in; the scheduling barrier keeps the
+            // compiler from reading every group's fragments up front (registers)
+            group(0, acc0);
+#pragma unroll
+            for (int j = 1; j < G; ++j) {
+                group(j, (j & 1) ? acc1 : acc0);
+                fold(j - 1, (j & 1) ? acc0 : acc1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            fold(G - 1, ((G - 1) & 1) ? acc1 : acc0);
+            float val[NV];
+#pragma unroll
+            for (int v = 0; v < NV; ++v) val[v] = o[v];
+            store_rows(val, (long long)tile * kTileVecs + col, half);
+        }
     };
 
     const int m = (n_tiles - 1 - t0) / stride + 1;       // the grid never exceeds the tiles
@@ -1503,7 +1579,8 @@ struct srft_plan {
     uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
     uint4* wfold = nullptr;     // write-path fragments of the folded form (device), when fold_q
     float* inv_lam2 = nullptr;  // 1 / (lambda * max(lambda, 1e-6)) per channel (device): scores in the rotated domain
-    int grid_scores = 0;        // persistent grid of the scores kernel
+    int grid_scores = 0;        // persistent grid of the scores kernel (32 rows of queries)
+    int grid_scores16 = 0;      // the same with 16 rows
     bool fold_dq = false;       // read path contracts even and odd codes separately (half the matrix work)
     bool fold_q = false;        // write path contracts even and odd inputs separately (half the matrix work)
     float unscale_w = 1.0f;     // 2^-e of the write matrix
@@ -1583,8 +1660,10 @@ int occupancy_grids(srft_plan* p, int cus) {
     p->grid_dq = cus * (bd > 0 ? bd : 1);
     if constexpr (D % 64 == 0) {
         int bs = 0;
-        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bs, srft_scores_kernel<D, 16>, 64, 0));
+        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bs, srft_scores_kernel<D, 16, false>, 64, 0));
         p->grid_scores = cus * (bs > 0 ? bs : 1);
+        SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bs, srft_scores_kernel<D, 8, true>, 64, 0));
+        p->grid_scores16 = cus * (bs > 0 ? bs : 1);
     }
     return SRFT_OK;
 }
@@ -1708,16 +1787,18 @@ template <int D>
 int launch_scores(const srft_plan* p, const float* wq, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
                   const float* scales, long long n_keys, float* out, hipStream_t st) {
     if constexpr (D % 64 == 0) {
-        hipLaunchKernelGGL(srft_scores_prepare_kernel<D>, dim3(1), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
+        const bool r16 = n_q <= 16;             // 16 MFMA rows are enough: half the matrix-core time
+        if (r16) hipLaunchKernelGGL((srft_scores_prepare_kernel<D, true>), dim3(1), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
+        else hipLaunchKernelGGL((srft_scores_prepare_kernel<D, false>), dim3(1), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
         SRFT_HIP(hipGetLastError());
         const long long n_tiles = (n_keys + kTileVecs - 1) / kTileVecs;
-        long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_scores;
+        long long grid = p->max_wgs > 0 ? p->max_wgs : (r16 ? p->grid_scores16 : p->grid_scores);
         if (grid > n_tiles) grid = n_tiles;
         if (grid > kMaxScoreWorkgroups) grid = kMaxScoreWorkgroups;      // each has its 64 floats of `dump`
         const int nv = (n_q + 1) / 2;            // result registers a lane has to store
-        auto kernel = nv <= 1 ? srft_scores_kernel<D, 1> : nv <= 2 ? srft_scores_kernel<D, 2>
-                    : nv <= 4 ? srft_scores_kernel<D, 4> : nv <= 8 ? srft_scores_kernel<D, 8>
-                                                                   : srft_scores_kernel<D, 16>;
+        auto kernel = nv <= 1 ? srft_scores_kernel<D, 1, true> : nv <= 2 ? srft_scores_kernel<D, 2, true>
+                    : nv <= 4 ? srft_scores_kernel<D, 4, true> : nv <= 8 ? srft_scores_kernel<D, 8, true>
+                                                                         : srft_scores_kernel<D, 16, false>;
         hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(64), 0, st, (const uint4*)qfrag,
                            (const uint2*)codes, scales, n_keys, out, n_q, p->gw, dump);
         SRFT_HIP(hipGetLastError());
