@@ -67,6 +67,32 @@ def test_scores_with_wide_groups_hadamard_and_a_grid_cap(B):
         plan.close()
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_every_query_count_and_nothing_written_outside(B, d):
+    # n_q = 1..32 walks every kernel instance (16 and 32 rows of queries, every store count) and every partly
+    # filled last store; the output sits between two guard zones that must come back untouched.
+    g, n_keys, guard = 32, 77, 4096
+    keys = W.gaussian_with_outliers(n_keys, d, seed=21, outliers=1, gain=10.0)
+    lam = W.lognormal_lambda(d, seed=22)
+    plan = B.Plan(d, g, 23, lam)
+    codes, scales = plan.quantize(torch.from_numpy(keys).cuda())
+    c, sc = codes.cpu().numpy(), scales.cpu().numpy()
+    back = O.dequantize_f64(c, sc, plan.signs, lam, g)
+    ws = torch.empty(B.lib().srft_scores_workspace_bytes(plan.handle), dtype=torch.uint8, device="cuda")
+    for n_q in range(1, 33):
+        q = W.gaussian_with_outliers(n_q, d, seed=100 + n_q)
+        buf = torch.full((guard + n_q * n_keys + guard,), -12345.0, dtype=torch.float32, device="cuda")
+        out = buf[guard:guard + n_q * n_keys].view(n_q, n_keys)
+        B.srft_kv_scores(plan.handle, torch.from_numpy(q).cuda(), codes, scales, out, ws)
+        torch.cuda.synchronize()
+        host = buf.cpu().numpy()
+        assert np.all(host[:guard] == -12345.0) and np.all(host[-guard:] == -12345.0), n_q
+        got = host[guard:-guard].reshape(n_q, n_keys).astype(np.float64)
+        ref = O.attention_scores(q, c, sc, plan.signs, lam, g)
+        assert np.all(np.abs(got - ref) <= _tolerance(q, back)), n_q
+    plan.close()
+
+
 def test_scores_argument_errors(B):
     L = B.lib()
     plan = B.Plan(128, 32, 1)
