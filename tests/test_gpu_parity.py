@@ -362,3 +362,10 @@ def test_workload_llama70b_full_size_launch(B):
     w = W.WORKLOADS["llama3-70b-128k"]
     for pi in (0, 159):
         _sampled_parity(B, w, pi, w.vectors_per_plan)
+
+
+def test_single_launch_beyond_4_gib(B):
+    # 20,000,003 vectors of d = 128: 5.1 GB of fp16 in one launch, so tile bases pass 2^32 bytes (64-bit scalar
+    # base + 32-bit lane offset) and the last tile is ragged; sampled rows against the oracle, properties on all.
+    _sampled_parity(B, W.WORKLOADS["llama3-70b-128k"], 7, 20_000_003)
+
