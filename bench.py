@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 MEASURED_TRAFFIC_PER_VECTOR = {
     # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch (factors from the copy kernel of known size) x 1024 /
     # vectors per dispatch, d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
-    ("llama3-70b-128k", "srft_quantize_kernel"): (131347.3 * 2.0 + 81965.7) * 1024 / 1048576,
-    ("llama3-70b-128k", "srft_dequantize_kernel"): (164638.2 * 2.0 + 1048578.4) * 1024 / (4 * 1048576),
+    ("llama3-70b-128k", "srft_quantize_kernel"): (131338.7 * 2.0 + 81962.4) * 1024 / 1048576,
+    ("llama3-70b-128k", "srft_dequantize_kernel"): (164623.8 * 2.0 + 1048576.1) * 1024 / (4 * 1048576),
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
@@ -41,6 +41,8 @@ def main() -> int:
     ap.add_argument("--workload", default="llama3-70b-128k")
     ap.add_argument("--plans", type=int, default=0, help="use only the first N plans (debugging; 0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-d256", action="store_true",
+                    help="skip the d = 256 side measurement that rides along with the default workload")
     ap.add_argument("--max-workgroups", type=int, default=0)
     ap.add_argument("--batched", choices=["auto", "on", "off"], default="auto",
                     help="several plans per launch (auto: when a plan has fewer than 65,536 vectors)")
@@ -177,6 +179,9 @@ def main() -> int:
         "paper_context_apple_m1": PAPER_CONTEXT,
     }
 
+    if w.name == "llama3-70b-128k" and not args.no_d256:
+        # the metric names d = 256 beside d = 128: the same launch shape (1,048,576 vectors per plan) at d = 256
+        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream)
     if args.ceiling:
         result["hbm_ceiling"] = mix_ceiling(B, torch, x, out, n_plans * n, d, G, stream)
     if args.power:
@@ -242,6 +247,53 @@ def main() -> int:
         pl.close()
     print(json.dumps(result))
     return 0
+
+
+def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=3):
+    """Write pass (a launch per plan) and read pass (one batched launch) over n_plans x n vectors of d = 256, g = 32:
+    N(0,1) times a lognormal(0,1) channel scale and lognormal(0,0.5) lambda per plan, as in the d = 256 config."""
+    d, g = 256, 32
+    G = d // g
+    gen = torch.Generator(device=dev)
+    x = torch.empty(n_plans, n, d, dtype=torch.float16, device=dev)
+    plans = []
+    for p in range(n_plans):
+        gen.manual_seed(256_000 + p)
+        gain = torch.exp(torch.randn(d, generator=gen, device=dev))
+        x[p] = (torch.randn(n, d, generator=gen, device=dev) * gain).half()
+        plans.append(B.Plan(d, g, 256_000 + p, W.lognormal_lambda(d, 256_000 + p)))
+    codes = torch.empty(n_plans, n, d // 2, dtype=torch.uint8, device=dev)
+    scales = torch.empty(n_plans, n, G, dtype=torch.float32, device=dev)
+    out = torch.empty(n_plans, n, d, dtype=torch.float16, device=dev)
+    h = [pl.handle for pl in plans]
+    table = B.BatchTable(h, list(out), list(codes), list(scales))
+
+    def pass_q():
+        for p in range(n_plans):
+            B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
+
+    def pass_d():
+        B.srft_kv_dequantize_batched(table, stream)
+
+    pass_q(); pass_d()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record(stream)
+    for _ in range(reps):
+        pass_q()
+    ev[1].record(stream)
+    for _ in range(reps):
+        pass_d()
+    ev[2].record(stream)
+    torch.cuda.synchronize()
+    nbytes = n_plans * n * (2 * d + d // 2 + 4 * G)
+    tq, td = ev[0].elapsed_time(ev[1]) / reps / 1e3, ev[1].elapsed_time(ev[2]) / reps / 1e3
+    for pl in plans:
+        pl.close()
+    return {"d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
+            "quantize": {"GBps": nbytes / tq / 1e9, "hbm_frac": nbytes / tq / 1e9 / HBM_PEAK_GBPS,
+                         "vectors_per_s": n_plans * n / tq},
+            "dequantize": {"GBps": nbytes / td / 1e9, "hbm_frac": nbytes / td / 1e9 / HBM_PEAK_GBPS,
+                           "vectors_per_s": n_plans * n / td}}
 
 
 def mix_ceiling(B, torch, x, out, total_vec, d, G, stream):

@@ -104,6 +104,22 @@ __device__ __forceinline__ void hold_in_registers(half8 (&a)[N][M], half8 (&b)[N
         for (int j = 0; j < M; ++j) asm volatile("" : "+v"(a[i][j]), "+v"(b[i][j]));
 }
 
+// The instruction arbiter of a compute unit favours its oldest wavefronts: of the workgroups that share a unit the
+// one dispatched first ran 25 % ahead of the others and left the unit early, while the kernel waited for the
+// last one.  Every workgroup therefore walks through the four wavefront priorities, one per stage, offset by its
+// place in the dispatch order: over four stages each has held each priority once, and they finish together
+// (end times of the workgroups 440..620 us -> 565..600 us at d = 128, 8 M vectors; launches 1.5-3.5 % shorter, the
+// scores kernel 5-12 %).  Not used where two workgroups per unit take turns on one accumulator set (the folded
+// write path at d = 256), which measured 1 % slower with it.
+__device__ __forceinline__ void rotate_priority(int stage) {
+    switch (((int)(blockIdx.x * 4 / gridDim.x) + stage) & 3) {
+        case 0: __builtin_amdgcn_s_setprio(0); break;
+        case 1: __builtin_amdgcn_s_setprio(1); break;
+        case 2: __builtin_amdgcn_s_setprio(2); break;
+        default: __builtin_amdgcn_s_setprio(3); break;
+    }
+}
+
 template <int N> struct Accs;          // one 32x32 accumulator tile per slab, as named registers
 template <> struct Accs<1> { floatx16 a; };
 template <> struct Accs<2> { floatx16 a, b; };
@@ -339,11 +355,13 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
     for (; k + 1 < m; k += 2) {
         const int tk = t0 + k * stride;
         __syncthreads();                         // stage k (odd)
+        rotate_priority(k);
         contract(1, acc_b);
         finish(acc_a, tk - stride);
         to_lds(0, pa0, pa1, pa2, pa3);
         fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
         __syncthreads();                         // stage k + 1 (even)
+        rotate_priority(k + 1);
         contract(0, acc_a);
         finish(acc_b, tk);
         to_lds(1, pb0, pb1, pb2, pb3);
@@ -696,12 +714,14 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     for (; k + 1 < m; k += 2) {
         const int tk = t0 + k * stride;
         __syncthreads();                         // stage k (odd)
+        rotate_priority(k);
         contract(1, eb, ob);
         finish(0, ea, oa, tk - stride);
         to_lds(0, pa0, pa1, pa2, pa3);
         fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
         publish(1, eb, ob);
         __syncthreads();                         // stage k + 1 (even)
+        rotate_priority(k + 1);
         contract(0, ea, oa);
         finish(1, eb, ob, tk);
         to_lds(1, pb0, pb1, pb2, pb3);
@@ -1099,11 +1119,13 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         for (; k + 1 < m; k += 2) {
             const int tk = t0 + k * stride;
             __syncthreads();                     // stage k (odd)
+            rotate_priority(k);
             flush(0, tk - stride);
             lean_body(1);
             to_lds(0, pa0, pa1, pas, pat);
             fetch(pa0, pa1, pas, pat, tk + 3 * stride);
             __syncthreads();                     // stage k + 1 (even)
+            rotate_priority(k + 1);
             flush(1, tk);
             lean_body(0);
             to_lds(1, pb0, pb1, pbs, pbt);
@@ -1129,8 +1151,10 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     to_lds(1, pb0, pb1, pbs, pbt);
     fetch(pb0, pb1, pbs, pbt, t0 + 3 * stride);
     // stage k: barrier; flush T_{k-2}; contract T_k (staging T_{k-1} under its first group); decode T_{k+1}
+    int stage_no = 1;
     auto odd_stage = [&](int tk, auto flush_first) __attribute__((always_inline)) {      // T_k in dec[1]
         __syncthreads();
+        rotate_priority(stage_no++);
         if constexpr (decltype(flush_first)::value) flush(1, tk - 2 * stride);
         tile_body(1, true, s_last, 0);
         s_last = scale_of(1, G - 1);
@@ -1139,6 +1163,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
     };
     auto even_stage = [&](int tk) __attribute__((always_inline)) {                       // T_k in dec[0]
         __syncthreads();
+        rotate_priority(stage_no++);
         flush(0, tk - 2 * stride);
         tile_body(0, true, s_last, 1);
         s_last = scale_of(0, G - 1);
@@ -1432,10 +1457,12 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
     for (; k + 1 < m; k += 2) {
         const int tk = t0 + k * stride;
         __syncthreads();                         // stage k (odd)
+        rotate_priority(k);
         fetch(rb, tk + 2 * stride);
         tile_scores(1, tk);
         to_lds(0, ra);
         __syncthreads();                         // stage k + 1 (even)
+        rotate_priority(k + 1);
         fetch(ra, tk + 3 * stride);
         tile_scores(0, tk + stride);
         to_lds(1, rb);
