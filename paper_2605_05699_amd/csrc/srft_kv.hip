@@ -34,9 +34,13 @@
 // described at srft_quantize_fold_tiles and at the FOLD parameter of srft_dequantize_tiles.
 //
 // Around the two paths: the same kernels serving several plans in one launch (a segment table passed as a
-// kernel argument), the per-channel abs-max statistic lambda is calibrated from, an 8-bit code width, and
-// a host-side cache manager (int4 store, fp16 residual window, dequantized view) built on the batched
-// launches.
+// kernel argument), the per-channel abs-max statistic lambda is calibrated from, an 8-bit code width, the
+// Walsh-Hadamard matrix in place of the DFT (the comparator of Sec. 3.1), scores of queries against the stored
+// record without reconstructing the keys, and a host-side cache manager (int4 store, fp16 residual window,
+// dequantized view) built on the batched launches.
+//
+// The kernels run at the socket's power limit with a throttled clock, so what shortens them is work per vector
+// (matrix instructions, vector instructions, LDS traffic), not more parallelism: see the folded forms.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
