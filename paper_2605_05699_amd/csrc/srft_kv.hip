@@ -1250,41 +1250,36 @@ template <int D, bool R16>
 __global__ void __launch_bounds__(64)
 srft_scores_prepare_kernel(const float* __restrict__ wq, const float* __restrict__ inv_lam2, int n_q,
                            uint4* __restrict__ qfrag) {
-    constexpr int G = D / 32;
     const int lane = threadIdx.x;
     if constexpr (R16) {
         const int r = lane & 15, kg = lane >> 4, a = r / 4, i = r % 4;
         const int qi = a < 2 ? 2 * i + a : 8 + 2 * i + (a - 2);          // query carried by MFMA row r
-#pragma unroll 1
-        for (int j = 0; j < G; ++j) {
-            half8 hi, lo;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int p = 8 * (4 * j + kg) + (e / 2) + 4 * (e % 2);  // the 4-bit decode order of the read path
-                const float v = qi < n_q ? wq[qi * D + p] * inv_lam2[p] : 0.0f;
-                hi[e] = (_Float16)v;
-                lo[e] = (_Float16)(v - (float)hi[e]);
-            }
-            qfrag[(j * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
-            qfrag[(j * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
-        }
-        return;
-    }
-    const int i = lane & 31, kh = lane >> 5;
-    const int qi = 2 * (4 * (i / 8) + i % 4) + (i / 4) % 2;              // query carried by MFMA row i
-#pragma unroll 1
-    for (int f = 0; f < 2 * G; ++f) {                                    // k-step f = 2 j + t: codes 16 f .. 16 f + 15
+        const int j = blockIdx.x;                                        // one workgroup per fragment: grid = G
         half8 hi, lo;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int p = 8 * (2 * f + kh) + (e / 2) + 4 * (e % 2);      // the 4-bit decode order of the read path
+            const int p = 8 * (4 * j + kg) + (e / 2) + 4 * (e % 2);      // the 4-bit decode order of the read path
             const float v = qi < n_q ? wq[qi * D + p] * inv_lam2[p] : 0.0f;
             hi[e] = (_Float16)v;
             lo[e] = (_Float16)(v - (float)hi[e]);
         }
-        qfrag[(f * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
-        qfrag[(f * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
+        qfrag[(j * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
+        qfrag[(j * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
+        return;
     }
+    const int i = lane & 31, kh = lane >> 5;
+    const int qi = 2 * (4 * (i / 8) + i % 4) + (i / 4) % 2;              // query carried by MFMA row i
+    const int f = blockIdx.x;                // k-step f = 2 j + t: codes 16 f .. 16 f + 15; grid = 2 G
+    half8 hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int p = 8 * (2 * f + kh) + (e / 2) + 4 * (e % 2);          // the 4-bit decode order of the read path
+        const float v = qi < n_q ? wq[qi * D + p] * inv_lam2[p] : 0.0f;
+        hi[e] = (_Float16)v;
+        lo[e] = (_Float16)(v - (float)hi[e]);
+    }
+    qfrag[(f * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
+    qfrag[(f * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
 }
 
 // Step 2.  codes [n_keys][D/16] 8-byte units, scales [n_keys][ns], out [n_q][n_keys] fp32.
@@ -1819,8 +1814,8 @@ int launch_scores(const srft_plan* p, const float* wq, uint4* qfrag, float* dump
                   const float* scales, long long n_keys, float* out, hipStream_t st) {
     if constexpr (D % 64 == 0) {
         const bool r16 = n_q <= 16;             // 16 MFMA rows are enough: half the matrix-core time
-        if (r16) hipLaunchKernelGGL((srft_scores_prepare_kernel<D, true>), dim3(1), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
-        else hipLaunchKernelGGL((srft_scores_prepare_kernel<D, false>), dim3(1), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
+        if (r16) hipLaunchKernelGGL((srft_scores_prepare_kernel<D, true>), dim3(D / 32), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
+        else hipLaunchKernelGGL((srft_scores_prepare_kernel<D, false>), dim3(D / 16), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
         SRFT_HIP(hipGetLastError());
         const long long n_tiles = (n_keys + kTileVecs - 1) / kTileVecs;
         long long grid = p->max_wgs > 0 ? p->max_wgs : (r16 ? p->grid_scores16 : p->grid_scores);
