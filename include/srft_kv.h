@@ -152,7 +152,7 @@ int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t 
  *   workspace_dev  srft_scores_workspace_bytes(plan) bytes of device memory (about 1 MiB), 16-byte aligned,
  *                  overwritten; two calls that may run at the same time need a workspace each.
  * For plans with d a multiple of 64, 4-bit codes and g >= 32 (else SRFT_ERR_BAD_D / _BAD_BITS / _BAD_GROUP).
- * Enqueues three small-to-large kernels on the stream: transform of the queries, operand set-up, the scan.
+ * Enqueues two kernels on the stream: transform of the queries into the scan's operand layout, then the scan.
  */
 int64_t srft_scores_workspace_bytes(const srft_plan_t* plan);
 int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,

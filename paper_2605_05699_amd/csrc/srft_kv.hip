@@ -192,12 +192,15 @@ __device__ __forceinline__ uint32_t pack4_bytes(const floatx16& acc, int base, f
 //         kOutAmax: no per-vector output; every lane keeps the running maximum of |w| of its 16 channels over the
 //         tiles it sees, lanes are reduced once at the end and one atomic max per channel and workgroup goes
 //         to wout, read as float[d] (srft_kv_channel_absmax: the statistic lambda is calibrated from, Sec. 7.1).
+//         kOutQFrag32 / kOutQFrag16: the vectors are queries of srft_kv_scores (one tile at most): w times
+//         scales[p] (there: 1 / (lambda max(lambda, 1e-6))), split into fp16 hi + lo and stored to wout as the
+//         A fragments of the scores kernel with 32 or 16 rows of queries (layouts described there).
 // GM    : group mode.  kGroup32: one scale per slab (g = 32, the deployed format).  kGroup16: one scale per
 //         lane (g = 16; a lane's 16 outputs are one group, no cross-lane step).  kGroupWide: g = 32 * gw with
 //         gw >= 2 slabs per group, up to the per-token case g = d; the slab maxima meet in LDS, which costs
 //         two more barriers per tile.
 enum { kGroup16 = 0, kGroup32 = 1, kGroupWide = 2 };
-enum { kOutCodes = 0, kOutRaw = 1, kOutAmax = 2 };
+enum { kOutCodes = 0, kOutRaw = 1, kOutAmax = 2, kOutQFrag32 = 3, kOutQFrag16 = 4 };
 // The work of one workgroup: tiles t0, t0 + stride, ... of one plan's n_vec vectors (t0 < number of tiles).
 // BITS  : 4 (two nibbles per byte) or 8 (one byte per value, scale = abs-max / 127; Sec. 3.2 steps 3-4)
 template <int D, int S, int OUT, int GM, int BITS>
@@ -287,6 +290,40 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
             each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) cmax[s][v] = fmaxf(cmax[s][v], fabsf(acc[v]));
+            });
+        } else if constexpr (OUT == kOutQFrag32 || OUT == kOutQFrag16) {
+            // lane (query col, half) holds the packed indices p0 .. p0 + 15 of its query: code units p0 / 8 and
+            // p0 / 8 + 1, whole.  Fragment element e of a unit is packed index 8 unit + e / 2 + 4 (e % 2) (the
+            // 4-bit decode order of the read path).  Rows of queries that do not exist are zero.
+            uint4* frag = reinterpret_cast<uint4*>(wout);
+            const int q = col;
+            each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
+                const int p0 = 32 * (wave * S + s) + 16 * half;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    half8 hi, lo;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int pp = 8 * i + (e / 2) + 4 * (e % 2);
+                        const float v = q <= lim ? (acc[pp] * unscale) * scales[p0 + pp] : 0.0f;
+                        hi[e] = (_Float16)v;
+                        lo[e] = (_Float16)(v - (float)hi[e]);
+                    }
+                    const int u = p0 / 8 + i;
+                    if constexpr (OUT == kOutQFrag16) {
+                        // MFMA row 4 a + i' carries query 2 i' + a (a < 2) or 8 + 2 i' + (a - 2); lane = 16 (u % 4) + row
+                        const int row = q < 8 ? 4 * (q % 2) + q / 2 : 4 * (2 + q % 2) + (q - 8) / 2;
+                        if (q < 16) {
+                            frag[((u / 4) * 2 + 0) * 64 + 16 * (u % 4) + row] = __builtin_bit_cast(uint4, hi);
+                            frag[((u / 4) * 2 + 1) * 64 + 16 * (u % 4) + row] = __builtin_bit_cast(uint4, lo);
+                        }
+                    } else {
+                        // MFMA row 8 (v / 4) + 4 h + v % 4 carries query 2 v + h; lane = 32 (u % 2) + row
+                        const int row = 8 * ((q / 2) / 4) + 4 * (q % 2) + (q / 2) % 4;
+                        frag[((u / 2) * 2 + 0) * 64 + 32 * (u % 2) + row] = __builtin_bit_cast(uint4, hi);
+                        frag[((u / 2) * 2 + 1) * 64 + 32 * (u % 2) + row] = __builtin_bit_cast(uint4, lo);
+                    }
+                }
             });
         } else if constexpr (OUT == kOutRaw) {
             each_acc(accs, [&](floatx16& acc, int s) __attribute__((always_inline)) {
@@ -1237,8 +1274,8 @@ srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
 // per workgroup, each walking its own tiles of 32 keys: codes are loaded coalesced, decoded into LDS (which
 // transposes them into B fragments), contracted group by group and folded with the group scales.
 //
-// Step 1 (srft_scores_prepare_kernel): q' from w = lambda * Q (s * q), which the write path's kernel computes
-// in its raw mode: q' = w / (lambda * max(lambda, 1e-6)), split into fp16 hi + lo, laid out as A fragments.
+// Step 1: q' = w / (lambda * max(lambda, 1e-6)) with w = lambda * Q (s * q), split into fp16 hi + lo and laid out as
+// A fragments.  The write path's plain kernel does it, in its kOutQFrag32 / kOutQFrag16 modes (one launch).
 // Two layouts, both chosen so that the first ceil(n_q / 2) result registers of the lanes hold all the queries
 // (a small group of queries costs few stores):
 //   32 rows (n_q > 16; v_mfma_f32_32x32x16_f16): [d/32 groups][2 k-steps][hi, lo][64 lanes]; MFMA row i (lane half
@@ -1246,42 +1283,7 @@ srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
 //   16 rows (R16, n_q <= 16; v_mfma_f32_16x16x32_f16, half the matrix-core time): [d/32 groups][hi, lo][64 lanes];
 //     lane l holds row l % 16 and the 8 codes of unit 4 j + l / 16 of group j.  MFMA row r = 4 a + i (result register i
 //     of the lanes 16 a .. 16 a + 15) carries query 2 i + a for a < 2 and 8 + 2 i + (a - 2) for a >= 2.
-template <int D, bool R16>
-__global__ void __launch_bounds__(64)
-srft_scores_prepare_kernel(const float* __restrict__ wq, const float* __restrict__ inv_lam2, int n_q,
-                           uint4* __restrict__ qfrag) {
-    const int lane = threadIdx.x;
-    if constexpr (R16) {
-        const int r = lane & 15, kg = lane >> 4, a = r / 4, i = r % 4;
-        const int qi = a < 2 ? 2 * i + a : 8 + 2 * i + (a - 2);          // query carried by MFMA row r
-        const int j = blockIdx.x;                                        // one workgroup per fragment: grid = G
-        half8 hi, lo;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int p = 8 * (4 * j + kg) + (e / 2) + 4 * (e % 2);      // the 4-bit decode order of the read path
-            const float v = qi < n_q ? wq[qi * D + p] * inv_lam2[p] : 0.0f;
-            hi[e] = (_Float16)v;
-            lo[e] = (_Float16)(v - (float)hi[e]);
-        }
-        qfrag[(j * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
-        qfrag[(j * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
-        return;
-    }
-    const int i = lane & 31, kh = lane >> 5;
-    const int qi = 2 * (4 * (i / 8) + i % 4) + (i / 4) % 2;              // query carried by MFMA row i
-    const int f = blockIdx.x;                // k-step f = 2 j + t: codes 16 f .. 16 f + 15; grid = 2 G
-    half8 hi, lo;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int p = 8 * (2 * f + kh) + (e / 2) + 4 * (e % 2);          // the 4-bit decode order of the read path
-        const float v = qi < n_q ? wq[qi * D + p] * inv_lam2[p] : 0.0f;
-        hi[e] = (_Float16)v;
-        lo[e] = (_Float16)(v - (float)hi[e]);
-    }
-    qfrag[(f * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
-    qfrag[(f * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
-}
-
+//
 // Step 2.  codes [n_keys][D/16] 8-byte units, scales [n_keys][ns], out [n_q][n_keys] fp32.
 // NV: result registers a lane stores per tile (NV >= ceil(n_q / 2), a power of two; 16 with 32 rows, <= 8 with 16).
 // Every lane stores NV times per tile whatever n_q and the tile are: a lane without a valid (query, key) writes
@@ -1644,6 +1646,10 @@ template <int D, int S>
 quantize_kernel_t quantize_instance(int out, int gm, int bits) {
     if (out == kOutRaw) return srft_quantize_kernel<D, S, kOutRaw, kGroup32, 4>;
     if (out == kOutAmax) return srft_quantize_kernel<D, S, kOutAmax, kGroup32, 4>;
+    if constexpr (S == 1 && D % 64 == 0) {       // the scores set-up always runs one slab per wavefront
+        if (out == kOutQFrag32) return srft_quantize_kernel<D, 1, kOutQFrag32, kGroup32, 4>;
+        if (out == kOutQFrag16) return srft_quantize_kernel<D, 1, kOutQFrag16, kGroup32, 4>;
+    }
     return bits == 8 ? quantize_codes_instance<D, S, 8>(gm) : quantize_codes_instance<D, S, 4>(gm);
 }
 template <int D>
@@ -1701,8 +1707,9 @@ int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* cod
     long long grid = p->max_wgs > 0 ? p->max_wgs : p->grid_q;
     if (grid > n_tiles) grid = n_tiles;
     const bool fold = p->fold_q && out == kOutCodes;
-    const quantize_kernel_t kernel = quantize_instance<D>(p->slabs_q, out, p->gm, fold, p->bits);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(fold ? D : 2 * D / p->slabs_q), 0, st,
+    const int slabs = (out == kOutQFrag32 || out == kOutQFrag16) ? 1 : p->slabs_q;
+    const quantize_kernel_t kernel = quantize_instance<D>(slabs, out, p->gm, fold, p->bits);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(fold ? D : 2 * D / slabs), 0, st,
                        fold ? p->wfold : p->wfrag, (const uint4*)x, n,
                        (uint2*)codes, scales, (float4*)wout, p->unscale_w, p->unscale_w / (p->bits == 8 ? 127.0f : 7.0f),
                        p->gw);
@@ -1810,13 +1817,10 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
     }
 
 template <int D>
-int launch_scores(const srft_plan* p, const float* wq, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
+int launch_scores(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
                   const float* scales, long long n_keys, float* out, hipStream_t st) {
     if constexpr (D % 64 == 0) {
         const bool r16 = n_q <= 16;             // 16 MFMA rows are enough: half the matrix-core time
-        if (r16) hipLaunchKernelGGL((srft_scores_prepare_kernel<D, true>), dim3(D / 32), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
-        else hipLaunchKernelGGL((srft_scores_prepare_kernel<D, false>), dim3(D / 16), dim3(64), 0, st, wq, p->inv_lam2, n_q, qfrag);
-        SRFT_HIP(hipGetLastError());
         const long long n_tiles = (n_keys + kTileVecs - 1) / kTileVecs;
         long long grid = p->max_wgs > 0 ? p->max_wgs : (r16 ? p->grid_scores16 : p->grid_scores);
         if (grid > n_tiles) grid = n_tiles;
@@ -1835,9 +1839,9 @@ int launch_scores(const srft_plan* p, const float* wq, uint4* qfrag, float* dump
 }
 
 int dispatch_occupancy(srft_plan* p, int cus) { SRFT_DISPATCH_D(p->d, occupancy_grids, p, cus) }
-int dispatch_scores(const srft_plan* p, const float* wq, uint4* qfrag, float* dump, int n_q, const uint8_t* c,
+int dispatch_scores(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t* c,
                     const float* s, long long n, float* o, hipStream_t st) {
-    SRFT_DISPATCH_D(p->d, launch_scores, p, wq, qfrag, dump, n_q, c, s, n, o, st)
+    SRFT_DISPATCH_D(p->d, launch_scores, p, qfrag, dump, n_q, c, s, n, o, st)
 }
 int dispatch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* c, float* s, float* w, int out,
                       hipStream_t st) { SRFT_DISPATCH_D(p->d, launch_quantize, p, x, n, c, s, w, out, st) }
@@ -2123,9 +2127,9 @@ int srft_kv_channel_absmax(const srft_plan_t* plan, const void* x_f16_dev, int64
 
 int64_t srft_scores_workspace_bytes(const srft_plan_t* plan) {
     if (!plan) return SRFT_ERR_NULL;
-    // w of up to 32 queries (fp32), then their A fragments: d/16 k-steps x (hi, lo) x 64 lanes x 16 bytes, then
-    // 64 floats per workgroup that absorb the stores of lanes without a valid (query, key)
-    return (int64_t)32 * plan->d * 4 + (int64_t)(plan->d / 16) * 2 * 64 * 16 + (int64_t)kMaxScoreWorkgroups * 64 * 4;
+    // the A fragments of up to 32 queries: d/16 k-steps x (hi, lo) x 64 lanes x 16 bytes, then 64 floats per
+    // workgroup that absorb the stores of lanes without a valid (query, key)
+    return (int64_t)(plan->d / 16) * 2 * 64 * 16 + (int64_t)kMaxScoreWorkgroups * 64 * 4;
 }
 
 int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
@@ -2141,12 +2145,13 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
         !aligned(workspace_dev, 16))
         return SRFT_ERR_ALIGN;
     hipStream_t st = (hipStream_t)hip_stream;
-    float* wq = (float*)workspace_dev;
-    uint4* qfrag = (uint4*)((char*)workspace_dev + (size_t)32 * plan->d * 4);
+    uint4* qfrag = (uint4*)workspace_dev;
     float* dump = (float*)((char*)qfrag + (size_t)(plan->d / 16) * 2 * 64 * 16);
-    const int rc = dispatch_quantize(plan, q_f16_dev, n_q, nullptr, nullptr, wq, kOutRaw, st);
+    // the write path's plain kernel transforms the queries and stores them as the scan's MFMA operands
+    const int rc = dispatch_quantize(plan, q_f16_dev, n_q, nullptr, plan->inv_lam2, (float*)qfrag,
+                                     n_q <= 16 ? kOutQFrag16 : kOutQFrag32, st);
     if (rc != SRFT_OK) return rc;
-    return dispatch_scores(plan, wq, qfrag, dump, n_q, codes_dev, scales_dev, n_keys, scores_dev, st);
+    return dispatch_scores(plan, qfrag, dump, n_q, codes_dev, scales_dev, n_keys, scores_dev, st);
 }
 
 int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host) {
