@@ -1351,12 +1351,12 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
     // lane (key, a) stores val[v] to row 2 v + a of out for v < its number of valid rows, elsewhere to its dump slot
     auto store_rows = [&](const float (&val)[NV], long long key, int a) __attribute__((always_inline)) {
         const int nv_lane = key < n_keys ? (n_q - a + 1) >> 1 : 0;
-        float* p = out + ((long long)a * n_keys + key);
+        long long at = (long long)a * n_keys + key;          // index of (row a, key); only used where it is valid
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            float* dst = v < nv_lane ? p : my_dump;
+            float* dst = v < nv_lane ? out + at : my_dump;
             *dst = val[v];
-            p += 2 * n_keys;
+            at += 2 * n_keys;
         }
         // With many queries the kernel mostly writes; letting a tile's stores complete before the next stage
         // measured 3-5 % faster than keeping them in flight (s_waitcnt vmcnt(0); the other counters at their maximum).
