@@ -1515,6 +1515,10 @@ srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long lon
             const int u = threadIdx.x + 256 * i;
             v[i] = STREAM ? stream_load(&s[u < r_units ? u : r_units - 1]) : s[u < r_units ? u : r_units - 1];
         }
+        // every thread consumes what it loaded, here: only w_units of the 256 threads store, and without this the
+        // compiler sinks the loads into the storing threads' branch, so that the others read nothing
+#pragma unroll
+        for (int i = 0; i < RU; ++i) asm volatile("" ::"v"(v[i].x), "v"(v[i].y), "v"(v[i].z), "v"(v[i].w));
         uint4 acc = v[0];
 #pragma unroll
         for (int i = 1; i < RU; ++i) { acc.x ^= v[i].x; acc.y ^= v[i].y; acc.z ^= v[i].z; acc.w ^= v[i].w; }
