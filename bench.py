@@ -319,6 +319,25 @@ def mix_ceiling(B, torch, x, out, total_vec, d, G, stream):
             best[str(wgs)] = n_tiles * (rb + wb) / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
         res[name + "_GBps_by_workgroups"] = best
         res[name + "_GBps"] = max(best.values())
+    # what the machine gives plain streams (16 KiB per tile on the side that moves): read only, write only, copy
+    os.environ["SRFT_MIX_STREAM"] = "0"
+    plain = {}
+    for name, (rb, wb) in (("read_only", (16384, 0)), ("write_only", (0, 16384)), ("copy", (16384, 16384)),
+                           ("read4_write1", (16384, 4096)), ("read1_write4", (4096, 16384))):
+        nt = min(2 << 30, a.numel(), b.numel()) // 16384       # up to 2 GiB per side, inside both buffers
+        best = 0.0
+        for wgs in (512, 1024, 4096, 16384):
+            for _ in range(2):
+                B.srft_stream_mix(a, b, nt, rb, wb, wgs, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                B.srft_stream_mix(a, b, nt, rb, wb, wgs, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            best = max(best, nt * (rb + wb) / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9)
+        plain[name] = best
+    res["plain_streams_GBps"] = plain
     return res
 
 

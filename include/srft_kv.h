@@ -244,7 +244,8 @@ int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* 
  * and writes write_bytes_per_tile contiguous bytes to dst_dev, with coalesced 16-byte accesses and no
  * arithmetic.  With 8192 : 2560 it has the write path's byte mix at d = 128 (32 vectors per tile), with
  * 2560 : 8192 the read path's; its rate is the ceiling the memory system offers such a kernel.
- * Byte counts must be positive multiples of 16; workgroups = 0 picks 3 per compute unit.  With SRFT_MIX_STREAM=1 in
+ * Byte counts must be multiples of 16, at most 32 KiB read per tile, and not both zero (one of them zero gives the
+ * read-only or the write-only stream); workgroups = 0 picks 3 per compute unit.  With SRFT_MIX_STREAM=1 in
  * the environment (read at every call) the accesses are non-temporal, as the read path's are.
  */
 int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int read_bytes_per_tile,

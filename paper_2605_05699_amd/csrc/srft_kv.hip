@@ -1509,11 +1509,13 @@ __global__ void __launch_bounds__(256)
 srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n_tiles, int r_units, int w_units) {
     for (long long t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const uint4* s = src + t * r_units;
-        uint4 v[RU];
+        uint4 v[RU] = {};
+        if (r_units > 0) {                       // uniform; r_units = 0 is the write-only stream
 #pragma unroll
-        for (int i = 0; i < RU; ++i) {
-            const int u = threadIdx.x + 256 * i;
-            v[i] = STREAM ? stream_load(&s[u < r_units ? u : r_units - 1]) : s[u < r_units ? u : r_units - 1];
+            for (int i = 0; i < RU; ++i) {
+                const int u = threadIdx.x + 256 * i;
+                v[i] = STREAM ? stream_load(&s[u < r_units ? u : r_units - 1]) : s[u < r_units ? u : r_units - 1];
+            }
         }
         // every thread consumes what it loaded, here: only w_units of the 256 threads store, and without this the
         // compiler sinks the loads into the storing threads' branch, so that the others read nothing
@@ -2386,8 +2388,8 @@ int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* 
 
 int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int read_bytes_per_tile,
                     int write_bytes_per_tile, int workgroups, void* hip_stream) {
-    if (n_tiles < 0 || read_bytes_per_tile <= 0 || write_bytes_per_tile <= 0 || read_bytes_per_tile % 16 ||
-        write_bytes_per_tile % 16 || workgroups < 0)
+    if (n_tiles < 0 || read_bytes_per_tile < 0 || write_bytes_per_tile < 0 || read_bytes_per_tile % 16 ||
+        write_bytes_per_tile % 16 || read_bytes_per_tile + write_bytes_per_tile == 0 || workgroups < 0)
         return SRFT_ERR_BAD_N;
     if (n_tiles == 0) return SRFT_OK;
     if (!src_dev || !dst_dev) return SRFT_ERR_NULL;
@@ -2398,7 +2400,7 @@ int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int rea
     long long grid = workgroups > 0 ? workgroups : (long long)cus * 3;
     if (grid > n_tiles) grid = n_tiles;
     const int r_units = read_bytes_per_tile / 16, w_units = write_bytes_per_tile / 16;
-    const int ru = (r_units + 255) / 256;
+    const int ru = r_units > 0 ? (r_units + 255) / 256 : 1;
     const char* env = std::getenv("SRFT_MIX_STREAM");          // 1: non-temporal accesses (read on every call)
     const bool stream = env && std::atoi(env) != 0;
     void (*kernel)(const uint4*, uint4*, long long, int, int) = nullptr;
