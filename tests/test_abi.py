@@ -75,6 +75,13 @@ def test_null_plan_and_size_errors(L):
     assert L.srft_stream_copy(None, None, 24, None) == -7
     assert L.srft_stream_copy(None, None, 32, None) == -1
     assert L.srft_stream_copy(None, None, 0, None) == 0
+    # the streaming measurement aid: byte counts are multiples of 16, not both zero; either may be zero
+    for rb, wb in ((0, 0), (-16, 16), (16, -16), (24, 16), (16, 8)):
+        assert L.srft_stream_mix(None, None, 4, rb, wb, 0, None) == -7, (rb, wb)
+    assert L.srft_stream_mix(None, None, -1, 16, 16, 0, None) == -7
+    assert L.srft_stream_mix(None, None, 0, 16, 0, 0, None) == 0          # no tiles: nothing to do
+    assert L.srft_stream_mix(None, None, 4, 16, 0, 0, None) == -1         # read-only is a valid shape; pointers are not
+    assert L.srft_stream_mix(None, None, 4, 0, 16, 0, None) == -1
     # lambda from the calibration statistic: host only
     amax = (C.c_float * 4)(2.0, 0.0, 1e-9, 0.5)
     lam = (C.c_float * 4)()
