@@ -9,6 +9,11 @@ and the write path does so only for plans with fewer than 65,536 vectors (for la
 Inputs are synthetic, seeded, and resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Beside the contract's keys the line carries per-path figures ("quantize", "dequantize"), for the default workload a
+side measurement of the same launch shape at d = 256 ("d256_same_launch_shape", skip with --no-d256), and on request
+the streaming ceilings of the memory system (--ceiling), power and clock per path (--power), the decode-step append
+(--decode-append) and scores against the stored keys (--scores).
 """
 from __future__ import annotations
 
@@ -26,6 +31,13 @@ MEASURED_TRAFFIC_PER_VECTOR = {
     # vectors per dispatch, d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
     ("llama3-70b-128k", "srft_quantize_kernel"): (131338.7 * 2.0 + 81962.4) * 1024 / 1048576,
     ("llama3-70b-128k", "srft_dequantize_kernel"): (164623.8 * 2.0 + 1048576.1) * 1024 / (4 * 1048576),
+}
+
+# What a kernel that only streams the same bytes reaches on this machine (bench.py --ceiling, best over grid sizes;
+# profiles/stream_ceiling_d128_mixes.txt), GB/s, by the dominant kernel of the default workload.
+MEASURED_STREAM_CEILING_GBPS = {
+    ("llama3-70b-128k", "srft_quantize_kernel"): 5461.0,       # 8192 B read : 2560 B written per tile
+    ("llama3-70b-128k", "srft_dequantize_kernel"): 5371.0,     # 2560 : 8192
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
@@ -175,7 +187,9 @@ def main() -> int:
                      "traffic": (MEASURED_TRAFFIC_PER_VECTOR[(w.name, dominant)] * total_vec / launches
                                  if (w.name, dominant) in MEASURED_TRAFFIC_PER_VECTOR else None),
                      "algorithmic_bytes_per_launch": total_vec * bytes_per_vec // launches,
-                     "avg_launch_ms": dom_l * 1e3},
+                     "avg_launch_ms": dom_l * 1e3,
+                     # context, not the roofline: the rate of a pure stream with this kernel's byte mix
+                     "stream_ceiling_GBps": MEASURED_STREAM_CEILING_GBPS.get((w.name, dominant))},
         "paper_context_apple_m1": PAPER_CONTEXT,
     }
 
