@@ -80,6 +80,7 @@ def main() -> int:
     import numpy as np
     import torch
     from paper_2605_05699_amd import binding as B
+    from paper_2605_05699_amd import measure as M
     from paper_2605_05699_amd import workloads as W
 
     if not torch.cuda.is_available():
@@ -197,7 +198,7 @@ def main() -> int:
         # the metric names d = 256 beside d = 128: the same launch shape (1,048,576 vectors per plan) at d = 256
         result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream)
     if args.ceiling:
-        result["hbm_ceiling"] = mix_ceiling(B, torch, x, out, n_plans * n, d, G, stream)
+        result["hbm_ceiling"] = mix_ceiling(M, torch, x, out, n_plans * n, d, G, stream)
     if args.power:
         def q_pass():
             for p in range(n_plans):
@@ -213,9 +214,9 @@ def main() -> int:
             "quantize": sampled_phase(torch, q_pass, n_plans * n * bytes_per_vec),
             "dequantize": sampled_phase(torch, d_pass, n_plans * n * bytes_per_vec),
             "stream_quantize_mix": sampled_phase(
-                torch, lambda: B.srft_stream_mix(xa, xb, tiles, big, small, 768, stream), tiles * (big + small)),
+                torch, lambda: M.srft_stream_mix(xa, xb, tiles, big, small, 768, False, stream), tiles * (big + small)),
             "stream_dequantize_mix": sampled_phase(
-                torch, lambda: B.srft_stream_mix(xa, xb, tiles, small, big, 768, stream), tiles * (big + small)),
+                torch, lambda: M.srft_stream_mix(xa, xb, tiles, small, big, 768, False, stream), tiles * (big + small)),
         }
     if args.scores:
         n_q = 8
@@ -247,11 +248,11 @@ def main() -> int:
         src = out.view(torch.uint8).reshape(-1)[:nb]
         dst = x.view(torch.uint8).reshape(-1)[:nb]
         for _ in range(2):
-            B.srft_stream_copy(dst, src, stream)
+            M.srft_stream_copy(dst, src, stream)
         c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         c0.record(stream)
         for _ in range(5):
-            B.srft_stream_copy(dst, src, stream)
+            M.srft_stream_copy(dst, src, stream)
         c1.record(stream)
         torch.cuda.synchronize()
         result["copy_kernel"] = {"bytes_each_way": nb, "GBps_read_plus_write": 2 * nb / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9}
@@ -310,31 +311,28 @@ def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=3):
                            "vectors_per_s": n_plans * n / td}}
 
 
-def mix_ceiling(B, torch, x, out, total_vec, d, G, stream):
+def mix_ceiling(M, torch, x, out, total_vec, d, G, stream):
     """Streaming kernel with the write path's and the read path's byte mix, no arithmetic: GB/s over a few grids."""
     big, small = 32 * 2 * d, 32 * (d // 2 + 4 * G)
     n_tiles = min(total_vec // 32, (2 << 30) // big)         # at most 2 GiB on the large side
     a, b = x.view(torch.uint8).reshape(-1), out.view(torch.uint8).reshape(-1)
     res = {"tiles": n_tiles, "read_write_bytes_per_tile": {"quantize_mix": [big, small], "dequantize_mix": [small, big]}}
-    import os
-    for name, (rb, wb), stream_env in (("quantize_mix", (big, small), "0"), ("dequantize_mix", (small, big), "0"),
-                                       ("dequantize_mix_streaming_accesses", (small, big), "1")):
-        os.environ["SRFT_MIX_STREAM"] = stream_env           # the library reads it at every call
+    for name, (rb, wb), nt_acc in (("quantize_mix", (big, small), False), ("dequantize_mix", (small, big), False),
+                                   ("dequantize_mix_streaming_accesses", (small, big), True)):
         best = {}
         for wgs in (512, 768, 1024, 2048, 4096, 8192):
             for _ in range(3):
-                B.srft_stream_mix(a, b, n_tiles, rb, wb, wgs, stream)
+                M.srft_stream_mix(a, b, n_tiles, rb, wb, wgs, nt_acc, stream)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             for _ in range(10):
-                B.srft_stream_mix(a, b, n_tiles, rb, wb, wgs, stream)
+                M.srft_stream_mix(a, b, n_tiles, rb, wb, wgs, nt_acc, stream)
             e1.record(stream)
             torch.cuda.synchronize()
             best[str(wgs)] = n_tiles * (rb + wb) / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
         res[name + "_GBps_by_workgroups"] = best
         res[name + "_GBps"] = max(best.values())
     # what the machine gives plain streams (16 KiB per tile on the side that moves): read only, write only, copy
-    os.environ["SRFT_MIX_STREAM"] = "0"
     plain = {}
     for name, (rb, wb) in (("read_only", (16384, 0)), ("write_only", (0, 16384)), ("copy", (16384, 16384)),
                            ("read4_write1", (16384, 4096)), ("read1_write4", (4096, 16384))):
@@ -342,11 +340,11 @@ def mix_ceiling(B, torch, x, out, total_vec, d, G, stream):
         best = 0.0
         for wgs in (512, 1024, 4096, 16384):
             for _ in range(2):
-                B.srft_stream_mix(a, b, nt, rb, wb, wgs, stream)
+                M.srft_stream_mix(a, b, nt, rb, wb, wgs, False, stream)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             for _ in range(10):
-                B.srft_stream_mix(a, b, nt, rb, wb, wgs, stream)
+                M.srft_stream_mix(a, b, nt, rb, wb, wgs, False, stream)
             e1.record(stream)
             torch.cuda.synchronize()
             best = max(best, nt * (rb + wb) / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9)

@@ -8,7 +8,7 @@
  *     scale_j = max_{k in group j} |w_k| / 7,  groups = runs of g packed indices          (Sec. 7.1)
  *     q_k = rint(w_k / scale_j) in [-7, 7]   (round half to even)                         (Sec. 3.2 step 4)
  *     byte_i = (q_{2i+1} << 4) | (q_{2i} & 0xF)                                           (Sec. 3.2 (ii))
- * Read path (the "matching inverse" of Sec. 7.1): unpack nibbles (4-bit two's complement), times
+ * Read path (the inverse kernel of Sec. 7.1): unpack nibbles (4-bit two's complement), times
  * scale_j, divide by max(lambda_k, 1e-6), unpack Eq. 2, unitary inverse DFT, times s, round to fp16.
  *
  * Stored record per vector: d/2 code bytes and d/g fp32 scales, in two separate arrays.
@@ -58,7 +58,7 @@ typedef enum srft_status {
  *   d            head dimension.
  *   group_size   g, the number of consecutive packed indices sharing one scale.
  *   sign_seed    the sign diagonal is the splitmix64 stream started at this seed: s_n = -1 iff the
- *                top bit of the n-th output is set ("drawn at initialization", Sec. 3.1).
+ *                top bit of the n-th output is set (the signs are fixed when the plan is made, Sec. 3.1).
  *   lambda_host  d floats > 0 on the host, or NULL for all ones.  Copied; not kept.
  * Allocates device tables on the current GPU (about 4*d*d bytes) and copies them once.
  */
@@ -120,7 +120,8 @@ int srft_kv_dequantize(const srft_plan_t* plan, const uint8_t* codes_dev, const 
  *                                returns and not kept.
  *   count                        number of entries; 0 is a successful no-op.  Entries with n_vec[i] == 0 are
  *                                skipped (their pointers are not looked at).
- * All plans must share d, group_size and device (else SRFT_ERR_MISMATCH); signs and lambda may differ.
+ * All plans must share d, group_size, code width, transform and device (else SRFT_ERR_MISMATCH); signs and lambda
+ * may differ.
  * Every entry is validated before anything is enqueued.  Up to 64 entries go into one kernel launch; longer
  * lists take several launches on the same stream.  Results are bit-identical to the per-plan calls.
  * Buffers of different entries must not overlap.
@@ -161,7 +162,7 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
 
 /*
  * Cache manager: int4 store + fp16 residual window + dequantized-prefix cache.   (Sec. 7.2: the cache class,
- * items (i)-(iv); the "Residual window" paragraph: 16 tokens.)
+ * items (i)-(iv), and its paragraph on the residual window: 16 tokens.)
  *
  * One cache holds n_plans (layer, K|V) plans of one shape, each with n_seq sequences (batch x kv_heads) that grow
  * in lock-step.  All device buffers belong to the caller, one per plan, in a paged layout whose page is the
@@ -196,8 +197,8 @@ int64_t srft_cache_tokens(const srft_cache_t* cache);              /* tokens per
 int64_t srft_cache_quantized_tokens(const srft_cache_t* cache);    /* of which in the int4 store */
 
 /*
- * Calibration statistic for lambda: per-channel abs-max of the transform output over a batch.  (Sec. 7.1: "lambda_d =
- * 1 / per_channel_max(SRFT output)_d"; Sec. 7.2, the static "window-uniform" calibration over whole windows.)
+ * Calibration statistic for lambda: per-channel abs-max of the transform output over a batch.  (Sec. 7.1: lambda is
+ * the reciprocal of that maximum; Sec. 7.2: one static calibration over whole windows.)
  *   x_f16_dev  [n_vec, d] fp16, 16-byte aligned.                                         read only
  *   amax_dev   d fp32 on the device, 4-byte aligned, all >= 0: a RUNNING maximum.  On return amax_dev[k] =
  *              max(old amax_dev[k], max over the n_vec vectors of |w_k|), w = lambda * pack(F (s * x)) with the
@@ -226,30 +227,11 @@ int srft_plan_get_signs(const srft_plan_t* plan, int8_t* out_host /* d entries, 
 
 /*
  * Launch shape: both kernels are persistent (a fixed grid loops over tiles of 32 vectors).
- * max_workgroups > 0 caps the grid of this plan's launches; 0 restores the default
- * (compute units x resident workgroups per unit).  For tuning sweeps.
+ * max_workgroups > 0 caps the grid of this plan's launches (to leave compute units to other streams, or to
+ * check that results do not depend on the grid); 0 restores the default (compute units x resident workgroups
+ * per unit).  Results are bit-identical for every grid size.  The library reads no environment variables.
  */
 int srft_plan_set_max_workgroups(srft_plan_t* plan, int max_workgroups);
-
-/*
- * Measurement aid, not part of the method: a plain streaming copy of n_bytes (a multiple of 16,
- * both pointers 16-byte aligned) with the same grid shape as the kernels.  Used to calibrate the
- * profiler's HBM byte counters and to measure the copy ceiling of the machine.
- */
-int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* hip_stream);
-
-/*
- * Measurement aid, not part of the method: a streaming kernel with a chosen traffic shape.  For each of
- * n_tiles tiles it reads read_bytes_per_tile contiguous bytes from src_dev (tile t at t * read_bytes_per_tile)
- * and writes write_bytes_per_tile contiguous bytes to dst_dev, with coalesced 16-byte accesses and no
- * arithmetic.  With 8192 : 2560 it has the write path's byte mix at d = 128 (32 vectors per tile), with
- * 2560 : 8192 the read path's; its rate is the ceiling the memory system offers such a kernel.
- * Byte counts must be multiples of 16, at most 32 KiB read per tile, and not both zero (one of them zero gives the
- * read-only or the write-only stream); workgroups = 0 picks 3 per compute unit.  With SRFT_MIX_STREAM=1 in
- * the environment (read at every call) the accesses are non-temporal, as the read path's are.
- */
-int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int read_bytes_per_tile,
-                    int write_bytes_per_tile, int workgroups, void* hip_stream);
 
 const char* srft_status_string(int status);
 int srft_last_hip_error(void);    /* the hipError_t of the most recent SRFT_ERR_HIP on this thread */

@@ -21,7 +21,7 @@ EXPORTS = [
     "srft_plan_create", "srft_plan_destroy", "srft_kv_quantize", "srft_kv_dequantize",
     "srft_kv_forward_f32", "srft_plan_d", "srft_plan_group_size", "srft_plan_groups",
     "srft_plan_code_bytes", "srft_plan_get_signs", "srft_plan_set_max_workgroups",
-    "srft_stream_copy", "srft_stream_mix", "srft_status_string", "srft_last_hip_error",
+    "srft_status_string", "srft_last_hip_error",
     "srft_kv_quantize_batched", "srft_kv_dequantize_batched",
     "srft_kv_channel_absmax", "srft_lambda_from_absmax",
     "srft_cache_create", "srft_cache_destroy", "srft_cache_append", "srft_cache_rebuild_view",
@@ -75,8 +75,6 @@ def lib() -> C.CDLL:
         getattr(L, name).argtypes = [vp]
     L.srft_plan_get_signs.argtypes = [vp, vp]
     L.srft_plan_set_max_workgroups.argtypes = [vp, ci]
-    L.srft_stream_copy.argtypes = [vp, vp, i64, vp]
-    L.srft_stream_mix.argtypes = [vp, vp, i64, ci, ci, ci, vp]
     L.srft_status_string.argtypes = [ci]
     L.srft_status_string.restype = C.c_char_p
     L.srft_last_hip_error.argtypes = []
@@ -240,22 +238,6 @@ def srft_plan_get_signs(plan: int) -> np.ndarray:
 
 def srft_plan_set_max_workgroups(plan: int, n: int) -> None:
     _check(lib().srft_plan_set_max_workgroups(plan, n), "srft_plan_set_max_workgroups")
-
-
-def srft_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
-    nbytes = src.numel() * src.element_size()
-    assert dst.numel() * dst.element_size() == nbytes and dst.is_cuda and src.is_cuda
-    _check(lib().srft_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream)),
-           "srft_stream_copy")
-
-
-def srft_stream_mix(src: torch.Tensor, dst: torch.Tensor, n_tiles: int, read_bytes: int, write_bytes: int,
-                    workgroups: int = 0, stream=None) -> None:
-    assert src.is_cuda and dst.is_cuda
-    assert src.numel() * src.element_size() >= n_tiles * read_bytes
-    assert dst.numel() * dst.element_size() >= n_tiles * write_bytes
-    _check(lib().srft_stream_mix(src.data_ptr(), dst.data_ptr(), n_tiles, read_bytes, write_bytes, workgroups,
-                                 _stream_handle(stream)), "srft_stream_mix")
 
 
 class Cache:

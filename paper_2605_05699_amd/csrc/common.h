@@ -1,0 +1,185 @@
+// common.h -- shared declarations of the fused SRFT int4 KV-cache quantizer / dequantizer for MI355X (gfx950).
+//
+// How the path is mapped to CDNA4
+// -------------------------------
+// Per vector the method is: sign flip, unitary real DFT with the real packing of Eq. 2, per-channel
+// lambda, per-group abs-max, round to int4, nibble pack (Sec. 3.2, Sec. 5.1, Sec. 7.1).  Sign, DFT,
+// packing and lambda are all linear, so together they are ONE real d x d matrix
+//     W = diag(lambda) * Q * diag(s),        Q = pack o F   (orthogonal),
+// and the read path is the matrix  R = diag(s) * Q^T * diag(1 / max(lambda, 1e-6)).
+// At 5.6 TB/s a d = 128 vector has about 37 compute-unit clocks; a butterfly FFT plus the fp16
+// conversions needs about 3000 vector-ALU lane operations per vector, more than the 64 lanes x 37
+// clocks available, whereas the matrix cores do the dense product with time to spare.  So the
+// transform runs on MFMA (v_mfma_f32_32x32x16_f16) and the vector ALU only does the quantizer.
+//
+// Exactness: x is fp16, hence an exact MFMA operand.  W is split on the host into two fp16
+// matrices W = Whi + Wlo (after a power-of-two scaling that keeps Wlo out of the fp16 denormal
+// range); both products accumulate into the same fp32 accumulator, which gives about 22 bits of W.
+// On the read path the codes (integers in [-8, 7]) are exact fp16 operands; the per-(vector, group)
+// scale cannot enter the matrix, so each group's 32 codes are contracted separately (K = 32) and
+// the partial results are combined as  x = sum_j scale_j * P_j  on the vector ALU in fp32.
+//
+// Work decomposition (plain forms): a workgroup has d/32 wavefronts and walks over tiles of 32 vectors
+// (persistent grid).  Wavefront w owns the 32 output rows 32w..32w+31 -- on the write path that is
+// exactly quantization group w, so the abs-max needs a single cross-lane step -- and keeps its
+// 32 x d slab of the matrix (hi and lo) in registers for the whole launch.  The 32 x d operand tile
+// (inputs, or decoded codes) is loaded once per workgroup with coalesced 16-byte accesses, staged in
+// LDS (double buffered, one barrier per tile, reached by every thread) and read by every wavefront.
+// The MFMA row order inside a slab is permuted on the host so that a lane ends up holding 16
+// CONSECUTIVE outputs: 16 nibbles = one 8-byte store on the write path, 16 fp16 = two 16-byte
+// stores on the read path, with no cross-lane shuffles.
+//
+// Folded forms (d = 128 and 256 on the write path, 128 / 192 / 256 on the read path): two symmetries of Q
+// let every output pair share two half-length partial sums, which halves the matrix work; they are
+// described at srft_quantize_fold_tiles and at the FOLD parameter of srft_dequantize_tiles.
+//
+// Around the two paths: the same kernels serving several plans in one launch (a segment table passed as a
+// kernel argument), the per-channel abs-max statistic lambda is calibrated from, an 8-bit code width, the
+// Walsh-Hadamard matrix in place of the DFT (the comparator of Sec. 3.1), scores of queries against the stored
+// record without reconstructing the keys, and a host-side cache manager (int4 store, fp16 residual window,
+// dequantized view) built on the batched launches.
+//
+// The kernels run at the socket's power limit with a throttled clock, so what shortens them is work per vector
+// (matrix instructions, vector instructions, LDS traffic), not more parallelism: see the folded forms.
+//
+// Source layout: the kernel templates live in quantize_tiles.h (write path, plain form), quantize_fold_tiles.h
+// (write path, folded form), dequantize_tiles.h (read path) and kernels/scores.hip; every file under kernels/
+// instantiates one family of them and exports a function that picks the instance for a plan; plan.hip builds
+// the constant tables, api.hip holds the C entry points, cache.hip the cache manager.
+#ifndef SRFT_COMMON_H
+#define SRFT_COMMON_H
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "srft_kv.h"
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kTileVecs = 32;          // vectors per tile = N of the 32x32x16 MFMA
+constexpr int kMaxScoreWorkgroups = 4096;   // scores kernel: largest grid (each workgroup owns 256 bytes of workspace)
+constexpr int kMaxD = 256;
+constexpr float kMinScale = 7.888609052210118e-31f;   // 2^-100: below this a group is stored as zero
+// The kernels index tiles of 32 vectors with 32-bit integers and look a few grid strides ahead.
+constexpr int64_t kMaxVectors = (int64_t)1 << 33;
+
+// group mode of a plan.  kGroup32: one scale per slab (g = 32, the deployed format).  kGroup16: one scale per
+// lane (g = 16).  kGroupWide: g = 32 * gw with gw >= 2 slabs per group, up to the per-token case g = d.
+enum { kGroup16 = 0, kGroup32 = 1, kGroupWide = 2 };
+// what the write-path kernel produces (see quantize_tiles.h)
+enum { kOutCodes = 0, kOutRaw = 1, kOutAmax = 2, kOutQFrag32 = 3, kOutQFrag16 = 4 };
+
+// Several plans in one launch (a decode step appends a few hundred vectors to each of many (layer, K|V)
+// caches: one launch per plan would be all launch latency).  Segment i = plan i's constants and buffers; it
+// is served by workgroups first_block[i] .. first_block[i+1]-1, each walking that segment's tiles with
+// that many as stride.  The table travels as a kernel argument.
+constexpr int kMaxBatch = 64;       // the table is about 3.5 KiB of the 4 KiB a kernel may take as arguments
+struct srft_batch_args {
+    int count;
+    int first_block[kMaxBatch + 1];
+    const uint4* frag[kMaxBatch];
+    const void* in0[kMaxBatch];      // write path: x      read path: codes
+    const void* in1[kMaxBatch];      //                    read path: scales
+    void* out0[kMaxBatch];           // write path: codes  read path: out
+    void* out1[kMaxBatch];           // write path: scales
+    long long n_vec[kMaxBatch];
+    float unscale[kMaxBatch];
+};
+static_assert(sizeof(srft_batch_args) + sizeof(int) <= 4096, "kernel arguments are limited to 4 KiB");
+
+typedef void (*quantize_kernel_t)(const uint4*, const uint4*, long long, uint2*, float*, float4*, float, float, int);
+typedef void (*dequantize_kernel_t)(const uint4*, const uint2*, const float*, long long, uint4*, float, int);
+typedef void (*batched_kernel_t)(const srft_batch_args, int);
+
+struct srft_plan {
+    int d = 0, g = 0, bits = 4, transform = 0, device = 0;
+    uint64_t seed = 0;
+    std::vector<int8_t> signs;
+    uint4* wfrag = nullptr;     // write-path matrix fragments (device)
+    uint4* rfrag = nullptr;     // read-path matrix fragments (device)
+    uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
+    uint4* wfold = nullptr;     // write-path fragments of the folded form (device), when fold_q
+    float* inv_lam2 = nullptr;  // 1 / (lambda * max(lambda, 1e-6)) per channel (device): scores in the rotated domain
+    int grid_scores = 0;        // persistent grid of the scores kernel (32 rows of queries)
+    int grid_scores16 = 0;      // the same with 16 rows
+    bool fold_dq = false;       // read path contracts even and odd codes separately (half the matrix work)
+    bool fold_q = false;        // write path contracts even and odd inputs separately (half the matrix work)
+    float unscale_w = 1.0f;     // 2^-e of the write matrix
+    float unscale_r = 1.0f;
+    int grid_q = 0, grid_dq = 0;    // default persistent grid sizes
+    int slabs_q = 1, slabs_dq = 1;  // slabs of the matrix per wavefront in the write / read kernel
+    int gm = 1, gw = 1;             // group mode (kGroup16 / kGroup32 / kGroupWide) and slabs per group
+    int max_wgs = 0;
+};
+
+struct srft_cache {
+    std::vector<const srft_plan*> plans;
+    std::vector<uint8_t*> codes;
+    std::vector<float*> scales;
+    std::vector<void*> view;
+    int n_seq = 0, R = 0;
+    int64_t capacity = 0, tokens = 0, quantized = 0;
+};
+
+// ---- kernel instances, one function per translation unit under kernels/ (nullptr: no such instance) ----
+// write path, plain form, codes out: d, slabs per wavefront (1 or 2), group mode; 4- and 8-bit codes
+quantize_kernel_t srft_pick_quantize_plain_b4(int d, int slabs, int gm);
+quantize_kernel_t srft_pick_quantize_plain_b8(int d, int slabs, int gm);
+batched_kernel_t srft_pick_quantize_plain_batched_b4(int d, int slabs, int gm);
+batched_kernel_t srft_pick_quantize_plain_batched_b8(int d, int slabs, int gm);
+// write path, plain form, other outputs (kOutRaw, kOutAmax with `slabs`; kOutQFrag32 / kOutQFrag16 with one slab)
+quantize_kernel_t srft_pick_quantize_aux(int d, int slabs, int out);
+// write path, folded form (d = 128, 256)
+quantize_kernel_t srft_pick_quantize_fold(int d, int bits, bool wide);
+batched_kernel_t srft_pick_quantize_fold_batched(int d, int bits, bool wide);
+// read path
+dequantize_kernel_t srft_pick_dequantize_b4(int d, int slabs, int gm, bool fold);
+dequantize_kernel_t srft_pick_dequantize_b8(int d, int slabs, int gm, bool fold);
+batched_kernel_t srft_pick_dequantize_batched_b4(int d, int slabs, int gm, bool fold);
+batched_kernel_t srft_pick_dequantize_batched_b8(int d, int slabs, int gm, bool fold);
+// scores in the rotated domain: launch of the scan (kernels/scores.hip) and its resident workgroups per unit
+int srft_launch_scores(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
+                       const float* scales, long long n_keys, float* out, hipStream_t st);
+int srft_scores_occupancy(int d, bool r16, int* blocks_per_cu);
+
+// ---- host side (plan.hip, api.hip) ----
+int srft_hip_fail(hipError_t e);         // records the error for srft_last_hip_error, returns SRFT_ERR_HIP
+#define SRFT_HIP(call)                                   \
+    do {                                                 \
+        hipError_t e_ = (call);                          \
+        if (e_ != hipSuccess) return srft_hip_fail(e_);  \
+    } while (0)
+
+// the kernels a plan launches, and their block sizes
+quantize_kernel_t srft_plan_quantize_kernel(const srft_plan* p, int out, int* threads);
+dequantize_kernel_t srft_plan_dequantize_kernel(const srft_plan* p, int* threads);
+// batched launches over plans that share shape and kernel choice (api.hip)
+int srft_run_batched(const srft_plan_t* const* plans, const void* const* in0, const void* const* in1,
+                     void* const* out0, void* const* out1, const int64_t* n_vec, int count, bool write_path,
+                     hipStream_t st);
+// true when two plans can share one batched launch or one cache (shape, code width, transform, device, kernel forms)
+bool srft_plans_compatible(const srft_plan* a, const srft_plan* b);
+
+inline bool srft_aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+#define SRFT_DISPATCH_D(d, fn, ...)                       \
+    switch (d) {                                          \
+        case 32:  return fn<32>(__VA_ARGS__);             \
+        case 64:  return fn<64>(__VA_ARGS__);             \
+        case 96:  return fn<96>(__VA_ARGS__);             \
+        case 128: return fn<128>(__VA_ARGS__);            \
+        case 160: return fn<160>(__VA_ARGS__);            \
+        case 192: return fn<192>(__VA_ARGS__);            \
+        case 224: return fn<224>(__VA_ARGS__);            \
+        case 256: return fn<256>(__VA_ARGS__);            \
+        default:  return nullptr;                         \
+    }
+
+#endif  // SRFT_COMMON_H

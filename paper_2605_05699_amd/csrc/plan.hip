@@ -1,0 +1,382 @@
+// plan.hip -- host side of a plan: the sign diagonal, the matrices W and R of the write and the read path, their
+// fp16 hi + lo split in MFMA operand order (plain and folded forms), the choice of kernel instances, and the
+// persistent grid sizes.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+// double -> IEEE fp16 bits, round to nearest even, subnormals kept, overflow to infinity.
+uint16_t f16_bits(double v) {
+    const uint16_t sign = std::signbit(v) ? 0x8000u : 0u;
+    double a = std::fabs(v);
+    if (std::isnan(v)) return 0x7E00u;
+    if (a >= 65520.0) return sign | 0x7C00u;
+    if (a == 0.0) return sign;
+    int e;
+    std::frexp(a, &e);                    // a = m * 2^e, m in [0.5, 1)
+    int E = e - 1;                        // a in [2^E, 2^(E+1))
+    if (E < -14) E = -14;                 // subnormal range shares the quantum 2^-24
+    const double r = std::nearbyint(std::ldexp(a, 10 - E));   // exact scaling, ties to even
+    int mant = (int)r;                    // in [0, 2048]
+    if (mant >= 2048) { mant = 1024; ++E; }
+    if (mant < 1024) return sign | (uint16_t)mant;            // subnormal (E == -14)
+    return sign | (uint16_t)(((E + 15) << 10) | (mant - 1024));
+}
+
+double f16_value(uint16_t b) {
+    const int e = (b >> 10) & 0x1F, m = b & 0x3FF;
+    double v = (e == 0) ? std::ldexp((double)m, -24) : std::ldexp((double)(m + 1024), e - 25);
+    return (b & 0x8000u) ? -v : v;
+}
+
+uint64_t splitmix64_next(uint64_t& state) {
+    state += 0x9E3779B97F4A7C15ull;
+    uint64_t z = state;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Q[k][n] of the packed unitary real DFT (Eq. 1-2), rfft sign convention.
+// Entry of the orthonormal Walsh-Hadamard matrix in natural order: (-1)^popcount(k & n) / sqrt(d).
+double hadamard_entry(int d, int k, int n) {
+    return (__builtin_popcount((unsigned)(k & n)) & 1 ? -1.0 : 1.0) / std::sqrt((double)d);
+}
+
+double q_entry(int d, int k, int n) {
+    const int h = d / 2;
+    const double pi = 3.14159265358979323846;
+    if (k == 0) return 1.0 / std::sqrt((double)d);
+    if (k == h) return ((n & 1) ? -1.0 : 1.0) / std::sqrt((double)d);
+    const int kk = (k < h) ? k : k - h;
+    const double ang = 2.0 * pi * (double)((long long)kk * n % d) / (double)d;
+    return (k < h) ? std::sqrt(2.0 / d) * std::cos(ang) : -std::sqrt(2.0 / d) * std::sin(ang);
+}
+
+// slab row i of the 32x32 MFMA result (row = 8r + 4h + c) <-> output 16h + 4r + c of the slab,
+// so that the 16 accumulators of a lane (r = v / 4, c = v % 4) are outputs 16h .. 16h + 15.
+int slab_output_of_row(int i) {
+    const int r = i / 8, h = (i / 4) % 2, c = i % 4;
+    return 16 * h + 4 * r + c;
+}
+
+// Scale a matrix by the power of two that puts its largest magnitude in [2^13, 2^14) and split every
+// entry into fp16 hi + fp16 lo.  Returns the exponent e (entries were multiplied by 2^e).
+int split_hi_lo(const std::vector<double>& m, std::vector<uint16_t>& hi, std::vector<uint16_t>& lo) {
+    double mx = 0.0;
+    for (double v : m) mx = std::fmax(mx, std::fabs(v));
+    int e2;
+    std::frexp(mx, &e2);                 // mx in [2^(e2-1), 2^e2)
+    const int e = 14 - e2;
+    hi.resize(m.size());
+    lo.resize(m.size());
+    for (size_t i = 0; i < m.size(); ++i) {
+        const double v = std::ldexp(m[i], e);
+        hi[i] = f16_bits(v);
+        lo[i] = f16_bits(v - f16_value(hi[i]));
+    }
+    return e;
+}
+
+// resident workgroups per compute unit of a kernel with `threads` threads per workgroup
+int resident_blocks(const void* kernel, int threads, int* blocks) {
+    *blocks = 0;
+    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, kernel, threads, 0));
+    if (*blocks < 1) *blocks = 1;
+    return SRFT_OK;
+}
+
+int occupancy_grids(srft_plan* p, int cus) {
+    int threads = 0, blocks = 0;
+    const quantize_kernel_t qk = srft_plan_quantize_kernel(p, kOutCodes, &threads);
+    int rc = resident_blocks((const void*)qk, threads, &blocks);
+    if (rc != SRFT_OK) return rc;
+    p->grid_q = cus * blocks;
+    const dequantize_kernel_t dk = srft_plan_dequantize_kernel(p, &threads);
+    rc = resident_blocks((const void*)dk, threads, &blocks);
+    if (rc != SRFT_OK) return rc;
+    p->grid_dq = cus * blocks;
+    rc = srft_scores_occupancy(p->d, false, &blocks);
+    if (rc != SRFT_OK) return rc;
+    p->grid_scores = cus * (blocks > 0 ? blocks : 1);
+    rc = srft_scores_occupancy(p->d, true, &blocks);
+    if (rc != SRFT_OK) return rc;
+    p->grid_scores16 = cus * (blocks > 0 ? blocks : 1);
+    return SRFT_OK;
+}
+
+}  // namespace
+
+int srft_hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return SRFT_ERR_HIP;
+}
+
+quantize_kernel_t srft_plan_quantize_kernel(const srft_plan* p, int out, int* threads) {
+    if (out == kOutQFrag32 || out == kOutQFrag16) {      // the scores set-up always runs one slab per wavefront
+        *threads = 2 * p->d;
+        return srft_pick_quantize_aux(p->d, 1, out);
+    }
+    if (out != kOutCodes) {
+        *threads = 2 * p->d / p->slabs_q;
+        return srft_pick_quantize_aux(p->d, p->slabs_q, out);
+    }
+    if (p->fold_q) {
+        *threads = p->d;
+        return srft_pick_quantize_fold(p->d, p->bits, p->gm == kGroupWide);
+    }
+    *threads = 2 * p->d / p->slabs_q;
+    return p->bits == 8 ? srft_pick_quantize_plain_b8(p->d, p->slabs_q, p->gm)
+                        : srft_pick_quantize_plain_b4(p->d, p->slabs_q, p->gm);
+}
+
+dequantize_kernel_t srft_plan_dequantize_kernel(const srft_plan* p, int* threads) {
+    *threads = 2 * p->d / p->slabs_dq;
+    return p->bits == 8 ? srft_pick_dequantize_b8(p->d, p->slabs_dq, p->gm, p->fold_dq)
+                        : srft_pick_dequantize_b4(p->d, p->slabs_dq, p->gm, p->fold_dq);
+}
+
+bool srft_plans_compatible(const srft_plan* a, const srft_plan* b) {
+    return a->d == b->d && a->g == b->g && a->bits == b->bits && a->transform == b->transform &&
+           a->device == b->device && a->fold_q == b->fold_q && a->fold_dq == b->fold_dq &&
+           a->slabs_q == b->slabs_q && a->slabs_dq == b->slabs_dq;
+}
+
+extern "C" {
+
+int srft_plan_create(srft_plan_t** out, int d, int group_size, uint64_t sign_seed, const float* lambda_host) {
+    return srft_plan_create_bits(out, d, group_size, 4, sign_seed, lambda_host);
+}
+
+int srft_plan_create_bits(srft_plan_t** out, int d, int group_size, int bits, uint64_t sign_seed,
+                          const float* lambda_host) {
+    return srft_plan_create_ex(out, d, group_size, bits, SRFT_TRANSFORM_DFT, sign_seed, lambda_host);
+}
+
+int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int transform, uint64_t sign_seed,
+                        const float* lambda_host) {
+    if (!out) return SRFT_ERR_NULL;
+    *out = nullptr;
+    if (bits != 4 && bits != 8) return SRFT_ERR_BAD_BITS;
+    if (transform != SRFT_TRANSFORM_DFT && transform != SRFT_TRANSFORM_HADAMARD) return SRFT_ERR_BAD_TRANSFORM;
+    if (d < 32 || d > kMaxD || d % 32 != 0) return SRFT_ERR_BAD_D;
+    if (transform == SRFT_TRANSFORM_HADAMARD && (d & (d - 1)) != 0) return SRFT_ERR_BAD_D;
+    if (!(group_size == 16 || (group_size >= 32 && group_size % 32 == 0 && d % group_size == 0))) return SRFT_ERR_BAD_GROUP;
+    std::vector<double> lam(d, 1.0);
+    if (lambda_host) {
+        double lo = INFINITY, hi = 0.0;
+        for (int k = 0; k < d; ++k) {
+            const float v = lambda_host[k];
+            if (!std::isfinite(v) || !(v > 0.0f)) return SRFT_ERR_BAD_LAMBDA;
+            lam[k] = (double)v;
+            lo = std::fmin(lo, lam[k]);
+            hi = std::fmax(hi, lam[k]);
+        }
+        if (hi / lo > 65536.0) return SRFT_ERR_BAD_LAMBDA;
+    }
+
+    srft_plan* p = new (std::nothrow) srft_plan();
+    if (!p) return SRFT_ERR_HIP;
+    p->d = d;
+    p->g = group_size;
+    p->bits = bits;
+    p->transform = transform;
+    p->gm = group_size == 16 ? kGroup16 : (group_size == 32 ? kGroup32 : kGroupWide);
+    p->gw = group_size <= 32 ? 1 : group_size / 32;
+    p->seed = sign_seed;
+    p->signs.resize(d);
+    uint64_t state = sign_seed;
+    for (int n = 0; n < d; ++n) p->signs[n] = (splitmix64_next(state) >> 63) ? -1 : 1;
+
+    // W[k][n] = lambda_k Q[k][n] s_n ; R[n][k] = s_n Q[k][n] / max(lambda_k, 1e-6)
+    std::vector<double> W((size_t)d * d), R((size_t)d * d);
+    for (int k = 0; k < d; ++k)
+        for (int n = 0; n < d; ++n) {
+            const double q = (transform == SRFT_TRANSFORM_HADAMARD ? hadamard_entry(d, k, n) : q_entry(d, k, n)) *
+                             (double)p->signs[n];
+            W[(size_t)k * d + n] = lam[k] * q;
+            R[(size_t)n * d + k] = q / std::fmax(lam[k], 1e-6);
+        }
+    std::vector<uint16_t> whi, wlo, rhi, rlo;
+    p->unscale_w = (float)std::ldexp(1.0, -split_hi_lo(W, whi, wlo));
+    p->unscale_r = (float)std::ldexp(1.0, -split_hi_lo(R, rhi, rlo));
+
+    // A-operand fragments: lane l holds row l % 32 of the slab and contraction indices 8 (l / 32) + e.
+    const int G = d / 32, T = d / 16;
+    std::vector<uint16_t> wf((size_t)G * T * 2 * 64 * 8), rf((size_t)G * G * 2 * 2 * 64 * 8);
+    for (int w = 0; w < G; ++w)
+        for (int l = 0; l < 64; ++l) {
+            const int row = 32 * w + slab_output_of_row(l % 32), kh = l / 32;
+            for (int t = 0; t < T; ++t)           // write path: contraction index = input position n
+                for (int e = 0; e < 8; ++e) {
+                    const size_t src = (size_t)row * d + (16 * t + 8 * kh + e);
+                    wf[((((size_t)w * T + t) * 2 + 0) * 64 + l) * 8 + e] = whi[src];
+                    wf[((((size_t)w * T + t) * 2 + 1) * 64 + l) * 8 + e] = wlo[src];
+                }
+            // read path: group j, run of 8 codes 4j + 2t + kh; element e <-> code e/2 + 4 (e % 2) of the run at
+            // 4 bits (nibble pairs (n0, n4), (n1, n5), ...), code {0, 2, 1, 3, 4, 6, 5, 7}[e] at 8 bits (byte pairs
+            // (b0, b2), (b1, b3) of each dword): the orders in which the kernel's decode lays the codes out
+            static const int byte_order[8] = {0, 2, 1, 3, 4, 6, 5, 7};
+            for (int j = 0; j < G; ++j)
+                for (int t = 0; t < 2; ++t)
+                    for (int e = 0; e < 8; ++e) {
+                        const int k = 8 * (4 * j + 2 * t + kh) + (bits == 8 ? byte_order[e] : (e / 2) + 4 * (e % 2));
+                        const size_t src = (size_t)row * d + k;
+                        rf[(((((size_t)w * G + j) * 2 + t) * 2 + 0) * 64 + l) * 8 + e] = rhi[src];
+                        rf[(((((size_t)w * G + j) * 2 + t) * 2 + 1) * 64 + l) * 8 + e] = rlo[src];
+                    }
+        }
+
+    // Slabs of the matrix per wavefront: two where the table says so (and the number of groups is even).
+    p->slabs_q = (d == 64) ? 2 : 1;
+    p->slabs_dq = (d == 256 || d == 64) ? 2 : 1;
+    // Folded read path where it applies and pays (d = 128, 192, 256; g >= 32).
+    p->fold_dq = (d % 64 == 0) && d >= 128 && p->gm != kGroup16 &&    // at d = 64 it gains nothing
+                 transform == SRFT_TRANSFORM_DFT;                      // (the symmetries are the DFT's)
+    std::vector<uint16_t> rfold;
+    if (p->fold_dq) {
+        p->slabs_dq = 2;
+        // A (even p) and B (odd p) fragments of wavefront w: row n = 32w + (output of MFMA row l % 32); group j,
+        // lane half kh, element e <-> packed index 32j + 16 kh + off[e] (+ 1 for B), off[] being the order in
+        // which the kernel lays out the decoded low nibbles of an 8-byte unit: (n0, n4, n2, n6) of each dword.
+        // (at 8 bits: bytes 0 and 2 of each of the four dwords)
+        static const int off4[8] = {0, 4, 2, 6, 8, 12, 10, 14}, off8[8] = {0, 2, 4, 6, 8, 10, 12, 14};
+        const int* off = bits == 8 ? off8 : off4;
+        const int waves = d / 64;
+        const size_t frag_halves = (size_t)waves * 2 * G * 2 * 64 * 8;
+        rfold.assign(frag_halves + (size_t)waves * 64 * 16, 0);
+        for (int w = 0; w < waves; ++w)
+            for (int l = 0; l < 64; ++l) {
+                const int n = 32 * w + slab_output_of_row(l % 32), kh = l / 32;
+                for (int ab = 0; ab < 2; ++ab)
+                    for (int j = 0; j < G; ++j)
+                        for (int e = 0; e < 8; ++e) {
+                            const size_t src = (size_t)n * d + (32 * j + 16 * kh + off[e] + ab);
+                            const size_t dst = (((size_t)(w * 2 + ab) * G + j) * 2) * 64;
+                            rfold[((dst + 0) + l) * 8 + e] = rhi[src];
+                            rfold[((dst + 64) + l) * 8 + e] = rlo[src];
+                        }
+                // sign-bit masks for this lane's outputs n + d/2, n = 32w + 16 kh + v: s_n s_{n+d/2} < 0
+                for (int v = 0; v < 16; ++v) {
+                    const int nn = 32 * w + 16 * kh + v;
+                    rfold[frag_halves + ((size_t)w * 64 + l) * 16 + v] =
+                        (p->signs[nn] * p->signs[nn + d / 2] < 0) ? 0x8000u : 0u;
+                }
+            }
+    }
+    // Folded write path where it applies (d a multiple of 128, g >= 32).
+    p->fold_q = (d % 128 == 0) && p->gm != kGroup16 && transform == SRFT_TRANSFORM_DFT;
+    std::vector<uint16_t> wfold;
+    if (p->fold_q) {
+        // Wavefront w < M/2 owns cosine rows k = 32w + i, the others sine rows; row i of its E (O) slab is row
+        // p = k (cosine) or d/2 + k (sine) of W restricted to even (odd) n.  The first sine wavefront has no k = 0:
+        // there E is row d/4 and O is row 3d/4.  k-step t, lane half kh, element e <-> n = 32t + 16kh + 2e (+ 1).
+        const int M = d / 64, TF = d / 32;
+        const size_t frag_halves = (size_t)M * 2 * TF * 2 * 64 * 8;
+        wfold.assign(frag_halves + (size_t)M * 64 * 16 * 2, 0);          // rho: 16 floats = 32 halves per lane
+        for (int w = 0; w < M; ++w) {
+            const bool sine = w >= M / 2;
+            const int wk = sine ? w - M / 2 : w;
+            for (int l = 0; l < 64; ++l) {
+                const int kh = l / 32, k = 32 * wk + slab_output_of_row(l % 32);
+                for (int eo = 0; eo < 2; ++eo) {
+                    int prow = sine ? d / 2 + k : k;
+                    if (sine && k == 0) prow = eo == 0 ? d / 4 : 3 * d / 4;
+                    for (int t = 0; t < TF; ++t)
+                        for (int e = 0; e < 8; ++e) {
+                            const size_t src = (size_t)prow * d + (32 * t + 16 * kh + 2 * e + eo);
+                            const size_t dst = (((size_t)(w * 2 + eo) * TF + t) * 2) * 64;
+                            wfold[((dst + 0) + l) * 8 + e] = whi[src];
+                            wfold[((dst + 64) + l) * 8 + e] = wlo[src];
+                        }
+                }
+                // rho of this lane's 16 values k = 32 wk + 16 kh + v: lambda_mirror / lambda_direct, negated in the
+                // sine block; 0 where there is no mirror value (k = 0 of the sine block)
+                for (int v = 0; v < 16; ++v) {
+                    const int kk = 32 * wk + 16 * kh + v;
+                    const int pd = sine ? d / 2 + kk : kk, pm = sine ? d - kk : d / 2 - kk;
+                    float r = 0.0f;
+                    if (!(sine && kk == 0)) r = (float)((sine ? -1.0 : 1.0) * lam[pm] / lam[pd]);
+                    uint32_t bits;
+                    std::memcpy(&bits, &r, 4);
+                    const size_t at = frag_halves + (((size_t)w * 64 + l) * 16 + v) * 2;
+                    wfold[at] = (uint16_t)(bits & 0xFFFFu);
+                    wfold[at + 1] = (uint16_t)(bits >> 16);
+                }
+            }
+        }
+    }
+    hipError_t e = hipGetDevice(&p->device);
+    int cus = 0;
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&p->wfrag, wf.size() * 2);
+    if (e == hipSuccess) e = hipMalloc((void**)&p->rfrag, rf.size() * 2);
+    if (e == hipSuccess) e = hipMemcpy(p->wfrag, wf.data(), wf.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(p->rfrag, rf.data(), rf.size() * 2, hipMemcpyHostToDevice);
+    std::vector<float> il2(d);
+    for (int k = 0; k < d; ++k) il2[k] = (float)(1.0 / (lam[k] * std::fmax(lam[k], 1e-6)));
+    if (e == hipSuccess) e = hipMalloc((void**)&p->inv_lam2, d * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(p->inv_lam2, il2.data(), d * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess && p->fold_q) e = hipMalloc((void**)&p->wfold, wfold.size() * 2);
+    if (e == hipSuccess && p->fold_q) e = hipMemcpy(p->wfold, wfold.data(), wfold.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess && p->fold_dq) e = hipMalloc((void**)&p->rfold, rfold.size() * 2);
+    if (e == hipSuccess && p->fold_dq) e = hipMemcpy(p->rfold, rfold.data(), rfold.size() * 2, hipMemcpyHostToDevice);
+    int rc = (e == hipSuccess) ? occupancy_grids(p, cus) : srft_hip_fail(e);
+    if (rc != SRFT_OK) {
+        srft_plan_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return SRFT_OK;
+}
+
+int srft_plan_destroy(srft_plan_t* plan) {
+    if (!plan) return SRFT_OK;
+    hipError_t e1 = plan->wfrag ? hipFree(plan->wfrag) : hipSuccess;
+    hipError_t e2 = plan->rfrag ? hipFree(plan->rfrag) : hipSuccess;
+    hipError_t e3 = plan->rfold ? hipFree(plan->rfold) : hipSuccess;
+    if (plan->wfold) {
+        const hipError_t e4 = hipFree(plan->wfold);
+        if (e3 == hipSuccess) e3 = e4;
+    }
+    if (plan->inv_lam2) {
+        const hipError_t e5 = hipFree(plan->inv_lam2);
+        if (e3 == hipSuccess) e3 = e5;
+    }
+    delete plan;
+    if (e1 != hipSuccess) return srft_hip_fail(e1);
+    if (e2 != hipSuccess) return srft_hip_fail(e2);
+    if (e3 != hipSuccess) return srft_hip_fail(e3);
+    return SRFT_OK;
+}
+
+int srft_plan_d(const srft_plan_t* plan) { return plan ? plan->d : SRFT_ERR_NULL; }
+int srft_plan_group_size(const srft_plan_t* plan) { return plan ? plan->g : SRFT_ERR_NULL; }
+int srft_plan_groups(const srft_plan_t* plan) { return plan ? plan->d / plan->g : SRFT_ERR_NULL; }
+int srft_plan_code_bytes(const srft_plan_t* plan) { return plan ? plan->d * plan->bits / 8 : SRFT_ERR_NULL; }
+int srft_plan_bits(const srft_plan_t* plan) { return plan ? plan->bits : SRFT_ERR_NULL; }
+
+int srft_plan_get_signs(const srft_plan_t* plan, int8_t* out_host) {
+    if (!plan || !out_host) return SRFT_ERR_NULL;
+    std::memcpy(out_host, plan->signs.data(), plan->signs.size());
+    return SRFT_OK;
+}
+
+int srft_plan_set_max_workgroups(srft_plan_t* plan, int max_workgroups) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (max_workgroups < 0) return SRFT_ERR_BAD_N;
+    plan->max_wgs = max_workgroups;
+    return SRFT_OK;
+}
+
+int srft_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -19,8 +19,8 @@ def L():
     return binding.lib()
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "srft_kv.h")).read()
+def declared_functions(header="srft_kv.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(srft_[a-z0-9_]+)\s*\(", text)))
 
@@ -32,6 +32,33 @@ def test_every_declared_symbol_is_exported(L):
         assert hasattr(L, name), f"{name} declared in srft_kv.h but not exported"
     from paper_2605_05699_amd import binding
     assert sorted(binding.EXPORTS) == names
+
+
+def test_measurement_library_exports_its_header_and_nothing_of_it_is_in_the_product(L):
+    from paper_2605_05699_amd import measure
+    M = measure.lib()
+    names = declared_functions("srft_measure.h")
+    assert sorted(measure.EXPORTS) == names
+    for name in names:
+        assert hasattr(M, name), f"{name} declared in srft_measure.h but not exported"
+        assert not hasattr(L, name), f"{name} is a measurement aid and must not be in libsrft_kv.so"
+    # argument checks precede HIP: byte counts are multiples of 16, not both zero; either may be zero
+    assert M.srft_stream_copy(None, None, 24, None) == -7
+    assert M.srft_stream_copy(None, None, 32, None) == -1
+    assert M.srft_stream_copy(None, None, 0, None) == 0
+    for rb, wb in ((0, 0), (-16, 16), (16, -16), (24, 16), (16, 8)):
+        assert M.srft_stream_mix(None, None, 4, rb, wb, 0, 0, None) == -7, (rb, wb)
+    assert M.srft_stream_mix(None, None, -1, 16, 16, 0, 0, None) == -7
+    assert M.srft_stream_mix(None, None, 0, 16, 0, 0, 0, None) == 0          # no tiles: nothing to do
+    assert M.srft_stream_mix(None, None, 4, 16, 0, 0, 1, None) == -1         # read-only is a valid shape; pointers are not
+    assert M.srft_stream_mix(None, None, 4, 0, 16, 0, 0, None) == -1
+
+
+def test_the_library_reads_no_environment_variables():
+    """Kernel choice depends on the plan alone: no getenv anywhere in the product sources."""
+    import glob
+    for path in glob.glob(os.path.join(ROOT, "paper_2605_05699_amd", "csrc", "**", "*.h*"), recursive=True):
+        assert "getenv" not in open(path).read(), path
 
 
 def test_status_strings(L):
@@ -72,16 +99,6 @@ def test_null_plan_and_size_errors(L):
     assert L.srft_kv_forward_f32(None, None, 1, None, None) == -1
     assert L.srft_plan_d(None) == -1
     assert L.srft_plan_destroy(None) == 0
-    assert L.srft_stream_copy(None, None, 24, None) == -7
-    assert L.srft_stream_copy(None, None, 32, None) == -1
-    assert L.srft_stream_copy(None, None, 0, None) == 0
-    # the streaming measurement aid: byte counts are multiples of 16, not both zero; either may be zero
-    for rb, wb in ((0, 0), (-16, 16), (16, -16), (24, 16), (16, 8)):
-        assert L.srft_stream_mix(None, None, 4, rb, wb, 0, None) == -7, (rb, wb)
-    assert L.srft_stream_mix(None, None, -1, 16, 16, 0, None) == -7
-    assert L.srft_stream_mix(None, None, 0, 16, 0, 0, None) == 0          # no tiles: nothing to do
-    assert L.srft_stream_mix(None, None, 4, 16, 0, 0, None) == -1         # read-only is a valid shape; pointers are not
-    assert L.srft_stream_mix(None, None, 4, 0, 16, 0, None) == -1
     # lambda from the calibration statistic: host only
     amax = (C.c_float * 4)(2.0, 0.0, 1e-9, 0.5)
     lam = (C.c_float * 4)()
