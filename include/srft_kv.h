@@ -161,6 +161,18 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
                    void* hip_stream);
 
 /*
+ * srft_kv_scores for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and results as
+ * srft_kv_scores without workspace_dev: the workspace is a static device array inside the library (1 MiB + 32 KiB
+ * per GPU, held until the process ends; its address is looked up when the plan is created).  Calls no hipMalloc,
+ * hipFree or other allocating routine.  A plan whose srft_scores_workspace_bytes exceeds that array is refused with
+ * SRFT_ERR_BAD_N (no plan this library creates does).  Every call on one GPU uses the same array: calls that may
+ * overlap on one GPU (different streams, or threads) race -- order them, or use srft_kv_scores with a workspace each.
+ */
+int srft_kv_scores_static(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
+                          const float* scales_dev, int64_t n_keys, float* scores_dev, void* hip_stream);
+
+/*
  * Cache manager: int4 store + fp16 residual window + dequantized-prefix cache.   (Sec. 7.2: the cache class,
  * items (i)-(iv), and its paragraph on the residual window: 16 tokens.)
  *

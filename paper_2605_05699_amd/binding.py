@@ -27,7 +27,7 @@ EXPORTS = [
     "srft_cache_create", "srft_cache_destroy", "srft_cache_append", "srft_cache_rebuild_view",
     "srft_cache_tokens", "srft_cache_quantized_tokens",
     "srft_plan_create_bits", "srft_plan_bits", "srft_plan_create_ex",
-    "srft_scores_workspace_bytes", "srft_kv_scores",
+    "srft_scores_workspace_bytes", "srft_kv_scores", "srft_kv_scores_static",
 ]
 
 
@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
     L.srft_cache_quantized_tokens.argtypes = [vp]
     L.srft_scores_workspace_bytes.argtypes = [vp]
     L.srft_kv_scores.argtypes = [vp, vp, ci, vp, vp, i64, vp, vp, vp]
+    L.srft_kv_scores_static.argtypes = [vp, vp, ci, vp, vp, i64, vp, vp]
     L.srft_kv_channel_absmax.argtypes = [vp, vp, i64, vp, vp]
     L.srft_lambda_from_absmax.argtypes = [vp, ci, vp]
     L.srft_kv_quantize_batched.argtypes = [vp, vp, vp, vp, vp, ci, vp]
@@ -210,6 +211,17 @@ def srft_kv_scores(plan: int, q: torch.Tensor, codes: torch.Tensor, scales: torc
                                 _dev_ptr(scales, torch.float32, "scales"), codes.shape[0],
                                 _dev_ptr(scores, torch.float32, "scores"), workspace.data_ptr(),
                                 _stream_handle(stream)), "srft_kv_scores")
+
+
+def srft_kv_scores_static(plan: int, q: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, scores: torch.Tensor,
+                          stream=None) -> None:
+    """srft_kv_scores with the library's static workspace: nothing is allocated and no workspace is passed."""
+    if scores.shape != (q.shape[0], codes.shape[0]):
+        raise ValueError("scores must be [n_q, n_keys]")
+    _check(lib().srft_kv_scores_static(plan, _dev_ptr(q, torch.float16, "q"), q.shape[0],
+                                       _dev_ptr(codes, torch.uint8, "codes"), _dev_ptr(scales, torch.float32, "scales"),
+                                       codes.shape[0], _dev_ptr(scores, torch.float32, "scores"),
+                                       _stream_handle(stream)), "srft_kv_scores_static")
 
 
 def srft_kv_channel_absmax(plan: int, x: torch.Tensor, amax: torch.Tensor, stream=None) -> None:

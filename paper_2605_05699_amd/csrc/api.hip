@@ -1,6 +1,7 @@
 // api.hip -- the C entry points of the write path, the read path and what sits around them: argument checks
 // (all before the first HIP call), grid sizing, launches.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 
 #include "common.h"
@@ -118,6 +119,31 @@ int srft_run_batched(const srft_plan_t* const* plans, const void* const* in0, co
     return SRFT_OK;
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Workspace of srft_kv_scores_static: a file-scope device array, so that the entry point allocates nothing.
+// Every GPU the library runs on holds its own copy of the array at its own address until the process ends.
+// In host code the array's name is only a stand-in for the symbol: the device address comes from
+// hipGetSymbolAddress, once per device with that device current, and only that address is ever handed to a
+// kernel.
+// ---------------------------------------------------------------------------------------------------------
+constexpr size_t kScoresQfragBytesMax = (size_t)(kMaxD / 16) * 2 * 64 * 16;                    // 32 KiB at d = 256
+constexpr size_t kScoresScratchBytes = kScoresQfragBytesMax + (size_t)kMaxScoreWorkgroups * 64 * 4;   // + 1 MiB
+static __device__ __align__(256) unsigned char scratch[kScoresScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// The address of `scratch` on `device`, which must be the current device; resolved on the first call per device.
+int srft_scores_scratch_prepare(int device) {
+    if (device < 0 || device >= kMaxDevices) return SRFT_ERR_HIP;
+    if (g_scratch_ptr[device].load(std::memory_order_acquire)) return SRFT_OK;
+    void* ptr = nullptr;
+    SRFT_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return srft_hip_fail(hipErrorInvalidSymbol);
+    g_scratch_ptr[device].store(ptr, std::memory_order_release);
+    return SRFT_OK;
+}
+
 extern "C" {
 
 int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, uint8_t* codes_dev,
@@ -177,6 +203,18 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
                                      n_q <= 16 ? kOutQFrag16 : kOutQFrag32, st);
     if (rc != SRFT_OK) return rc;
     return srft_launch_scores(plan, qfrag, dump, n_q, codes_dev, scales_dev, n_keys, scores_dev, st);
+}
+
+int srft_kv_scores_static(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
+                          const float* scales_dev, int64_t n_keys, float* scores_dev, void* hip_stream) {
+    if (!plan) return SRFT_ERR_NULL;
+    // the static workspace holds the operands of up to 32 queries at d <= 256 and the dump slots of the largest
+    // grid: anything a plan can ask for; a larger request is refused, never served from elsewhere
+    if (srft_scores_workspace_bytes(plan) > (int64_t)kScoresScratchBytes) return SRFT_ERR_BAD_N;
+    if (plan->device < 0 || plan->device >= kMaxDevices) return SRFT_ERR_HIP;
+    void* ws = g_scratch_ptr[plan->device].load(std::memory_order_acquire);   // resolved when the plan was created
+    if (!ws) return SRFT_ERR_NULL;
+    return srft_kv_scores(plan, q_f16_dev, n_q, codes_dev, scales_dev, n_keys, scores_dev, ws, hip_stream);
 }
 
 int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host) {

@@ -167,6 +167,10 @@ int srft_run_batched(const srft_plan_t* const* plans, const void* const* in0, co
 // true when two plans can share one batched launch or one cache (shape, code width, transform, device, kernel forms)
 bool srft_plans_compatible(const srft_plan* a, const srft_plan* b);
 
+// resolves, once per device, the device address of the static workspace of srft_kv_scores_static (api.hip);
+// called with `device` current when a plan is created
+int srft_scores_scratch_prepare(int device);
+
 inline bool srft_aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 #define SRFT_DISPATCH_D(d, fn, ...)                       \

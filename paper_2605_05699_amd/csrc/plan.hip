@@ -330,6 +330,7 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     if (e == hipSuccess && p->fold_dq) e = hipMalloc((void**)&p->rfold, rfold.size() * 2);
     if (e == hipSuccess && p->fold_dq) e = hipMemcpy(p->rfold, rfold.data(), rfold.size() * 2, hipMemcpyHostToDevice);
     int rc = (e == hipSuccess) ? occupancy_grids(p, cus) : srft_hip_fail(e);
+    if (rc == SRFT_OK) rc = srft_scores_scratch_prepare(p->device);
     if (rc != SRFT_OK) {
         srft_plan_destroy(p);
         return rc;
