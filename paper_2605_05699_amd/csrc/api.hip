@@ -16,10 +16,12 @@ int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* cod
     int threads = 0;
     const quantize_kernel_t kernel = srft_plan_quantize_kernel(p, out, &threads);
     if (!kernel) return SRFT_ERR_BAD_D;
-    const bool fold = p->fold_q && out == kOutCodes;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), 0, st, fold ? p->wfold : p->wfrag,
-                       (const uint4*)x, n, (uint2*)codes, scales, (float4*)wout, p->unscale_w,
-                       p->unscale_w / (p->bits == 8 ? 127.0f : 7.0f), p->gw);
+    const bool fold4 = p->fold4_q && out == kOutCodes, fold = p->fold_q && out == kOutCodes;
+    // the twice-folded form carries the matrix scaling inside its per-channel factors
+    const float unscale = fold4 ? 1.0f : p->unscale_w;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), 0, st,
+                       fold4 ? p->wfold4 : fold ? p->wfold : p->wfrag, (const uint4*)x, n, (uint2*)codes, scales,
+                       (float4*)wout, unscale, unscale / (p->bits == 8 ? 127.0f : 7.0f), p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
@@ -58,7 +60,10 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
     batched_kernel_t kernel = nullptr;
     int threads = 0;
     if (write_path) {
-        if (p->fold_q) {
+        if (p->fold4_q) {
+            kernel = srft_pick_quantize_fold4_batched(p->bits);
+            threads = 256;
+        } else if (p->fold_q) {
             kernel = srft_pick_quantize_fold_batched(p->d, p->bits, p->gm == kGroupWide);
             threads = p->d;
         } else {
@@ -101,7 +106,7 @@ int srft_run_batched(const srft_plan_t* const* plans, const void* const* in0, co
     for (int i = 0; i <= count; ++i) {
         if (i < count && n_vec[i] > 0) {
             const int k = a.count++;
-            a.frag[k] = write_path ? (plans[i]->fold_q ? plans[i]->wfold : plans[i]->wfrag)
+            a.frag[k] = write_path ? (plans[i]->fold4_q ? plans[i]->wfold4 : plans[i]->fold_q ? plans[i]->wfold : plans[i]->wfrag)
                                    : (plans[i]->fold_dq ? plans[i]->rfold : plans[i]->rfrag);
             a.in0[k] = in0[i];
             a.in1[k] = write_path ? nullptr : in1[i];

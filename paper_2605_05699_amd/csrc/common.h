@@ -106,11 +106,13 @@ struct srft_plan {
     uint4* rfrag = nullptr;     // read-path matrix fragments (device)
     uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
     uint4* wfold = nullptr;     // write-path fragments of the folded form (device), when fold_q
+    uint4* wfold4 = nullptr;    // write-path table of the twice-folded form (device), when fold4_q
     float* inv_lam2 = nullptr;  // 1 / (lambda * max(lambda, 1e-6)) per channel (device): scores in the rotated domain
     int grid_scores = 0;        // persistent grid of the scores kernel (32 rows of queries)
     int grid_scores16 = 0;      // the same with 16 rows
     bool fold_dq = false;       // read path contracts even and odd codes separately (half the matrix work)
     bool fold_q = false;        // write path contracts even and odd inputs separately (half the matrix work)
+    bool fold4_q = false;       // write path contracts the inputs in four classes n mod 4 (a quarter of the work)
     float unscale_w = 1.0f;     // 2^-e of the write matrix
     float unscale_r = 1.0f;
     int grid_q = 0, grid_dq = 0;    // default persistent grid sizes
@@ -139,6 +141,10 @@ quantize_kernel_t srft_pick_quantize_aux(int d, int slabs, int out);
 // write path, folded form (d = 128, 256)
 quantize_kernel_t srft_pick_quantize_fold(int d, int bits, bool wide);
 batched_kernel_t srft_pick_quantize_fold_batched(int d, int bits, bool wide);
+// write path, folded twice (d = 256, g = 32); the size of its table in 16-byte units
+quantize_kernel_t srft_pick_quantize_fold4(int bits);
+batched_kernel_t srft_pick_quantize_fold4_batched(int bits);
+int srft_fold4_table_units(void);
 // read path
 dequantize_kernel_t srft_pick_dequantize_b4(int d, int slabs, int gm, bool fold);
 dequantize_kernel_t srft_pick_dequantize_b8(int d, int slabs, int gm, bool fold);

@@ -86,6 +86,74 @@ int split_hi_lo(const std::vector<double>& m, std::vector<uint16_t>& hi, std::ve
     return e;
 }
 
+// Table of the twice-folded write path (d = 256, g = 32): see quantize_fold4_tiles.h for what the kernel does with it.
+// Wavefront w = 0 .. 3 is (cosine, classes 0|2), (cosine, 1|3), (sine, 0|2), (sine, 1|3).  Its two 32 x 64 slabs a
+// and c hold, for k1 = 0 .. 31 and the inputs n = 4 n1 + class, the entries Q[k1][n] s_n (cosine) or Q[128 + k1][n] s_n
+// (sine), the c slab of the odd-class wavefronts negated.  Row k1 = 0 of the sine slabs carries the row k = 32 of the
+// transform instead, (-1)^n1 sqrt(2/d) s_n per class, times 1/sqrt 2 in the odd classes (not negated).
+// lambda is applied after the contraction: rho_d / rho_m are +-lambda of the packed index a lane's value lands on,
+// times the 2^-e of the fp16 scaling, times sqrt 2 for the two values of the rows k1 = 0 that are bins 64.
+void build_fold4_table(const std::vector<int8_t>& signs, const std::vector<double>& lam, std::vector<uint32_t>& out) {
+    const int d = 256, T = 4;
+    std::vector<double> rows((size_t)4 * 2 * 32 * 64);
+    for (int w = 0; w < 4; ++w)
+        for (int ac = 0; ac < 2; ++ac) {
+            const bool sine = w >= 2, oddw = w & 1;
+            const int cls = (oddw ? 1 : 0) + 2 * ac;
+            for (int k1 = 0; k1 < 32; ++k1)
+                for (int n1 = 0; n1 < 64; ++n1) {
+                    const int n = 4 * n1 + cls;
+                    double v;
+                    if (sine && k1 == 0) {
+                        v = ((n1 & 1) ? -1.0 : 1.0) * std::sqrt(2.0 / d) * (oddw ? std::sqrt(0.5) : 1.0);
+                    } else {
+                        v = q_entry(d, sine ? d / 2 + k1 : k1, n);
+                        if (oddw && ac == 1) v = -v;
+                    }
+                    rows[(((size_t)w * 2 + ac) * 32 + k1) * 64 + n1] = v * (double)signs[n];
+                }
+        }
+    std::vector<uint16_t> hi, lo;
+    const double u = std::ldexp(1.0, -split_hi_lo(rows, hi, lo));
+    out.assign((size_t)srft_fold4_table_units() * 4, 0);
+    uint16_t* frag = reinterpret_cast<uint16_t*>(out.data());
+    for (int w = 0; w < 4; ++w)
+        for (int ac = 0; ac < 2; ++ac)
+            for (int t = 0; t < T; ++t)
+                for (int l = 0; l < 64; ++l) {
+                    const int k1 = slab_output_of_row(l % 32), kh = l / 32;
+                    for (int e = 0; e < 8; ++e) {
+                        const size_t src = (((size_t)w * 2 + ac) * 32 + k1) * 64 + (16 * t + 8 * kh + e);
+                        const size_t dst = ((((size_t)(w * 2 + ac) * T + t) * 2) * 64);
+                        frag[((dst + 0) + l) * 8 + e] = hi[src];
+                        frag[((dst + 64) + l) * 8 + e] = lo[src];
+                    }
+                }
+    float* rho = reinterpret_cast<float*>(out.data()) + (size_t)4 * 2 * T * 2 * 64 * 4;
+    const double r2 = std::sqrt(2.0);
+    for (int k1 = 0; k1 < 32; ++k1) {
+        // direct runs: wave 0 -> k1, wave 1 -> 192 + k1, wave 2 -> 128 + k1, wave 3 -> 64 + k1
+        rho[0 * 64 + k1] = (float)(u * lam[k1]);
+        rho[1 * 64 + k1] = (float)(-u * lam[192 + k1] * (k1 == 0 ? r2 : 1.0));
+        rho[2 * 64 + k1] = (float)(u * lam[128 + k1]);            // k1 = 0 is replaced by Nyquist in the kernel
+        rho[3 * 64 + k1] = (float)(u * lam[64 + k1] * (k1 == 0 ? r2 : 1.0));
+        // mirror runs: wave 0 -> 128 - k1, wave 1 -> 192 - k1, wave 2 -> 256 - k1, wave 3 -> 64 - k1 (none at k1 = 0)
+        rho[0 * 64 + 32 + k1] = k1 ? (float)(u * lam[128 - k1]) : 0.0f;
+        rho[1 * 64 + 32 + k1] = k1 ? (float)(-u * lam[192 - k1]) : 0.0f;
+        rho[2 * 64 + 32 + k1] = k1 ? (float)(-u * lam[256 - k1]) : 0.0f;
+        rho[3 * 64 + 32 + k1] = k1 ? (float)(-u * lam[64 - k1]) : 0.0f;
+    }
+    float* misc = rho + 4 * 64;          // per wave: beta1, beta2 (bottom of the mirror group), Nyquist scale, tau
+    const float m0[4] = {(float)(u * lam[96]), (float)(-u * lam[96]), 0.0f, 1.0f};          // z96 = A0 - Am
+    const float m1[4] = {(float)(-u * lam[160]), (float)(-u * lam[160]), 0.0f, -1.0f};      // z160 = -(A2 + Ap)
+    const float m2[4] = {(float)(u * lam[224]), (float)(-u * lam[224]), (float)(u * lam[128]), 1.0f};   // z224 = A2 - Ap
+    const float m3[4] = {(float)(u * lam[32]), (float)(u * lam[32]), 0.0f, 1.0f};           // z32 = A0 + Am
+    std::memcpy(misc + 0, m0, 16);
+    std::memcpy(misc + 4, m1, 16);
+    std::memcpy(misc + 8, m2, 16);
+    std::memcpy(misc + 12, m3, 16);
+}
+
 // resident workgroups per compute unit of a kernel with `threads` threads per workgroup
 int resident_blocks(const void* kernel, int threads, int* blocks) {
     *blocks = 0;
@@ -129,6 +197,10 @@ quantize_kernel_t srft_plan_quantize_kernel(const srft_plan* p, int out, int* th
         *threads = 2 * p->d / p->slabs_q;
         return srft_pick_quantize_aux(p->d, p->slabs_q, out);
     }
+    if (p->fold4_q) {
+        *threads = 256;
+        return srft_pick_quantize_fold4(p->bits);
+    }
     if (p->fold_q) {
         *threads = p->d;
         return srft_pick_quantize_fold(p->d, p->bits, p->gm == kGroupWide);
@@ -146,7 +218,7 @@ dequantize_kernel_t srft_plan_dequantize_kernel(const srft_plan* p, int* threads
 
 bool srft_plans_compatible(const srft_plan* a, const srft_plan* b) {
     return a->d == b->d && a->g == b->g && a->bits == b->bits && a->transform == b->transform &&
-           a->device == b->device && a->fold_q == b->fold_q && a->fold_dq == b->fold_dq &&
+           a->device == b->device && a->fold_q == b->fold_q && a->fold4_q == b->fold4_q && a->fold_dq == b->fold_dq &&
            a->slabs_q == b->slabs_q && a->slabs_dq == b->slabs_dq;
 }
 
@@ -314,6 +386,10 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
             }
         }
     }
+    // Twice-folded write path at d = 256 with the deployed group size; it replaces the once-folded form there.
+    p->fold4_q = (d == 256) && p->gm == kGroup32 && transform == SRFT_TRANSFORM_DFT;
+    std::vector<uint32_t> wfold4;
+    if (p->fold4_q) build_fold4_table(p->signs, lam, wfold4);
     hipError_t e = hipGetDevice(&p->device);
     int cus = 0;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
@@ -327,6 +403,8 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     if (e == hipSuccess) e = hipMemcpy(p->inv_lam2, il2.data(), d * sizeof(float), hipMemcpyHostToDevice);
     if (e == hipSuccess && p->fold_q) e = hipMalloc((void**)&p->wfold, wfold.size() * 2);
     if (e == hipSuccess && p->fold_q) e = hipMemcpy(p->wfold, wfold.data(), wfold.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess && p->fold4_q) e = hipMalloc((void**)&p->wfold4, wfold4.size() * 4);
+    if (e == hipSuccess && p->fold4_q) e = hipMemcpy(p->wfold4, wfold4.data(), wfold4.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess && p->fold_dq) e = hipMalloc((void**)&p->rfold, rfold.size() * 2);
     if (e == hipSuccess && p->fold_dq) e = hipMemcpy(p->rfold, rfold.data(), rfold.size() * 2, hipMemcpyHostToDevice);
     int rc = (e == hipSuccess) ? occupancy_grids(p, cus) : srft_hip_fail(e);
@@ -347,6 +425,10 @@ int srft_plan_destroy(srft_plan_t* plan) {
     if (plan->wfold) {
         const hipError_t e4 = hipFree(plan->wfold);
         if (e3 == hipSuccess) e3 = e4;
+    }
+    if (plan->wfold4) {
+        const hipError_t e6 = hipFree(plan->wfold4);
+        if (e3 == hipSuccess) e3 = e6;
     }
     if (plan->inv_lam2) {
         const hipError_t e5 = hipFree(plan->inv_lam2);

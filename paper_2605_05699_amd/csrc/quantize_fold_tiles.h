@@ -3,6 +3,17 @@
 #define SRFT_QUANTIZE_FOLD_TILES_H
 #include "device_util.h"
 
+// tuning constants (compile time)
+#ifndef SRFT_QF_LEAN_MIN_D
+#define SRFT_QF_LEAN_MIN_D 256
+#endif
+#ifndef SRFT_QF_RHO_LDS_MIN_D
+#define SRFT_QF_RHO_LDS_MIN_D 256
+#endif
+#ifndef SRFT_QF_WG_PER_CU_256
+#define SRFT_QF_WG_PER_CU_256 2
+#endif
+
 // ------------------------------------------------------------------------------------------
 // write path, folded form: half the matrix work, for d a multiple of 128 and g = 32
 // ------------------------------------------------------------------------------------------
@@ -44,7 +55,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     constexpr int ROW = U + 1;
     constexpr int NT = 64 * M;
     constexpr int DUMMY = 2 * M + 1;     // exchange slot for values nobody reads
-    constexpr bool LEAN = (D >= 256);    // registers for one accumulator set only
+    constexpr bool LEAN = (D >= SRFT_QF_LEAN_MIN_D);    // registers for one accumulator set only
     static_assert(M % 2 == 0, "the cosine and the sine block each need whole wavefronts");
     __shared__ uint4 lds[2][kTileVecs * ROW];
     __shared__ float xch[2][(DUMMY + 1) * kTileVecs];
@@ -73,7 +84,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         olo[t] = __builtin_bit_cast(half8, wfold[(((wave * 2 + 1) * T + t) * 2 + 1) * 64 + lane]);
     }
     // rho: in registers, or (large d, where registers are short) in LDS, re-read for every tile
-    constexpr bool RHO_LDS = (D >= 256);
+    constexpr bool RHO_LDS = (D >= SRFT_QF_RHO_LDS_MIN_D);
     __shared__ uint4 rho_s[RHO_LDS ? 4 * NT : 1];
     float rho[16];
     {
@@ -346,7 +357,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
 
 // two wavefronts per SIMD (8 per compute unit): the register allocator is told to stay within 256 VGPRs
 template <int D, int BITS, bool WIDE>
-__global__ void __launch_bounds__(D, 2)
+__global__ void __launch_bounds__(D, (D >= 256 ? SRFT_QF_WG_PER_CU_256 : 2))
 srft_quantize_fold_kernel(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
                           uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__,
                           float unscale, float scale_mul, int gw) {
@@ -355,7 +366,7 @@ srft_quantize_fold_kernel(const uint4* __restrict__ wfold, const uint4* __restri
 }
 
 template <int D, int BITS, bool WIDE>
-__global__ void __launch_bounds__(D, 2)
+__global__ void __launch_bounds__(D, (D >= 256 ? SRFT_QF_WG_PER_CU_256 : 2))
 srft_quantize_fold_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
     srft_quantize_fold_tiles<D, BITS, WIDE>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
