@@ -108,6 +108,7 @@ def test_decode_append_of_the_d96_workload_against_the_oracle(B):
     for pi in range(w.n_plans):
         xh, c, sc, o = (t.cpu().numpy() for t in (xs[pi], codes[pi], scales[pi], outs[pi]))
         q = P.check_quantize(xh, plans[pi].signs, lams[pi], w.g, c, sc)
+        assert q["ill_conditioned_groups"] == 0
         P.check_dequantize(c, sc, plans[pi].signs, lams[pi], w.g, o)
         mism += q["mismatches"]
         tot += q["n"] * w.d
@@ -190,7 +191,7 @@ def test_full_size_plans_in_the_launch_shape_the_benchmark_times(B):
         it = torch.from_numpy(idx).cuda()
         _, lam, _ = W.plan_constants(w, (0, 1, 159)[i])
         c, s, o = (t[it].cpu().numpy() for t in got[0][i:i + 1] + got[1][i:i + 1] + got[2][i:i + 1])
-        P.check_quantize(xs[i][it].cpu().numpy(), p.signs, lam, w.g, c, s)
+        assert P.check_quantize(xs[i][it].cpu().numpy(), p.signs, lam, w.g, c, s)["ill_conditioned_groups"] == 0
         P.check_dequantize(c, s, p.signs, lam, w.g, o)
     for p in plans:
         p.close()

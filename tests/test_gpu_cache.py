@@ -65,8 +65,9 @@ def test_cache_matches_the_model_through_a_ragged_append_schedule(B, d, R):
         assert np.array_equal(view[:, n_q:].view(np.uint16), x[p][:, n_q:].view(np.uint16))
         assert np.array_equal(view[:, n_q:].view(np.uint16), ref[:, n_q:].view(np.uint16))
         # the store against the oracle's quantizer, the prefix against the oracle's read path of the GPU's codes
-        P.check_quantize(x[p][:, :n_q].reshape(-1, d), plans[p].signs, lams[p], g, codes.reshape(-1, d // 2),
-                         scales.reshape(-1, d // g))
+        q = P.check_quantize(x[p][:, :n_q].reshape(-1, d), plans[p].signs, lams[p], g, codes.reshape(-1, d // 2),
+                             scales.reshape(-1, d // g))
+        assert q["ill_conditioned_groups"] == 0
         P.check_dequantize(codes.reshape(-1, d // 2), scales.reshape(-1, d // g), plans[p].signs, lams[p], g,
                            view[:, :n_q].reshape(-1, d))
         # and the prefix is what the library's own read path gives for the stored record (bitwise)
@@ -132,7 +133,8 @@ def test_decode_workload_shape_and_capacity_errors(B):
     view = _tokens(cache.view[p], 20).cpu().numpy()
     codes = _tokens(cache.codes[p], 16).cpu().numpy().reshape(-1, w.d // 2)
     scales = _tokens(cache.scales[p], 16).cpu().numpy().reshape(-1, w.d // w.g)
-    P.check_quantize(xs[:, :16].reshape(-1, w.d), plans[p].signs, lams[p], w.g, codes, scales)
+    assert P.check_quantize(xs[:, :16].reshape(-1, w.d), plans[p].signs, lams[p], w.g, codes,
+                            scales)["ill_conditioned_groups"] == 0
     P.check_dequantize(codes, scales, plans[p].signs, lams[p], w.g, view[:, :16].reshape(-1, w.d))
     assert np.array_equal(view[:, 16:].view(np.uint16), model.view()[:, 16:].view(np.uint16))
     # capacity: 12 more tokens fit, 13 do not, and a refused append changes nothing

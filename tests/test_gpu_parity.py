@@ -290,6 +290,8 @@ def _full_parity(B, w, plans, n_vec=None):
         xh, c, sc, o = x.cpu().numpy(), codes.cpu().numpy(), scales.cpu().numpy(), out.cpu().numpy()
         q = P.check_quantize(xh, plan.signs, lam, w.g, c, sc)
         r = P.check_dequantize(c, sc, plan.signs, lam, w.g, o)
+        # the workloads' data has no cancellation-dominated group: nothing is exempt from the relative checks
+        assert q["ill_conditioned_groups"] == 0, (w.name, pi, q["ill_conditioned_groups"])
         stats.append((pi, q["n"], q["mismatches"], q["scale_max_rel"], r["bit_identical_fraction"]))
         plan.close()
     tot = sum(s[1] for s in stats) * w.d
@@ -328,6 +330,7 @@ def _sampled_parity(B, w, plan_idx, n_vec, quant=True):
     xh, c, sc, o = (t[it].cpu().numpy() for t in (x, codes, scales, out))
     q = P.check_quantize(xh, plan.signs, lam, w.g, c, sc)
     r = P.check_dequantize(c, sc, plan.signs, lam, w.g, o)
+    assert q["ill_conditioned_groups"] == 0, (w.name, plan_idx, q["ill_conditioned_groups"])
     # whole-tensor properties that hold at any size: code range and (scale == 0) <=> (all codes zero)
     lo, hi = codes & 0xF, codes >> 4
     assert int(((lo == 8) | (hi == 8)).sum()) == 0, "nibble -8 produced by the write path"
@@ -354,14 +357,44 @@ def test_workload_decode_append_and_prefix(B):
     w = W.WORKLOADS["decode-d96"]
     # append step: 512 new vectors per plan; full parity on a few plans
     _full_parity(B, w, plans=[0, 1, 62, 63], n_vec=w.append_vectors_per_plan)
-    # prefix read: one plan's full 4,194,304-vector prefix in one launch
+    # prefix read: one plan's full 4,194,304-vector prefix in one launch, three more plans at 262,144 vectors
     _sampled_parity(B, w, 5, w.vectors_per_plan)
+    for pi in (0, 31, 63):
+        _sampled_parity(B, w, pi, 262_144)
 
 
 def test_workload_llama70b_full_size_launch(B):
     w = W.WORKLOADS["llama3-70b-128k"]
+    # two plans at the full 1,048,576 vectors of a launch, six more spread over the 160 at 65,536 vectors
     for pi in (0, 159):
         _sampled_parity(B, w, pi, w.vectors_per_plan)
+    for pi in (1, 40, 41, 80, 119, 158):
+        _sampled_parity(B, w, pi, 65_536)
+
+
+def test_d256_at_the_launch_size_the_bench_times(B):
+    # d = 256 (the Gemma-shaped plans' constants and data) at 1,048,576 vectors per launch: the shape of the bench's
+    # d = 256 line.  Write path per plan, read path through the batched entry point over all plans at once, which
+    # must give the same bytes as the per-plan launches that the sampled check holds against the oracle.
+    w = W.WORKLOADS["gemma3-1b-4k"]
+    n = 1 << 20
+    for pi in (0, 51):
+        _sampled_parity(B, w, pi, n)
+    plans, xs = [], []
+    for pi in (2, 3, 4):
+        plan, _ = _plan_for(B, w, pi)
+        plans.append(plan)
+        xs.append(W.make_kv(w, pi, n_vec=n, device="cuda"))
+    recs = [pl.quantize(x) for pl, x in zip(plans, xs)]
+    outs = [pl.dequantize(c, sc) for pl, (c, sc) in zip(plans, recs)]
+    batched = [torch.empty_like(o) for o in outs]
+    table = B.BatchTable([pl.handle for pl in plans], batched, [c for c, _ in recs], [sc for _, sc in recs])
+    B.srft_kv_dequantize_batched(table)
+    torch.cuda.synchronize()
+    for a, b in zip(outs, batched):
+        assert torch.equal(a, b)
+    for pl in plans:
+        pl.close()
 
 
 def test_single_launch_beyond_4_gib(B):
