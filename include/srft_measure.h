@@ -28,11 +28,13 @@ int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* 
  * bytes to dst_dev, with coalesced 16-byte accesses and no arithmetic.  With 8192 : 2560 it has the write path's
  * byte mix at d = 128 (32 vectors per tile), with 2560 : 8192 the read path's.
  * Byte counts must be multiples of 16, at most 32 KiB read per tile, and not both zero (one of them zero gives
- * the read-only or the write-only stream); workgroups = 0 picks 3 per compute unit; nontemporal != 0 uses
- * non-temporal loads and stores, as the read path does.
+ * the read-only or the write-only stream); workgroups = 0 picks 3 per compute unit.  `access` is a bit set:
+ * 1 = non-temporal loads and stores; 2 = every lane reads 64 contiguous bytes with four 16-byte loads (the
+ * shape a per-lane de-interleave of 32 consecutive inputs needs; read_bytes_per_tile must then be a multiple of
+ * 16 KiB) instead of loads that cover 1 KiB per wavefront contiguously.
  */
 int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int read_bytes_per_tile,
-                    int write_bytes_per_tile, int workgroups, int nontemporal, void* hip_stream);
+                    int write_bytes_per_tile, int workgroups, int access, void* hip_stream);
 
 int srft_measure_last_hip_error(void);    /* the hipError_t of the most recent SRFT_ERR_HIP of this library */
 

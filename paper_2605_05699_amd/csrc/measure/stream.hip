@@ -27,7 +27,9 @@ srft_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, long lo
 // workgroup walks tiles, reads r_units 16-byte units and writes w_units units per tile, all coalesced.
 // Its rate is the ceiling the memory system offers a kernel with the same traffic shape.
 // STREAM: non-temporal loads and stores (what the read path uses)
-template <int RU, bool STREAM>   // RU = ceil(r_units / 256): loads per thread and tile, all issued before any is used
+// CHUNK: 16-byte units a thread reads next to each other (1: a wavefront's load covers 1 KiB contiguously; 4: every
+// lane reads 64 contiguous bytes with four loads, so that each load touches a quarter of every cache line it visits)
+template <int RU, bool STREAM, int CHUNK = 1>   // RU = ceil(r_units / 256): loads per thread and tile, all issued before any is used
 __global__ void __launch_bounds__(256)
 srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n_tiles, int r_units, int w_units) {
     for (long long t = blockIdx.x; t < n_tiles; t += gridDim.x) {
@@ -36,7 +38,8 @@ srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long lon
         if (r_units > 0) {                       // uniform; r_units = 0 is the write-only stream
 #pragma unroll
             for (int i = 0; i < RU; ++i) {
-                const int u = threadIdx.x + 256 * i;
+                const int u = CHUNK == 1 ? threadIdx.x + 256 * i
+                                         : (int)threadIdx.x * CHUNK + i % CHUNK + 256 * CHUNK * (i / CHUNK);
                 v[i] = STREAM ? stream_load(&s[u < r_units ? u : r_units - 1]) : s[u < r_units ? u : r_units - 1];
             }
         }
@@ -88,7 +91,8 @@ int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* 
 }
 
 int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int read_bytes_per_tile,
-                    int write_bytes_per_tile, int workgroups, int nontemporal, void* hip_stream) {
+                    int write_bytes_per_tile, int workgroups, int access, void* hip_stream) {
+    const int nontemporal = access;
     if (n_tiles < 0 || read_bytes_per_tile < 0 || write_bytes_per_tile < 0 || read_bytes_per_tile % 16 ||
         write_bytes_per_tile % 16 || read_bytes_per_tile + write_bytes_per_tile == 0 || workgroups < 0)
         return SRFT_ERR_BAD_N;
@@ -102,11 +106,13 @@ int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int rea
     if (grid > n_tiles) grid = n_tiles;
     const int r_units = read_bytes_per_tile / 16, w_units = write_bytes_per_tile / 16;
     const int ru = r_units > 0 ? (r_units + 255) / 256 : 1;
-    const bool stream = nontemporal != 0;
+    const bool stream = (nontemporal & 1) != 0, chunk4 = (nontemporal & 2) != 0;
+    if (chunk4 && r_units % 1024 != 0) return SRFT_ERR_BAD_N;
     void (*kernel)(const uint4*, uint4*, long long, int, int) = nullptr;
 #define SRFT_MIX_CASE(N)                                                                                          \
     case N:                                                                                                       \
-        kernel = stream ? srft_mix_kernel<N, true> : srft_mix_kernel<N, false>;                                  \
+        kernel = chunk4 ? (stream ? srft_mix_kernel<N, true, 4> : srft_mix_kernel<N, false, 4>)                  \
+                        : (stream ? srft_mix_kernel<N, true> : srft_mix_kernel<N, false>);                       \
         break;
     switch (ru) {
         SRFT_MIX_CASE(1) SRFT_MIX_CASE(2) SRFT_MIX_CASE(3) SRFT_MIX_CASE(4)

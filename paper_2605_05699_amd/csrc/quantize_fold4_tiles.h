@@ -41,6 +41,13 @@
 #define SRFT_QUANTIZE_FOLD4_TILES_H
 #include "device_util.h"
 
+#ifdef SRFT_F4_TRACE
+__device__ unsigned long long* srft_trace_buf;
+#define F4_STAMP(i) do { __builtin_amdgcn_sched_barrier(0); if (trace && lane == 0) trace[(i)] = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#else
+#define F4_STAMP(i) do {} while (0)
+#endif
+
 constexpr int kFold4FragUnits = 4 * 2 * 4 * 2 * 64;          // 16-byte units of fragments in wf4
 constexpr int kFold4RhoFloats = 4 * 64;
 constexpr int kFold4Units = kFold4FragUnits + kFold4RhoFloats / 4 + 4;
@@ -61,6 +68,12 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
     __shared__ uint4 exch[2][4][4][64];                  // send of every wavefront: [wave][4 x 4 floats][lane]
     __shared__ float xch[2][NSLOT * kTileVecs];
     __shared__ __align__(16) float rho_s[4][64];
+    // the record of a finished tile, staged for coalesced stores one stage later: code rows of CROW 8-byte units
+    // (one more than a row has, so that the lanes of a wavefront hit different banks), 8 scales per vector
+    constexpr int CU8 = (BITS == 8 ? D : D / 2) / 8;     // 8-byte units per code row
+    constexpr int CROW = CU8 + 1;
+    __shared__ uint2 cstage[2][kTileVecs * CROW];
+    __shared__ __align__(16) float sstage[2][kTileVecs * G];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -104,14 +117,17 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
         if (tile > n_tiles - 1) tile = n_tiles - 1;
         const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
         const uint4* src = x + (long long)tile * kTileVecs * U + (unsigned)(min(frow, lim) * U + 4 * fchunk);
+#ifdef SRFT_F4_NT_LOAD
+        a = stream_load(src); b = stream_load(src + 1); c = stream_load(src + 2); d = stream_load(src + 3);
+#else
         a = src[0];
         b = src[1];
         c = src[2];
         d = src[3];
+#endif
     };
     // 32 consecutive inputs -> for each class the 8 that belong to it (positions c, c + 4, ... of the chunk)
     auto to_lds = [&](int buf, const uint4& a, const uint4& b, const uint4& c, const uint4& d) __attribute__((always_inline)) {
-        __builtin_amdgcn_sched_barrier(0);       // the first use of the prefetched registers stays behind the tail's stores
         constexpr uint32_t kLo = 0x05040100u, kHi = 0x07060302u;
         uint4* row = &lds[buf][frow * ROW + fchunk];
         row[0] = make_uint4(__builtin_amdgcn_perm(a.z, a.x, kLo), __builtin_amdgcn_perm(b.z, b.x, kLo),
@@ -232,27 +248,43 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
         float sd, id, sm, im;
         scale_of(md, sd, id);
         scale_of(mm, sm, im);
-        if constexpr (BITS == 8) {               // 16 values = 16 bytes: the same unit indices, in 16-byte units
-            const uint4 pd = make_uint4(pack4v(dv[0], dv[1], dv[2], dv[3], id), pack4v(dv[4], dv[5], dv[6], dv[7], id),
-                                        pack4v(dv[8], dv[9], dv[10], dv[11], id), pack4v(dv[12], dv[13], dv[14], dv[15], id));
-            const uint4 pm = make_uint4(pack4v(bottom, mv[15], mv[14], mv[13], im), pack4v(mv[12], mv[11], mv[10], mv[9], im),
-                                        pack4v(mv[8], mv[7], mv[6], mv[5], im), pack4v(mv[4], mv[3], mv[2], mv[1], im));
-            uint4* crow = reinterpret_cast<uint4*>(codes) + row0 * (D / 16);
-            crow[(unsigned)(c * (D / 16) + base_d / 16 + half)] = pd;
-            crow[(unsigned)(c * (D / 16) + p_top / 16 - 1 - half)] = pm;
+        uint2* crow = &cstage[b][col * CROW];
+        if constexpr (BITS == 8) {               // 16 values = 16 bytes = two 8-byte units
+            crow[base_d / 8 + 2 * half] = make_uint2(pack4v(dv[0], dv[1], dv[2], dv[3], id), pack4v(dv[4], dv[5], dv[6], dv[7], id));
+            crow[base_d / 8 + 2 * half + 1] = make_uint2(pack4v(dv[8], dv[9], dv[10], dv[11], id), pack4v(dv[12], dv[13], dv[14], dv[15], id));
+            crow[p_top / 8 - 2 - 2 * half] = make_uint2(pack4v(bottom, mv[15], mv[14], mv[13], im), pack4v(mv[12], mv[11], mv[10], mv[9], im));
+            crow[p_top / 8 - 1 - 2 * half] = make_uint2(pack4v(mv[8], mv[7], mv[6], mv[5], im), pack4v(mv[4], mv[3], mv[2], mv[1], im));
         } else {
             uint2 pd, pm;
             pd.x = pack8v(dv[0], dv[1], dv[2], dv[3], dv[4], dv[5], dv[6], dv[7], id);
             pd.y = pack8v(dv[8], dv[9], dv[10], dv[11], dv[12], dv[13], dv[14], dv[15], id);
             pm.x = pack8v(bottom, mv[15], mv[14], mv[13], mv[12], mv[11], mv[10], mv[9], im);
             pm.y = pack8v(mv[8], mv[7], mv[6], mv[5], mv[4], mv[3], mv[2], mv[1], im);
-            uint2* crow = codes + row0 * (D / 16);
-            crow[(unsigned)(c * (D / 16) + base_d / 16 + half)] = pd;
-            crow[(unsigned)(c * (D / 16) + p_top / 16 - 1 - half)] = pm;
+            crow[base_d / 16 + half] = pd;
+            crow[p_top / 16 - 1 - half] = pm;
         }
-        float* srow = scales + row0 * G;         // both halves store the same values
-        srow[(unsigned)(c * G + base_d / 32)] = sd;
-        srow[(unsigned)(c * G + slot_in)] = sm;
+        // both halves hold both scales: the lower lanes stage the direct group's, the upper lanes the mirror group's
+        sstage[b][col * G + (half ? slot_in : base_d / 32)] = half ? sm : sd;
+    };
+
+    // staged record of `tile` -> global memory: 16 bytes per thread, whole rows next to each other (rows past the end
+    // alias to the last row); the first wavefront also moves the scales
+    auto flush = [&](int b, int tile) __attribute__((always_inline)) {
+        const long long row0 = (long long)tile * kTileVecs;
+        const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
+        constexpr int PIECES = CU8 / 2;                  // 16-byte pieces per code row
+        uint4* cbase = reinterpret_cast<uint4*>(codes) + row0 * PIECES;
+#pragma unroll
+        for (int i = 0; i < kTileVecs * PIECES / NT; ++i) {
+            const int u = tid + i * NT, r = u / PIECES, pc = u % PIECES;
+            const uint2 lo = cstage[b][r * CROW + 2 * pc], hi = cstage[b][r * CROW + 2 * pc + 1];
+            cbase[(unsigned)(min(r, lim) * PIECES + pc)] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+        if (wave == 0) {                                 // uniform per wavefront
+            const int r = lane >> 1, hf = lane & 1;
+            const float4 v = *reinterpret_cast<const float4*>(&sstage[b][r * G + 4 * hf]);
+            reinterpret_cast<float4*>(scales + row0 * G)[(unsigned)(min(r, lim) * 2 + hf)] = v;
+        }
     };
 
     const int m = (n_tiles - 1 - t0) / stride + 1;
@@ -273,32 +305,54 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
     int k = 1;
     for (; k + 1 < m; k += 2) {
         const int tk = t0 + k * stride;
+#ifdef SRFT_F4_TRACE
+        unsigned long long* trace = (blockIdx.x < 1024 && k < 40) ? srft_trace_buf + ((size_t)(blockIdx.x * 4 + wave) * 40 + k) * 8 : nullptr;
+#endif
+        F4_STAMP(0);
         __syncthreads();                         // stage k (odd)
+        F4_STAMP(1);
         rotate_priority(k);
+        if (k >= 2) flush(1, tk - 2 * stride);
         contract(1, ab, cb);
+        F4_STAMP(2);
         finish(0, aa, tk - stride);
+        F4_STAMP(3);
         to_lds(0, pa0, pa1, pa2, pa3);
         fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
         hand_over(1, ab, cb);
+        F4_STAMP(4);
         __syncthreads();                         // stage k + 1 (even)
+        F4_STAMP(5);
         rotate_priority(k + 1);
+        flush(0, tk - stride);
         contract(0, aa, ca);
         finish(1, ab, tk);
+        F4_STAMP(6);
         to_lds(1, pb0, pb1, pb2, pb3);
         fetch(pb0, pb1, pb2, pb3, tk + 4 * stride);
         hand_over(0, aa, ca);
+        F4_STAMP(7);
     }
+    // finish(b, ...) stages into buffer b, flush(b, ...) stores it one barrier later
     if (k < m) {                                 // one more odd stage
         const int tk = t0 + k * stride;
         __syncthreads();
+        if (k >= 2) flush(1, tk - 2 * stride);
         contract(1, ab, cb);
         finish(0, aa, tk - stride);
         hand_over(1, ab, cb);
         __syncthreads();
+        flush(0, tk - stride);
         finish(1, ab, tk);
-    } else {
         __syncthreads();
-        finish(0, aa, t0 + (k - 1) * stride);
+        flush(1, tk);
+    } else {
+        const int tl = t0 + (k - 1) * stride;    // the last stage was even (or stage 0): its tile's keep is in aa
+        __syncthreads();
+        if (k >= 2) flush(1, tl - stride);
+        finish(0, aa, tl);
+        __syncthreads();
+        flush(0, tl);
     }
 }
 
