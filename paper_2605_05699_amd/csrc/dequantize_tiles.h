@@ -34,7 +34,7 @@ template <int D, int S, int KS, bool FOLD, int BITS>
 __device__ __forceinline__ void
 srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes_raw,
                       const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
-                      float unscale, int gw, const int t0, const int stride) {
+                      float unscale, int gw, const int t0, const int stride, const int t_end) {
     constexpr int G = FOLD ? D / 32 : D / 32 * (2 / KS);  // groups per vector as contracted
     constexpr int NSMAX = D / 16;         // most scales a vector can have (g = 16)
     constexpr bool kPerStep = (KS == 1 && !FOLD);         // g = 16: a scale per k-step of the full matrix
@@ -260,7 +260,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         stage_out(b);
     };
 
-    const int m = (n_tiles - 1 - t0) / stride + 1;
+    const int m = (t_end - 1 - t0) / stride + 1;            // tiles of this workgroup: t0, t0 + stride, ... < t_end
     CodeUnit pa0, pa1, pb0, pb1;                 // prefetched code units of the next two tiles
     float pas, pat, pbs, pbt;                    // and up to two floats each of their scale tiles
     float s_last;                                // scale of the last group of the tile contracted last
@@ -371,7 +371,9 @@ __global__ void __launch_bounds__(2 * D / S)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
                        const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                        float unscale, int gw) {
-    srft_dequantize_tiles<D, S, KS, FOLD, BITS>(rfrag, codes, scales, n_vec, out, unscale, gw, blockIdx.x, gridDim.x);
+    int t0, stride, t_end;
+    if (!srft_tile_range(n_vec, t0, stride, t_end)) return;
+    srft_dequantize_tiles<D, S, KS, FOLD, BITS>(rfrag, codes, scales, n_vec, out, unscale, gw, t0, stride, t_end);
 }
 
 template <int D, int S, int KS, bool FOLD, int BITS>
@@ -380,7 +382,8 @@ srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
     srft_dequantize_tiles<D, S, KS, FOLD, BITS>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
                                     (uint4*)a.out0[i], a.unscale[i], gw, blockIdx.x - a.first_block[i],
-                                    a.first_block[i + 1] - a.first_block[i]);
+                                    a.first_block[i + 1] - a.first_block[i],
+                                    (int)((a.n_vec[i] + kTileVecs - 1) / kTileVecs));
 }
 
 #endif  // SRFT_DEQUANTIZE_TILES_H

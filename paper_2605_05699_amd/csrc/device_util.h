@@ -171,4 +171,27 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
 // Every branch in the kernels is uniform over the workgroup.
 // ------------------------------------------------------------------------------------------
 
+// Which tiles a workgroup of a per-plan launch walks: first tile, stride, and the end (exclusive) of its range.
+// SRFT_XCD_MAP = 0: tile = blockIdx + k gridDim over all tiles.  SRFT_XCD_MAP = 1: workgroups are dealt to the 8
+// accelerator dies round-robin (die = blockIdx mod 8), and each die gets one contiguous eighth of the tiles, which
+// its workgroups walk with stride gridDim / 8 (grids that are not a multiple of 8 fall back to the plain map).
+#ifndef SRFT_XCD_MAP
+#define SRFT_XCD_MAP 0
+#endif
+__device__ __forceinline__ bool srft_tile_range(long long n_vec, int& t0, int& stride, int& t_end) {
+    const int n_tiles = (int)((n_vec + kTileVecs - 1) / kTileVecs);
+    t0 = blockIdx.x;
+    stride = gridDim.x;
+    t_end = n_tiles;
+#if SRFT_XCD_MAP
+    if ((gridDim.x & 7) == 0 && n_tiles >= (int)gridDim.x) {
+        const int per_die = (n_tiles + 7) >> 3, die = blockIdx.x & 7;
+        stride = gridDim.x >> 3;
+        t0 = die * per_die + (blockIdx.x >> 3);
+        t_end = min(n_tiles, (die + 1) * per_die);
+    }
+#endif
+    return t0 < t_end;
+}
+
 #endif  // SRFT_DEVICE_UTIL_H

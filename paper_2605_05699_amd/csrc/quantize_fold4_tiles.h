@@ -43,7 +43,11 @@
 
 #ifdef SRFT_F4_TRACE
 __device__ unsigned long long* srft_trace_buf;
+#if SRFT_F4_TRACE == 2
+#define F4_STAMP(i) do {} while (0)
+#else
 #define F4_STAMP(i) do { __builtin_amdgcn_sched_barrier(0); if (trace && lane == 0) trace[(i)] = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#endif
 #else
 #define F4_STAMP(i) do {} while (0)
 #endif
@@ -56,7 +60,7 @@ template <int BITS>
 __device__ __forceinline__ void
 srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict__ x, long long n_vec,
                           uint2* __restrict__ codes, float* __restrict__ scales, float scale_mul, const int t0,
-                          const int stride) {
+                          const int stride, const int t_end) {
     constexpr int D = 256;
     constexpr int G = D / 32;            // groups per vector
     constexpr int T = 4;                 // k-steps per class (K = 64)
@@ -278,7 +282,13 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
         for (int i = 0; i < kTileVecs * PIECES / NT; ++i) {
             const int u = tid + i * NT, r = u / PIECES, pc = u % PIECES;
             const uint2 lo = cstage[b][r * CROW + 2 * pc], hi = cstage[b][r * CROW + 2 * pc + 1];
+            
+#ifdef SRFT_F4_NT_STORE
+            stream_store(&cbase[(unsigned)(min(r, lim) * PIECES + pc)], make_uint4(lo.x, lo.y, hi.x, hi.y));
+#else
             cbase[(unsigned)(min(r, lim) * PIECES + pc)] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+#endif
+
         }
         if (wave == 0) {                                 // uniform per wavefront
             const int r = lane >> 1, hf = lane & 1;
@@ -287,7 +297,18 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
         }
     };
 
-    const int m = (n_tiles - 1 - t0) / stride + 1;
+#if defined(SRFT_F4_TRACE) && SRFT_F4_TRACE == 2
+    struct BlockStamp {
+        unsigned long long* r;
+        __device__ BlockStamp(unsigned long long* p) : r(p) {
+            if (r) { r[0] = __builtin_amdgcn_s_memrealtime(); r[1] = __builtin_readcyclecounter();
+                     unsigned id, xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(id));
+                     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc)); r[2] = id; r[3] = xcc; }
+        }
+        __device__ ~BlockStamp() { if (r) { r[4] = __builtin_amdgcn_s_memrealtime(); r[5] = __builtin_readcyclecounter(); } }
+    } block_stamp((tid == 0 && blockIdx.x < 4096) ? srft_trace_buf + (size_t)blockIdx.x * 8 : nullptr);
+#endif
+    const int m = (t_end - 1 - t0) / stride + 1;            // tiles of this workgroup: t0, t0 + stride, ... < t_end
     uint4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3;
     floatx16 aa, ca, ab, cb;                     // two accumulator sets; after hand_over the a of a set holds keep
     fetch(pa0, pa1, pa2, pa3, t0);
@@ -305,7 +326,7 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
     int k = 1;
     for (; k + 1 < m; k += 2) {
         const int tk = t0 + k * stride;
-#ifdef SRFT_F4_TRACE
+#if defined(SRFT_F4_TRACE) && SRFT_F4_TRACE != 2
         unsigned long long* trace = (blockIdx.x < 1024 && k < 40) ? srft_trace_buf + ((size_t)(blockIdx.x * 4 + wave) * 40 + k) * 8 : nullptr;
 #endif
         F4_STAMP(0);
@@ -361,7 +382,9 @@ __global__ void __launch_bounds__(256, 2)
 srft_quantize_fold4_kernel(const uint4* __restrict__ wf4, const uint4* __restrict__ x, long long n_vec,
                            uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__,
                            float, float scale_mul, int) {
-    srft_quantize_fold4_tiles<BITS>(wf4, x, n_vec, codes, scales, scale_mul, blockIdx.x, gridDim.x);
+    int t0, stride, t_end;
+    if (!srft_tile_range(n_vec, t0, stride, t_end)) return;
+    srft_quantize_fold4_tiles<BITS>(wf4, x, n_vec, codes, scales, scale_mul, t0, stride, t_end);
 }
 
 template <int BITS>
@@ -370,7 +393,8 @@ srft_quantize_fold4_batched_kernel(const srft_batch_args a, int) {
     const int i = srft_segment_of_block(a, blockIdx.x);
     srft_quantize_fold4_tiles<BITS>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
                                     (float*)a.out1[i], 1.0f / (BITS == 8 ? 127.0f : 7.0f),
-                                    blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i]);
+                                    blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i],
+                                    (int)((a.n_vec[i] + kTileVecs - 1) / kTileVecs));
 }
 
 #endif  // SRFT_QUANTIZE_FOLD4_TILES_H

@@ -10,6 +10,12 @@
 #ifndef SRFT_QF_RHO_LDS_MIN_D
 #define SRFT_QF_RHO_LDS_MIN_D 256
 #endif
+#ifndef SRFT_QF_STAGE_OUT
+#define SRFT_QF_STAGE_OUT 1          // the record goes through LDS and is stored as whole rows one stage later
+#endif
+#ifndef SRFT_QF_NT_STORE
+#define SRFT_QF_NT_STORE 1           // non-temporal stores of the staged rows (+2.5 % at d = 128; nothing at d = 256)
+#endif
 #ifndef SRFT_QF_WG_PER_CU_256
 #define SRFT_QF_WG_PER_CU_256 2
 #endif
@@ -47,7 +53,7 @@ template <int D, int BITS, bool WIDE>
 __device__ __forceinline__ void
 srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
                          uint2* __restrict__ codes, float* __restrict__ scales, float unscale, float scale_mul,
-                         int gw, const int t0, const int stride) {
+                         int gw, const int t0, const int stride, const int t_end) {
     constexpr int M = D / 64;            // wavefronts per workgroup
     constexpr int G = D / 32;            // groups per vector
     constexpr int T = D / 32;            // k-steps per slab (K = D / 2)
@@ -60,6 +66,13 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     __shared__ uint4 lds[2][kTileVecs * ROW];
     __shared__ float xch[2][(DUMMY + 1) * kTileVecs];
     __shared__ float gmax[WIDE ? 2 : 1][WIDE ? kTileVecs * G : 1];     // maxima of the 32-runs of a tile (WIDE)
+    // The record of a finished tile is staged here and stored one stage later, 16 bytes per thread over whole rows:
+    // stored directly, a tile's record is 8-byte pieces and single floats, a write request each.
+    constexpr bool STAGE = SRFT_QF_STAGE_OUT != 0;
+    constexpr int CU8 = (BITS == 8 ? D : D / 2) / 8;     // 8-byte units per code row
+    constexpr int CROW = CU8 + 1;                        // padded: the lanes of a wavefront hit different banks
+    __shared__ uint2 cstage[STAGE ? 2 : 1][STAGE ? kTileVecs * CROW : 1];
+    __shared__ float sstage[STAGE ? 2 : 1][STAGE ? kTileVecs * G : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -232,6 +245,28 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         float sd, id, sm, im;
         scale_of(md, sd, id);
         scale_of(mm, sm, im);
+        if constexpr (STAGE) {
+            const int ns = WIDE ? G / gw : G;
+            uint2* crow = &cstage[b][col * CROW];
+            if constexpr (BITS == 8) {           // 16 values = 16 bytes = two 8-byte units
+                crow[base_d / 8 + 2 * half] = make_uint2(pack4v(dv[0], dv[1], dv[2], dv[3], id), pack4v(dv[4], dv[5], dv[6], dv[7], id));
+                crow[base_d / 8 + 2 * half + 1] = make_uint2(pack4v(dv[8], dv[9], dv[10], dv[11], id), pack4v(dv[12], dv[13], dv[14], dv[15], id));
+                crow[p_top / 8 - 2 - 2 * half] = make_uint2(pack4v(bottom, mv[15], mv[14], mv[13], im), pack4v(mv[12], mv[11], mv[10], mv[9], im));
+                crow[p_top / 8 - 1 - 2 * half] = make_uint2(pack4v(mv[8], mv[7], mv[6], mv[5], im), pack4v(mv[4], mv[3], mv[2], mv[1], im));
+            } else {
+                uint2 pd, pm;
+                pd.x = pack8v(dv[0], dv[1], dv[2], dv[3], dv[4], dv[5], dv[6], dv[7], id);
+                pd.y = pack8v(dv[8], dv[9], dv[10], dv[11], dv[12], dv[13], dv[14], dv[15], id);
+                pm.x = pack8v(bottom, mv[15], mv[14], mv[13], mv[12], mv[11], mv[10], mv[9], im);
+                pm.y = pack8v(mv[8], mv[7], mv[6], mv[5], mv[4], mv[3], mv[2], mv[1], im);
+                crow[base_d / 16 + half] = pd;
+                crow[p_top / 16 - 1 - half] = pm;
+            }
+            // both halves hold both scales: the lower lanes stage the direct group's, the upper lanes the mirror group's
+            const int jd = WIDE ? base_d / 32 / gw : base_d / 32, jm = WIDE ? slot_in / gw : slot_in;
+            sstage[b][col * ns + (half ? jm : jd)] = half ? sm : sd;
+            return;
+        }
         if constexpr (BITS == 8) {               // 16 values = 16 bytes: the same unit indices, in 16-byte units
             const uint4 pd = make_uint4(pack4v(dv[0], dv[1], dv[2], dv[3], id), pack4v(dv[4], dv[5], dv[6], dv[7], id),
                                         pack4v(dv[8], dv[9], dv[10], dv[11], id), pack4v(dv[12], dv[13], dv[14], dv[15], id));
@@ -262,7 +297,32 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         }
     };
 
-    const int m = (n_tiles - 1 - t0) / stride + 1;
+    // staged record of `tile` -> global memory (rows past the end alias to the last row)
+    auto flush = [&](int b, int tile) __attribute__((always_inline)) {
+        if constexpr (STAGE) {
+            const long long row0 = (long long)tile * kTileVecs;
+            const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
+            constexpr int PIECES = CU8 / 2;              // 16-byte pieces per code row
+            uint4* cbase = reinterpret_cast<uint4*>(codes) + row0 * PIECES;
+#pragma unroll
+            for (int i = 0; i < kTileVecs * PIECES / NT; ++i) {
+                const int u = tid + i * NT, r = u / PIECES, pc = u % PIECES;
+                const uint2 lo = cstage[b][r * CROW + 2 * pc], hi = cstage[b][r * CROW + 2 * pc + 1];
+                
+#if SRFT_QF_NT_STORE
+            stream_store(&cbase[(unsigned)(min(r, lim) * PIECES + pc)], make_uint4(lo.x, lo.y, hi.x, hi.y));
+#else
+            cbase[(unsigned)(min(r, lim) * PIECES + pc)] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+#endif
+
+            }
+            const int ns = WIDE ? G / gw : G;            // 32 ns floats, next to each other in memory
+            if (tid < kTileVecs * ns)
+                (scales + row0 * ns)[(unsigned)(min(tid / ns, lim) * ns + tid % ns)] = sstage[b][tid];
+        }
+    };
+
+    const int m = (t_end - 1 - t0) / stride + 1;            // tiles of this workgroup: t0, t0 + stride, ... < t_end
     uint4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3;
     floatx16 ea, oa, eb, ob;
     fetch(pa0, pa1, pa2, pa3, t0);
@@ -288,6 +348,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         for (; k + 1 < m; k += 2) {
             const int tk = t0 + k * stride;
             __syncthreads();                     // stage k (odd)
+            if (k >= 2) flush(1, tk - 2 * stride);
             finish(0, ea, oa, tk - stride);
             __builtin_amdgcn_sched_barrier(0);   // no second accumulator set: the tail ends before the MFMAs begin
             contract(1, ea, oa);
@@ -295,6 +356,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
             fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
             publish(1, ea, oa);
             __syncthreads();                     // stage k + 1 (even)
+            flush(0, tk - stride);
             finish(1, ea, oa, tk);
             __builtin_amdgcn_sched_barrier(0);
             contract(0, ea, oa);
@@ -305,15 +367,23 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         if (k < m) {                             // one more odd stage
             const int tk = t0 + k * stride;
             __syncthreads();
+            if (k >= 2) flush(1, tk - 2 * stride);
             finish(0, ea, oa, tk - stride);
             __builtin_amdgcn_sched_barrier(0);
             contract(1, ea, oa);
             publish(1, ea, oa);
             __syncthreads();
+            flush(0, tk - stride);
             finish(1, ea, oa, tk);
+            if constexpr (STAGE) __syncthreads();
+            flush(1, tk);
         } else {
+            const int tl = t0 + (k - 1) * stride;
             __syncthreads();
-            finish(0, ea, oa, t0 + (k - 1) * stride);
+            if (k >= 2) flush(1, tl - stride);
+            finish(0, ea, oa, tl);
+            if constexpr (STAGE) __syncthreads();
+            flush(0, tl);
         }
         return;
     }
@@ -328,6 +398,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         const int tk = t0 + k * stride;
         __syncthreads();                         // stage k (odd)
         rotate_priority(k);
+        if (k >= 2) flush(1, tk - 2 * stride);
         contract(1, eb, ob);
         finish(0, ea, oa, tk - stride);
         to_lds(0, pa0, pa1, pa2, pa3);
@@ -335,6 +406,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         publish(1, eb, ob);
         __syncthreads();                         // stage k + 1 (even)
         rotate_priority(k + 1);
+        flush(0, tk - stride);
         contract(0, ea, oa);
         finish(1, eb, ob, tk);
         to_lds(1, pb0, pb1, pb2, pb3);
@@ -344,14 +416,22 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     if (k < m) {                                 // one more odd stage
         const int tk = t0 + k * stride;
         __syncthreads();
+        if (k >= 2) flush(1, tk - 2 * stride);
         contract(1, eb, ob);
         finish(0, ea, oa, tk - stride);
         publish(1, eb, ob);
         __syncthreads();
+        flush(0, tk - stride);
         finish(1, eb, ob, tk);
+        if constexpr (STAGE) __syncthreads();
+        flush(1, tk);
     } else {
+        const int tl = t0 + (k - 1) * stride;
         __syncthreads();
-        finish(0, ea, oa, t0 + (k - 1) * stride);
+        if (k >= 2) flush(1, tl - stride);
+        finish(0, ea, oa, tl);
+        if constexpr (STAGE) __syncthreads();
+        flush(0, tl);
     }
 }
 
@@ -361,8 +441,9 @@ __global__ void __launch_bounds__(D, (D >= 256 ? SRFT_QF_WG_PER_CU_256 : 2))
 srft_quantize_fold_kernel(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
                           uint2* __restrict__ codes, float* __restrict__ scales, float4* __restrict__,
                           float unscale, float scale_mul, int gw) {
-    srft_quantize_fold_tiles<D, BITS, WIDE>(wfold, x, n_vec, codes, scales, unscale, scale_mul, gw, blockIdx.x,
-                                            gridDim.x);
+    int t0, stride, t_end;
+    if (!srft_tile_range(n_vec, t0, stride, t_end)) return;
+    srft_quantize_fold_tiles<D, BITS, WIDE>(wfold, x, n_vec, codes, scales, unscale, scale_mul, gw, t0, stride, t_end);
 }
 
 template <int D, int BITS, bool WIDE>
@@ -371,7 +452,8 @@ srft_quantize_fold_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
     srft_quantize_fold_tiles<D, BITS, WIDE>(a.frag[i], (const uint4*)a.in0[i], a.n_vec[i], (uint2*)a.out0[i],
                                             (float*)a.out1[i], a.unscale[i], a.unscale[i] / (BITS == 8 ? 127.0f : 7.0f),
-                                            gw, blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i]);
+                                            gw, blockIdx.x - a.first_block[i], a.first_block[i + 1] - a.first_block[i],
+                                            (int)((a.n_vec[i] + kTileVecs - 1) / kTileVecs));
 }
 
 #endif  // SRFT_QUANTIZE_FOLD_TILES_H
