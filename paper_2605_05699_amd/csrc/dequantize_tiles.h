@@ -3,6 +3,10 @@
 #define SRFT_DEQUANTIZE_TILES_H
 #include "device_util.h"
 
+#ifndef SRFT_DQ_HALF_PIPE
+#define SRFT_DQ_HALF_PIPE 1            // folded read path with one accumulator per slab: pinned half-group pipeline
+#endif
+
 // rfrag : [D/32 waves][D/32 groups][2 k-steps][hi, lo][64 lanes] 16-byte A-operand fragments of R
 // codes : [n_vec][D/16] 8-byte units; scales : [n_vec][D/32]; out : [n_vec][D/8] 16-byte units of fp16
 //
@@ -249,6 +253,46 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
                 fold((j & 1) ? acc0 : acc1, scale_of(b, j - 1), j == 1);
             }
             fold(((G - 1) & 1) ? acc1 : acc0, scale_of(b, G - 1), G == 1);
+        } else if constexpr (FOLD && SRFT_DQ_HALF_PIPE) {
+            // One accumulator per slab, software-pipelined at half-group granularity: while the two MFMAs of one slab
+            // (64 clocks of the matrix pipe) run, the other slab's previous result is folded in (16 multiply-adds, 64
+            // clocks of the vector ALU).  The order is pinned: left alone, the compiler puts a group's four MFMAs in
+            // front of its 32 multiply-adds, and the second slab's fold then waits for the pipe to drain.
+            // B fragments are read two half-steps ahead, the group scales once per tile.
+            const uint4* rowp = &dec[b][col * ROW + 2 * half];      // units 4j + 2 half (+ 1): even / odd codes of group j
+            float sc = scale_of(b, 0), sc_next = sc;    // the scale of the next group is read one step ahead
+            half8 fa = __builtin_bit_cast(half8, rowp[0]), fb = __builtin_bit_cast(half8, rowp[1]);
+            half8 fa_next = G > 1 ? __builtin_bit_cast(half8, rowp[4]) : fa, fb_next = fb;
+            acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[0][0], fa, floatx16{0}, 0, 0, 0);
+            acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[0][0], fa, acc0[0], 0, 0, 0);
+            acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[G][0], fb, floatx16{0}, 0, 0, 0);
+            acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[G][0], fb, acc0[1], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (j + 1 < G) {
+                    fb_next = __builtin_bit_cast(half8, rowp[4 * (j + 1) + 1]);
+                    sc_next = scale_of(b, j + 1);
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[0][v] = j == 0 ? acc0[0][v] * sc : fmaf(acc0[0][v], sc, o[0][v]);
+                if (j + 1 < G) {
+                    fa = fa_next;
+                    acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[j + 1][0], fa, floatx16{0}, 0, 0, 0);
+                    acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j + 1][0], fa, acc0[0], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (j + 2 < G) fa_next = __builtin_bit_cast(half8, rowp[4 * (j + 2)]);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[1][v] = j == 0 ? acc0[1][v] * sc : fmaf(acc0[1][v], sc, o[1][v]);
+                sc = sc_next;
+                if (j + 1 < G) {
+                    fb = fb_next;
+                    acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[G + j + 1][0], fb, floatx16{0}, 0, 0, 0);
+                    acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[G + j + 1][0], fb, acc0[1], 0, 0, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         } else {
 #pragma unroll
             for (int j = 0; j < G; ++j) {
@@ -367,7 +411,8 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
 }
 
 template <int D, int S, int KS, bool FOLD, int BITS>
-__global__ void __launch_bounds__(2 * D / S)
+// (two workgroups per compute unit at d = 256: the register allocator stays within 256 VGPRs)
+__global__ void __launch_bounds__(2 * D / S, (FOLD && D == 256) ? 2 : 1)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
                        const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                        float unscale, int gw) {
@@ -377,7 +422,8 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
 }
 
 template <int D, int S, int KS, bool FOLD, int BITS>
-__global__ void __launch_bounds__(2 * D / S)
+// (two workgroups per compute unit at d = 256: the register allocator stays within 256 VGPRs)
+__global__ void __launch_bounds__(2 * D / S, (FOLD && D == 256) ? 2 : 1)
 srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
     srft_dequantize_tiles<D, S, KS, FOLD, BITS>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
