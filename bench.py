@@ -11,9 +11,16 @@ Inputs are synthetic, seeded, and resident in HBM before the timed region.  Prin
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 
 Beside the contract's keys the line carries per-path figures ("quantize", "dequantize"), for the default workload a
-side measurement of the same launch shape at d = 256 ("d256_same_launch_shape", skip with --no-d256), and on request
-the streaming ceilings of the memory system (--ceiling), power and clock per path (--power), the decode-step append
+side measurement of the same launch shape at d = 256 ("d256_same_launch_shape", skip with --no-d256) and one timed
+step of each of the other four configurations ("all_configs", skip with --no-all-configs: they are parity-test
+cases, cache-resident or launch-bound except the d = 96 prefix read, and are flagged so), and on request the
+streaming ceilings of the memory system (--ceiling), power and clock per path (--power), the decode-step append
 (--decode-append) and scores against the stored keys (--scores).
+
+Clocks: every duration in the line is HIP-event time on the stream the kernels are launched on (torch's current
+stream, which is the stream handed to the library); "value" alone uses the host clock around the synchronised
+timed region.  Back-to-back launches overlap their tails by a few per cent, so the per-launch average from events
+is slightly below the kernel durations a profiler lists.
 """
 from __future__ import annotations
 
@@ -24,20 +31,18 @@ import time
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 
-# HBM traffic measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/), in bytes per vector, for the
-# default workload; scaled below by the vectors one launch processes.  None until a counter run has been recorded.
+# HBM traffic measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; profiles/hbm_traffic_d128_llama3-70b-128k.txt),
+# in bytes per vector, keyed by the kernel symbol the measurement was taken on: a kernel without a recorded counter
+# run reports null.  (FETCH_SIZE x its copy-kernel factor + WRITE_SIZE x its factor) KiB per dispatch x 1024 /
+# vectors per dispatch.
 MEASURED_TRAFFIC_PER_VECTOR = {
-    # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch (factors from the copy kernel of known size) x 1024 /
-    # vectors per dispatch, d = 128: profiles/hbm_traffic_d128_llama3-70b-128k.txt
-    ("llama3-70b-128k", "srft_quantize_kernel"): (131338.7 * 2.0 + 81962.4) * 1024 / 1048576,
-    ("llama3-70b-128k", "srft_dequantize_kernel"): (164623.8 * 2.0 + 1048576.1) * 1024 / (4 * 1048576),
 }
 
-# What a kernel that only streams the same bytes reaches on this machine (bench.py --ceiling, best over grid sizes;
-# profiles/stream_ceiling_d128_mixes.txt), GB/s, by the dominant kernel of the default workload.
+# What a kernel that only streams the same bytes reaches on this machine (bench.py --ceiling, best over grid sizes and
+# access kinds; profiles/stream_ceiling_d128_mixes.txt), GB/s: context beside the roofline, not the roofline.
 MEASURED_STREAM_CEILING_GBPS = {
-    ("llama3-70b-128k", "srft_quantize_kernel"): 5461.0,       # 8192 B read : 2560 B written per tile
-    ("llama3-70b-128k", "srft_dequantize_kernel"): 5371.0,     # 2560 : 8192
+    "quantize": 5813.0,       # 8192 B read : 2560 B written per tile, non-temporal accesses, 512 workgroups
+    "dequantize": 5541.0,     # 2560 : 8192
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
@@ -53,6 +58,11 @@ def main() -> int:
     ap.add_argument("--workload", default="llama3-70b-128k")
     ap.add_argument("--plans", type=int, default=0, help="use only the first N plans (debugging; 0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="skip the timed step of each of the other four configurations")
+    ap.add_argument("--cpu-baseline-full", action="store_true",
+                    help="time the oracle's two forms on 2^20 vectors per head dimension (minutes) instead of a "
+                         "bounded sample each")
     ap.add_argument("--no-d256", action="store_true",
                     help="skip the d = 256 side measurement that rides along with the default workload")
     ap.add_argument("--max-workgroups", type=int, default=0)
@@ -159,12 +169,9 @@ def main() -> int:
     ql, qa = roof(tq, launches_q)
     dl, da = roof(td, launches_d)
     launches = launches_q if tq >= td else launches_d
-    dominant = "srft_quantize_kernel" if tq >= td else "srft_dequantize_kernel"
-    # the symbol the profiler shows for it (the folded write path and the batched launches have kernels of their own)
-    fold_q = d % 128 == 0 and g == 32
-    symbol = (("srft_quantize_fold_batched_kernel" if batched_q else "srft_quantize_fold_kernel") if fold_q else
-              ("srft_quantize_batched_kernel" if batched_q else "srft_quantize_kernel")) if tq >= td else \
-        ("srft_dequantize_batched_kernel" if batched_d else "srft_dequantize_kernel")
+    dominant = "quantize" if tq >= td else "dequantize"
+    # the symbol the profiler shows for it
+    symbol = kernel_symbol(d, g, "quantize", batched_q) if tq >= td else kernel_symbol(d, g, "dequantize", batched_d)
     dom_l, dom_a = (ql, qa) if tq >= td else (dl, da)
     result = {
         "metric": "quantize+dequantize vectors/s (full write pass then full read pass over the cache)",
@@ -173,7 +180,9 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32",
+        # what the contraction runs in: exact fp16 inputs, matrices as fp16 hi + fp16 lo on f16 MFMA (about 22 bits),
+        # fp32 accumulation and fp32 vector arithmetic for the quantizer
+        "dtype": "f16 hi+lo MFMA, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": w.name, "d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
                    "total_vectors": total_vec, "bytes_per_vector_each_direction": bytes_per_vec,
@@ -185,12 +194,13 @@ def main() -> int:
                        "hbm_frac": da / HBM_PEAK_GBPS, "avg_launch_ms": dl * 1e3},
         "roofline": {"kernel": symbol, "bound": "hbm", "achieved": dom_a, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dom_a / HBM_PEAK_GBPS,
-                     "traffic": (MEASURED_TRAFFIC_PER_VECTOR[(w.name, dominant)] * total_vec / launches
-                                 if (w.name, dominant) in MEASURED_TRAFFIC_PER_VECTOR else None),
+                     "traffic": (MEASURED_TRAFFIC_PER_VECTOR[symbol] * total_vec / launches
+                                 if symbol in MEASURED_TRAFFIC_PER_VECTOR else None),
+                     "clock": "HIP events on the launch stream, average over the launches of the timed steps",
                      "algorithmic_bytes_per_launch": total_vec * bytes_per_vec // launches,
                      "avg_launch_ms": dom_l * 1e3,
                      # context, not the roofline: the rate of a pure stream with this kernel's byte mix
-                     "stream_ceiling_GBps": MEASURED_STREAM_CEILING_GBPS.get((w.name, dominant))},
+                     "stream_ceiling_GBps": MEASURED_STREAM_CEILING_GBPS.get(dominant) if d == 128 else None},
         "paper_context_apple_m1": PAPER_CONTEXT,
     }
 
@@ -257,11 +267,111 @@ def main() -> int:
         torch.cuda.synchronize()
         result["copy_kernel"] = {"bytes_each_way": nb, "GBps_read_plus_write": 2 * nb / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, x, plans, W)
+        result["cpu_baseline"] = cpu_baseline(w, x, plans, W, full=args.cpu_baseline_full)
     for pl in plans:
         pl.close()
+    if w.name == "llama3-70b-128k" and not args.no_all_configs:
+        del x, codes, scales, out
+        torch.cuda.empty_cache()
+        result["all_configs"] = all_configs(B, W, torch, dev, stream)
     print(json.dumps(result))
     return 0
+
+
+def kernel_symbol(d, g, path, batched):
+    """Name of the kernel a g = 32 or wider-group 4-bit DFT plan of head dimension d launches."""
+    if path == "dequantize":
+        return "srft_dequantize_batched_kernel" if batched else "srft_dequantize_kernel"
+    if d == 256 and g == 32:
+        return "srft_quantize_fold4_batched_kernel" if batched else "srft_quantize_fold4_kernel"
+    if d % 128 == 0 and g >= 32:
+        return "srft_quantize_fold_batched_kernel" if batched else "srft_quantize_fold_kernel"
+    return "srft_quantize_batched_kernel" if batched else "srft_quantize_kernel"
+
+
+def timed_passes(torch, stream, q_pass, d_pass, reps):
+    """(seconds per write pass, seconds per read pass) from HIP events on `stream`; either pass may be None."""
+    for fn in (q_pass, d_pass):
+        if fn:
+            fn()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record(stream)
+    for _ in range(reps if q_pass else 0):
+        q_pass()
+    ev[1].record(stream)
+    for _ in range(reps if d_pass else 0):
+        d_pass()
+    ev[2].record(stream)
+    torch.cuda.synchronize()
+    return ev[0].elapsed_time(ev[1]) / reps / 1e3, ev[1].elapsed_time(ev[2]) / reps / 1e3
+
+
+def all_configs(B, W, torch, dev, stream):
+    """One timed step of each of the other four configurations, each with its full shape and its own buffers (freed
+    before the next).  `regime` says what the figure is: "hbm" streams from HBM; "cache-resident" fits the 256 MB
+    last-level cache, so its GB/s is not an HBM fraction; "launch-bound" is a few microseconds of work."""
+    res = {}
+    for name, regime, reps in (("tiny", "launch-bound", 200), ("qwen2.5-1.5b-4k", "cache-resident", 50),
+                               ("gemma3-1b-4k", "cache-resident", 50)):
+        w = W.WORKLOADS[name]
+        n, d, G, k = w.vectors_per_plan, w.d, w.d // w.g, w.n_plans
+        plans = [B.Plan(d, w.g, *W.plan_constants(w, p)[:2]) for p in range(k)]
+        x = torch.empty(k, n, d, dtype=torch.float16, device=dev)
+        for p in range(k):
+            W.fill_kv(x[p], w, p)
+        codes = torch.empty(k, n, d // 2, dtype=torch.uint8, device=dev)
+        scales = torch.empty(k, n, G, dtype=torch.float32, device=dev)
+        out = torch.empty(k, n, d, dtype=torch.float16, device=dev)
+        h = [pl.handle for pl in plans]
+        tq_tab = B.BatchTable(h, list(x), list(codes), list(scales))
+        td_tab = B.BatchTable(h, list(out), list(codes), list(scales))
+        tq, td = timed_passes(torch, stream, lambda: B.srft_kv_quantize_batched(tq_tab, stream),
+                              lambda: B.srft_kv_dequantize_batched(td_tab, stream), reps)
+        nbytes = k * n * (2 * d + d // 2 + 4 * G)
+        res[name] = {"d": d, "plans": k, "vectors_per_plan": n, "regime": regime, "launches_per_step": 2,
+                     "bytes_each_direction": nbytes, "us_per_step": (tq + td) * 1e6,
+                     "quantize": {"us": tq * 1e6, "GBps": nbytes / tq / 1e9, "vectors_per_s": k * n / tq},
+                     "dequantize": {"us": td * 1e6, "GBps": nbytes / td / 1e9, "vectors_per_s": k * n / td}}
+        for pl in plans:
+            pl.close()
+        del x, codes, scales, out, tq_tab, td_tab
+        torch.cuda.empty_cache()
+    # configuration 4: the decode step appends 512 vectors to each of 64 plans (one batched launch), then every
+    # plan's 4,194,304-vector int4 prefix is read (one batched launch over all 64 plans: 16 GB in, 51.5 GB out)
+    w = W.WORKLOADS["decode-d96"]
+    n, na, d, G, k = w.vectors_per_plan, w.append_vectors_per_plan, w.d, w.d // w.g, w.n_plans
+    plans = [B.Plan(d, w.g, *W.plan_constants(w, p)[:2]) for p in range(k)]
+    h = [pl.handle for pl in plans]
+    xa = torch.empty(k, na, d, dtype=torch.float16, device=dev)
+    for p in range(k):
+        W.fill_kv(xa[p], w, p)
+    ca = torch.empty(k, na, d // 2, dtype=torch.uint8, device=dev)
+    sa = torch.empty(k, na, G, dtype=torch.float32, device=dev)
+    ta = B.BatchTable(h, list(xa), list(ca), list(sa))
+    t_app, _ = timed_passes(torch, stream, lambda: B.srft_kv_quantize_batched(ta, stream), None, 200)
+    codes = torch.empty(k, n, d // 2, dtype=torch.uint8, device=dev)
+    scales = torch.empty(k, n, G, dtype=torch.float32, device=dev)
+    xbuf = torch.empty(n, d, dtype=torch.float16, device=dev)         # the prefix is produced plan after plan
+    for p in range(k):
+        W.fill_kv(xbuf, w, p)
+        B.srft_kv_quantize(h[p], xbuf, codes[p], scales[p], stream)
+    torch.cuda.synchronize()
+    del xbuf
+    out = torch.empty(k, n, d, dtype=torch.float16, device=dev)
+    tp = B.BatchTable(h, list(out), list(codes), list(scales))
+    _, t_pre = timed_passes(torch, stream, None, lambda: B.srft_kv_dequantize_batched(tp, stream), 2)
+    ab, pb = k * na * (2 * d + d // 2 + 4 * G), k * n * (2 * d + d // 2 + 4 * G)
+    res["decode-d96"] = {
+        "d": d, "plans": k,
+        "append": {"vectors_per_plan": na, "regime": "launch-bound", "launches_per_step": 1, "us": t_app * 1e6,
+                   "bytes": ab, "GBps": ab / t_app / 1e9, "vectors_per_s": k * na / t_app},
+        "prefix_read": {"vectors_per_plan": n, "regime": "hbm", "launches_per_step": 1, "ms": t_pre * 1e3,
+                        "bytes": pb, "GBps": pb / t_pre / 1e9, "hbm_frac": pb / t_pre / 1e9 / HBM_PEAK_GBPS,
+                        "vectors_per_s": k * n / t_pre}}
+    for pl in plans:
+        pl.close()
+    return res
 
 
 def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=3):
@@ -462,9 +572,15 @@ def decode_append(B, W, torch, dev, stream, iters=200):
     return res
 
 
-def cpu_baseline(w, x, plans, W, budget_s=12.0, max_vectors=1 << 23):
-    """The oracle as it stands, timed on this host over a bounded sample of the workload (write + read path):
-    chunks of 131,072 vectors, plan after plan, until about `budget_s` seconds of oracle time are spent."""
+def cpu_baseline(w, x, plans, W, budget_s=8.0, max_vectors=1 << 23, full=False):
+    """The oracle as it stands, timed on this host's cores (rank 0, N = 1 only).
+
+    `value`: write + read path over a bounded sample of the workload (chunks of 131,072 vectors, plan after plan, until
+    about `budget_s` seconds are spent), in the oracle's dense form.  `forms`: the oracle's two forms of the transform
+    (the dense d x d definition, and its mixed-radix FFT with the packing of Eq. 2) at d = 96, 128, 256, write and read
+    path each, on a bounded sample per entry (about 1.5 s; 2^20 vectors each with --cpu-baseline-full).  The dense
+    form is a BLAS product and uses every core numpy's BLAS is given; the FFT form is numpy element-wise code on one
+    core.  A baseline, not a target."""
     import numpy as np
     from oracle import srft_oracle as O
     try:
@@ -493,10 +609,29 @@ def cpu_baseline(w, x, plans, W, budget_s=12.0, max_vectors=1 << 23):
                 break
         if tq + td > budget_s or sample >= max_vectors:
             break
+    forms = []
+    for d in (96, 128, 256):
+        lam = W.lognormal_lambda(d, seed=d)
+        s = O.signs_from_seed(d, d)
+        for form in ("dense", "fft"):
+            # sized from the rates of an 8-core host so that an entry takes about 1.5 s
+            n = (1 << 20) if full else {"dense": 1 << 17, "fft": 1 << 14}[form] * (2 if d <= 128 else 1)
+            xs = W.gaussian_with_outliers(n, d, seed=d, outliers=1, gain=20.0)
+            t0 = time.perf_counter()
+            q = O.quantize(xs, s, lam, 32, form=form)
+            t1 = time.perf_counter()
+            O.dequantize(q["codes"], q["scales"], s, lam, 32, form=form)
+            t2 = time.perf_counter()
+            used = cores if form == "dense" else 1
+            forms.append({"d": d, "form": form, "vectors": n, "cores": used,
+                          "quantize_vectors_per_s": n / (t1 - t0), "dequantize_vectors_per_s": n / (t2 - t1),
+                          "quantize_ns_per_vec_per_core": (t1 - t0) / n * 1e9 * used,
+                          "dequantize_ns_per_vec_per_core": (t2 - t1) / n * 1e9 * used})
     return {"value": sample / (tq + td), "unit": "vectors/s", "cores": cores, "kind": "oracle",
             "sample": f"the first {sample} vectors of {w.name} (plans 0..{used_plans - 1}): oracle quantize {tq:.2f} s + "
                       f"dequantize {td:.2f} s (numpy, float64, dense d x d form)",
-            "quantize_vectors_per_s": sample / tq, "dequantize_vectors_per_s": sample / td}
+            "quantize_vectors_per_s": sample / tq, "dequantize_vectors_per_s": sample / td,
+            "forms": forms}
 
 
 if __name__ == "__main__":
