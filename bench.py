@@ -76,6 +76,9 @@ def main() -> int:
     ap.add_argument("--scores", action="store_true",
                     help="also time srft_kv_scores (8 queries against plan 0's stored keys, read from the int4 record) "
                          "beside dequantizing those keys")
+    ap.add_argument("--butterfly", action="store_true",
+                    help="also time the write path in its butterfly form (fp32 FFT on the vector ALU, "
+                         "srft_kv_quantize_butterfly; d = 128 only) over the same plans, a launch per plan")
     ap.add_argument("--power", action="store_true",
                     help="also run each path, and the streaming kernel with its byte mix, for about 3 s each while "
                          "sampling socket power and shader clock with amd-smi")
@@ -207,6 +210,19 @@ def main() -> int:
     if w.name == "llama3-70b-128k" and not args.no_d256:
         # the metric names d = 256 beside d = 128: the same launch shape (1,048,576 vectors per plan) at d = 256
         result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream)
+    if args.butterfly and d == 128 and g == 32:
+        def b_pass():
+            for p in range(n_plans):
+                B.srft_kv_quantize_butterfly(h[p], x[p], codes[p], scales[p], stream)
+        tb, _ = timed_passes(torch, stream, b_pass, None, args.steps)
+        result["quantize_butterfly_form"] = {
+            "what": "same plans, same record, the transform as fp32 FFT butterflies on the vector ALU (one vector per "
+                    "lane) instead of the matrix-core contraction; a launch per plan",
+            "GBps": total_vec * bytes_per_vec / tb / 1e9, "hbm_frac": total_vec * bytes_per_vec / tb / 1e9 / HBM_PEAK_GBPS,
+            "vectors_per_s": total_vec / tb, "avg_launch_ms": tb / n_plans * 1e3,
+            "matrix_core_form_GBps": qa, "ratio_matrix_core_over_butterfly": qa / (total_vec * bytes_per_vec / tb / 1e9)}
+        B.srft_kv_quantize_batched(table_q, stream) if batched_q else [
+            B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream) for p in range(n_plans)]   # restore the record
     if args.ceiling:
         result["hbm_ceiling"] = mix_ceiling(M, torch, x, out, n_plans * n, d, G, stream)
     if args.power:

@@ -134,6 +134,17 @@ int srft_kv_dequantize_batched(const srft_plan_t* const* plans, const uint8_t* c
                                void* const* out_f16_dev, int count, void* hip_stream);
 
 /*
+ * The write path with the transform done as FFT butterflies on the vector ALU, in fp32: a complex FFT of half the
+ * length and a Hermitian unpack (Sec. 3.2; the form of the kernel of Sec. 7.1) in place of the matrix-core contraction
+ * that srft_kv_quantize uses.  Same arguments and the same record, except that scales_dev must be 16-byte aligned; for
+ * plans with d = 128, g = 32, 4-bit codes and the DFT (else SRFT_ERR_BAD_D / _BAD_GROUP / _BAD_BITS / _BAD_TRANSFORM).
+ * It exists so that the two forms can be timed side by side (bench.py --butterfly); it is the slower one on this
+ * machine, and codes may differ from srft_kv_quantize's where a value sits at a rounding boundary.
+ */
+int srft_kv_quantize_butterfly(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec,
+                               uint8_t* codes_dev, float* scales_dev, void* hip_stream);
+
+/*
  * The transform alone, quantization disabled: w = lambda * pack(F (s * x)) in fp32.  (Eq. 1-2, Sec. 5.1)
  *   x_f16_dev [n_vec, d] fp16, 16-byte aligned; w_f32_dev [n_vec, d] fp32, 16-byte aligned, written.
  * Same kernel as the write path up to the abs-max; exists so that the transform can be checked

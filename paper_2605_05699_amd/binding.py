@@ -27,7 +27,7 @@ EXPORTS = [
     "srft_cache_create", "srft_cache_destroy", "srft_cache_append", "srft_cache_rebuild_view",
     "srft_cache_tokens", "srft_cache_quantized_tokens",
     "srft_plan_create_bits", "srft_plan_bits", "srft_plan_create_ex",
-    "srft_scores_workspace_bytes", "srft_kv_scores", "srft_kv_scores_static",
+    "srft_scores_workspace_bytes", "srft_kv_scores", "srft_kv_scores_static", "srft_kv_quantize_butterfly",
 ]
 
 
@@ -58,6 +58,7 @@ def lib() -> C.CDLL:
     L.srft_plan_destroy.argtypes = [vp]
     L.srft_kv_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
     L.srft_kv_dequantize.argtypes = [vp, vp, vp, i64, vp, vp]
+    L.srft_kv_quantize_butterfly.argtypes = [vp, vp, i64, vp, vp, vp]
     L.srft_kv_forward_f32.argtypes = [vp, vp, i64, vp, vp]
     L.srft_cache_create.argtypes = [C.POINTER(vp), vp, ci, ci, i64, ci, vp, vp, vp]
     L.srft_cache_destroy.argtypes = [vp]
@@ -143,6 +144,13 @@ def srft_kv_quantize(plan: int, x: torch.Tensor, codes: torch.Tensor, scales: to
                                   _dev_ptr(codes, torch.uint8, "codes"),
                                   _dev_ptr(scales, torch.float32, "scales"), _stream_handle(stream)),
            "srft_kv_quantize")
+
+
+def srft_kv_quantize_butterfly(plan: int, x: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, stream=None) -> None:
+    """The write path with the transform as vector-ALU FFT butterflies (d = 128, g = 32, 4-bit): the comparison form."""
+    _check(lib().srft_kv_quantize_butterfly(plan, _dev_ptr(x, torch.float16, "x"), x.shape[0],
+                                            _dev_ptr(codes, torch.uint8, "codes"), _dev_ptr(scales, torch.float32, "scales"),
+                                            _stream_handle(stream)), "srft_kv_quantize_butterfly")
 
 
 def srft_kv_dequantize(plan: int, codes: torch.Tensor, scales: torch.Tensor, out: torch.Tensor, stream=None) -> None:

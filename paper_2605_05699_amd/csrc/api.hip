@@ -161,6 +161,21 @@ int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_v
     return launch_quantize(plan, x_f16_dev, n_vec, codes_dev, scales_dev, nullptr, kOutCodes, (hipStream_t)hip_stream);
 }
 
+int srft_kv_quantize_butterfly(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, uint8_t* codes_dev,
+                               float* scales_dev, void* hip_stream) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (plan->d != 128) return SRFT_ERR_BAD_D;
+    if (plan->gm != kGroup32) return SRFT_ERR_BAD_GROUP;
+    if (plan->bits != 4) return SRFT_ERR_BAD_BITS;
+    if (plan->transform != SRFT_TRANSFORM_DFT) return SRFT_ERR_BAD_TRANSFORM;
+    if (n_vec < 0 || n_vec > kMaxVectors) return SRFT_ERR_BAD_N;
+    if (n_vec == 0) return SRFT_OK;
+    if (!x_f16_dev || !codes_dev || !scales_dev || !plan->bfly) return SRFT_ERR_NULL;
+    if (!srft_aligned(x_f16_dev, 16) || !srft_aligned(codes_dev, 16) || !srft_aligned(scales_dev, 16)) return SRFT_ERR_ALIGN;
+    return srft_launch_quantize_butterfly(plan->bfly, x_f16_dev, n_vec, codes_dev, scales_dev, plan->max_wgs,
+                                          (hipStream_t)hip_stream);
+}
+
 int srft_kv_forward_f32(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, float* w_f32_dev,
                         void* hip_stream) {
     if (!plan) return SRFT_ERR_NULL;

@@ -107,6 +107,7 @@ struct srft_plan {
     uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
     uint4* wfold = nullptr;     // write-path fragments of the folded form (device), when fold_q
     uint4* wfold4 = nullptr;    // write-path table of the twice-folded form (device), when fold4_q
+    float* bfly = nullptr;      // table of the butterfly form of the write path (device), d = 128 / g = 32 / 4-bit only
     float* inv_lam2 = nullptr;  // 1 / (lambda * max(lambda, 1e-6)) per channel (device): scores in the rotated domain
     int grid_scores = 0;        // persistent grid of the scores kernel (32 rows of queries)
     int grid_scores16 = 0;      // the same with 16 rows
@@ -150,6 +151,9 @@ dequantize_kernel_t srft_pick_dequantize_b4(int d, int slabs, int gm, bool fold)
 dequantize_kernel_t srft_pick_dequantize_b8(int d, int slabs, int gm, bool fold);
 batched_kernel_t srft_pick_dequantize_batched_b4(int d, int slabs, int gm, bool fold);
 batched_kernel_t srft_pick_dequantize_batched_b8(int d, int slabs, int gm, bool fold);
+// write path with the transform as FFT butterflies on the vector ALU (d = 128, g = 32, 4-bit; the comparison form)
+int srft_launch_quantize_butterfly(const float* table_dev, const void* x, long long n_vec, uint8_t* codes, float* scales,
+                                   int max_workgroups, hipStream_t st);
 // scores in the rotated domain: launch of the scan (kernels/scores.hip) and its resident workgroups per unit
 int srft_launch_scores(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
                        const float* scales, long long n_keys, float* out, hipStream_t st);

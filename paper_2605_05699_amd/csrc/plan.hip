@@ -390,6 +390,23 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     p->fold4_q = (d == 256) && p->gm == kGroup32 && transform == SRFT_TRANSFORM_DFT;
     std::vector<uint32_t> wfold4;
     if (p->fold4_q) build_fold4_table(p->signs, lam, wfold4);
+    // Butterfly form of the write path (comparison kernel): per packed index lambda times the packing constant of
+    // Eq. 2 -- 1/sqrt d for DC and Nyquist, sqrt(2/d) elsewhere, halved where the unpack leaves a factor 2 (every
+    // bin except 0, 32 and 64) -- then the sign diagonal as sign-bit masks of the packed fp16 pairs.
+    std::vector<float> bfly;
+    if (d == 128 && p->gm == kGroup32 && bits == 4 && transform == SRFT_TRANSFORM_DFT) {
+        bfly.resize(128 + 64);
+        for (int k = 0; k < 128; ++k) {
+            const int bin = k < 64 ? k : k - 64;
+            double c = (k == 0 || k == 64) ? 1.0 / std::sqrt(128.0) : std::sqrt(2.0 / 128.0);
+            if (bin != 0 && bin != 32) c *= 0.5;
+            bfly[k] = (float)(lam[k] * c);
+        }
+        for (int j = 0; j < 64; ++j) {
+            const uint32_t m = (p->signs[2 * j] < 0 ? 0x8000u : 0u) | (p->signs[2 * j + 1] < 0 ? 0x80000000u : 0u);
+            std::memcpy(&bfly[128 + j], &m, 4);
+        }
+    }
     hipError_t e = hipGetDevice(&p->device);
     int cus = 0;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
@@ -403,6 +420,8 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     if (e == hipSuccess) e = hipMemcpy(p->inv_lam2, il2.data(), d * sizeof(float), hipMemcpyHostToDevice);
     if (e == hipSuccess && p->fold_q) e = hipMalloc((void**)&p->wfold, wfold.size() * 2);
     if (e == hipSuccess && p->fold_q) e = hipMemcpy(p->wfold, wfold.data(), wfold.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess && !bfly.empty()) e = hipMalloc((void**)&p->bfly, bfly.size() * 4);
+    if (e == hipSuccess && !bfly.empty()) e = hipMemcpy(p->bfly, bfly.data(), bfly.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess && p->fold4_q) e = hipMalloc((void**)&p->wfold4, wfold4.size() * 4);
     if (e == hipSuccess && p->fold4_q) e = hipMemcpy(p->wfold4, wfold4.data(), wfold4.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess && p->fold_dq) e = hipMalloc((void**)&p->rfold, rfold.size() * 2);
@@ -425,6 +444,10 @@ int srft_plan_destroy(srft_plan_t* plan) {
     if (plan->wfold) {
         const hipError_t e4 = hipFree(plan->wfold);
         if (e3 == hipSuccess) e3 = e4;
+    }
+    if (plan->bfly) {
+        const hipError_t e7 = hipFree(plan->bfly);
+        if (e3 == hipSuccess) e3 = e7;
     }
     if (plan->wfold4) {
         const hipError_t e6 = hipFree(plan->wfold4);
