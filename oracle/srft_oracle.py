@@ -39,6 +39,12 @@ What each function follows:
                               step streams the stored prefix ... before attention
                               can read it"): inner products of queries with the
                               reconstructed keys, written as exactly that.
+* ``attention_output`` /
+  ``softmax_rows`` /
+  ``decode_attention``     -- the rest of that consumer (Sec. 1; Sec. 7.2, where
+                              attention reads the dequantized prefix): weights times
+                              the reconstructed values, the row softmax between the
+                              two, and their composition, each as its plain definition.
 * ``channel_absmax`` /
   ``lambda_from_absmax``   -- Sec. 7.1: lambda_d = 1 / per_channel_max(SRFT
                               output)_d, the maximum taken over a calibration
@@ -357,3 +363,28 @@ def attention_scores(q_f16, codes, scales, s, lam, g: int, form: str = "dense", 
     keys = dequantize_f64(codes, scales, s, lam, g, form=form, bits=bits)
     return q @ keys.T
 
+
+
+def attention_output(weights, codes, scales, s, lam, g: int, form: str = "dense", bits: int = 4) -> np.ndarray:
+    """out[i] = sum_t weights[i, t] * v_t, v_t the read path's reconstruction of value t before its fp16 rounding;
+    float64 [n_q, d].  The plain definition: reconstruct every value, take the weighted sums.  (A kernel may sum in
+    the rotated domain and apply one inverse transform per query instead: the transform is linear.)
+    """
+    w = np.asarray(weights, dtype=np.float64)
+    values = dequantize_f64(codes, scales, s, lam, g, form=form, bits=bits)
+    return w @ values
+
+
+def softmax_rows(scores, scale: float = 1.0) -> np.ndarray:
+    """Row-wise softmax of scale * scores in float64: exp(x - max x) / sum exp(x - max x)."""
+    x = np.asarray(scores, dtype=np.float64) * float(scale)
+    e = np.exp(x - x.max(axis=1, keepdims=True))
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def decode_attention(q_f16, k_codes, k_scales, s_k, lam_k, v_codes, v_scales, s_v, lam_v, g: int, scale: float,
+                     form: str = "dense", bits: int = 4) -> np.ndarray:
+    """One decode step of attention over a stored cache: softmax(scale * q K^T) V with K and V the reconstructions
+    of the two records (each with its own signs and lambda); float64 [n_q, d]."""
+    scores = attention_scores(q_f16, k_codes, k_scales, s_k, lam_k, g, form=form, bits=bits)
+    return attention_output(softmax_rows(scores, scale), v_codes, v_scales, s_v, lam_v, g, form=form, bits=bits)

@@ -367,3 +367,71 @@ def test_attention_scores_by_loops_and_in_the_rotated_domain():
     rec8 = O.quantize(keys, s, lam, g, bits=8)
     got8 = O.attention_scores(q, rec8["codes"], rec8["scales"], s, lam, g, bits=8)
     assert np.abs(got8 - exact).max() < np.abs(got - exact).max()
+
+
+# ----------------------------------------------------------------------------- weights times the stored values
+def test_attention_output_by_loops_special_weights_and_in_the_rotated_domain():
+    d, g, n_q, n_v = 32, 16, 3, 19
+    rng = np.random.RandomState(21)
+    vals = rng.standard_normal((n_v, d)).astype(np.float16)
+    w = rng.rand(n_q, n_v)
+    s = O.signs_from_seed(9, d)
+    lam = np.exp(0.4 * rng.standard_normal(d)).astype(np.float32)
+    rec = O.quantize(vals, s, lam, g)
+    got = O.attention_output(w, rec["codes"], rec["scales"], s, lam, g)
+    assert got.shape == (n_q, d)
+    back = O.dequantize_f64(rec["codes"], rec["scales"], s, lam, g)
+    # (a) element by element in plain loops
+    for i in range(n_q):
+        for n in range(d):
+            assert abs(got[i, n] - sum(float(w[i, t]) * back[t, n] for t in range(n_v))) < 1e-12
+    # (b) a one-hot weight row returns that value's reconstruction, a uniform row their mean; the map is linear in w
+    onehot = np.zeros((1, n_v)); onehot[0, 7] = 1.0
+    assert np.array_equal(O.attention_output(onehot, rec["codes"], rec["scales"], s, lam, g)[0], back[7])
+    uni = np.full((1, n_v), 1.0 / n_v)
+    assert np.allclose(O.attention_output(uni, rec["codes"], rec["scales"], s, lam, g)[0], back.mean(axis=0), atol=1e-14)
+    w2 = rng.rand(n_q, n_v)
+    lhs = O.attention_output(2.0 * w - 3.0 * w2, rec["codes"], rec["scales"], s, lam, g)
+    rhs = 2.0 * got - 3.0 * O.attention_output(w2, rec["codes"], rec["scales"], s, lam, g)
+    assert np.allclose(lhs, rhs, atol=1e-12)
+    # (c) summed in the rotated domain, one inverse transform per query (what a kernel may do): the same numbers
+    z = (rec["q"].astype(np.float64).reshape(n_v, d // g, g) * rec["scales"].astype(np.float64)[..., None]).reshape(n_v, d)
+    acc = (w @ z) / np.maximum(lam.astype(np.float64), 1e-6)
+    assert np.allclose(got, O.srft_inverse(acc, s), rtol=1e-12, atol=1e-12)
+    # (d) against the exact weighted sum of the unquantized values: as close as 4 bits allow
+    exact = w @ vals.astype(np.float64)
+    assert np.abs(got - exact).max() < 0.25 * np.abs(vals.astype(np.float64)).max() * w.sum(axis=1).max()
+
+
+def test_softmax_rows_and_decode_attention():
+    rng = np.random.RandomState(5)
+    x = rng.standard_normal((4, 11)) * 3
+    p = O.softmax_rows(x, 0.7)
+    assert np.allclose(p.sum(axis=1), 1.0, atol=1e-15) and (p > 0).all()
+    # by the definition with Python scalars, and invariance to a shift of a row
+    import math
+    for i in range(4):
+        den = sum(math.exp(0.7 * x[i, t]) for t in range(11))
+        for t in range(11):
+            assert abs(p[i, t] - math.exp(0.7 * x[i, t]) / den) < 1e-14
+    assert np.allclose(O.softmax_rows(x + 100.0, 0.7), p, atol=1e-12)
+    assert np.allclose(O.softmax_rows(np.zeros((2, 5))), 0.2)
+    big = np.array([[0.0, 1000.0, -1000.0]])
+    assert np.allclose(O.softmax_rows(big), [[0.0, 1.0, 0.0]])            # no overflow
+    # decode attention is the composition, with separate constants for K and V
+    d, g, n_q, n_t = 32, 32, 2, 13
+    k = rng.standard_normal((n_t, d)).astype(np.float16); v = rng.standard_normal((n_t, d)).astype(np.float16)
+    q = rng.standard_normal((n_q, d)).astype(np.float16)
+    sk, sv = O.signs_from_seed(1, d), O.signs_from_seed(2, d)
+    lk = np.exp(0.3 * rng.standard_normal(d)).astype(np.float32); lv = np.exp(0.3 * rng.standard_normal(d)).astype(np.float32)
+    rk, rv = O.quantize(k, sk, lk, g), O.quantize(v, sv, lv, g)
+    got = O.decode_attention(q, rk["codes"], rk["scales"], sk, lk, rv["codes"], rv["scales"], sv, lv, g, d ** -0.5)
+    kb = O.dequantize_f64(rk["codes"], rk["scales"], sk, lk, g); vb = O.dequantize_f64(rv["codes"], rv["scales"], sv, lv, g)
+    for i in range(n_q):
+        sc = [d ** -0.5 * sum(float(q[i, n]) * kb[t, n] for n in range(d)) for t in range(n_t)]
+        m = max(sc); e = [math.exp(a - m) for a in sc]; z = sum(e)
+        for n in range(d):
+            assert abs(got[i, n] - sum(e[t] / z * vb[t, n] for t in range(n_t))) < 1e-12
+    # a single key: the output is that value's reconstruction whatever the query
+    one = O.decode_attention(q, rk["codes"][:1], rk["scales"][:1], sk, lk, rv["codes"][:1], rv["scales"][:1], sv, lv, g, 1.0)
+    assert np.allclose(one, np.broadcast_to(vb[:1], one.shape), atol=1e-14)
