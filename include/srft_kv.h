@@ -172,6 +172,39 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
                    void* hip_stream);
 
 /*
+ * Weighted sums of stored values, without reconstructing the values: the other half of attention over the stored
+ * cache.    (Sec. 1 and Sec. 7.2: attention reads the prefix the cache holds; Eq. 1-2: the transform is linear.)
+ *     out[i] = sum_t weights[i][t] * v_t,   v_t the read path's reconstruction of value t (before its fp16 rounding)
+ * computed as one inverse transform per query of  sum_t weights[i][t] * code_t * scale_t : only the record is read.
+ *   weights_f32_dev [n_q, n_keys] fp32 row-major, 4-byte aligned, 1 <= n_q <= 32 (e.g. softmax of srft_kv_scores).
+ *   codes_dev       [n_keys, d/2] bytes, 16-byte aligned;  scales_dev [n_keys, d/g] fp32: the plan's record.
+ *   out_f32_dev     [n_q, d] fp32, written.
+ *   workspace_dev   srft_attend_workspace_bytes(plan) bytes of device memory (16 MiB at d = 128), 16-byte aligned,
+ *                   overwritten; calls that may run at the same time need a workspace each.
+ * n_keys >= 1.  For plans with d a multiple of 64, 4-bit codes and g >= 32 (else SRFT_ERR_BAD_D / _BAD_BITS /
+ * _BAD_GROUP).  Enqueues two kernels: partial sums per workgroup (fp32, on the matrix cores), then their sum in a
+ * fixed order and the inverse transform.  The result does not depend on timing.
+ */
+int64_t srft_attend_workspace_bytes(const srft_plan_t* plan);
+int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_q, const uint8_t* codes_dev,
+                   const float* scales_dev, int64_t n_keys, float* out_f32_dev, void* workspace_dev,
+                   void* hip_stream);
+
+/*
+ * One decode step of attention over a stored cache: out = softmax(softmax_scale * q K^T) V with K and V read from
+ * their records (plan_k, plan_v: same d, own signs and lambda each).    (Sec. 1; Sec. 7.2)
+ * srft_kv_scores, a row softmax in place, srft_kv_attend, on one stream.  q_f16_dev [n_q, d] fp16 (16-byte aligned),
+ * out_f32_dev [n_q, d] fp32; workspace_dev: srft_decode_attention_workspace_bytes(plan_k, plan_v, n_q, n_keys) bytes,
+ * 256-byte aligned (it holds the n_q x n_keys scores).  Shapes and limits as for the two calls it is made of.
+ */
+int64_t srft_decode_attention_workspace_bytes(const srft_plan_t* plan_k, const srft_plan_t* plan_v, int n_q,
+                                              int64_t n_keys);
+int srft_kv_decode_attention(const srft_plan_t* plan_k, const srft_plan_t* plan_v, const void* q_f16_dev, int n_q,
+                             const uint8_t* k_codes_dev, const float* k_scales_dev, const uint8_t* v_codes_dev,
+                             const float* v_scales_dev, int64_t n_keys, float softmax_scale, float* out_f32_dev,
+                             void* workspace_dev, void* hip_stream);
+
+/*
  * srft_kv_scores for callers that cannot allocate device memory or pass a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and results as
  * srft_kv_scores without workspace_dev: the workspace is a static device array inside the library (1 MiB + 32 KiB

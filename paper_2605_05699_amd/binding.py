@@ -28,6 +28,7 @@ EXPORTS = [
     "srft_cache_tokens", "srft_cache_quantized_tokens",
     "srft_plan_create_bits", "srft_plan_bits", "srft_plan_create_ex",
     "srft_scores_workspace_bytes", "srft_kv_scores", "srft_kv_scores_static", "srft_kv_quantize_butterfly",
+    "srft_attend_workspace_bytes", "srft_kv_attend", "srft_decode_attention_workspace_bytes", "srft_kv_decode_attention",
 ]
 
 
@@ -68,6 +69,10 @@ def lib() -> C.CDLL:
     L.srft_cache_quantized_tokens.argtypes = [vp]
     L.srft_scores_workspace_bytes.argtypes = [vp]
     L.srft_kv_scores.argtypes = [vp, vp, ci, vp, vp, i64, vp, vp, vp]
+    L.srft_attend_workspace_bytes.argtypes = [vp]
+    L.srft_kv_attend.argtypes = [vp, vp, ci, vp, vp, i64, vp, vp, vp]
+    L.srft_decode_attention_workspace_bytes.argtypes = [vp, vp, ci, i64]
+    L.srft_kv_decode_attention.argtypes = [vp, vp, vp, ci, vp, vp, vp, vp, i64, C.c_float, vp, vp, vp]
     L.srft_kv_scores_static.argtypes = [vp, vp, ci, vp, vp, i64, vp, vp]
     L.srft_kv_channel_absmax.argtypes = [vp, vp, i64, vp, vp]
     L.srft_lambda_from_absmax.argtypes = [vp, ci, vp]
@@ -84,6 +89,8 @@ def lib() -> C.CDLL:
         if name != "srft_status_string":
             getattr(L, name).restype = ci
     L.srft_scores_workspace_bytes.restype = i64
+    L.srft_attend_workspace_bytes.restype = i64
+    L.srft_decode_attention_workspace_bytes.restype = i64
     L.srft_cache_tokens.restype = i64
     L.srft_cache_quantized_tokens.restype = i64
     _lib = L
@@ -230,6 +237,35 @@ def srft_kv_scores_static(plan: int, q: torch.Tensor, codes: torch.Tensor, scale
                                        _dev_ptr(codes, torch.uint8, "codes"), _dev_ptr(scales, torch.float32, "scales"),
                                        codes.shape[0], _dev_ptr(scores, torch.float32, "scores"),
                                        _stream_handle(stream)), "srft_kv_scores_static")
+
+
+def srft_kv_attend(plan: int, weights: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, out: torch.Tensor,
+                   workspace: torch.Tensor, stream=None) -> None:
+    """out [n_q, d] fp32 <- weights [n_q, n_keys] fp32 times the values stored as (codes, scales)."""
+    if workspace.numel() * workspace.element_size() < lib().srft_attend_workspace_bytes(plan):
+        raise ValueError("workspace too small")
+    if weights.shape[1] != codes.shape[0] or out.shape[0] != weights.shape[0]:
+        raise ValueError("weights must be [n_q, n_keys], out [n_q, d]")
+    _check(lib().srft_kv_attend(plan, _dev_ptr(weights, torch.float32, "weights"), weights.shape[0],
+                                _dev_ptr(codes, torch.uint8, "codes"), _dev_ptr(scales, torch.float32, "scales"),
+                                codes.shape[0], _dev_ptr(out, torch.float32, "out"), workspace.data_ptr(),
+                                _stream_handle(stream)), "srft_kv_attend")
+
+
+def srft_kv_decode_attention(plan_k: int, plan_v: int, q: torch.Tensor, k_codes: torch.Tensor, k_scales: torch.Tensor,
+                             v_codes: torch.Tensor, v_scales: torch.Tensor, softmax_scale: float, out: torch.Tensor,
+                             workspace: torch.Tensor, stream=None) -> None:
+    """out [n_q, d] fp32 <- softmax(softmax_scale * q K^T) V over the two stored records."""
+    n_q, n_keys = q.shape[0], k_codes.shape[0]
+    if workspace.numel() * workspace.element_size() < lib().srft_decode_attention_workspace_bytes(plan_k, plan_v, n_q, n_keys):
+        raise ValueError("workspace too small")
+    if v_codes.shape[0] != n_keys:
+        raise ValueError("keys and values must be as many")
+    _check(lib().srft_kv_decode_attention(plan_k, plan_v, _dev_ptr(q, torch.float16, "q"), n_q,
+                                          _dev_ptr(k_codes, torch.uint8, "k_codes"), _dev_ptr(k_scales, torch.float32, "k_scales"),
+                                          _dev_ptr(v_codes, torch.uint8, "v_codes"), _dev_ptr(v_scales, torch.float32, "v_scales"),
+                                          n_keys, float(softmax_scale), _dev_ptr(out, torch.float32, "out"),
+                                          workspace.data_ptr(), _stream_handle(stream)), "srft_kv_decode_attention")
 
 
 def srft_kv_channel_absmax(plan: int, x: torch.Tensor, amax: torch.Tensor, stream=None) -> None:

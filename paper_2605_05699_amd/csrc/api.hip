@@ -237,6 +237,65 @@ int srft_kv_scores_static(const srft_plan_t* plan, const void* q_f16_dev, int n_
     return srft_kv_scores(plan, q_f16_dev, n_q, codes_dev, scales_dev, n_keys, scores_dev, ws, hip_stream);
 }
 
+static int attend_supported(const srft_plan_t* plan) {
+    if (plan->d % 64 != 0) return SRFT_ERR_BAD_D;
+    if (plan->bits != 4) return SRFT_ERR_BAD_BITS;
+    if (plan->gm == kGroup16) return SRFT_ERR_BAD_GROUP;
+    return SRFT_OK;
+}
+
+int64_t srft_attend_workspace_bytes(const srft_plan_t* plan) {
+    if (!plan) return SRFT_ERR_NULL;
+    return (int64_t)kMaxAttendStripes * 32 * plan->d * 4;        // the partial sums of every workgroup
+}
+
+int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_q, const uint8_t* codes_dev,
+                   const float* scales_dev, int64_t n_keys, float* out_f32_dev, void* workspace_dev, void* hip_stream) {
+    if (!plan) return SRFT_ERR_NULL;
+    const int rc = attend_supported(plan);
+    if (rc != SRFT_OK) return rc;
+    if (n_q < 1 || n_q > 32 || n_keys < 1 || n_keys > kMaxVectors) return SRFT_ERR_BAD_N;
+    if (!weights_f32_dev || !codes_dev || !scales_dev || !out_f32_dev || !workspace_dev) return SRFT_ERR_NULL;
+    if (!srft_aligned(weights_f32_dev, 4) || !srft_aligned(codes_dev, 16) || !srft_aligned(scales_dev, 4) ||
+        !srft_aligned(out_f32_dev, 4) || !srft_aligned(workspace_dev, 16))
+        return SRFT_ERR_ALIGN;
+    return srft_launch_attend(plan, weights_f32_dev, n_q, codes_dev, scales_dev, n_keys, out_f32_dev,
+                              (float*)workspace_dev, (hipStream_t)hip_stream);
+}
+
+int64_t srft_decode_attention_workspace_bytes(const srft_plan_t* plan_k, const srft_plan_t* plan_v, int n_q,
+                                              int64_t n_keys) {
+    if (!plan_k || !plan_v) return SRFT_ERR_NULL;
+    if (n_q < 1 || n_q > 32 || n_keys < 1 || n_keys > kMaxVectors) return SRFT_ERR_BAD_N;
+    const int64_t scores = ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256;
+    return scores + std::max(srft_scores_workspace_bytes(plan_k), srft_attend_workspace_bytes(plan_v));
+}
+
+int srft_kv_decode_attention(const srft_plan_t* plan_k, const srft_plan_t* plan_v, const void* q_f16_dev, int n_q,
+                             const uint8_t* k_codes_dev, const float* k_scales_dev, const uint8_t* v_codes_dev,
+                             const float* v_scales_dev, int64_t n_keys, float softmax_scale, float* out_f32_dev,
+                             void* workspace_dev, void* hip_stream) {
+    if (!plan_k || !plan_v) return SRFT_ERR_NULL;
+    int rc = attend_supported(plan_v);
+    if (rc != SRFT_OK) return rc;
+    if (plan_k->d != plan_v->d || plan_k->device != plan_v->device) return SRFT_ERR_MISMATCH;
+    if (n_q < 1 || n_q > 32 || n_keys < 1 || n_keys > kMaxVectors || !std::isfinite(softmax_scale)) return SRFT_ERR_BAD_N;
+    if (!out_f32_dev || !workspace_dev || !v_codes_dev || !v_scales_dev) return SRFT_ERR_NULL;
+    if (!srft_aligned(workspace_dev, 256) || !srft_aligned(out_f32_dev, 4) || !srft_aligned(v_codes_dev, 16) ||
+        !srft_aligned(v_scales_dev, 4))
+        return SRFT_ERR_ALIGN;
+    float* scores = (float*)workspace_dev;
+    void* rest = (char*)workspace_dev + ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // scores of the queries against the stored keys, their row softmax in place, weights times the stored values;
+    // the same workspace serves the first and the third step, which run one after the other on the stream
+    rc = srft_kv_scores(plan_k, q_f16_dev, n_q, k_codes_dev, k_scales_dev, n_keys, scores, rest, hip_stream);
+    if (rc != SRFT_OK) return rc;
+    rc = srft_launch_softmax_rows(scores, n_q, n_keys, softmax_scale, st);
+    if (rc != SRFT_OK) return rc;
+    return srft_launch_attend(plan_v, scores, n_q, v_codes_dev, v_scales_dev, n_keys, out_f32_dev, (float*)rest, st);
+}
+
 int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host) {
     if (!amax_host || !lambda_host) return SRFT_ERR_NULL;
     if (d < 1) return SRFT_ERR_BAD_D;

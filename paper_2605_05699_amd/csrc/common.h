@@ -66,6 +66,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kTileVecs = 32;          // vectors per tile = N of the 32x32x16 MFMA
 constexpr int kMaxScoreWorkgroups = 4096;   // scores kernel: largest grid (each workgroup owns 256 bytes of workspace)
 constexpr int kMaxD = 256;
+constexpr int kMaxAttendStripes = 512;      // value-side kernel: most workgroups per channel slab (each owns 32 x d floats of workspace)
 constexpr float kMinScale = 7.888609052210118e-31f;   // 2^-100: below this a group is stored as zero
 // The kernels index tiles of 32 vectors with 32-bit integers and look a few grid strides ahead.
 constexpr int64_t kMaxVectors = (int64_t)1 << 33;
@@ -107,6 +108,9 @@ struct srft_plan {
     uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
     uint4* wfold = nullptr;     // write-path fragments of the folded form (device), when fold_q
     uint4* wfold4 = nullptr;    // write-path table of the twice-folded form (device), when fold4_q
+    float* rmat_f32 = nullptr;  // R^T in fp32, [k][n] = s_n Q[k][n] / max(lambda_k, 1e-6) (device): the one inverse transform per
+                                // query of srft_kv_attend
+    int compute_units = 0;
     float* bfly = nullptr;      // table of the butterfly form of the write path (device), d = 128 / g = 32 / 4-bit only
     float* inv_lam2 = nullptr;  // 1 / (lambda * max(lambda, 1e-6)) per channel (device): scores in the rotated domain
     int grid_scores = 0;        // persistent grid of the scores kernel (32 rows of queries)
@@ -158,6 +162,14 @@ int srft_launch_quantize_butterfly(const float* table_dev, const void* x, long l
 int srft_launch_scores(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
                        const float* scales, long long n_keys, float* out, hipStream_t st);
 int srft_scores_occupancy(int d, bool r16, int* blocks_per_cu);
+
+// weighted sums of the stored values in the rotated domain (kernels/attend.hip): workgroups per channel slab for
+// n_keys values, and the two launches (partial sums per workgroup into `part`, then reduction + inverse transform)
+int srft_attend_stripes(const srft_plan* p, long long n_keys);
+int srft_launch_attend(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, const float* scales,
+                       long long n_keys, float* out, float* part, hipStream_t st);
+// row softmax of scale * x, in place, rows of n floats (kernels/softmax.hip)
+int srft_launch_softmax_rows(float* x, int rows, long long n, float scale, hipStream_t st);
 
 // ---- host side (plan.hip, api.hip) ----
 int srft_hip_fail(hipError_t e);         // records the error for srft_last_hip_error, returns SRFT_ERR_HIP

@@ -414,6 +414,12 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     if (e == hipSuccess) e = hipMalloc((void**)&p->rfrag, rf.size() * 2);
     if (e == hipSuccess) e = hipMemcpy(p->wfrag, wf.data(), wf.size() * 2, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(p->rfrag, rf.data(), rf.size() * 2, hipMemcpyHostToDevice);
+    std::vector<float> rmat((size_t)d * d);
+    for (int n = 0; n < d; ++n)
+        for (int k = 0; k < d; ++k) rmat[(size_t)k * d + n] = (float)R[(size_t)n * d + k];
+    if (e == hipSuccess) e = hipMalloc((void**)&p->rmat_f32, rmat.size() * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(p->rmat_f32, rmat.data(), rmat.size() * sizeof(float), hipMemcpyHostToDevice);
+    p->compute_units = cus;
     std::vector<float> il2(d);
     for (int k = 0; k < d; ++k) il2[k] = (float)(1.0 / (lam[k] * std::fmax(lam[k], 1e-6)));
     if (e == hipSuccess) e = hipMalloc((void**)&p->inv_lam2, d * sizeof(float));
@@ -444,6 +450,10 @@ int srft_plan_destroy(srft_plan_t* plan) {
     if (plan->wfold) {
         const hipError_t e4 = hipFree(plan->wfold);
         if (e3 == hipSuccess) e3 = e4;
+    }
+    if (plan->rmat_f32) {
+        const hipError_t e8 = hipFree(plan->rmat_f32);
+        if (e3 == hipSuccess) e3 = e8;
     }
     if (plan->bfly) {
         const hipError_t e7 = hipFree(plan->bfly);
