@@ -267,6 +267,27 @@ def main() -> int:
         result["scores"] = {"queries": n_q, "keys": n, "us": ts * 1e6, "keys_per_s": n / ts,
                             "GBps_record_plus_scores": n * (rec_bytes + 4 * n_q) / ts / 1e9,
                             "dequantize_same_keys_us": tdq * 1e6}
+        # the value side: weights (the softmax of those scores) times plan 1's stored values, and the whole decode step
+        if n_plans > 1:
+            B.srft_kv_quantize(h[1], x[1], codes[1], scales[1], stream)
+            wts = torch.softmax(sc_out * d ** -0.5, dim=1)
+            att = torch.empty(n_q, d, dtype=torch.float32, device=dev)
+            wsa = torch.empty(B.lib().srft_attend_workspace_bytes(h[1]), dtype=torch.uint8, device=dev)
+            ta = timed(lambda: B.srft_kv_attend(h[1], wts, codes[1], scales[1], att, wsa, stream))
+            wsd = torch.empty(B.lib().srft_decode_attention_workspace_bytes(h[0], h[1], n_q, n), dtype=torch.uint8,
+                              device=dev)
+            tda = timed(lambda: B.srft_kv_decode_attention(h[0], h[1], q, codes[0], scales[0], codes[1], scales[1],
+                                                           d ** -0.5, att, wsd, stream))
+            result["attend"] = {
+                "queries": n_q, "values": n, "us": ta * 1e6, "values_per_s": n / ta,
+                "bytes_read_per_value": {"record": rec_bytes, "weights": 4 * n_q, "dequantized_prefix_instead": 2 * d},
+                "GBps_record_plus_weights": n * (rec_bytes + 4 * n_q) / ta / 1e9,
+                "hbm_frac": n * (rec_bytes + 4 * n_q) / ta / 1e9 / HBM_PEAK_GBPS}
+            result["decode_attention"] = {
+                "queries": n_q, "keys": n, "us": tda * 1e6,
+                "what": "scores over the K record, row softmax, weights times the V record: both records read once, "
+                        "the n_q x n_keys scores written, read three times and rewritten by the softmax, read once more",
+                "dequantize_K_and_V_instead_us": 2 * tdq * 1e6}
     if args.decode_append:
         result["decode_append"] = decode_append(B, W, torch, dev, stream)
     if args.copy_bytes:

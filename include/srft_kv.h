@@ -179,11 +179,11 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
  *   weights_f32_dev [n_q, n_keys] fp32 row-major, 4-byte aligned, 1 <= n_q <= 32 (e.g. softmax of srft_kv_scores).
  *   codes_dev       [n_keys, d/2] bytes, 16-byte aligned;  scales_dev [n_keys, d/g] fp32: the plan's record.
  *   out_f32_dev     [n_q, d] fp32, written.
- *   workspace_dev   srft_attend_workspace_bytes(plan) bytes of device memory (16 MiB at d = 128), 16-byte aligned,
+ *   workspace_dev   srft_attend_workspace_bytes(plan) bytes of device memory (about 17 MiB at d = 128), 16-byte aligned,
  *                   overwritten; calls that may run at the same time need a workspace each.
  * n_keys >= 1.  For plans with d a multiple of 64, 4-bit codes and g >= 32 (else SRFT_ERR_BAD_D / _BAD_BITS /
- * _BAD_GROUP).  Enqueues two kernels: partial sums per workgroup (fp32, on the matrix cores), then their sum in a
- * fixed order and the inverse transform.  The result does not depend on timing.
+ * _BAD_GROUP).  Enqueues three kernels: partial sums per workgroup (fp32, on the matrix cores), their sum in a fixed
+ * order (two levels), and the inverse transform.  The result does not depend on timing.
  */
 int64_t srft_attend_workspace_bytes(const srft_plan_t* plan);
 int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_q, const uint8_t* codes_dev,

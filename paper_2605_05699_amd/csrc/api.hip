@@ -246,7 +246,7 @@ static int attend_supported(const srft_plan_t* plan) {
 
 int64_t srft_attend_workspace_bytes(const srft_plan_t* plan) {
     if (!plan) return SRFT_ERR_NULL;
-    return (int64_t)kMaxAttendStripes * 32 * plan->d * 4;        // the partial sums of every workgroup
+    return (int64_t)(kMaxAttendStripes + 16) * 32 * plan->d * 4;  // the partial sums of every workgroup, and of their first-level sums
 }
 
 int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_q, const uint8_t* codes_dev,
@@ -268,7 +268,8 @@ int64_t srft_decode_attention_workspace_bytes(const srft_plan_t* plan_k, const s
     if (!plan_k || !plan_v) return SRFT_ERR_NULL;
     if (n_q < 1 || n_q > 32 || n_keys < 1 || n_keys > kMaxVectors) return SRFT_ERR_BAD_N;
     const int64_t scores = ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256;
-    return scores + std::max(srft_scores_workspace_bytes(plan_k), srft_attend_workspace_bytes(plan_v));
+    return scores + srft_softmax_stats_bytes(32) +
+           std::max(srft_scores_workspace_bytes(plan_k), srft_attend_workspace_bytes(plan_v));
 }
 
 int srft_kv_decode_attention(const srft_plan_t* plan_k, const srft_plan_t* plan_v, const void* q_f16_dev, int n_q,
@@ -285,13 +286,14 @@ int srft_kv_decode_attention(const srft_plan_t* plan_k, const srft_plan_t* plan_
         !srft_aligned(v_scales_dev, 4))
         return SRFT_ERR_ALIGN;
     float* scores = (float*)workspace_dev;
-    void* rest = (char*)workspace_dev + ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256;
+    void* stats = (char*)workspace_dev + ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256;
+    void* rest = (char*)stats + srft_softmax_stats_bytes(32);
     hipStream_t st = (hipStream_t)hip_stream;
     // scores of the queries against the stored keys, their row softmax in place, weights times the stored values;
     // the same workspace serves the first and the third step, which run one after the other on the stream
     rc = srft_kv_scores(plan_k, q_f16_dev, n_q, k_codes_dev, k_scales_dev, n_keys, scores, rest, hip_stream);
     if (rc != SRFT_OK) return rc;
-    rc = srft_launch_softmax_rows(scores, n_q, n_keys, softmax_scale, st);
+    rc = srft_launch_softmax_rows(scores, n_q, n_keys, softmax_scale, stats, st);
     if (rc != SRFT_OK) return rc;
     return srft_launch_attend(plan_v, scores, n_q, v_codes_dev, v_scales_dev, n_keys, out_f32_dev, (float*)rest, st);
 }

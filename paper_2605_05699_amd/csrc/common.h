@@ -66,7 +66,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kTileVecs = 32;          // vectors per tile = N of the 32x32x16 MFMA
 constexpr int kMaxScoreWorkgroups = 4096;   // scores kernel: largest grid (each workgroup owns 256 bytes of workspace)
 constexpr int kMaxD = 256;
-constexpr int kMaxAttendStripes = 512;      // value-side kernel: most workgroups per channel slab (each owns 32 x d floats of workspace)
+constexpr int kMaxAttendStripes = 1024;      // value-side kernel: most workgroups per channel slab (each owns 32 x d floats of workspace)
 constexpr float kMinScale = 7.888609052210118e-31f;   // 2^-100: below this a group is stored as zero
 // The kernels index tiles of 32 vectors with 32-bit integers and look a few grid strides ahead.
 constexpr int64_t kMaxVectors = (int64_t)1 << 33;
@@ -169,7 +169,8 @@ int srft_attend_stripes(const srft_plan* p, long long n_keys);
 int srft_launch_attend(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, const float* scales,
                        long long n_keys, float* out, float* part, hipStream_t st);
 // row softmax of scale * x, in place, rows of n floats (kernels/softmax.hip)
-int srft_launch_softmax_rows(float* x, int rows, long long n, float scale, hipStream_t st);
+int64_t srft_softmax_stats_bytes(int rows);      // workspace of the softmax: per-chunk maxima and sums
+int srft_launch_softmax_rows(float* x, int rows, long long n, float scale, void* stats, hipStream_t st);
 
 // ---- host side (plan.hip, api.hip) ----
 int srft_hip_fail(hipError_t e);         // records the error for srft_last_hip_error, returns SRFT_ERR_HIP

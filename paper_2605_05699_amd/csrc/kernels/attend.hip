@@ -24,7 +24,7 @@ constexpr int kAttendTileKeys = 64;
 
 // D: head dimension; GS: groups of 32 channels per wavefront (slab = 32 GS channels); SLABS = D / (32 GS)
 template <int D, int GS>
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(64, 5)         // five one-wavefront workgroups per compute unit (LDS): within 256 VGPRs
 srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2* __restrict__ codes,
                               const float* __restrict__ scales, long long n_keys, int gw, float* __restrict__ part,
                               int stripes) {
@@ -32,8 +32,11 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
     constexpr int UN = 2 * GS;                               // code units (16 channels) per key in the slab
     constexpr int SLOTS = 32 * GS + UN;                      // B tile: one 16-byte slot per channel, one spare per unit
     static_assert(G % GS == 0 && UN * 8 <= 64, "eight key blocks of UN threads each");
-    __shared__ uint4 bt[2][8 * SLOTS];                       // [key block of 8][channel slot]: 8 keys of one channel
-    __shared__ __align__(16) float st[2][GS * kAttendTileKeys];   // scales, [group][key]
+    // one buffer each: a workgroup is one wavefront, whose LDS accesses complete in program order
+    __shared__ uint4 bt[1][8 * SLOTS];                       // [key block of 8][channel slot]: 8 keys of one channel
+    __shared__ __align__(16) float st[1][GS * kAttendTileKeys];   // scales, [group][key]
+    constexpr int WROW = kAttendTileKeys + 4;                // padded row: the 32 query rows are read bank-conflict free
+    __shared__ __align__(16) float wt[1][32 * WROW];         // weights, [query][key] (rows past n_q stay zero)
     const int lane = threadIdx.x, col = lane & 31, half = lane >> 5;
     const int slab = blockIdx.x % SLABS, stripe = blockIdx.x / SLABS;
     const int ns = G / gw;                                   // scales per key
@@ -41,14 +44,17 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
     // transposing threads: key block kb (8 keys), unit u (16 channels of the slab)
     const int kb = lane / UN, u = lane % UN;
     const bool mover = lane < 8 * UN;
-    const int qrow = min(col, n_q - 1);                      // A rows past the last query repeat it, times zero
-    const float qmask = col < n_q ? 1.0f : 0.0f;
 
     floatx16 acc[GS];
 #pragma unroll
     for (int j = 0; j < GS; ++j) acc[j] = floatx16{0};
 
+    // rows of wt that no query fills are read by the A operand: zero them once
+    for (int i = n_q; i < 32; ++i) {
+        wt[0][i * WROW + lane] = 0.0f;
+    }
     struct Prefetch { uint2 c[8]; float s[GS]; };
+    float wreg[32];                                          // weights of the next tile (one key per lane)
     // codes of this thread's 8 keys x 1 unit; the tile's scales (one key per lane); keys past the end alias to
     // the last key -- their weights are taken as zero below
     auto fetch = [&](Prefetch& p, long long tile) __attribute__((always_inline)) {
@@ -61,6 +67,19 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
         const long long t = min(t0 + lane, n_keys - 1);
 #pragma unroll
         for (int j = 0; j < GS; ++j) p.s[j] = scales[t * ns + (slab * GS + j) / gw];
+    };
+    // the weights of key t0 + lane, one query after the other (each load covers 256 contiguous bytes of a row);
+    // keys past the end carry weight zero
+    auto fetch_w = [&](long long tile) __attribute__((always_inline)) {
+        const long long t = tile * kAttendTileKeys + lane;
+        const bool live = t < n_keys;
+        const long long tc = min(t, n_keys - 1);
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            if (i < n_q) {                       // uniform
+                const float v = w[(long long)i * n_keys + tc];
+                wreg[i] = live ? v : 0.0f;
+            }
     };
     auto to_lds = [&](int b, const Prefetch& p) __attribute__((always_inline)) {
         // decode8 gives, per dword of 8 nibbles, the packed pairs (n0, n4), (n1, n5), (n2, n6), (n3, n7)
@@ -92,31 +111,32 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
         }
 #pragma unroll
         for (int j = 0; j < GS; ++j) st[b][j * kAttendTileKeys + lane] = p.s[j];
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            if (i < n_q) wt[b][i * WROW + lane] = wreg[i];
     };
     // the tile in bt[b] / st[b]: acc_j += (w * scale_j) . codes_j over its 64 keys
-    auto contract = [&](int b, long long tile) __attribute__((always_inline)) {
-        const long long t0 = tile * kAttendTileKeys;
-        const float* wrow = w + (long long)qrow * n_keys;
+    auto contract = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
         for (int kap = 0; kap < 4; ++kap) {                  // k-steps of 16 keys; this lane: keys 16 kap + 8 half + e
-            const long long tk = t0 + 16 * kap + 8 * half;
-            float wv[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const long long t = tk + e;
-                wv[e] = t < n_keys ? wrow[t] * qmask : 0.0f;
-            }
+            const float4 w0 = *reinterpret_cast<const float4*>(&wt[b][col * WROW + 16 * kap + 8 * half]);
+            const float4 w1 = *reinterpret_cast<const float4*>(&wt[b][col * WROW + 16 * kap + 8 * half + 4]);
+            const float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
 #pragma unroll
             for (int j = 0; j < GS; ++j) {
                 const float4 s0 = *reinterpret_cast<const float4*>(&st[b][j * kAttendTileKeys + 16 * kap + 8 * half]);
                 const float4 s1 = *reinterpret_cast<const float4*>(&st[b][j * kAttendTileKeys + 16 * kap + 8 * half + 4]);
                 const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+                // a = w * scale as fp16 hi + fp16 lo: hi is a truncated to fp16 (two values per conversion), a - hi is exact
+                // in fp32, lo is that remainder truncated to fp16: about 21 bits of a
                 half8 ahi, alo;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float a = wv[e] * sc[e];
-                    ahi[e] = (_Float16)a;
-                    alo[e] = (_Float16)(a - (float)ahi[e]);
+                for (int e = 0; e < 8; e += 2) {
+                    const float a0 = wv[e] * sc[e], a1 = wv[e + 1] * sc[e + 1];
+                    const auto h2 = __builtin_amdgcn_cvt_pkrtz(a0, a1);
+                    const auto l2 = __builtin_amdgcn_cvt_pkrtz(a0 - (float)h2[0], a1 - (float)h2[1]);
+                    ahi[e] = h2[0]; ahi[e + 1] = h2[1];
+                    alo[e] = l2[0]; alo[e + 1] = l2[1];
                 }
                 const int ch = 32 * j + col;
                 const half8 bf = __builtin_bit_cast(half8, bt[b][(2 * kap + half) * SLOTS + ch + ch / 16]);
@@ -126,19 +146,32 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
         }
     };
 
-    // tiles of this stripe: stripe, stripe + stripes, ...
+    // tiles of this stripe: stripe, stripe + stripes, ...; codes, scales and weights are prefetched two tiles ahead
+    // in two named register sets (two tiles per trip)
+    const long long m = stripe < n_tiles ? (n_tiles - 1 - stripe) / stripes + 1 : 0;
     Prefetch pa, pb;
-    long long tile = stripe;
-    if (tile < n_tiles) {
-        fetch(pa, tile);
-        int b = 0;
-        for (; tile < n_tiles; tile += stripes) {
-            to_lds(b, pa);
-            if (tile + stripes < n_tiles) fetch(pb, tile + stripes);
+    auto tile_of = [&](long long k) { return min(stripe + k * stripes, n_tiles - 1); };   // past the end: re-read the last
+    if (m > 0) {
+        fetch(pa, tile_of(0));
+        fetch_w(tile_of(0));
+        fetch(pb, tile_of(1));
+        long long k = 0;
+        for (; k + 1 < m; k += 2) {
+            to_lds(0, pa);
+            fetch_w(tile_of(k + 1));
+            fetch(pa, tile_of(k + 2));
             __syncthreads();                     // one wavefront: orders the LDS writes before the reads
-            contract(b, tile);
-            pa = pb;
-            b ^= 1;
+            contract(0);
+            to_lds(0, pb);
+            fetch_w(tile_of(k + 2));
+            fetch(pb, tile_of(k + 3));
+            __syncthreads();
+            contract(0);
+        }
+        if (k < m) {
+            to_lds(0, pa);
+            __syncthreads();
+            contract(0);
         }
     }
     // the sums of this workgroup: part[stripe][query][channel]; the accumulator of lane (col, half) holds rows
@@ -153,15 +186,26 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
         }
 }
 
-// out[i][n] = sum_k rmat[k][n] * (sum over stripes of part[stripe][i][k]);  rmat[k][n] = s_n Q[k][n] / max(lambda_k, 1e-6)
+// first level of the fixed-order sum: part2[c][i][n] = sum over the stripes c, c + kAttendFan, ... of part[stripe][i][n]
+constexpr int kAttendFan = 16;
 template <int D>
 __global__ void __launch_bounds__(D)
-srft_attend_finish_kernel(const float* __restrict__ part, int stripes, const float* __restrict__ rmat,
-                          float* __restrict__ out) {
+srft_attend_reduce_kernel(const float* __restrict__ part, int stripes, float* __restrict__ part2) {
+    const int i = blockIdx.x, c = blockIdx.y, n = threadIdx.x;
+    float sum = 0.0f;
+    for (int sidx = c; sidx < stripes; sidx += kAttendFan) sum += part[((long long)sidx * 32 + i) * D + n];
+    part2[((long long)c * 32 + i) * D + n] = sum;
+}
+
+// out[i][n] = sum_k rmat[k][n] * (sum over c of part2[c][i][k]);  rmat[k][n] = s_n Q[k][n] / max(lambda_k, 1e-6)
+template <int D>
+__global__ void __launch_bounds__(D)
+srft_attend_finish_kernel(const float* __restrict__ part2, const float* __restrict__ rmat, float* __restrict__ out) {
     __shared__ float accs[D];
     const int i = blockIdx.x, n = threadIdx.x;
     float sum = 0.0f;
-    for (int sidx = 0; sidx < stripes; ++sidx) sum += part[((long long)sidx * 32 + i) * D + n];
+#pragma unroll
+    for (int c = 0; c < kAttendFan; ++c) sum += part2[((long long)c * 32 + i) * D + n];
     accs[n] = sum;
     __syncthreads();
     float o = 0.0f;
@@ -177,7 +221,11 @@ int launch(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, co
     hipLaunchKernelGGL((srft_attend_accumulate_kernel<D, GS>), dim3((unsigned)(stripes * SLABS)), dim3(64), 0, st, w, n_q,
                        (const uint2*)codes, scales, n_keys, p->gw, part, stripes);
     SRFT_HIP(hipGetLastError());
-    hipLaunchKernelGGL(srft_attend_finish_kernel<D>, dim3((unsigned)n_q), dim3(D), 0, st, (const float*)part, stripes,
+    float* part2 = part + (size_t)kMaxAttendStripes * 32 * D;
+    hipLaunchKernelGGL(srft_attend_reduce_kernel<D>, dim3((unsigned)n_q, kAttendFan), dim3(D), 0, st, (const float*)part,
+                       stripes, part2);
+    SRFT_HIP(hipGetLastError());
+    hipLaunchKernelGGL(srft_attend_finish_kernel<D>, dim3((unsigned)n_q), dim3(D), 0, st, (const float*)part2,
                        (const float*)p->rmat_f32, out);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
@@ -186,9 +234,9 @@ int launch(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, co
 }  // namespace
 
 int srft_attend_stripes(const srft_plan* p, long long n_keys) {
-    // workgroups per launch: two per compute unit and slab, at most one per tile, at most kMaxAttendStripes
+    // workgroups per launch: four per compute unit and slab, at most one per tile, at most kMaxAttendStripes
     const long long n_tiles = (n_keys + kAttendTileKeys - 1) / kAttendTileKeys;
-    long long s = p->max_wgs > 0 ? p->max_wgs : 2LL * p->compute_units;
+    long long s = p->max_wgs > 0 ? p->max_wgs : 4LL * p->compute_units;
     if (s > kMaxAttendStripes) s = kMaxAttendStripes;
     if (s > n_tiles) s = n_tiles;
     return (int)(s < 1 ? 1 : s);
