@@ -326,10 +326,11 @@ def kernel_symbol(d, g, path, batched):
     return "srft_quantize_batched_kernel" if batched else "srft_quantize_kernel"
 
 
-def timed_passes(torch, stream, q_pass, d_pass, reps):
-    """(seconds per write pass, seconds per read pass) from HIP events on `stream`; either pass may be None."""
+def timed_passes(torch, stream, q_pass, d_pass, reps, warm=1):
+    """(seconds per write pass, seconds per read pass) from HIP events on `stream`; either pass may be None.
+    `warm` untimed passes of each come first."""
     for fn in (q_pass, d_pass):
-        if fn:
+        for _ in range(warm if fn else 0):
             fn()
     torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -364,7 +365,7 @@ def all_configs(B, W, torch, dev, stream):
         tq_tab = B.BatchTable(h, list(x), list(codes), list(scales))
         td_tab = B.BatchTable(h, list(out), list(codes), list(scales))
         tq, td = timed_passes(torch, stream, lambda: B.srft_kv_quantize_batched(tq_tab, stream),
-                              lambda: B.srft_kv_dequantize_batched(td_tab, stream), reps)
+                              lambda: B.srft_kv_dequantize_batched(td_tab, stream), reps, warm=reps)
         nbytes = k * n * (2 * d + d // 2 + 4 * G)
         res[name] = {"d": d, "plans": k, "vectors_per_plan": n, "regime": regime, "launches_per_step": 2,
                      "bytes_each_direction": nbytes, "us_per_step": (tq + td) * 1e6,
@@ -411,9 +412,12 @@ def all_configs(B, W, torch, dev, stream):
     return res
 
 
-def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=3):
+def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10):
     """Write pass (a launch per plan) and read pass (one batched launch) over n_plans x n vectors of d = 256, g = 32:
-    N(0,1) times a lognormal(0,1) channel scale and lognormal(0,0.5) lambda per plan, as in the d = 256 config."""
+    N(0,1) times a lognormal(0,1) channel scale and lognormal(0,0.5) lambda per plan, as in the d = 256 config.
+    `warm` untimed passes of each path precede the `reps` timed ones (about 25 ms each way): after the idle gap in
+    which the plans are built the first few milliseconds of work run 20-30 % slower than the steady state that the
+    main step (160 launches, warmed up by a whole step) is timed in."""
     d, g = 256, 32
     G = d // g
     gen = torch.Generator(device=dev)
@@ -437,7 +441,12 @@ def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=3):
     def pass_d():
         B.srft_kv_dequantize_batched(table, stream)
 
-    pass_q(); pass_d()
+    for _ in range(warm):
+        pass_q()
+    for _ in range(warm):
+        pass_d()
+    for _ in range(2):
+        pass_q()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     ev[0].record(stream)
     for _ in range(reps):

@@ -254,43 +254,52 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
             }
             fold(((G - 1) & 1) ? acc1 : acc0, scale_of(b, G - 1), G == 1);
         } else if constexpr (FOLD && SRFT_DQ_HALF_PIPE) {
-            // One accumulator per slab, software-pipelined at half-group granularity: while the two MFMAs of one slab
-            // (64 clocks of the matrix pipe) run, the other slab's previous result is folded in (16 multiply-adds, 64
-            // clocks of the vector ALU).  The order is pinned: left alone, the compiler puts a group's four MFMAs in
-            // front of its 32 multiply-adds, and the second slab's fold then waits for the pipe to drain.
-            // B fragments are read two half-steps ahead, the group scales once per tile.
+            // One accumulator per slab, software-pipelined at half-group granularity.  The MFMA pairs go A_0, B_0, A_1,
+            // B_1, ...; each result is folded in (16 multiply-adds) one half-step after its pair, under the other
+            // slab's pair.  A wavefront issues in order, and a second MFMA cannot issue while the first occupies the
+            // matrix pipe (32 clocks): the order is therefore pinned as  MFMA, 8 multiply-adds, MFMA, 8 multiply-adds,
+            // so that the vector ALU has work exactly while the pipe is taken.  Left alone, the compiler puts the two
+            // MFMAs back to back and the wavefront idles behind the second.
+            // B fragments are read two half-steps ahead, the group scale one step ahead.
             const uint4* rowp = &dec[b][col * ROW + 2 * half];      // units 4j + 2 half (+ 1): even / odd codes of group j
-            float sc = scale_of(b, 0), sc_next = sc;    // the scale of the next group is read one step ahead
+            float sc = scale_of(b, 0), sc_next = sc;
             half8 fa = __builtin_bit_cast(half8, rowp[0]), fb = __builtin_bit_cast(half8, rowp[1]);
-            half8 fa_next = G > 1 ? __builtin_bit_cast(half8, rowp[4]) : fa, fb_next = fb;
+            half8 fa_next = fa, fb_next = fb;
             acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[0][0], fa, floatx16{0}, 0, 0, 0);
             acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[0][0], fa, acc0[0], 0, 0, 0);
-            acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[G][0], fb, floatx16{0}, 0, 0, 0);
-            acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[G][0], fb, acc0[1], 0, 0, 0);
+            auto pin_half_step = [&]() __attribute__((always_inline)) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);      // eight vector-ALU instructions
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+            };
 #pragma unroll
             for (int j = 0; j < G; ++j) {
+                // B_j on the matrix pipe, A_j folded in
+                __builtin_amdgcn_sched_barrier(0);
+                if (j + 1 < G) fa_next = __builtin_bit_cast(half8, rowp[4 * (j + 1)]);
+                acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[G + j][0], fb, floatx16{0}, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 8; ++v) o[0][v] = j == 0 ? acc0[0][v] * sc : fmaf(acc0[0][v], sc, o[0][v]);
+                acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[G + j][0], fb, acc0[1], 0, 0, 0);
+#pragma unroll
+                for (int v = 8; v < 16; ++v) o[0][v] = j == 0 ? acc0[0][v] * sc : fmaf(acc0[0][v], sc, o[0][v]);
+                pin_half_step();
+                // A_{j+1} on the matrix pipe, B_j folded in
                 __builtin_amdgcn_sched_barrier(0);
                 if (j + 1 < G) {
                     fb_next = __builtin_bit_cast(half8, rowp[4 * (j + 1) + 1]);
                     sc_next = scale_of(b, j + 1);
+                    acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[j + 1][0], fa_next, floatx16{0}, 0, 0, 0);
                 }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[0][v] = j == 0 ? acc0[0][v] * sc : fmaf(acc0[0][v], sc, o[0][v]);
-                if (j + 1 < G) {
-                    fa = fa_next;
-                    acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[j + 1][0], fa, floatx16{0}, 0, 0, 0);
-                    acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j + 1][0], fa, acc0[0], 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                if (j + 2 < G) fa_next = __builtin_bit_cast(half8, rowp[4 * (j + 2)]);
+                for (int v = 0; v < 8; ++v) o[1][v] = j == 0 ? acc0[1][v] * sc : fmaf(acc0[1][v], sc, o[1][v]);
+                if (j + 1 < G) acc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[j + 1][0], fa_next, acc0[0], 0, 0, 0);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[1][v] = j == 0 ? acc0[1][v] * sc : fmaf(acc0[1][v], sc, o[1][v]);
+                for (int v = 8; v < 16; ++v) o[1][v] = j == 0 ? acc0[1][v] * sc : fmaf(acc0[1][v], sc, o[1][v]);
+                if (j + 1 < G) pin_half_step();
                 sc = sc_next;
-                if (j + 1 < G) {
-                    fb = fb_next;
-                    acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[G + j + 1][0], fb, floatx16{0}, 0, 0, 0);
-                    acc0[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[G + j + 1][0], fb, acc0[1], 0, 0, 0);
-                }
+                fb = fb_next;
             }
             __builtin_amdgcn_sched_barrier(0);
         } else {
