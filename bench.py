@@ -31,18 +31,22 @@ import time
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 
-# HBM traffic measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; profiles/hbm_traffic_d128_llama3-70b-128k.txt),
-# in bytes per vector, keyed by the kernel symbol the measurement was taken on: a kernel without a recorded counter
-# run reports null.  (FETCH_SIZE x its copy-kernel factor + WRITE_SIZE x its factor) KiB per dispatch x 1024 /
+# HBM traffic measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; profiles/hbm_traffic_d128_d256.txt), in bytes per
+# vector, keyed by the kernel symbol and head dimension the measurement was taken on: a kernel without a recorded
+# counter run reports null.  (FETCH_SIZE x its copy-kernel factor + WRITE_SIZE x its factor) KiB per dispatch x 1024 /
 # vectors per dispatch.
 MEASURED_TRAFFIC_PER_VECTOR = {
+    ("srft_quantize_fold_kernel", 128): 336.53,
+    ("srft_dequantize_batched_kernel", 128): 336.38,
+    ("srft_quantize_fold4_kernel", 256): 672.80,
+    ("srft_dequantize_batched_kernel", 256): 673.22,
 }
 
 # What a kernel that only streams the same bytes reaches on this machine (bench.py --ceiling, best over grid sizes and
 # access kinds; profiles/stream_ceiling_d128_mixes.txt), GB/s: context beside the roofline, not the roofline.
 MEASURED_STREAM_CEILING_GBPS = {
-    "quantize": 5813.0,       # 8192 B read : 2560 B written per tile, non-temporal accesses, 512 workgroups
-    "dequantize": 5541.0,     # 2560 : 8192
+    "quantize": 5857.0,       # 8192 B read : 2560 B written per tile, non-temporal accesses, 512 workgroups (plain: 5439)
+    "dequantize": 5475.0,     # 2560 : 8192, non-temporal, 768 workgroups (plain: 5403)
 }
 
 PAPER_CONTEXT = {   # Apple M1 GPU, Metal, fp32 input (paper Sec. 7.1): another machine, not a target
@@ -80,8 +84,12 @@ def main() -> int:
                     help="also time the write path in its butterfly form (fp32 FFT on the vector ALU, "
                          "srft_kv_quantize_butterfly; d = 128 only) over the same plans, a launch per plan")
     ap.add_argument("--power", action="store_true",
-                    help="also run each path, and the streaming kernel with its byte mix, for about 3 s each while "
-                         "sampling socket power and shader clock with amd-smi")
+                    help="also run each path at d = 128 and d = 256 (8 x 1,048,576 vectors), on N(0,1) and on all-zero "
+                         "data, and the streaming kernel with its byte mix, for about 3 s each while sampling socket "
+                         "power and shader clock with amd-smi")
+    ap.add_argument("--formats", action="store_true",
+                    help="also time one 8,388,608-vector launch shape over every head dimension and record format "
+                         "(group sizes, 8-bit codes, Walsh-Hadamard comparator), 30 launches each way")
     ap.add_argument("--copy-bytes", type=int, default=0,
                     help="also run the library's plain copy kernel over this many bytes (counter calibration)")
     args = ap.parse_args()
@@ -197,8 +205,8 @@ def main() -> int:
                        "hbm_frac": da / HBM_PEAK_GBPS, "avg_launch_ms": dl * 1e3},
         "roofline": {"kernel": symbol, "bound": "hbm", "achieved": dom_a, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dom_a / HBM_PEAK_GBPS,
-                     "traffic": (MEASURED_TRAFFIC_PER_VECTOR[symbol] * total_vec / launches
-                                 if symbol in MEASURED_TRAFFIC_PER_VECTOR else None),
+                     "traffic": (MEASURED_TRAFFIC_PER_VECTOR[(symbol, d)] * total_vec / launches
+                                 if (symbol, d) in MEASURED_TRAFFIC_PER_VECTOR else None),
                      "clock": "HIP events on the launch stream, average over the launches of the timed steps",
                      "algorithmic_bytes_per_launch": total_vec * bytes_per_vec // launches,
                      "avg_launch_ms": dom_l * 1e3,
@@ -226,24 +234,10 @@ def main() -> int:
     if args.ceiling:
         result["hbm_ceiling"] = mix_ceiling(M, torch, x, out, n_plans * n, d, G, stream)
     if args.power:
-        def q_pass():
-            for p in range(n_plans):
-                B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
-
-        def d_pass():
-            for p in range(n_plans):
-                B.srft_kv_dequantize(h[p], codes[p], scales[p], out[p], stream)
-        big, small = 32 * 2 * d, 32 * (d // 2 + 4 * G)
-        tiles = min(n_plans * n // 32, (2 << 30) // big)
-        xa, xb = x.view(torch.uint8).reshape(-1), out.view(torch.uint8).reshape(-1)
-        result["power"] = {
-            "quantize": sampled_phase(torch, q_pass, n_plans * n * bytes_per_vec),
-            "dequantize": sampled_phase(torch, d_pass, n_plans * n * bytes_per_vec),
-            "stream_quantize_mix": sampled_phase(
-                torch, lambda: M.srft_stream_mix(xa, xb, tiles, big, small, 768, False, stream), tiles * (big + small)),
-            "stream_dequantize_mix": sampled_phase(
-                torch, lambda: M.srft_stream_mix(xa, xb, tiles, small, big, 768, False, stream), tiles * (big + small)),
-        }
+        result["power"] = {"d128": power_phases(B, M, W, torch, dev, stream, 128),
+                           "d256": power_phases(B, M, W, torch, dev, stream, 256)}
+    if args.formats:
+        result["formats"] = formats_sweep(B, W, torch, dev, stream)
     if args.scores:
         n_q = 8
         q = W.make_kv(w, 1, n_vec=n_q, device=dev)
@@ -474,7 +468,20 @@ def mix_ceiling(M, torch, x, out, total_vec, d, G, stream):
     a, b = x.view(torch.uint8).reshape(-1), out.view(torch.uint8).reshape(-1)
     res = {"tiles": n_tiles, "read_write_bytes_per_tile": {"quantize_mix": [big, small], "dequantize_mix": [small, big]}}
     for name, (rb, wb), nt_acc in (("quantize_mix", (big, small), False), ("dequantize_mix", (small, big), False),
-                                   ("dequantize_mix_streaming_accesses", (small, big), True)):
+                                   ("quantize_mix_streaming_accesses", (big, small), 1),
+                                   ("dequantize_mix_streaming_accesses", (small, big), 1),
+                                   # every die walks a contiguous eighth of the tiles (plain / streaming accesses)
+                                   ("quantize_mix_die_contiguous", (big, small), 4),
+                                   ("dequantize_mix_die_contiguous", (small, big), 4),
+                                   ("quantize_mix_die_contiguous_streaming_accesses", (big, small), 5),
+                                   ("dequantize_mix_die_contiguous_streaming_accesses", (small, big), 5),
+                                   # the write mix at d = 256 (16 KiB in : 5 KiB out per tile): 16 bytes per lane and
+                                   # load, against every lane reading 64 contiguous bytes with four loads
+                                   ("quantize_mix_d256", (16384, 5120), 0),
+                                   ("quantize_mix_d256_streaming_accesses", (16384, 5120), 1),
+                                   ("quantize_mix_d256_64B_per_lane", (16384, 5120), 2),
+                                   ("quantize_mix_d256_64B_per_lane_streaming_accesses", (16384, 5120), 3)):
+        n_tiles = min(total_vec // 32, (2 << 30) // max(rb, wb))
         best = {}
         for wgs in (512, 768, 1024, 2048, 4096, 8192):
             for _ in range(3):
@@ -548,6 +555,69 @@ def sampled_phase(torch, fn, bytes_per_call, seconds=3.0):
     return {"GBps": calls * bytes_per_call / (e0.elapsed_time(e1) * 1e-3) / 1e9, "samples": len(use),
             "socket_power_W": sum(a for a, _ in use) / max(1, len(use)),
             "shader_clock_MHz": sum(b for _, b in use) / max(1, len(use))}
+
+
+def formats_sweep(B, W, torch, dev, stream, n=1 << 23, reps=30, warm=10):
+    """Steady-state rate of both paths for every head dimension and record format: one plan, n vectors per launch,
+    N(0,1) input, lognormal lambda; `warm` untimed launches, then `reps` timed ones, each way."""
+    rows = []
+    for d, g, bits, tr in [(32, 32, 4, "dft"), (64, 32, 4, "dft"), (96, 32, 4, "dft"), (128, 32, 4, "dft"),
+                           (192, 32, 4, "dft"), (256, 32, 4, "dft"),
+                           (128, 16, 4, "dft"), (128, 64, 4, "dft"), (128, 128, 4, "dft"), (128, 32, 8, "dft"),
+                           (128, 128, 8, "dft"), (128, 32, 4, "hadamard"), (256, 32, 8, "dft"), (256, 256, 4, "dft"),
+                           (96, 32, 8, "dft")]:
+        plan = B.Plan(d, g, 3, W.lognormal_lambda(d, 1), bits=bits, transform=tr)
+        x = torch.randn(n, d, device=dev, dtype=torch.float16)
+        codes, scales = plan.quantize(x)
+        out = plan.dequantize(codes, scales)
+        tq, td = timed_passes(torch, stream, lambda: B.srft_kv_quantize(plan.handle, x, codes, scales, stream),
+                              lambda: B.srft_kv_dequantize(plan.handle, codes, scales, out, stream), reps, warm=warm)
+        nb = n * (2 * d + d * bits // 8 + 4 * d // g)
+        rows.append({"d": d, "group": g, "bits": bits, "transform": tr, "bytes_per_vector": nb // n,
+                     "quantize_GBps": nb / tq / 1e9, "dequantize_GBps": nb / td / 1e9,
+                     "quantize_us": tq * 1e6, "dequantize_us": td * 1e6})
+        plan.close()
+        del x, codes, scales, out
+        torch.cuda.empty_cache()
+    return {"vectors_per_launch": n, "launches_timed": reps, "rows": rows}
+
+
+def power_phases(B, M, W, torch, dev, stream, d, n_plans=8, n=1 << 20):
+    """Sustained rate, socket power and shader clock of both paths over n_plans x n vectors of head dimension d
+    (g = 32, 4 bits): on N(0,1) input, on all-zero input (the same instruction stream with nothing toggling in the
+    data paths), and of a pure stream with each path's byte mix."""
+    G = d // 32
+    x = torch.randn(n_plans, n, d, device=dev).half()
+    plans = [B.Plan(d, 32, 7_000 + p, W.lognormal_lambda(d, 7_000 + p)) for p in range(n_plans)]
+    codes = torch.empty(n_plans, n, d // 2, dtype=torch.uint8, device=dev)
+    scales = torch.empty(n_plans, n, G, dtype=torch.float32, device=dev)
+    out = torch.empty_like(x)
+    h = [pl.handle for pl in plans]
+    table = B.BatchTable(h, list(out), list(codes), list(scales))
+
+    def q_pass():
+        for p in range(n_plans):
+            B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
+
+    def d_pass():
+        B.srft_kv_dequantize_batched(table, stream)
+    nbytes = n_plans * n * (2 * d + d // 2 + 4 * G)
+    big, small = 32 * 2 * d, 32 * (d // 2 + 4 * G)
+    tiles = min(n_plans * n // 32, (2 << 30) // big)
+    xa, xb = x.view(torch.uint8).reshape(-1), out.view(torch.uint8).reshape(-1)
+    res = {"plans": n_plans, "vectors_per_plan": n}
+    res["quantize"] = sampled_phase(torch, q_pass, nbytes)
+    res["dequantize"] = sampled_phase(torch, d_pass, nbytes)
+    res["stream_quantize_mix"] = sampled_phase(
+        torch, lambda: M.srft_stream_mix(xa, xb, tiles, big, small, 768, False, stream), tiles * (big + small))
+    res["stream_dequantize_mix"] = sampled_phase(
+        torch, lambda: M.srft_stream_mix(xa, xb, tiles, small, big, 768, False, stream), tiles * (big + small))
+    x.zero_()
+    res["quantize_all_zero_input"] = sampled_phase(torch, q_pass, nbytes)       # leaves zero codes and scales
+    res["dequantize_all_zero_record"] = sampled_phase(torch, d_pass, nbytes)
+    for pl in plans:
+        pl.close()
+    return res
 
 
 def decode_append(B, W, torch, dev, stream, iters=200):

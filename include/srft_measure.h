@@ -31,7 +31,8 @@ int srft_stream_copy(void* dst_dev, const void* src_dev, int64_t n_bytes, void* 
  * the read-only or the write-only stream); workgroups = 0 picks 3 per compute unit.  `access` is a bit set:
  * 1 = non-temporal loads and stores; 2 = every lane reads 64 contiguous bytes with four 16-byte loads (the
  * shape a per-lane de-interleave of 32 consecutive inputs needs; read_bytes_per_tile must then be a multiple of
- * 16 KiB) instead of loads that cover 1 KiB per wavefront contiguously.
+ * 16 KiB) instead of loads that cover 1 KiB per wavefront contiguously; 4 = every accelerator die (workgroup index
+ * mod 8) walks one contiguous eighth of the tiles instead of every eighth tile (grids that are a multiple of 8).
  */
 int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int read_bytes_per_tile,
                     int write_bytes_per_tile, int workgroups, int access, void* hip_stream);

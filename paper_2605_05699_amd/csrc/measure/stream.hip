@@ -31,8 +31,19 @@ srft_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, long lo
 // lane reads 64 contiguous bytes with four loads, so that each load touches a quarter of every cache line it visits)
 template <int RU, bool STREAM, int CHUNK = 1>   // RU = ceil(r_units / 256): loads per thread and tile, all issued before any is used
 __global__ void __launch_bounds__(256)
-srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n_tiles, int r_units, int w_units) {
-    for (long long t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+srft_mix_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n_tiles, int r_units, int w_units,
+                int die_map) {
+    // die_map: workgroup b runs on accelerator die b mod 8 (the hardware deals workgroups round-robin); each die then
+    // gets one contiguous eighth of the tiles, walked by its workgroups with stride gridDim / 8.  Otherwise tile =
+    // blockIdx + k gridDim, so that neighbouring tiles go to different dies.
+    long long t0 = blockIdx.x, stride = gridDim.x, t_end = n_tiles;
+    if (die_map && (gridDim.x & 7) == 0 && n_tiles >= (long long)gridDim.x) {
+        const long long per_die = (n_tiles + 7) >> 3, die = blockIdx.x & 7;
+        stride = gridDim.x >> 3;
+        t0 = die * per_die + (blockIdx.x >> 3);
+        t_end = n_tiles < (die + 1) * per_die ? n_tiles : (die + 1) * per_die;
+    }
+    for (long long t = t0; t < t_end; t += stride) {
         const uint4* s = src + t * r_units;
         uint4 v[RU] = {};
         if (r_units > 0) {                       // uniform; r_units = 0 is the write-only stream
@@ -108,7 +119,7 @@ int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int rea
     const int ru = r_units > 0 ? (r_units + 255) / 256 : 1;
     const bool stream = (nontemporal & 1) != 0, chunk4 = (nontemporal & 2) != 0;
     if (chunk4 && r_units % 1024 != 0) return SRFT_ERR_BAD_N;
-    void (*kernel)(const uint4*, uint4*, long long, int, int) = nullptr;
+    void (*kernel)(const uint4*, uint4*, long long, int, int, int) = nullptr;
 #define SRFT_MIX_CASE(N)                                                                                          \
     case N:                                                                                                       \
         kernel = chunk4 ? (stream ? srft_mix_kernel<N, true, 4> : srft_mix_kernel<N, false, 4>)                  \
@@ -121,7 +132,7 @@ int srft_stream_mix(const void* src_dev, void* dst_dev, int64_t n_tiles, int rea
     }
 #undef SRFT_MIX_CASE
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, (const uint4*)src_dev,
-                       (uint4*)dst_dev, (long long)n_tiles, r_units, w_units);
+                       (uint4*)dst_dev, (long long)n_tiles, r_units, w_units, (nontemporal & 4) ? 1 : 0);
     MEASURE_HIP(hipGetLastError());
     return SRFT_OK;
 }

@@ -41,17 +41,6 @@
 #define SRFT_QUANTIZE_FOLD4_TILES_H
 #include "device_util.h"
 
-#ifdef SRFT_F4_TRACE
-__device__ unsigned long long* srft_trace_buf;
-#if SRFT_F4_TRACE == 2
-#define F4_STAMP(i) do {} while (0)
-#else
-#define F4_STAMP(i) do { __builtin_amdgcn_sched_barrier(0); if (trace && lane == 0) trace[(i)] = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
-#endif
-#else
-#define F4_STAMP(i) do {} while (0)
-#endif
-
 constexpr int kFold4FragUnits = 4 * 2 * 4 * 2 * 64;          // 16-byte units of fragments in wf4
 constexpr int kFold4RhoFloats = 4 * 64;
 constexpr int kFold4Units = kFold4FragUnits + kFold4RhoFloats / 4 + 4;
@@ -121,14 +110,10 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
         if (tile > n_tiles - 1) tile = n_tiles - 1;
         const int lim = (tile == n_tiles - 1) ? last_lim : kTileVecs - 1;
         const uint4* src = x + (long long)tile * kTileVecs * U + (unsigned)(min(frow, lim) * U + 4 * fchunk);
-#ifdef SRFT_F4_NT_LOAD
-        a = stream_load(src); b = stream_load(src + 1); c = stream_load(src + 2); d = stream_load(src + 3);
-#else
-        a = src[0];
+        a = src[0];          // plain loads: four loads touch every line, and non-temporal ones then fetch it again
         b = src[1];
         c = src[2];
         d = src[3];
-#endif
     };
     // 32 consecutive inputs -> for each class the 8 that belong to it (positions c, c + 4, ... of the chunk)
     auto to_lds = [&](int buf, const uint4& a, const uint4& b, const uint4& c, const uint4& d) __attribute__((always_inline)) {
@@ -282,13 +267,7 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
         for (int i = 0; i < kTileVecs * PIECES / NT; ++i) {
             const int u = tid + i * NT, r = u / PIECES, pc = u % PIECES;
             const uint2 lo = cstage[b][r * CROW + 2 * pc], hi = cstage[b][r * CROW + 2 * pc + 1];
-            
-#ifdef SRFT_F4_NT_STORE
-            stream_store(&cbase[(unsigned)(min(r, lim) * PIECES + pc)], make_uint4(lo.x, lo.y, hi.x, hi.y));
-#else
             cbase[(unsigned)(min(r, lim) * PIECES + pc)] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-#endif
-
         }
         if (wave == 0) {                                 // uniform per wavefront
             const int r = lane >> 1, hf = lane & 1;
@@ -297,17 +276,6 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
         }
     };
 
-#if defined(SRFT_F4_TRACE) && SRFT_F4_TRACE == 2
-    struct BlockStamp {
-        unsigned long long* r;
-        __device__ BlockStamp(unsigned long long* p) : r(p) {
-            if (r) { r[0] = __builtin_amdgcn_s_memrealtime(); r[1] = __builtin_readcyclecounter();
-                     unsigned id, xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(id));
-                     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc)); r[2] = id; r[3] = xcc; }
-        }
-        __device__ ~BlockStamp() { if (r) { r[4] = __builtin_amdgcn_s_memrealtime(); r[5] = __builtin_readcyclecounter(); } }
-    } block_stamp((tid == 0 && blockIdx.x < 4096) ? srft_trace_buf + (size_t)blockIdx.x * 8 : nullptr);
-#endif
     const int m = (t_end - 1 - t0) / stride + 1;            // tiles of this workgroup: t0, t0 + stride, ... < t_end
     uint4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3;
     floatx16 aa, ca, ab, cb;                     // two accumulator sets; after hand_over the a of a set holds keep
@@ -326,33 +294,22 @@ srft_quantize_fold4_tiles(const uint4* __restrict__ wf4, const uint4* __restrict
     int k = 1;
     for (; k + 1 < m; k += 2) {
         const int tk = t0 + k * stride;
-#if defined(SRFT_F4_TRACE) && SRFT_F4_TRACE != 2
-        unsigned long long* trace = (blockIdx.x < 1024 && k < 40) ? srft_trace_buf + ((size_t)(blockIdx.x * 4 + wave) * 40 + k) * 8 : nullptr;
-#endif
-        F4_STAMP(0);
         __syncthreads();                         // stage k (odd)
-        F4_STAMP(1);
         rotate_priority(k);
         if (k >= 2) flush(1, tk - 2 * stride);
         contract(1, ab, cb);
-        F4_STAMP(2);
         finish(0, aa, tk - stride);
-        F4_STAMP(3);
         to_lds(0, pa0, pa1, pa2, pa3);
         fetch(pa0, pa1, pa2, pa3, tk + 3 * stride);
         hand_over(1, ab, cb);
-        F4_STAMP(4);
         __syncthreads();                         // stage k + 1 (even)
-        F4_STAMP(5);
         rotate_priority(k + 1);
         flush(0, tk - stride);
         contract(0, aa, ca);
         finish(1, ab, tk);
-        F4_STAMP(6);
         to_lds(1, pb0, pb1, pb2, pb3);
         fetch(pb0, pb1, pb2, pb3, tk + 4 * stride);
         hand_over(0, aa, ca);
-        F4_STAMP(7);
     }
     // finish(b, ...) stages into buffer b, flush(b, ...) stores it one barrier later
     if (k < m) {                                 // one more odd stage

@@ -46,7 +46,7 @@ def srft_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
 
 def srft_stream_mix(src: torch.Tensor, dst: torch.Tensor, n_tiles: int, read_bytes: int, write_bytes: int,
                     workgroups: int = 0, nontemporal=False, stream=None) -> None:
-    """nontemporal: bool, or the access bit set of the C entry point (1 non-temporal, 2 = 64 bytes per lane)."""
+    """nontemporal: bool, or the access bit set of the C entry point (1 non-temporal, 2 = 64 bytes per lane, 4 = a contiguous eighth of the tiles per die)."""
     assert src.is_cuda and dst.is_cuda
     assert src.numel() * src.element_size() >= n_tiles * read_bytes
     assert dst.numel() * dst.element_size() >= n_tiles * write_bytes
