@@ -279,8 +279,9 @@ def main() -> int:
                 "hbm_frac": n * (rec_bytes + 4 * n_q) / ta / 1e9 / HBM_PEAK_GBPS}
             result["decode_attention"] = {
                 "queries": n_q, "keys": n, "us": tda * 1e6,
-                "what": "scores over the K record, row softmax, weights times the V record: both records read once, "
-                        "the n_q x n_keys scores written, read three times and rewritten by the softmax, read once more",
+                "what": "scores over the K record, statistics of their row softmax, the V record weighted with "
+                        "exp(scale * score - maximum) / sum formed from the raw scores as they are loaded: both "
+                        "records read once, the n_q x n_keys scores written once and read twice",
                 "dequantize_K_and_V_instead_us": 2 * tdq * 1e6}
     if args.decode_append:
         result["decode_append"] = decode_append(B, W, torch, dev, stream)

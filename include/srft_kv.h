@@ -179,7 +179,7 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
  *   weights_f32_dev [n_q, n_keys] fp32 row-major, 4-byte aligned, 1 <= n_q <= 32 (e.g. softmax of srft_kv_scores).
  *   codes_dev       [n_keys, d/2] bytes, 16-byte aligned;  scales_dev [n_keys, d/g] fp32: the plan's record.
  *   out_f32_dev     [n_q, d] fp32, written.
- *   workspace_dev   srft_attend_workspace_bytes(plan) bytes of device memory (about 17 MiB at d = 128), 16-byte aligned,
+ *   workspace_dev   srft_attend_workspace_bytes(plan) bytes of device memory (about 34 MiB at d = 128), 16-byte aligned,
  *                   overwritten; calls that may run at the same time need a workspace each.
  * n_keys >= 1.  For plans with d a multiple of 64, 4-bit codes and g >= 32 (else SRFT_ERR_BAD_D / _BAD_BITS /
  * _BAD_GROUP).  Enqueues three kernels: partial sums per workgroup (fp32, on the matrix cores), their sum in a fixed
@@ -193,7 +193,9 @@ int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_
 /*
  * One decode step of attention over a stored cache: out = softmax(softmax_scale * q K^T) V with K and V read from
  * their records (plan_k, plan_v: same d, own signs and lambda each).    (Sec. 1; Sec. 7.2)
- * srft_kv_scores, a row softmax in place, srft_kv_attend, on one stream.  q_f16_dev [n_q, d] fp16 (16-byte aligned),
+ * On one stream: srft_kv_scores; the (maximum, sum of exponentials) of every row of scores; the weighted sums of
+ * srft_kv_attend, whose kernel forms the weights exp(softmax_scale * score - maximum) / sum from the raw scores as it
+ * loads them (the scores are written once and read twice).  q_f16_dev [n_q, d] fp16 (16-byte aligned),
  * out_f32_dev [n_q, d] fp32; workspace_dev: srft_decode_attention_workspace_bytes(plan_k, plan_v, n_q, n_keys) bytes,
  * 256-byte aligned (it holds the n_q x n_keys scores).  Shapes and limits as for the two calls it is made of.
  */

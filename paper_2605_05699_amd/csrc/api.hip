@@ -246,7 +246,7 @@ static int attend_supported(const srft_plan_t* plan) {
 
 int64_t srft_attend_workspace_bytes(const srft_plan_t* plan) {
     if (!plan) return SRFT_ERR_NULL;
-    return (int64_t)(kMaxAttendStripes + 16) * 32 * plan->d * 4;  // the partial sums of every workgroup, and of their first-level sums
+    return (int64_t)(kMaxAttendStripes + kAttendFan) * 32 * plan->d * 4;  // the partial sums of every workgroup, and of their first-level sums
 }
 
 int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_q, const uint8_t* codes_dev,
@@ -260,7 +260,7 @@ int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_
         !srft_aligned(out_f32_dev, 4) || !srft_aligned(workspace_dev, 16))
         return SRFT_ERR_ALIGN;
     return srft_launch_attend(plan, weights_f32_dev, n_q, codes_dev, scales_dev, n_keys, out_f32_dev,
-                              (float*)workspace_dev, (hipStream_t)hip_stream);
+                              (float*)workspace_dev, nullptr, 1.0f, (hipStream_t)hip_stream);
 }
 
 int64_t srft_decode_attention_workspace_bytes(const srft_plan_t* plan_k, const srft_plan_t* plan_v, int n_q,
@@ -288,14 +288,18 @@ int srft_kv_decode_attention(const srft_plan_t* plan_k, const srft_plan_t* plan_
     float* scores = (float*)workspace_dev;
     void* stats = (char*)workspace_dev + ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256;
     void* rest = (char*)stats + srft_softmax_stats_bytes(32);
+    // the per-row (maximum, 1 / sum) pairs follow the per-chunk ones
+    float2* row_stats = (float2*)((char*)rest - 32 * sizeof(float2));
     hipStream_t st = (hipStream_t)hip_stream;
-    // scores of the queries against the stored keys, their row softmax in place, weights times the stored values;
-    // the same workspace serves the first and the third step, which run one after the other on the stream
+    // scores of the queries against the stored keys; the statistics of their row softmax; the stored values weighted
+    // with exp(scale * score - maximum) / sum, formed from the raw scores as the value-side kernel loads them.
+    // The same workspace serves the first and the third step, which run one after the other on the stream.
     rc = srft_kv_scores(plan_k, q_f16_dev, n_q, k_codes_dev, k_scales_dev, n_keys, scores, rest, hip_stream);
     if (rc != SRFT_OK) return rc;
-    rc = srft_launch_softmax_rows(scores, n_q, n_keys, softmax_scale, stats, st);
+    rc = srft_launch_softmax_row_stats(scores, n_q, n_keys, softmax_scale, stats, row_stats, st);
     if (rc != SRFT_OK) return rc;
-    return srft_launch_attend(plan_v, scores, n_q, v_codes_dev, v_scales_dev, n_keys, out_f32_dev, (float*)rest, st);
+    return srft_launch_attend(plan_v, scores, n_q, v_codes_dev, v_scales_dev, n_keys, out_f32_dev, (float*)rest,
+                              row_stats, softmax_scale, st);
 }
 
 int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host) {

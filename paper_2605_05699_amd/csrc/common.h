@@ -66,7 +66,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kTileVecs = 32;          // vectors per tile = N of the 32x32x16 MFMA
 constexpr int kMaxScoreWorkgroups = 4096;   // scores kernel: largest grid (each workgroup owns 256 bytes of workspace)
 constexpr int kMaxD = 256;
-constexpr int kMaxAttendStripes = 1024;      // value-side kernel: most workgroups per channel slab (each owns 32 x d floats of workspace)
+constexpr int kMaxAttendStripes = 2048;      // value-side kernel: most workgroups per channel slab (each owns 32 x d floats of workspace)
+constexpr int kAttendFan = 64;                // value-side kernel: first-level sums the partial results are added into
 constexpr float kMinScale = 7.888609052210118e-31f;   // 2^-100: below this a group is stored as zero
 // The kernels index tiles of 32 vectors with 32-bit integers and look a few grid strides ahead.
 constexpr int64_t kMaxVectors = (int64_t)1 << 33;
@@ -164,13 +165,18 @@ int srft_launch_scores(const srft_plan* p, uint4* qfrag, float* dump, int n_q, c
 int srft_scores_occupancy(int d, bool r16, int* blocks_per_cu);
 
 // weighted sums of the stored values in the rotated domain (kernels/attend.hip): workgroups per channel slab for
-// n_keys values, and the two launches (partial sums per workgroup into `part`, then reduction + inverse transform)
-int srft_attend_stripes(const srft_plan* p, long long n_keys);
+// n_q queries over n_keys values, and the three launches (partial sums per workgroup into `part`, their fixed-order
+// reduction, the inverse transform).  row_stats: nullptr (w holds the weights), or per query the (maximum, 1 / sum)
+// of the row softmax of softmax_scale * w: w then holds raw scores and the weights are formed as they are loaded.
+int srft_attend_stripes(const srft_plan* p, int n_q, long long n_keys);
 int srft_launch_attend(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, const float* scales,
-                       long long n_keys, float* out, float* part, hipStream_t st);
-// row softmax of scale * x, in place, rows of n floats (kernels/softmax.hip)
-int64_t srft_softmax_stats_bytes(int rows);      // workspace of the softmax: per-chunk maxima and sums
-int srft_launch_softmax_rows(float* x, int rows, long long n, float scale, void* stats, hipStream_t st);
+                       long long n_keys, float* out, float* part, const float2* row_stats, float softmax_scale,
+                       hipStream_t st);
+// statistics of the row softmax of scale * x, rows of n floats (kernels/softmax.hip): row_stats[row] = (maximum,
+// 1 / sum of exponentials); chunk_stats: srft_softmax_stats_bytes(rows) bytes of workspace
+int64_t srft_softmax_stats_bytes(int rows);
+int srft_launch_softmax_row_stats(const float* x, int rows, long long n, float scale, void* chunk_stats,
+                                  float2* row_stats, hipStream_t st);
 
 // ---- host side (plan.hip, api.hip) ----
 int srft_hip_fail(hipError_t e);         // records the error for srft_last_hip_error, returns SRFT_ERR_HIP

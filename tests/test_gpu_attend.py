@@ -34,7 +34,7 @@ def _tolerance(w64, vals64):
 
 
 @pytest.mark.parametrize("d", [64, 128, 192, 256])
-@pytest.mark.parametrize("n_q,n_keys", [(1, 1), (8, 33), (32, 1000), (5, 4097), (3, 64)])
+@pytest.mark.parametrize("n_q,n_keys", [(1, 1), (8, 33), (32, 1000), (5, 4097), (3, 64), (12, 300), (16, 129), (17, 100)])
 def test_attend_matches_the_definition(B, d, n_q, n_keys):
     g = 32
     vals = W.gaussian_with_outliers(n_keys, d, seed=3 * d + n_keys, outliers=1, gain=10.0)
@@ -98,7 +98,7 @@ def test_attend_over_many_tiles_wide_groups_a_grid_cap_and_argument_checks(B):
     p96.close()
 
 
-@pytest.mark.parametrize("d,n_q,n_keys", [(128, 8, 5000), (256, 4, 1234), (64, 32, 777)])
+@pytest.mark.parametrize("d,n_q,n_keys", [(128, 8, 5000), (256, 4, 1234), (64, 32, 777), (128, 16, 70001), (192, 9, 40)])
 def test_decode_attention_matches_the_definition(B, d, n_q, n_keys):
     g = 32
     k = W.gaussian_with_outliers(n_keys, d, seed=d + 1, outliers=1, gain=15.0)
