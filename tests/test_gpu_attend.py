@@ -127,3 +127,42 @@ def test_decode_attention_matches_the_definition(B, d, n_q, n_keys):
     assert np.abs(got - ref).max() <= tol, float(np.abs(got - ref).max() / tol)
     pk.close()
     pv.close()
+
+
+def test_decode_attention_replayed_from_a_hip_graph_equals_the_eager_calls(B):
+    """The entry point only enqueues kernels on the caller's stream (no allocation, no memset), so a caller may record
+    it into a HIP graph.  Three replays, each after new queries were written into the captured buffer by ordinary eager
+    work, must equal the eager call on the same inputs bit for bit (the summation order is fixed)."""
+    d, g, n_q, n_keys = 128, 32, 8, 20_000
+    k = W.gaussian_with_outliers(n_keys, d, seed=31, outliers=1, gain=15.0)
+    v = W.gaussian_with_outliers(n_keys, d, seed=32, outliers=0)
+    pk, pv = B.Plan(d, g, 41, W.lognormal_lambda(d, seed=3)), B.Plan(d, g, 42, W.lognormal_lambda(d, seed=4))
+    kc, ks = pk.quantize(torch.from_numpy(k).cuda())
+    vc, vs = pv.quantize(torch.from_numpy(v).cuda())
+    scale = d ** -0.5
+    q = torch.zeros(n_q, d, dtype=torch.float16, device="cuda")
+    out = torch.zeros(n_q, d, dtype=torch.float32, device="cuda")
+    nbytes = B.lib().srft_decode_attention_workspace_bytes(pk.handle, pv.handle, n_q, n_keys)
+    ws, ws_eager = (torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2))
+    q.copy_(torch.from_numpy(W.gaussian_with_outliers(n_q, d, seed=50, outliers=0)))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):              # one eager call on the capture stream first
+        B.srft_kv_decode_attention(pk.handle, pv.handle, q, kc, ks, vc, vs, scale, out, ws, side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        B.srft_kv_decode_attention(pk.handle, pv.handle, q, kc, ks, vc, vs, scale, out, ws, torch.cuda.current_stream())
+    for rep in range(3):
+        q.copy_(torch.from_numpy(W.gaussian_with_outliers(n_q, d, seed=60 + rep, outliers=1, gain=3.0)))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        eager = torch.empty_like(out)
+        B.srft_kv_decode_attention(pk.handle, pv.handle, q, kc, ks, vc, vs, scale, eager, ws_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager), rep
+        assert torch.isfinite(got).all() and got.abs().max() > 0
+    pk.close()
+    pv.close()
