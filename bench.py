@@ -182,7 +182,7 @@ def main() -> int:
     launches = launches_q if tq >= td else launches_d
     dominant = "quantize" if tq >= td else "dequantize"
     # the symbol the profiler shows for it
-    symbol = kernel_symbol(d, g, "quantize", batched_q) if tq >= td else kernel_symbol(d, g, "dequantize", batched_d)
+    symbol = kernel_symbol(B, h[0], "quantize", batched_q) if tq >= td else kernel_symbol(B, h[0], "dequantize", batched_d)
     dom_l, dom_a = (ql, qa) if tq >= td else (dl, da)
     result = {
         "metric": "quantize+dequantize vectors/s (full write pass then full read pass over the cache)",
@@ -320,15 +320,16 @@ def main() -> int:
     return 0
 
 
-def kernel_symbol(d, g, path, batched):
-    """Name of the kernel a g = 32 or wider-group 4-bit DFT plan of head dimension d launches."""
+def kernel_symbol(B, plan_handle, path, batched):
+    """Name of the kernel the plan's launches of `path` ("quantize" / "dequantize") run: the form comes from the
+    library (srft_plan_form), so the name cannot drift from what is launched."""
+    form = B.lib().srft_plan_form(plan_handle, 0 if path == "quantize" else 1)
+    if form < 0:
+        raise RuntimeError(f"srft_plan_form: {form}")
     if path == "dequantize":
         return "srft_dequantize_batched_kernel" if batched else "srft_dequantize_kernel"
-    if d == 256 and g == 32:
-        return "srft_quantize_fold4_batched_kernel" if batched else "srft_quantize_fold4_kernel"
-    if d % 128 == 0 and g >= 32:
-        return "srft_quantize_fold_batched_kernel" if batched else "srft_quantize_fold_kernel"
-    return "srft_quantize_batched_kernel" if batched else "srft_quantize_kernel"
+    stem = ("srft_quantize", "srft_quantize_fold", "srft_quantize_fold4")[form]
+    return stem + ("_batched_kernel" if batched else "_kernel")
 
 
 def timed_passes(torch, stream, q_pass, d_pass, reps, warm=1):

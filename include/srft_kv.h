@@ -281,6 +281,10 @@ int srft_plan_group_size(const srft_plan_t* plan);    /* g */
 int srft_plan_groups(const srft_plan_t* plan);        /* d / g: scales per vector */
 int srft_plan_code_bytes(const srft_plan_t* plan);    /* code bytes per vector: d / 2 at 4 bits, d at 8 */
 int srft_plan_bits(const srft_plan_t* plan);          /* 4 or 8 */
+/* Which form of the transform the plan's launches run: path 0 = write, 1 = read; returns 0 = the whole matrix
+ * (plain form), 1 = folded once, 2 = folded twice (the factorisations that the symmetries of Eq. 1-2 allow; the
+ * record is the same in every form), or SRFT_ERR_NULL / SRFT_ERR_BAD_N. */
+int srft_plan_form(const srft_plan_t* plan, int path);
 int srft_plan_get_signs(const srft_plan_t* plan, int8_t* out_host /* d entries, each -1 or +1 */);
 
 /*

@@ -26,7 +26,7 @@ EXPORTS = [
     "srft_kv_channel_absmax", "srft_lambda_from_absmax",
     "srft_cache_create", "srft_cache_destroy", "srft_cache_append", "srft_cache_rebuild_view",
     "srft_cache_tokens", "srft_cache_quantized_tokens",
-    "srft_plan_create_bits", "srft_plan_bits", "srft_plan_create_ex",
+    "srft_plan_create_bits", "srft_plan_bits", "srft_plan_form", "srft_plan_create_ex",
     "srft_scores_workspace_bytes", "srft_kv_scores", "srft_kv_scores_static", "srft_kv_quantize_butterfly",
     "srft_attend_workspace_bytes", "srft_kv_attend", "srft_decode_attention_workspace_bytes", "srft_kv_decode_attention",
 ]
@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
     L.srft_plan_create_bits.argtypes = [C.POINTER(vp), ci, ci, ci, u64, vp]
     L.srft_plan_create_ex.argtypes = [C.POINTER(vp), ci, ci, ci, ci, u64, vp]
     L.srft_plan_bits.argtypes = [vp]
+    L.srft_plan_form.argtypes = [vp, ci]
     L.srft_plan_destroy.argtypes = [vp]
     L.srft_kv_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
     L.srft_kv_dequantize.argtypes = [vp, vp, vp, i64, vp, vp]

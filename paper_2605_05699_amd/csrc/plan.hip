@@ -479,6 +479,12 @@ int srft_plan_group_size(const srft_plan_t* plan) { return plan ? plan->g : SRFT
 int srft_plan_groups(const srft_plan_t* plan) { return plan ? plan->d / plan->g : SRFT_ERR_NULL; }
 int srft_plan_code_bytes(const srft_plan_t* plan) { return plan ? plan->d * plan->bits / 8 : SRFT_ERR_NULL; }
 int srft_plan_bits(const srft_plan_t* plan) { return plan ? plan->bits : SRFT_ERR_NULL; }
+int srft_plan_form(const srft_plan_t* plan, int path) {
+    if (!plan) return SRFT_ERR_NULL;
+    if (path == 0) return plan->fold4_q ? 2 : plan->fold_q ? 1 : 0;
+    if (path == 1) return plan->fold_dq ? 1 : 0;
+    return SRFT_ERR_BAD_N;
+}
 
 int srft_plan_get_signs(const srft_plan_t* plan, int8_t* out_host) {
     if (!plan || !out_host) return SRFT_ERR_NULL;

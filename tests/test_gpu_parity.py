@@ -402,3 +402,17 @@ def test_single_launch_beyond_4_gib(B):
     # base + 32-bit lane offset) and the last tile is ragged; sampled rows against the oracle, properties on all.
     _sampled_parity(B, W.WORKLOADS["llama3-70b-128k"], 7, 20_000_003)
 
+
+
+def test_plan_form_reports_the_factorisation_each_plan_runs(B):
+    """srft_plan_form is what bench.py names the timed kernel by: once-folded write path at d = 128, twice-folded at
+    d = 256 with g = 32, plain elsewhere; folded read path at d = 128, 192, 256 with g >= 32."""
+    L = B.lib()
+    expect = {(128, 32, "dft"): (1, 1), (256, 32, "dft"): (2, 1), (256, 64, "dft"): (1, 1), (96, 32, "dft"): (0, 0),
+              (192, 32, "dft"): (0, 1), (64, 32, "dft"): (0, 0), (128, 16, "dft"): (0, 0), (128, 32, "hadamard"): (0, 0)}
+    for (d, g, tr), (fw, fr) in expect.items():
+        plan = B.Plan(d, g, 1, None, transform=tr)
+        assert (L.srft_plan_form(plan.handle, 0), L.srft_plan_form(plan.handle, 1)) == (fw, fr), (d, g, tr)
+        assert L.srft_plan_form(plan.handle, 2) == -7
+        plan.close()
+    assert L.srft_plan_form(None, 0) == -1
