@@ -591,7 +591,19 @@ def formats_sweep(B, W, torch, dev, stream, n=1 << 23, reps=30, warm=10):
         plan.close()
         del x, codes, scales, out
         torch.cuda.empty_cache()
-    return {"vectors_per_launch": n, "launches_timed": reps, "rows": rows}
+    # the lambda calibration statistic (per-channel abs-max of the transform's output): reads 2 d bytes per vector
+    cal = []
+    for d in (96, 128, 256):
+        plan = B.Plan(d, 32, 3, None)
+        x = torch.randn(n, d, device=dev, dtype=torch.float16)
+        amax = torch.zeros(d, dtype=torch.float32, device=dev)
+        tc, _ = timed_passes(torch, stream, lambda: B.srft_kv_channel_absmax(plan.handle, x, amax, stream), None, reps,
+                             warm=warm)
+        cal.append({"d": d, "us": tc * 1e6, "GBps_input_read": n * 2 * d / tc / 1e9})
+        plan.close()
+        del x
+        torch.cuda.empty_cache()
+    return {"vectors_per_launch": n, "launches_timed": reps, "rows": rows, "channel_absmax": cal}
 
 
 def power_phases(B, M, W, torch, dev, stream, d, n_plans=8, n=1 << 20):

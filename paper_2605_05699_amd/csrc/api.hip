@@ -16,7 +16,7 @@ int launch_quantize(const srft_plan* p, const void* x, long long n, uint8_t* cod
     int threads = 0;
     const quantize_kernel_t kernel = srft_plan_quantize_kernel(p, out, &threads);
     if (!kernel) return SRFT_ERR_BAD_D;
-    const bool fold4 = p->fold4_q && out == kOutCodes, fold = p->fold_q && out == kOutCodes;
+    const bool fold4 = p->fold4_q && out == kOutCodes, fold = p->fold_q && (out == kOutCodes || out == kOutAmax);
     // the twice-folded form carries the matrix scaling inside its per-channel factors
     const float unscale = fold4 ? 1.0f : p->unscale_w;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), 0, st,

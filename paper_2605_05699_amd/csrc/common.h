@@ -146,6 +146,7 @@ batched_kernel_t srft_pick_quantize_plain_batched_b8(int d, int slabs, int gm);
 quantize_kernel_t srft_pick_quantize_aux(int d, int slabs, int out);
 // write path, folded form (d = 128, 256)
 quantize_kernel_t srft_pick_quantize_fold(int d, int bits, bool wide);
+quantize_kernel_t srft_pick_quantize_fold_amax(int d);      // the abs-max statistic through the once-folded contraction
 batched_kernel_t srft_pick_quantize_fold_batched(int d, int bits, bool wide);
 // write path, folded twice (d = 256, g = 32); the size of its table in 16-byte units
 quantize_kernel_t srft_pick_quantize_fold4(int bits);

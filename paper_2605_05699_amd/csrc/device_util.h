@@ -172,6 +172,15 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
 // Every branch in the kernels is uniform over the workgroup.
 // ------------------------------------------------------------------------------------------
 
+// Running maximum of non-negative floats kept as their bit patterns (they order alike).  All workgroups of a launch
+// update the same few cache lines at about the same time, and atomics to one line are served one after the other:
+// the current value is read first (from L2, past the caches of this compute unit), and the atomic is only sent when
+// it would raise it -- of N similar contributions about ln N do.
+__device__ __forceinline__ void atomic_max_nonneg(unsigned int* p, float v) {
+    const unsigned int bits = __float_as_uint(v);
+    if (bits > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(p, bits);
+}
+
 // Which tiles a workgroup of a per-plan launch walks: first tile, stride, and the end (exclusive) of its range.
 // SRFT_XCD_MAP = 0: tile = blockIdx + k gridDim over all tiles.  SRFT_XCD_MAP = 1: workgroups are dealt to the 8
 // accelerator dies round-robin (die = blockIdx mod 8), and each die gets one contiguous eighth of the tiles, which

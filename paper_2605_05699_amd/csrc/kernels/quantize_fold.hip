@@ -18,6 +18,9 @@ batched_kernel_t pick_batched(int bits, bool wide) {
 quantize_kernel_t srft_pick_quantize_fold(int d, int bits, bool wide) {
     return d == 128 ? pick<128>(bits, wide) : d == 256 ? pick<256>(bits, wide) : nullptr;
 }
+quantize_kernel_t srft_pick_quantize_fold_amax(int d) {
+    return d == 128 ? srft_quantize_fold_amax_kernel<128> : d == 256 ? srft_quantize_fold_amax_kernel<256> : nullptr;
+}
 batched_kernel_t srft_pick_quantize_fold_batched(int d, int bits, bool wide) {
     return d == 128 ? pick_batched<128>(bits, wide) : d == 256 ? pick_batched<256>(bits, wide) : nullptr;
 }

@@ -193,6 +193,10 @@ quantize_kernel_t srft_plan_quantize_kernel(const srft_plan* p, int out, int* th
         *threads = 2 * p->d;
         return srft_pick_quantize_aux(p->d, 1, out);
     }
+    if (out == kOutAmax && p->fold_q) {                  // the statistic does not depend on the groups: folded wherever the table exists
+        *threads = p->d;
+        return srft_pick_quantize_fold_amax(p->d);
+    }
     if (out != kOutCodes) {
         *threads = 2 * p->d / p->slabs_q;
         return srft_pick_quantize_aux(p->d, p->slabs_q, out);

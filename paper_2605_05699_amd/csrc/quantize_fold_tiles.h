@@ -49,11 +49,15 @@
 // of the 32-runs meet in LDS (gmax), which costs one more barrier per tile, in the middle of the stage.
 //
 // wfold : [d/64 waves][E, O][d/32 k-steps][hi, lo][64 lanes] fragments, then [d/64 waves][64 lanes][4] x 4 floats rho
-template <int D, int BITS, bool WIDE>
+// AMAX: no record; every lane keeps the running maximum of |w| of its 32 packed indices (direct run, mirror run and
+//       the bottom element of its mirror block: together the lanes of a vector cover every index once) over all the
+//       tiles it sees; at the end the 32 vectors' lanes are reduced and one atomic maximum per channel goes to `amax`,
+//       read as unsigned[d] (srft_kv_channel_absmax: the statistic lambda is calibrated from, Sec. 7.1).
+template <int D, int BITS, bool WIDE, bool AMAX = false>
 __device__ __forceinline__ void
 srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
                          uint2* __restrict__ codes, float* __restrict__ scales, float unscale, float scale_mul,
-                         int gw, const int t0, const int stride, const int t_end) {
+                         int gw, const int t0, const int stride, const int t_end, unsigned int* __restrict__ amax = nullptr) {
     constexpr int M = D / 64;            // wavefronts per workgroup
     constexpr int G = D / 32;            // groups per vector
     constexpr int T = D / 32;            // k-steps per slab (K = D / 2)
@@ -68,7 +72,8 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     __shared__ float gmax[WIDE ? 2 : 1][WIDE ? kTileVecs * G : 1];     // maxima of the 32-runs of a tile (WIDE)
     // The record of a finished tile is staged here and stored one stage later, 16 bytes per thread over whole rows:
     // stored directly, a tile's record is 8-byte pieces and single floats, a write request each.
-    constexpr bool STAGE = SRFT_QF_STAGE_OUT != 0;
+    constexpr bool STAGE = SRFT_QF_STAGE_OUT != 0 && !AMAX;
+    static_assert(!AMAX || (BITS == 4 && !WIDE), "the statistic has one instance per d");
     constexpr int CU8 = (BITS == 8 ? D : D / 2) / 8;     // 8-byte units per code row
     constexpr int CROW = CU8 + 1;                        // padded: the lanes of a wavefront hit different banks
     __shared__ uint2 cstage[STAGE ? 2 : 1][STAGE ? kTileVecs * CROW : 1];
@@ -100,6 +105,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
     constexpr bool RHO_LDS = (D >= SRFT_QF_RHO_LDS_MIN_D);
     __shared__ uint4 rho_s[RHO_LDS ? 4 * NT : 1];
     float rho[16];
+    float amd[AMAX ? 16 : 1] = {}, amm[AMAX ? 16 : 1] = {};     // running maxima of the direct and the mirror run (AMAX)
     {
         const uint4* rp = wfold + M * 2 * T * 2 * 64 + (wave * 64 + lane) * 4;
 #pragma unroll
@@ -222,6 +228,16 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         // bottom element of this lane's aligned mirror block
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mv[0]), __float_as_uint(mv[0]), false, false);
         const float bottom = half ? below : __uint_as_float(sw[1]);      // [1]: the upper lanes' value, in all lanes
+        if constexpr (AMAX) {                    // rows past the end alias to the last row: a maximum does not mind
+            amm[0] = fmaxf(amm[0], fabsf(bottom));
+            amd[0] = fmaxf(amd[0], fabsf(dv[0]));
+#pragma unroll
+            for (int v = 1; v < 16; ++v) {
+                amd[v] = fmaxf(amd[v], fabsf(dv[v]));
+                amm[v] = fmaxf(amm[v], fabsf(mv[v]));
+            }
+            return;
+        }
         float md = fmaxf(fabsf(dv[0]), fabsf(dv[1])), mm = fmaxf(fabsf(bottom), fabsf(mv[1]));
 #pragma unroll
         for (int v = 2; v < 16; ++v) {
@@ -322,6 +338,25 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         }
     };
 
+    // AMAX: lanes of one half hold the same 32 indices for 32 different vectors: butterfly over the 32, then one atomic
+    // per channel (non-negative floats order like their bit patterns)
+    auto emit_amax = [&]() __attribute__((always_inline)) {
+        if constexpr (AMAX) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float md = amd[v], mm = amm[v];
+#pragma unroll
+                for (int step = 1; step < 32; step *= 2) {
+                    md = fmaxf(md, __shfl_xor(md, step, 64));
+                    mm = fmaxf(mm, __shfl_xor(mm, step, 64));
+                }
+                if (col == 0) {
+                    atomic_max_nonneg(&amax[base_d + 16 * half + v], md * unscale);
+                    atomic_max_nonneg(&amax[p_top - 16 * half - (v == 0 ? 16 : v)], mm * unscale);
+                }
+            }
+        }
+    };
     const int m = (t_end - 1 - t0) / stride + 1;            // tiles of this workgroup: t0, t0 + stride, ... < t_end
     uint4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3;
     floatx16 ea, oa, eb, ob;
@@ -385,6 +420,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
             if constexpr (STAGE) __syncthreads();
             flush(0, tl);
         }
+        emit_amax();
         return;
     }
     // stage 0
@@ -433,6 +469,7 @@ srft_quantize_fold_tiles(const uint4* __restrict__ wfold, const uint4* __restric
         if constexpr (STAGE) __syncthreads();
         flush(0, tl);
     }
+    emit_amax();
 }
 
 // two wavefronts per SIMD (8 per compute unit): the register allocator is told to stay within 256 VGPRs
@@ -444,6 +481,20 @@ srft_quantize_fold_kernel(const uint4* __restrict__ wfold, const uint4* __restri
     int t0, stride, t_end;
     if (!srft_tile_range(n_vec, t0, stride, t_end)) return;
     srft_quantize_fold_tiles<D, BITS, WIDE>(wfold, x, n_vec, codes, scales, unscale, scale_mul, gw, t0, stride, t_end);
+}
+
+// the abs-max statistic through the folded contraction: amax is float[d] read as unsigned, updated with atomic maxima
+// (at d = 256 the 32 running maxima do not fit beside the matrix in 256 registers, and with them in scratch the kernel
+// takes twice as long: one workgroup per compute unit)
+template <int D>
+__global__ void __launch_bounds__(D, (D >= 256 ? 1 : 2))
+srft_quantize_fold_amax_kernel(const uint4* __restrict__ wfold, const uint4* __restrict__ x, long long n_vec,
+                               uint2* __restrict__, float* __restrict__, float4* __restrict__ amax, float unscale,
+                               float scale_mul, int gw) {
+    int t0, stride, t_end;
+    if (!srft_tile_range(n_vec, t0, stride, t_end)) return;
+    srft_quantize_fold_tiles<D, 4, false, true>(wfold, x, n_vec, nullptr, nullptr, unscale, scale_mul, gw, t0, stride, t_end,
+                                                reinterpret_cast<unsigned int*>(amax));
 }
 
 template <int D, int BITS, bool WIDE>

@@ -250,7 +250,7 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
                 float mx = cmax[s][v];
 #pragma unroll
                 for (int step = 1; step < 32; step *= 2) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
-                if (col == 0) atomicMax(&amax[32 * (wave * S + s) + 16 * half + v], __float_as_uint(mx * unscale));
+                if (col == 0) atomic_max_nonneg(&amax[32 * (wave * S + s) + 16 * half + v], mx * unscale);
             }
     }
 }
