@@ -288,9 +288,10 @@ def main() -> int:
                 "hbm_frac": n * (rec_bytes + 4 * n_q) / ta / 1e9 / HBM_PEAK_GBPS}
             result["decode_attention"] = {
                 "queries": n_q, "keys": n, "us": tda * 1e6,
-                "what": "scores over the K record, statistics of their row softmax, the V record weighted with "
-                        "exp(scale * score - maximum) / sum formed from the raw scores as they are loaded: both "
-                        "records read once, the n_q x n_keys scores written once and read twice",
+                "what": "scores over the K record (the scan keeps the row maxima), the V record weighted with "
+                        "exp(scale * score - maximum) formed from the raw scores as they are loaded, divided by the sums "
+                        "of those weights at the end: both records read once, the n_q x n_keys scores written once and "
+                        "read once",
                 "replayed_from_a_hip_graph_us": tdg * 1e6,
                 "dequantize_K_and_V_instead_us": 2 * tdq * 1e6}
     if args.decode_append:

@@ -193,9 +193,10 @@ int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_
 /*
  * One decode step of attention over a stored cache: out = softmax(softmax_scale * q K^T) V with K and V read from
  * their records (plan_k, plan_v: same d, own signs and lambda each).    (Sec. 1; Sec. 7.2)
- * On one stream: srft_kv_scores; the (maximum, sum of exponentials) of every row of scores; the weighted sums of
- * srft_kv_attend, whose kernel forms the weights exp(softmax_scale * score - maximum) / sum from the raw scores as it
- * loads them (the scores are written once and read twice).  q_f16_dev [n_q, d] fp16 (16-byte aligned),
+ * On one stream: srft_kv_scores, whose scan also keeps the maximum of softmax_scale * score per row; then the weighted
+ * sums of srft_kv_attend, whose kernel forms the weights exp(softmax_scale * score - maximum) from the raw scores as it
+ * loads them, carries their sums along and divides by them at the end (the scores are written once and read once; the
+ * row softmax has no pass of its own).  q_f16_dev [n_q, d] fp16 (16-byte aligned),
  * out_f32_dev [n_q, d] fp32; workspace_dev: srft_decode_attention_workspace_bytes(plan_k, plan_v, n_q, n_keys) bytes,
  * 256-byte aligned (it holds the n_q x n_keys scores).  Shapes and limits as for the two calls it is made of.
  */

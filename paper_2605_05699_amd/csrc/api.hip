@@ -203,8 +203,9 @@ int64_t srft_scores_workspace_bytes(const srft_plan_t* plan) {
     return (int64_t)(plan->d / 16) * 2 * 64 * 16 + (int64_t)kMaxScoreWorkgroups * 64 * 4;
 }
 
-int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
-                   const float* scales_dev, int64_t n_keys, float* scores_dev, void* workspace_dev, void* hip_stream) {
+static int scores_with_row_max(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
+                               const float* scales_dev, int64_t n_keys, float* scores_dev, void* workspace_dev,
+                               unsigned int* row_max, float sign, void* hip_stream) {
     if (!plan) return SRFT_ERR_NULL;
     if (plan->d % 64 != 0) return SRFT_ERR_BAD_D;
     if (plan->bits != 4) return SRFT_ERR_BAD_BITS;
@@ -219,10 +220,17 @@ int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, cons
     uint4* qfrag = (uint4*)workspace_dev;
     float* dump = (float*)((char*)qfrag + (size_t)(plan->d / 16) * 2 * 64 * 16);
     // the write path's plain kernel transforms the queries and stores them as the scan's MFMA operands
-    const int rc = launch_quantize(plan, q_f16_dev, n_q, nullptr, plan->inv_lam2, (float*)qfrag,
+    // (and clears the row maxima, if the caller wants them)
+    const int rc = launch_quantize(plan, q_f16_dev, n_q, (uint8_t*)row_max, plan->inv_lam2, (float*)qfrag,
                                      n_q <= 16 ? kOutQFrag16 : kOutQFrag32, st);
     if (rc != SRFT_OK) return rc;
-    return srft_launch_scores(plan, qfrag, dump, n_q, codes_dev, scales_dev, n_keys, scores_dev, st);
+    return srft_launch_scores(plan, qfrag, dump, n_q, codes_dev, scales_dev, n_keys, scores_dev, row_max, sign, st);
+}
+
+int srft_kv_scores(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
+                   const float* scales_dev, int64_t n_keys, float* scores_dev, void* workspace_dev, void* hip_stream) {
+    return scores_with_row_max(plan, q_f16_dev, n_q, codes_dev, scales_dev, n_keys, scores_dev, workspace_dev, nullptr,
+                               1.0f, hip_stream);
 }
 
 int srft_kv_scores_static(const srft_plan_t* plan, const void* q_f16_dev, int n_q, const uint8_t* codes_dev,
@@ -246,7 +254,7 @@ static int attend_supported(const srft_plan_t* plan) {
 
 int64_t srft_attend_workspace_bytes(const srft_plan_t* plan) {
     if (!plan) return SRFT_ERR_NULL;
-    return (int64_t)(kMaxAttendStripes + kAttendFan) * 32 * plan->d * 4;  // the partial sums of every workgroup, and of their first-level sums
+    return (int64_t)srft_attend_workspace_floats(plan->d) * 4;
 }
 
 int srft_kv_attend(const srft_plan_t* plan, const float* weights_f32_dev, int n_q, const uint8_t* codes_dev,
@@ -268,8 +276,7 @@ int64_t srft_decode_attention_workspace_bytes(const srft_plan_t* plan_k, const s
     if (!plan_k || !plan_v) return SRFT_ERR_NULL;
     if (n_q < 1 || n_q > 32 || n_keys < 1 || n_keys > kMaxVectors) return SRFT_ERR_BAD_N;
     const int64_t scores = ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256;
-    return scores + srft_softmax_stats_bytes(32) +
-           std::max(srft_scores_workspace_bytes(plan_k), srft_attend_workspace_bytes(plan_v));
+    return scores + kRowMaxCopies * 32 * 4 + std::max(srft_scores_workspace_bytes(plan_k), srft_attend_workspace_bytes(plan_v));
 }
 
 int srft_kv_decode_attention(const srft_plan_t* plan_k, const srft_plan_t* plan_v, const void* q_f16_dev, int n_q,
@@ -286,20 +293,18 @@ int srft_kv_decode_attention(const srft_plan_t* plan_k, const srft_plan_t* plan_
         !srft_aligned(v_scales_dev, 4))
         return SRFT_ERR_ALIGN;
     float* scores = (float*)workspace_dev;
-    void* stats = (char*)workspace_dev + ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256;
-    void* rest = (char*)stats + srft_softmax_stats_bytes(32);
-    // the per-row (maximum, 1 / sum) pairs follow the per-chunk ones
-    float2* row_stats = (float2*)((char*)rest - 32 * sizeof(float2));
+    unsigned int* row_max = (unsigned int*)((char*)workspace_dev + ((int64_t)n_q * n_keys * 4 + 255) / 256 * 256);
+    void* rest = (char*)row_max + kRowMaxCopies * 32 * 4;
     hipStream_t st = (hipStream_t)hip_stream;
-    // scores of the queries against the stored keys; the statistics of their row softmax; the stored values weighted
-    // with exp(scale * score - maximum) / sum, formed from the raw scores as the value-side kernel loads them.
-    // The same workspace serves the first and the third step, which run one after the other on the stream.
-    rc = srft_kv_scores(plan_k, q_f16_dev, n_q, k_codes_dev, k_scales_dev, n_keys, scores, rest, hip_stream);
-    if (rc != SRFT_OK) return rc;
-    rc = srft_launch_softmax_row_stats(scores, n_q, n_keys, softmax_scale, stats, row_stats, st);
+    // Scores of the queries against the stored keys, the scan keeping the maximum of softmax_scale * score per row;
+    // then the stored values weighted with exp(softmax_scale * score - maximum), formed from the raw scores as the
+    // value-side kernel loads them, the sums of those weights carried along and divided out at the end: the row
+    // softmax has no pass of its own.  The same workspace serves both steps, which run one after the other.
+    rc = scores_with_row_max(plan_k, q_f16_dev, n_q, k_codes_dev, k_scales_dev, n_keys, scores, rest, row_max,
+                             softmax_scale < 0.0f ? -1.0f : 1.0f, hip_stream);
     if (rc != SRFT_OK) return rc;
     return srft_launch_attend(plan_v, scores, n_q, v_codes_dev, v_scales_dev, n_keys, out_f32_dev, (float*)rest,
-                              row_stats, softmax_scale, st);
+                              row_max, softmax_scale, st);
 }
 
 int srft_lambda_from_absmax(const float* amax_host, int d, float* lambda_host) {

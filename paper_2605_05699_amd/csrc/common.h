@@ -68,6 +68,7 @@ constexpr int kMaxScoreWorkgroups = 4096;   // scores kernel: largest grid (each
 constexpr int kMaxD = 256;
 constexpr int kMaxAttendStripes = 2048;      // value-side kernel: most workgroups per channel slab (each owns 32 x d floats of workspace)
 constexpr int kAttendFan = 64;                // value-side kernel: first-level sums the partial results are added into
+constexpr int kRowMaxCopies = 64;            // copies of the per-query score maxima (a cache line each), so that the scan's atomics spread
 constexpr float kMinScale = 7.888609052210118e-31f;   // 2^-100: below this a group is stored as zero
 // The kernels index tiles of 32 vectors with 32-bit integers and look a few grid strides ahead.
 constexpr int64_t kMaxVectors = (int64_t)1 << 33;
@@ -161,23 +162,24 @@ batched_kernel_t srft_pick_dequantize_batched_b8(int d, int slabs, int gm, bool 
 int srft_launch_quantize_butterfly(const float* table_dev, const void* x, long long n_vec, uint8_t* codes, float* scales,
                                    int max_workgroups, hipStream_t st);
 // scores in the rotated domain: launch of the scan (kernels/scores.hip) and its resident workgroups per unit
+// row_max: nullptr, or kRowMaxCopies x 32 cleared words: copy (workgroup mod kRowMaxCopies) receives, per query, the
+// ordered code (srft_ordered_code) of the maximum of sign * score over that workgroup's keys
 int srft_launch_scores(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
-                       const float* scales, long long n_keys, float* out, hipStream_t st);
+                       const float* scales, long long n_keys, float* out, unsigned int* row_max, float sign,
+                       hipStream_t st);
 int srft_scores_occupancy(int d, bool r16, int* blocks_per_cu);
 
 // weighted sums of the stored values in the rotated domain (kernels/attend.hip): workgroups per channel slab for
 // n_q queries over n_keys values, and the three launches (partial sums per workgroup into `part`, their fixed-order
-// reduction, the inverse transform).  row_stats: nullptr (w holds the weights), or per query the (maximum, 1 / sum)
-// of the row softmax of softmax_scale * w: w then holds raw scores and the weights are formed as they are loaded.
+// reduction, the inverse transform).  row_max: nullptr (w holds the weights), or the kRowMaxCopies x 32 ordered codes of
+// the maxima of sign(softmax_scale) * w over the keys, as srft_launch_scores leaves them: w then holds raw scores, the
+// weights exp(softmax_scale * w - maximum) are formed as the scores are loaded, their sums are carried along and the
+// result is divided by them (a row softmax without a pass of its own).
 int srft_attend_stripes(const srft_plan* p, int n_q, long long n_keys);
+size_t srft_attend_workspace_floats(int d);
 int srft_launch_attend(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, const float* scales,
-                       long long n_keys, float* out, float* part, const float2* row_stats, float softmax_scale,
+                       long long n_keys, float* out, float* part, const unsigned int* row_max, float softmax_scale,
                        hipStream_t st);
-// statistics of the row softmax of scale * x, rows of n floats (kernels/softmax.hip): row_stats[row] = (maximum,
-// 1 / sum of exponentials); chunk_stats: srft_softmax_stats_bytes(rows) bytes of workspace
-int64_t srft_softmax_stats_bytes(int rows);
-int srft_launch_softmax_row_stats(const float* x, int rows, long long n, float scale, void* chunk_stats,
-                                  float2* row_stats, hipStream_t st);
 
 // ---- host side (plan.hip, api.hip) ----
 int srft_hip_fail(hipError_t e);         // records the error for srft_last_hip_error, returns SRFT_ERR_HIP

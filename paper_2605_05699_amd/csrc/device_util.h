@@ -181,6 +181,17 @@ __device__ __forceinline__ void atomic_max_nonneg(unsigned int* p, float v) {
     if (bits > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(p, bits);
 }
 
+// An unsigned code of a float that orders like the float (negative floats: all bits flipped; others: sign bit set),
+// so that an unsigned atomic maximum is a float maximum.  The code 0 lies below every float's: cleared memory is "no
+// value yet".
+__device__ __forceinline__ unsigned int srft_ordered_code(float f) {
+    const unsigned int b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float srft_ordered_value(unsigned int c) {
+    return __uint_as_float((c & 0x80000000u) ? (c & 0x7FFFFFFFu) : ~c);
+}
+
 // Which tiles a workgroup of a per-plan launch walks: first tile, stride, and the end (exclusive) of its range.
 // SRFT_XCD_MAP = 0: tile = blockIdx + k gridDim over all tiles.  SRFT_XCD_MAP = 1: workgroups are dealt to the 8
 // accelerator dies round-robin (die = blockIdx mod 8), and each die gets one contiguous eighth of the tiles, which

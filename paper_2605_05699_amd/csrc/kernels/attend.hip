@@ -26,13 +26,15 @@ constexpr int kAttendTileKeys = 64;
 // NQB: query rows the kernel carries (n_q <= NQB).  8 and 16 run on v_mfma_f32_16x16x32_f16 (16 query rows, 32 keys
 // per instruction: half the matrix-core time and half the operand-forming work of the 32-row form), 32 on
 // v_mfma_f32_32x32x16_f16.
-// row_stats: nullptr, or per query (row maximum of softmax_scale * w, 1 / sum of exponentials): w then holds raw
-// scores, and the weight exp(softmax_scale * w - maximum) / sum is formed as the scores are loaded.
+// row_max: nullptr, or per query the ordered code of the maximum of sign(softmax_scale) * w over the keys: w then
+// holds raw scores, the weight exp(softmax_scale * w - maximum) is formed as the scores are loaded, and the workgroup
+// leaves the sum of its weights per query in den_part[stripe][32] (slab 0 only) for the final division.
 template <int D, int GS, int NQB>
 __global__ void __launch_bounds__(64, NQB <= 8 ? 8 : NQB <= 16 ? 7 : 5)    // one-wavefront workgroups: as many per unit as LDS allows
 srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2* __restrict__ codes,
                               const float* __restrict__ scales, long long n_keys, int gw, float* __restrict__ part,
-                              int stripes, const float2* __restrict__ row_stats, float softmax_scale) {
+                              int stripes, const unsigned int* __restrict__ row_max, float softmax_scale,
+                              float* __restrict__ den_part) {
     constexpr bool R16 = NQB <= 16;
     constexpr int ROWS = R16 ? 16 : 32;                      // rows of the MFMA A operand
     constexpr int G = D / 32, SLABS = G / GS, C = D / 16;    // C: 8-byte code units per row
@@ -58,14 +60,21 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
 #pragma unroll
     for (int j = 0; j < NACC; ++j) acc[j] = Acc{0};
 
-    // softmax statistics of the rows (uniform: scalar registers); rows past n_q alias to the last row
-    float row_max[NQB], row_inv[NQB];
-    if (row_stats) {
+    // row maxima of softmax_scale * score (uniform: scalar registers); rows past n_q alias to the last row
+    float rmax[NQB], wsum[NQB];
+#pragma unroll
+    for (int i = 0; i < NQB; ++i) {
+        rmax[i] = 0.0f;
+        wsum[i] = 0.0f;
+    }
+    if (row_max) {                               // uniform: lane l reads copy l, the wavefront takes the maximum
+        static_assert(kRowMaxCopies == 64, "one copy per lane");
 #pragma unroll
         for (int i = 0; i < NQB; ++i) {
-            const float2 rs = row_stats[min(i, n_q - 1)];
-            row_max[i] = rs.x;
-            row_inv[i] = rs.y;
+            unsigned int code = row_max[lane * 32 + min(i, n_q - 1)];
+#pragma unroll
+            for (int step = 32; step > 0; step >>= 1) code = max(code, (unsigned int)__shfl_xor((int)code, step, 64));
+            rmax[i] = fabsf(softmax_scale) * srft_ordered_value(code);
         }
     }
     struct Prefetch { uint2 c[8]; float s[GS]; };
@@ -96,12 +105,15 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
         float v[NQB];
 #pragma unroll
         for (int i = 0; i < NQB; ++i) v[i] = (w + (long long)min(i, n_q - 1) * n_keys + t0)[(unsigned)rl];
-        if (row_stats) {                         // uniform
+        if (row_max) {                           // uniform
 #pragma unroll
-            for (int i = 0; i < NQB; ++i) v[i] = __expf(fmaf(softmax_scale, v[i], -row_max[i])) * row_inv[i];
+            for (int i = 0; i < NQB; ++i) v[i] = __expf(fmaf(softmax_scale, v[i], -rmax[i]));
         }
 #pragma unroll
-        for (int i = 0; i < NQB; ++i) wreg[i] = (live && i < n_q) ? v[i] : 0.0f;
+        for (int i = 0; i < NQB; ++i) {
+            wreg[i] = (live && i < n_q) ? v[i] : 0.0f;
+            wsum[i] += wreg[i];
+        }
     };
     // Codes -> B fragments.  The 8 keys x 16 channels block of this thread is transposed as bytes (a byte holds the
     // nibbles of channels 2 c and 2 c + 1): four 4 x 4 byte transposes give, per channel pair and half of the keys,
@@ -243,6 +255,16 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
             contract();
         }
     }
+    // the sums of this workgroup's weights, lane by lane in a fixed order
+    if (den_part && slab == 0) {                 // uniform
+#pragma unroll
+        for (int i = 0; i < NQB; ++i) {
+            float t = wsum[i];
+#pragma unroll
+            for (int step = 32; step > 0; step >>= 1) t += __shfl_xor(t, step, 64);
+            if (lane == 0) den_part[stripe * 32 + i] = t;
+        }
+    }
     // the sums of this workgroup: part[stripe][query][channel]
     float* dst = part + (long long)stripe * 32 * D;
     if constexpr (R16) {
@@ -266,11 +288,28 @@ srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2*
 }
 
 // first level of the fixed-order sum: part2[c][i][n] = sum over the stripes c, c + kAttendFan, ... of part[stripe][i][n]
-// (eight loads in flight per thread; the eight running sums are added in a fixed order)
+// (eight loads in flight per thread; the eight running sums are added in a fixed order).  With den_part, the blocks
+// c = kAttendFan add the stripes' sums of weights of query i instead: den[i], thread by thread in a fixed order.
 template <int D>
 __global__ void __launch_bounds__(D)
-srft_attend_reduce_kernel(const float* __restrict__ part, int stripes, float* __restrict__ part2) {
+srft_attend_reduce_kernel(const float* __restrict__ part, int stripes, float* __restrict__ part2,
+                          const float* __restrict__ den_part, float* __restrict__ den) {
+    __shared__ float red[D / 64];
     const int i = blockIdx.x, c = blockIdx.y, n = threadIdx.x;
+    if (c == kAttendFan) {                       // uniform per block
+        float t = 0.0f;
+        for (int sidx = n; sidx < stripes; sidx += D) t += den_part[sidx * 32 + i];
+#pragma unroll
+        for (int step = 32; step > 0; step >>= 1) t += __shfl_xor(t, step, 64);
+        if ((n & 63) == 0) red[n >> 6] = t;
+        __syncthreads();
+        if (n == 0) {
+            float total = red[0];
+            for (int k = 1; k < D / 64; ++k) total += red[k];
+            den[i] = total;
+        }
+        return;
+    }
     float sum[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     for (int s0 = c; s0 < stripes; s0 += 8 * kAttendFan) {
 #pragma unroll
@@ -282,15 +321,18 @@ srft_attend_reduce_kernel(const float* __restrict__ part, int stripes, float* __
     part2[((long long)c * 32 + i) * D + n] = ((sum[0] + sum[1]) + (sum[2] + sum[3])) + ((sum[4] + sum[5]) + (sum[6] + sum[7]));
 }
 
-// out[i][n] = sum_k rmat[k][n] * (sum over c of part2[c][i][k]);  rmat[k][n] = s_n Q[k][n] / max(lambda_k, 1e-6).
+// out[i][n] = sum_k rmat[k][n] * (sum over c of part2[c][i][k]) / den[i];  rmat[k][n] = s_n Q[k][n] / max(lambda_k, 1e-6);
+// without den the divisor is 1.
 // A workgroup of 4 D threads per query: quarter q of the threads adds the first-level sums c = q (mod 4) of channel n,
 // then takes the quarter q of the k range of output n; both sets of four partial results meet in LDS, in a fixed order.
 template <int D>
 __global__ void __launch_bounds__(4 * D)
-srft_attend_finish_kernel(const float* __restrict__ part2, const float* __restrict__ rmat, float* __restrict__ out) {
+srft_attend_finish_kernel(const float* __restrict__ part2, const float* __restrict__ rmat, float* __restrict__ out,
+                          const float* __restrict__ den) {
     __shared__ float quarter[4][D];
     __shared__ float accs[D];
     const int i = blockIdx.x, n = threadIdx.x % D, q = threadIdx.x / D;
+    const float inv_den = den ? 1.0f / den[i] : 1.0f;
     float sum = 0.0f;
 #pragma unroll
     for (int c = q; c < kAttendFan; c += 4) sum += part2[((long long)c * 32 + i) * D + n];
@@ -303,35 +345,38 @@ srft_attend_finish_kernel(const float* __restrict__ part2, const float* __restri
     for (int k = 0; k < D / 4; ++k) o = fmaf(rmat[(q * (D / 4) + k) * D + n], accs[q * (D / 4) + k], o);   // all loads in flight
     quarter[q][n] = o;
     __syncthreads();
-    if (q == 0) out[(long long)i * D + n] = (quarter[0][n] + quarter[1][n]) + (quarter[2][n] + quarter[3][n]);
+    if (q == 0) out[(long long)i * D + n] = ((quarter[0][n] + quarter[1][n]) + (quarter[2][n] + quarter[3][n])) * inv_den;
 }
 
 template <int D, int GS, int NQB>
 int launch_rows(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, const float* scales, long long n_keys,
-                float* out, float* part, int stripes, const float2* row_stats, float softmax_scale, hipStream_t st) {
+                float* out, float* part, int stripes, const unsigned int* row_max, float softmax_scale, hipStream_t st) {
     constexpr int SLABS = D / 32 / GS;
-    hipLaunchKernelGGL((srft_attend_accumulate_kernel<D, GS, NQB>), dim3((unsigned)(stripes * SLABS)), dim3(64), 0, st, w,
-                       n_q, (const uint2*)codes, scales, n_keys, p->gw, part, stripes, row_stats, softmax_scale);
-    SRFT_HIP(hipGetLastError());
+    // workspace: part [kMaxAttendStripes][32][D], part2 [kAttendFan][32][D], den_part [kMaxAttendStripes][32], den [32]
     float* part2 = part + (size_t)kMaxAttendStripes * 32 * D;
-    hipLaunchKernelGGL(srft_attend_reduce_kernel<D>, dim3((unsigned)n_q, kAttendFan), dim3(D), 0, st, (const float*)part,
-                       stripes, part2);
+    float* den_part = row_max ? part2 + (size_t)kAttendFan * 32 * D : nullptr;
+    float* den = row_max ? den_part + (size_t)kMaxAttendStripes * 32 : nullptr;
+    hipLaunchKernelGGL((srft_attend_accumulate_kernel<D, GS, NQB>), dim3((unsigned)(stripes * SLABS)), dim3(64), 0, st, w,
+                       n_q, (const uint2*)codes, scales, n_keys, p->gw, part, stripes, row_max, softmax_scale, den_part);
+    SRFT_HIP(hipGetLastError());
+    hipLaunchKernelGGL(srft_attend_reduce_kernel<D>, dim3((unsigned)n_q, kAttendFan + (row_max ? 1 : 0)), dim3(D), 0, st,
+                       (const float*)part, stripes, part2, (const float*)den_part, den);
     SRFT_HIP(hipGetLastError());
     hipLaunchKernelGGL(srft_attend_finish_kernel<D>, dim3((unsigned)n_q), dim3(4 * D), 0, st, (const float*)part2,
-                       (const float*)p->rmat_f32, out);
+                       (const float*)p->rmat_f32, out, (const float*)den);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
 
 template <int D, int GS>
 int launch(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, const float* scales, long long n_keys,
-           float* out, float* part, const float2* row_stats, float softmax_scale, hipStream_t st) {
+           float* out, float* part, const unsigned int* row_max, float softmax_scale, hipStream_t st) {
     const int stripes = srft_attend_stripes(p, n_q, n_keys);
     if (n_q <= 8)
-        return launch_rows<D, GS, 8>(p, w, n_q, codes, scales, n_keys, out, part, stripes, row_stats, softmax_scale, st);
+        return launch_rows<D, GS, 8>(p, w, n_q, codes, scales, n_keys, out, part, stripes, row_max, softmax_scale, st);
     if (n_q <= 16)
-        return launch_rows<D, GS, 16>(p, w, n_q, codes, scales, n_keys, out, part, stripes, row_stats, softmax_scale, st);
-    return launch_rows<D, GS, 32>(p, w, n_q, codes, scales, n_keys, out, part, stripes, row_stats, softmax_scale, st);
+        return launch_rows<D, GS, 16>(p, w, n_q, codes, scales, n_keys, out, part, stripes, row_max, softmax_scale, st);
+    return launch_rows<D, GS, 32>(p, w, n_q, codes, scales, n_keys, out, part, stripes, row_max, softmax_scale, st);
 }
 
 }  // namespace
@@ -346,14 +391,18 @@ int srft_attend_stripes(const srft_plan* p, int n_q, long long n_keys) {
     return (int)(s < 1 ? 1 : s);
 }
 
+size_t srft_attend_workspace_floats(int d) {
+    return (size_t)(kMaxAttendStripes + kAttendFan) * 32 * d + (size_t)(kMaxAttendStripes + kAttendFan) * 32;
+}
+
 int srft_launch_attend(const srft_plan* p, const float* w, int n_q, const uint8_t* codes, const float* scales,
-                       long long n_keys, float* out, float* part, const float2* row_stats, float softmax_scale,
+                       long long n_keys, float* out, float* part, const unsigned int* row_max, float softmax_scale,
                        hipStream_t st) {
     switch (p->d) {
-        case 64: return launch<64, 2>(p, w, n_q, codes, scales, n_keys, out, part, row_stats, softmax_scale, st);
-        case 128: return launch<128, 4>(p, w, n_q, codes, scales, n_keys, out, part, row_stats, softmax_scale, st);
-        case 192: return launch<192, 3>(p, w, n_q, codes, scales, n_keys, out, part, row_stats, softmax_scale, st);
-        case 256: return launch<256, 4>(p, w, n_q, codes, scales, n_keys, out, part, row_stats, softmax_scale, st);
+        case 64: return launch<64, 2>(p, w, n_q, codes, scales, n_keys, out, part, row_max, softmax_scale, st);
+        case 128: return launch<128, 4>(p, w, n_q, codes, scales, n_keys, out, part, row_max, softmax_scale, st);
+        case 192: return launch<192, 3>(p, w, n_q, codes, scales, n_keys, out, part, row_max, softmax_scale, st);
+        case 256: return launch<256, 4>(p, w, n_q, codes, scales, n_keys, out, part, row_max, softmax_scale, st);
         default: return SRFT_ERR_BAD_D;
     }
 }

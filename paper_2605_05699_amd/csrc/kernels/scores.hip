@@ -32,7 +32,8 @@
 template <int D, int NV, bool R16>
 __global__ void __launch_bounds__(64, (D <= 128 || R16) ? 2 : 1)
 srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ codes, const float* __restrict__ scales,
-                   long long n_keys, float* __restrict__ out, int n_q, int gw, float* __restrict__ dump) {
+                   long long n_keys, float* __restrict__ out, int n_q, int gw, float* __restrict__ dump,
+                   unsigned int* __restrict__ row_max, float sign) {
     constexpr int G = D / 32, U = D / 8, ROW = U + 1, C = D / 16;
     constexpr int PER = C / 2;           // 8-byte code units per lane and tile (32 C units, 64 lanes)
     constexpr int SROW = G + 1;
@@ -48,6 +49,12 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
     const int last_lim = (int)(n_keys - 1 - (long long)(n_tiles - 1) * kTileVecs);
     const int t0 = blockIdx.x, stride = gridDim.x;
     float* const my_dump = dump + (size_t)blockIdx.x * 64 + lane;
+    // running maximum of sign * score over this lane's valid (query, key) pairs, per result register: what a softmax
+    // over the rows needs first (row_max: nullptr, or kRowMaxCopies x 32 order-preserving codes of such maxima, see
+    // srft_ordered_code, one copy updated with atomic maxima when the workgroup is done)
+    float vmax[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) vmax[v] = -INFINITY;
 
     half8 qhi[NF], qlo[NF];
 #pragma unroll
@@ -96,6 +103,7 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
             float* dst = v < nv_lane ? out + at : my_dump;
             *dst = val[v];
             at += 2 * n_keys;
+            vmax[v] = fmaxf(vmax[v], v < nv_lane ? sign * val[v] : -INFINITY);
         }
         // With many queries the kernel mostly writes; letting a tile's stores complete before the next stage
         // measured 3-5 % faster than keeping them in flight (s_waitcnt vmcnt(0); the other counters at their maximum).
@@ -211,12 +219,31 @@ srft_scores_kernel(const uint4* __restrict__ qfrag, const uint2* __restrict__ co
         __syncthreads();
         tile_scores(1, t0 + k * stride);
     }
+    if (row_max) {                               // uniform
+        // lanes with the same a hold the same queries (2 v + a) for different keys: R16 a = bit 4 of the lane (after the
+        // swap of tile_scores), else a = bit 5; the maximum runs over the other five lane bits
+        constexpr int kABit = R16 ? 16 : 32;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            float mx = vmax[v];
+#pragma unroll
+            for (int step = 1; step < 64; step *= 2)
+                if (step != kABit) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
+            const int a = (lane & kABit) ? 1 : 0, q = 2 * v + a;
+            if ((lane & (63 ^ kABit)) == 0 && q < n_q) {
+                const unsigned int code = srft_ordered_code(mx);
+                // kRowMaxCopies copies, a cache line each: atomics to one line are served one after the other
+                unsigned int* slot = &row_max[(blockIdx.x % kRowMaxCopies) * 32 + q];
+                atomicMax(slot, code);
+            }
+        }
+    }
 }
 
 namespace {
 template <int D>
 int launch(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t* codes, const float* scales,
-           long long n_keys, float* out, hipStream_t st) {
+           long long n_keys, float* out, unsigned int* row_max, float sign, hipStream_t st) {
     if constexpr (D % 64 == 0) {
         const bool r16 = n_q <= 16;             // 16 MFMA rows are enough: half the matrix-core time
         const long long n_tiles = (n_keys + kTileVecs - 1) / kTileVecs;
@@ -228,7 +255,7 @@ int launch(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t
                     : nv <= 4 ? srft_scores_kernel<D, 4, true> : nv <= 8 ? srft_scores_kernel<D, 8, true>
                                                                          : srft_scores_kernel<D, 16, false>;
         hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(64), 0, st, (const uint4*)qfrag,
-                           (const uint2*)codes, scales, n_keys, out, n_q, p->gw, dump);
+                           (const uint2*)codes, scales, n_keys, out, n_q, p->gw, dump, row_max, sign);
         SRFT_HIP(hipGetLastError());
         return SRFT_OK;
     } else {
@@ -249,12 +276,13 @@ int occupancy(bool r16, int* blocks) {
 }  // namespace
 
 int srft_launch_scores(const srft_plan* p, uint4* qfrag, float* dump, int n_q, const uint8_t* codes,
-                       const float* scales, long long n_keys, float* out, hipStream_t st) {
+                       const float* scales, long long n_keys, float* out, unsigned int* row_max, float sign,
+                       hipStream_t st) {
     switch (p->d) {
-        case 64: return launch<64>(p, qfrag, dump, n_q, codes, scales, n_keys, out, st);
-        case 128: return launch<128>(p, qfrag, dump, n_q, codes, scales, n_keys, out, st);
-        case 192: return launch<192>(p, qfrag, dump, n_q, codes, scales, n_keys, out, st);
-        case 256: return launch<256>(p, qfrag, dump, n_q, codes, scales, n_keys, out, st);
+        case 64: return launch<64>(p, qfrag, dump, n_q, codes, scales, n_keys, out, row_max, sign, st);
+        case 128: return launch<128>(p, qfrag, dump, n_q, codes, scales, n_keys, out, row_max, sign, st);
+        case 192: return launch<192>(p, qfrag, dump, n_q, codes, scales, n_keys, out, row_max, sign, st);
+        case 256: return launch<256>(p, qfrag, dump, n_q, codes, scales, n_keys, out, row_max, sign, st);
         default: return SRFT_ERR_BAD_D;
     }
 }

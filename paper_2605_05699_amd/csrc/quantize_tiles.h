@@ -82,6 +82,14 @@ srft_quantize_tiles(const uint4* __restrict__ wfrag, const uint4* __restrict__ x
         if constexpr (PER > 2) { put1(buf, c, 2); put1(buf, d, 3); }
     };
     float cmax[OUT == kOutAmax ? S : 1][16] = {};            // running per-channel maxima (kOutAmax)
+    if constexpr (OUT == kOutQFrag32 || OUT == kOutQFrag16) {
+        // the scores set-up launch (one workgroup) also clears the row maxima that the scan will update with atomic
+        // maxima, when the caller wants them: `codes` then points to kRowMaxCopies x 32 words
+        if (codes) {                             // uniform
+            unsigned int* words = reinterpret_cast<unsigned int*>(codes);
+            for (int i = tid; i < kRowMaxCopies * 32; i += NT) words[i] = 0u;
+        }
+    }
     using Acc = Accs<S>;
     auto contract = [&](int b, Acc& accs) __attribute__((always_inline)) {
         const uint4* rowp = &lds[b][col * ROW + half];
