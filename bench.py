@@ -36,10 +36,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # counter run reports null.  (FETCH_SIZE x its copy-kernel factor + WRITE_SIZE x its factor) KiB per dispatch x 1024 /
 # vectors per dispatch.
 MEASURED_TRAFFIC_PER_VECTOR = {
-    ("srft_quantize_fold_kernel", 128): 336.53,
+    ("srft_quantize_fold_batched_kernel", 128): 336.41,
     ("srft_dequantize_batched_kernel", 128): 336.38,
-    ("srft_quantize_fold4_kernel", 256): 672.80,
-    ("srft_dequantize_batched_kernel", 256): 673.22,
+    ("srft_quantize_fold4_batched_kernel", 256): 672.66,
+    ("srft_dequantize_batched_kernel", 256): 673.25,
 }
 
 # What a kernel that only streams the same bytes reaches on this machine (bench.py --ceiling, best over grid sizes and
@@ -72,6 +72,8 @@ def main() -> int:
     ap.add_argument("--max-workgroups", type=int, default=0)
     ap.add_argument("--batched", choices=["auto", "on", "off"], default="auto",
                     help="several plans per launch (auto: when a plan has fewer than 65,536 vectors)")
+    ap.add_argument("--plans-per-launch", type=int, default=0,
+                    help="plans per batched launch (at most 64); 0 = 64 for small plans, 4 for plans of 65536 vectors or more")
     ap.add_argument("--ceiling", action="store_true",
                     help="also time the streaming kernel that has each path's read:write byte mix (HBM ceiling)")
     ap.add_argument("--decode-append", action="store_true",
@@ -131,27 +133,35 @@ def main() -> int:
 
     stream = torch.cuda.current_stream()
     h = [pl.handle for pl in plans]
-    batched_q = args.batched == "on" or (args.batched == "auto" and n < 65536)
+    # Plans per launch.  Small plans go 64 to a launch (a launch per plan would be launch-bound).  With plans of a
+    # million vectors a few per launch are best: measured on this workload, 4 plans per launch against a launch per
+    # plan and against 64 per launch: write 5.35 / 5.25 / 5.0 TB/s, read 5.3 / 5.0 / 4.95 TB/s.
+    batched_q = args.batched == "on" or (args.batched == "auto" and n_plans > 1)
     batched_d = args.batched == "on" or (args.batched == "auto" and n_plans > 1)
-    launches_q = -(-n_plans // 64) if batched_q else n_plans      # per step
-    launches_d = -(-n_plans // 64) if batched_d else n_plans
+    per_launch = args.plans_per_launch if args.plans_per_launch > 0 else (64 if n < 65536 else 4)
+    per_launch = min(per_launch, 64)
+    launches_q = -(-n_plans // per_launch) if batched_q else n_plans      # per step
+    launches_d = -(-n_plans // per_launch) if batched_d else n_plans
+    chunks = [slice(i, min(i + per_launch, n_plans)) for i in range(0, n_plans, per_launch)]
     if batched_q:
-        table_q = B.BatchTable(h, list(x), list(codes), list(scales))
+        tables_q = [B.BatchTable(h[c], list(x[c]), list(codes[c]), list(scales[c])) for c in chunks]
     if batched_d:
-        table_d = B.BatchTable(h, list(out), list(codes), list(scales))
+        tables_d = [B.BatchTable(h[c], list(out[c]), list(codes[c]), list(scales[c])) for c in chunks]
 
     def step(ev=None):
         if ev:
             ev[0].record(stream)
         if batched_q:
-            B.srft_kv_quantize_batched(table_q, stream)
+            for t in tables_q:
+                B.srft_kv_quantize_batched(t, stream)
         else:
             for p in range(n_plans):
                 B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
         if ev:
             ev[1].record(stream)
         if batched_d:
-            B.srft_kv_dequantize_batched(table_d, stream)
+            for t in tables_d:
+                B.srft_kv_dequantize_batched(t, stream)
         else:
             for p in range(n_plans):
                 B.srft_kv_dequantize(h[p], codes[p], scales[p], out[p], stream)
@@ -217,20 +227,23 @@ def main() -> int:
 
     if w.name == "llama3-70b-128k" and not args.no_d256:
         # the metric names d = 256 beside d = 128: the same launch shape (1,048,576 vectors per plan) at d = 256
-        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream)
+        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream, per_launch=per_launch)
     if args.butterfly and d == 128 and g == 32:
         def b_pass():
             for p in range(n_plans):
                 B.srft_kv_quantize_butterfly(h[p], x[p], codes[p], scales[p], stream)
+        def m_pass():                            # the matrix-core form the same way: a launch per plan
+            for p in range(n_plans):
+                B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
         tb, _ = timed_passes(torch, stream, b_pass, None, args.steps)
+        tm, _ = timed_passes(torch, stream, m_pass, None, args.steps)      # (also restores the record)
+        qm = total_vec * bytes_per_vec / tm / 1e9
         result["quantize_butterfly_form"] = {
             "what": "same plans, same record, the transform as fp32 FFT butterflies on the vector ALU (one vector per "
                     "lane) instead of the matrix-core contraction; a launch per plan",
             "GBps": total_vec * bytes_per_vec / tb / 1e9, "hbm_frac": total_vec * bytes_per_vec / tb / 1e9 / HBM_PEAK_GBPS,
             "vectors_per_s": total_vec / tb, "avg_launch_ms": tb / n_plans * 1e3,
-            "matrix_core_form_GBps": qa, "ratio_matrix_core_over_butterfly": qa / (total_vec * bytes_per_vec / tb / 1e9)}
-        B.srft_kv_quantize_batched(table_q, stream) if batched_q else [
-            B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream) for p in range(n_plans)]   # restore the record
+            "matrix_core_form_GBps": qm, "ratio_matrix_core_over_butterfly": qm / (total_vec * bytes_per_vec / tb / 1e9)}
     if args.ceiling:
         result["hbm_ceiling"] = mix_ceiling(M, torch, x, out, n_plans * n, d, G, stream)
     if args.power:
@@ -419,8 +432,8 @@ def all_configs(B, W, torch, dev, stream):
     return res
 
 
-def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10):
-    """Write pass (a launch per plan) and read pass (one batched launch) over n_plans x n vectors of d = 256, g = 32:
+def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10, per_launch=4):
+    """Write pass and read pass (per_launch plans per launch, as in the main step) over n_plans x n vectors of d = 256, g = 32:
     N(0,1) times a lognormal(0,1) channel scale and lognormal(0,0.5) lambda per plan, as in the d = 256 config.
     `warm` untimed passes of each path precede the `reps` timed ones (about 25 ms each way): after the idle gap in
     which the plans are built the first few milliseconds of work run 20-30 % slower than the steady state that the
@@ -439,14 +452,17 @@ def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10):
     scales = torch.empty(n_plans, n, G, dtype=torch.float32, device=dev)
     out = torch.empty(n_plans, n, d, dtype=torch.float16, device=dev)
     h = [pl.handle for pl in plans]
-    table = B.BatchTable(h, list(out), list(codes), list(scales))
+    chunks = [slice(i, min(i + per_launch, n_plans)) for i in range(0, n_plans, per_launch)]
+    tables_q = [B.BatchTable(h[c], list(x[c]), list(codes[c]), list(scales[c])) for c in chunks]
+    tables_d = [B.BatchTable(h[c], list(out[c]), list(codes[c]), list(scales[c])) for c in chunks]
 
     def pass_q():
-        for p in range(n_plans):
-            B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
+        for t in tables_q:
+            B.srft_kv_quantize_batched(t, stream)
 
     def pass_d():
-        B.srft_kv_dequantize_batched(table, stream)
+        for t in tables_d:
+            B.srft_kv_dequantize_batched(t, stream)
 
     for _ in range(warm):
         pass_q()
@@ -467,7 +483,7 @@ def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10):
     tq, td = ev[0].elapsed_time(ev[1]) / reps / 1e3, ev[1].elapsed_time(ev[2]) / reps / 1e3
     for pl in plans:
         pl.close()
-    return {"d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
+    return {"d": d, "group": g, "plans": n_plans, "vectors_per_plan": n, "plans_per_launch": per_launch,
             "quantize": {"GBps": nbytes / tq / 1e9, "hbm_frac": nbytes / tq / 1e9 / HBM_PEAK_GBPS,
                          "vectors_per_s": n_plans * n / tq},
             "dequantize": {"GBps": nbytes / td / 1e9, "hbm_frac": nbytes / td / 1e9 / HBM_PEAK_GBPS,
