@@ -397,6 +397,33 @@ def test_d256_at_the_launch_size_the_bench_times(B):
         pl.close()
 
 
+@pytest.mark.parametrize("name", ["llama3-70b-128k", "gemma3-1b-4k"])
+def test_four_plans_per_launch_as_the_bench_times_them(B, name):
+    # bench.py puts 4 plans of 1,048,576 vectors into every launch, both directions (d = 128: the headline workload;
+    # d = 256: its side measurement).  The batched launches must produce the bytes of the per-plan launches, which
+    # _sampled_parity holds against the oracle at this size (plans 0 and 159 / 0 and 51 above).
+    w = W.WORKLOADS[name]
+    n = 1 << 20
+    plans, xs = [], []
+    for pi in (0, 1, w.n_plans - 2, w.n_plans - 1):
+        plan, _ = _plan_for(B, w, pi)
+        plans.append(plan)
+        xs.append(W.make_kv(w, pi, n_vec=n, device="cuda"))
+    recs = [pl.quantize(x) for pl, x in zip(plans, xs)]
+    outs = [pl.dequantize(c, sc) for pl, (c, sc) in zip(plans, recs)]
+    h = [pl.handle for pl in plans]
+    codes_b = [torch.empty_like(c) for c, _ in recs]
+    scales_b = [torch.empty_like(sc) for _, sc in recs]
+    outs_b = [torch.empty_like(o) for o in outs]
+    B.srft_kv_quantize_batched(B.BatchTable(h, xs, codes_b, scales_b))
+    B.srft_kv_dequantize_batched(B.BatchTable(h, outs_b, codes_b, scales_b))
+    torch.cuda.synchronize()
+    for (c, sc), cb, sb, o, ob in zip(recs, codes_b, scales_b, outs, outs_b):
+        assert torch.equal(c, cb) and torch.equal(sc, sb) and torch.equal(o, ob)
+    for pl in plans:
+        pl.close()
+
+
 def test_single_launch_beyond_4_gib(B):
     # 20,000,003 vectors of d = 128: 5.1 GB of fp16 in one launch, so tile bases pass 2^32 bytes (64-bit scalar
     # base + 32-bit lane offset) and the last tile is ragged; sampled rows against the oracle, properties on all.
