@@ -435,3 +435,39 @@ def test_softmax_rows_and_decode_attention():
     # a single key: the output is that value's reconstruction whatever the query
     one = O.decode_attention(q, rk["codes"][:1], rk["scales"][:1], sk, lk, rv["codes"][:1], rv["scales"][:1], sv, lv, g, 1.0)
     assert np.allclose(one, np.broadcast_to(vb[:1], one.shape), atol=1e-14)
+
+
+def test_an_fp16_matrix_needs_its_second_half_on_every_k_step():
+    """Why the GPU applies the d x d matrix W = diag(lambda) Q diag(s) as fp16 hi + fp16 lo everywhere (a design check on
+    the CPU; nothing of the HIP path is involved).  Acceptance criterion (b) lets a code differ only where r = w / scale
+    is within 1e-4 of a rounding boundary, so the kernel's r must be good to well under 1e-4.  With W rounded to one
+    fp16 (after a power-of-two scaling) the error of r is several 1e-4 on every row; keeping the second half on 7 of
+    the 8 k-steps of 16 inputs, or on the worse three quarters of the rows, still leaves a large share of the codes
+    with an error above 1e-4.  With both halves everywhere it is about 1e-7."""
+    d, g = 128, 32
+    rng = np.random.RandomState(0)
+    s = O.signs_from_seed(7, d).astype(np.float64)
+    lam = np.exp(0.5 * rng.standard_normal(d))
+    W = lam[:, None] * O.srft_matrix(d) * s[None, :]
+    e = 14 - int(np.ceil(np.log2(np.abs(W).max())))
+    Ws = W * 2.0 ** e
+    hi = Ws.astype(np.float16).astype(np.float64)
+    lo = (Ws - hi).astype(np.float16).astype(np.float64)
+    x = rng.standard_normal((4096, d)).astype(np.float16).astype(np.float64)
+    w_exact = x @ W.T
+    scale = np.repeat(np.abs(w_exact.reshape(-1, d // g, g)).max(axis=2) / 7.0, g, axis=1)
+
+    def dr(M):
+        return np.abs((x @ M.T) / 2.0 ** e - w_exact) / scale
+
+    both = dr(hi + lo)
+    assert both.max() < 1e-5
+    hi_only = dr(hi)
+    assert (hi_only > 1e-4).mean() > 0.7 and hi_only.max(axis=0).min() > 1e-4        # every row, most codes
+    most_steps = hi.copy()
+    most_steps[:, :112] += lo[:, :112]                                                # lo on 7 of the 8 k-steps
+    assert (dr(most_steps) > 1e-4).mean() > 0.3
+    worst_rows = np.argsort(-hi_only.max(axis=0))[: 3 * d // 4]
+    most_rows = hi.copy()
+    most_rows[worst_rows] += lo[worst_rows]
+    assert (dr(most_rows) > 1e-4).mean() > 0.1
