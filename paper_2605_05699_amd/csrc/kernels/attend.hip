@@ -30,7 +30,8 @@ constexpr int kAttendTileKeys = 64;
 // holds raw scores, the weight exp(softmax_scale * w - maximum) is formed as the scores are loaded, and the workgroup
 // leaves the sum of its weights per query in den_part[stripe][32] (slab 0 only) for the final division.
 template <int D, int GS, int NQB>
-__global__ void __launch_bounds__(64, NQB <= 8 ? 8 : NQB <= 16 ? 7 : 5)    // one-wavefront workgroups: as many per unit as LDS allows
+// (second bound: wavefronts per SIMD the register allocator aims for; LDS allows 8 / 7 / 5 workgroups per compute unit)
+__global__ void __launch_bounds__(64, NQB <= 16 ? 3 : 2)
 srft_attend_accumulate_kernel(const float* __restrict__ w, int n_q, const uint2* __restrict__ codes,
                               const float* __restrict__ scales, long long n_keys, int gw, float* __restrict__ part,
                               int stripes, const unsigned int* __restrict__ row_max, float softmax_scale,
