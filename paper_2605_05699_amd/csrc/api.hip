@@ -34,8 +34,8 @@ int launch_dequantize(const srft_plan* p, const uint8_t* codes, const float* sca
     int threads = 0;
     const dequantize_kernel_t kernel = srft_plan_dequantize_kernel(p, &threads);
     if (!kernel) return SRFT_ERR_BAD_D;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), 0, st, p->fold_dq ? p->rfold : p->rfrag,
-                       (const uint2*)codes, scales, n, (uint4*)out, p->unscale_r, p->gw);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), 0, st, srft_plan_read_table(p),
+                       (const uint2*)codes, scales, n, (uint4*)out, srft_plan_read_unscale(p), p->gw);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }
@@ -71,6 +71,9 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
                                   : srft_pick_quantize_plain_batched_b4(p->d, p->slabs_q, p->gm);
             threads = 2 * p->d / p->slabs_q;
         }
+    } else if (p->fold4_dq) {
+        kernel = srft_pick_dequantize_fold4_batched(p->bits);
+        threads = 256;
     } else {
         kernel = p->bits == 8 ? srft_pick_dequantize_batched_b8(p->d, p->slabs_dq, p->gm, p->fold_dq)
                               : srft_pick_dequantize_batched_b4(p->d, p->slabs_dq, p->gm, p->fold_dq);
@@ -107,13 +110,13 @@ int srft_run_batched(const srft_plan_t* const* plans, const void* const* in0, co
         if (i < count && n_vec[i] > 0) {
             const int k = a.count++;
             a.frag[k] = write_path ? (plans[i]->fold4_q ? plans[i]->wfold4 : plans[i]->fold_q ? plans[i]->wfold : plans[i]->wfrag)
-                                   : (plans[i]->fold_dq ? plans[i]->rfold : plans[i]->rfrag);
+                                   : srft_plan_read_table(plans[i]);
             a.in0[k] = in0[i];
             a.in1[k] = write_path ? nullptr : in1[i];
             a.out0[k] = out0[i];
             a.out1[k] = write_path ? out1[i] : nullptr;
             a.n_vec[k] = n_vec[i];
-            a.unscale[k] = write_path ? plans[i]->unscale_w : plans[i]->unscale_r;
+            a.unscale[k] = write_path ? plans[i]->unscale_w : srft_plan_read_unscale(plans[i]);
         }
         if (a.count == kMaxBatch || (i == count && a.count > 0)) {
             const int rc = launch_batched(plans[0], a, write_path, st);

@@ -110,6 +110,7 @@ struct srft_plan {
     uint4* rfold = nullptr;     // read-path fragments of the folded form (device), when fold_dq
     uint4* wfold = nullptr;     // write-path fragments of the folded form (device), when fold_q
     uint4* wfold4 = nullptr;    // write-path table of the twice-folded form (device), when fold4_q
+    uint4* rfold4 = nullptr;    // read-path table of the twice-folded form (device), when fold4_dq
     float* rmat_f32 = nullptr;  // R^T in fp32, [k][n] = s_n Q[k][n] / max(lambda_k, 1e-6) (device): the one inverse transform per
                                 // query of srft_kv_attend
     int compute_units = 0;
@@ -120,8 +121,10 @@ struct srft_plan {
     bool fold_dq = false;       // read path contracts even and odd codes separately (half the matrix work)
     bool fold_q = false;        // write path contracts even and odd inputs separately (half the matrix work)
     bool fold4_q = false;       // write path contracts the inputs in four classes n mod 4 (a quarter of the work)
+    bool fold4_dq = false;      // read path contracts (cosine | sine) x (even | odd) codes apart (a quarter of the work)
     float unscale_w = 1.0f;     // 2^-e of the write matrix
     float unscale_r = 1.0f;
+    float unscale_r4 = 1.0f;    // 2^-e of the twice-folded read table
     int grid_q = 0, grid_dq = 0;    // default persistent grid sizes
     int slabs_q = 1, slabs_dq = 1;  // slabs of the matrix per wavefront in the write / read kernel
     int gm = 1, gw = 1;             // group mode (kGroup16 / kGroup32 / kGroupWide) and slabs per group
@@ -158,6 +161,10 @@ dequantize_kernel_t srft_pick_dequantize_b4(int d, int slabs, int gm, bool fold)
 dequantize_kernel_t srft_pick_dequantize_b8(int d, int slabs, int gm, bool fold);
 batched_kernel_t srft_pick_dequantize_batched_b4(int d, int slabs, int gm, bool fold);
 batched_kernel_t srft_pick_dequantize_batched_b8(int d, int slabs, int gm, bool fold);
+// read path, folded twice (d = 256, g >= 32); the size of its table in 16-byte units and the offsets of its parts
+dequantize_kernel_t srft_pick_dequantize_fold4(int bits);
+batched_kernel_t srft_pick_dequantize_fold4_batched(int bits);
+int srft_rfold4_table_units(void);
 // write path with the transform as FFT butterflies on the vector ALU (d = 128, g = 32, 4-bit; the comparison form)
 int srft_launch_quantize_butterfly(const float* table_dev, const void* x, long long n_vec, uint8_t* codes, float* scales,
                                    int max_workgroups, hipStream_t st);
@@ -192,6 +199,9 @@ int srft_hip_fail(hipError_t e);         // records the error for srft_last_hip_
 // the kernels a plan launches, and their block sizes
 quantize_kernel_t srft_plan_quantize_kernel(const srft_plan* p, int out, int* threads);
 dequantize_kernel_t srft_plan_dequantize_kernel(const srft_plan* p, int* threads);
+// the table and the matrix scaling the read-path kernel of a plan takes
+inline const uint4* srft_plan_read_table(const srft_plan* p) { return p->fold4_dq ? p->rfold4 : p->fold_dq ? p->rfold : p->rfrag; }
+inline float srft_plan_read_unscale(const srft_plan* p) { return p->fold4_dq ? p->unscale_r4 : p->unscale_r; }
 // batched launches over plans that share shape and kernel choice (api.hip)
 int srft_run_batched(const srft_plan_t* const* plans, const void* const* in0, const void* const* in1,
                      void* const* out0, void* const* out1, const int64_t* n_vec, int count, bool write_path,
