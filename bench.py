@@ -341,7 +341,8 @@ def kernel_symbol(B, plan_handle, path, batched):
     if form < 0:
         raise RuntimeError(f"srft_plan_form: {form}")
     if path == "dequantize":
-        return "srft_dequantize_batched_kernel" if batched else "srft_dequantize_kernel"
+        stem = "srft_dequantize_fold4" if form == 2 else "srft_dequantize"
+        return stem + ("_batched_kernel" if batched else "_kernel")
     stem = ("srft_quantize", "srft_quantize_fold", "srft_quantize_fold4")[form]
     return stem + ("_batched_kernel" if batched else "_kernel")
 

@@ -72,8 +72,8 @@ int launch_batched(const srft_plan* p, srft_batch_args& a, bool write_path, hipS
             threads = 2 * p->d / p->slabs_q;
         }
     } else if (p->fold4_dq) {
-        kernel = srft_pick_dequantize_fold4_batched(p->bits);
-        threads = 256;
+        kernel = srft_pick_dequantize_fold4_batched(p->d, p->bits);
+        threads = p->d;
     } else {
         kernel = p->bits == 8 ? srft_pick_dequantize_batched_b8(p->d, p->slabs_dq, p->gm, p->fold_dq)
                               : srft_pick_dequantize_batched_b4(p->d, p->slabs_dq, p->gm, p->fold_dq);

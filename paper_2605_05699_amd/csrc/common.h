@@ -161,10 +161,10 @@ dequantize_kernel_t srft_pick_dequantize_b4(int d, int slabs, int gm, bool fold)
 dequantize_kernel_t srft_pick_dequantize_b8(int d, int slabs, int gm, bool fold);
 batched_kernel_t srft_pick_dequantize_batched_b4(int d, int slabs, int gm, bool fold);
 batched_kernel_t srft_pick_dequantize_batched_b8(int d, int slabs, int gm, bool fold);
-// read path, folded twice (d = 256, g >= 32); the size of its table in 16-byte units and the offsets of its parts
-dequantize_kernel_t srft_pick_dequantize_fold4(int bits);
-batched_kernel_t srft_pick_dequantize_fold4_batched(int bits);
-int srft_rfold4_table_units(void);
+// read path, folded twice (d = 128 and 256, g >= 32); the size of its table in 16-byte units
+dequantize_kernel_t srft_pick_dequantize_fold4(int d, int bits);
+batched_kernel_t srft_pick_dequantize_fold4_batched(int d, int bits);
+int srft_rfold4_table_units(int d);
 // write path with the transform as FFT butterflies on the vector ALU (d = 128, g = 32, 4-bit; the comparison form)
 int srft_launch_quantize_butterfly(const float* table_dev, const void* x, long long n_vec, uint8_t* codes, float* scales,
                                    int max_workgroups, hipStream_t st);

@@ -1,4 +1,4 @@
-// dequantize_fold4_tiles.h -- read path at d = 256, folded twice: a quarter of the dense matrix work, half the
+// dequantize_fold4_tiles.h -- read path at d = 128 and 256, folded twice: a quarter of the dense matrix work, half the
 // scale fold of the once-folded form.
 //
 // With h = d/2 the inverse of Eq. 1-2 is  u_n = C_n + S_n,  C_n the sum over the packed indices p <= h (DC, the cosine
@@ -39,27 +39,32 @@
 #define SRFT_DEQUANTIZE_FOLD4_TILES_H
 #include "device_util.h"
 
-constexpr int kRFold4FragUnits = 4 * 2 * 4 * 2 * 64;
-constexpr int kRFold4HalfUnits = 4 * 2 * 6;
-constexpr int kRFold4Units = kRFold4FragUnits + kRFold4HalfUnits + 4;
+// sizes of the table's parts (16-byte units) at head dimension d: NW = d/64 wavefronts, d/64 groups per half
+constexpr int srft_rfold4_frag_units(int d) { return (d / 64) * 2 * (d / 64) * 2 * 64; }
+constexpr int srft_rfold4_half_units(int d) { return (d / 64) * 2 * 6; }
+constexpr int srft_rfold4_units(int d) { return srft_rfold4_frag_units(d) + srft_rfold4_half_units(d) + d / 64; }
 
-template <int BITS>
+template <int D, int BITS>
 __device__ __forceinline__ void
 srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restrict__ codes_raw,
                             const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                             float unscale, int gw, const int t0, const int stride, const int t_end) {
-    constexpr int D = 256, U = D / 8, ROW = U + 1, C = D / 16, NT = 256, SROW = 9;
+    static_assert(D == 128 || D == 256, "one or two blocks of 32 values of m per class");
+    constexpr int NB = D / 128, NW = 2 * NB, GH = D / 64;      // m blocks per class, wavefronts, groups per half of the record
+    constexpr int LG = D == 256 ? 3 : 2;                        // log2 of the groups per vector at g = 32
+    constexpr int U = D / 8, ROW = U + 1, C = D / 16, NT = 64 * NW, SROW = D / 32 + 1;
+    constexpr int kFragUnits = srft_rfold4_frag_units(D), kHalfUnits = srft_rfold4_half_units(D);
     using CodeUnit = std::conditional_t<BITS == 8, uint4, uint2>;
     const CodeUnit* __restrict__ codes = reinterpret_cast<const CodeUnit*>(codes_raw);
     const int sh = __builtin_ctz((unsigned)gw);  // g = 32 gw, gw a power of two: group j uses scale j >> sh
-    const int ns = 8 >> sh;                      // scales per vector
+    const int ns = (D / 32) >> sh;               // scales per vector
     __shared__ uint4 dec[2][kTileVecs * ROW];    // decoded codes of T_k in dec[k % 2]: per code unit [even p][odd p]
     __shared__ uint4 stg[kTileVecs * ROW];       // finished fp16 rows of the tile staged last
-    __shared__ uint4 xch[2 * 2 * 4 * 64];        // [sent by: cosine, sine][m block][quarter][lane]: `send`, fp32
+    __shared__ uint4 xch[2 * NB * 4 * 64];       // [sent by: cosine, sine][m block][quarter][lane]: `send`, fp32
     __shared__ float scl[2][kTileVecs * SROW];   // scales (times 2^-e) of T_k in scl[k % 2]
-    __shared__ float s_own32[2][32];             // own[m = 32] of the second cosine / sine wavefront
-    __shared__ float s_neg64[32];                // -So_64
-    __shared__ float s_c64[4][32];               // Ce_64: one partial sum per wavefront (group)
+    __shared__ float s_own32[2][32];             // own[m = 32] of the second cosine / sine wavefront (d = 256)
+    __shared__ float s_neg64[32];                // -So at m = d/4, the row above the last block
+    __shared__ float s_c64[NW][32];              // Ce at m = d/4: one partial sum per wavefront (group)
     // Stores that only some lanes make go to this array from the other lanes, a word per thread: the code between the
     // barriers stays one straight-line block (a branch after the pinned MFMA / multiply-add pipeline lets the
     // compiler sink the multiply-adds out of it).
@@ -68,22 +73,22 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // uniform: kept in a scalar register
     const int col = lane & 31, half = lane >> 5;
-    const int sine = wave >> 1, blk = wave & 1;
+    const int sine = wave / NB, blk = wave % NB;
     const int n_tiles = (int)((n_vec + kTileVecs - 1) / kTileVecs);
     const int last_lim = (int)(n_vec - 1 - (long long)(n_tiles - 1) * kTileVecs);
 
-    half8 rhi[2][4], rlo[2][4];                  // [class][group]
+    half8 rhi[2][GH], rlo[2][GH];                // [class][group]
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int f = ((wave * 2 + c) * 4 + j) * 2;
+        for (int j = 0; j < GH; ++j) {
+            const int f = ((wave * 2 + c) * GH + j) * 2;
             rhi[c][j] = __builtin_bit_cast(half8, tab[(f + 0) * 64 + lane]);
             rlo[c][j] = __builtin_bit_cast(half8, tab[(f + 1) * 64 + lane]);
         }
-    __shared__ uint4 s_half[kRFold4HalfUnits];   // per (wavefront, lane half): 4 units of sign masks, 2 of coefficients
-    if (tid < kRFold4HalfUnits) s_half[tid] = tab[kRFold4FragUnits + tid];     // visible after the first barrier
-    const float c_nyq = __uint_as_float(tab[kRFold4FragUnits + kRFold4HalfUnits + wave].x);   // uniform; 0 on the sine side
+    __shared__ uint4 s_half[kHalfUnits];   // per (wavefront, lane half): 4 units of sign masks, 2 of coefficients
+    if (tid < kHalfUnits) s_half[tid] = tab[kFragUnits + tid];     // visible after the first barrier
+    const float c_nyq = __uint_as_float(tab[kFragUnits + kHalfUnits + wave].x);   // uniform; 0 on the sine side
     const uint4* mine = &s_half[(wave * 2 + half) * 6];
 
     // ---- loads and decode: as in the once-folded kernel (two code units and one scale per thread) ----
@@ -99,7 +104,7 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
         fetch1(c1, 1, codes + row0 * C, lim);
         int e = tid;
         if (e > 32 * ns - 1) e = 32 * ns - 1;
-        s0 = (scales + row0 * ns)[(unsigned)(min(e >> (3 - sh), lim) * ns + (e & (ns - 1)))];
+        s0 = (scales + row0 * ns)[(unsigned)(min(e >> (LG - sh), lim) * ns + (e & (ns - 1)))];
     };
     auto put1 = [&](int b, const CodeUnit& v, int i) __attribute__((always_inline)) {
         const int u = tid + i * NT, r = u / C, c = u % C;
@@ -116,18 +121,18 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
     auto to_lds = [&](int b, const CodeUnit& c0, const CodeUnit& c1, float s0) __attribute__((always_inline)) {
         put1(b, c0, 0);
         put1(b, c1, 1);
-        float* dst = tid < 32 * ns ? &scl[b][(tid >> (3 - sh)) * SROW + (tid & (ns - 1))] : &s_dump[tid];
+        float* dst = tid < 32 * ns ? &scl[b][(tid >> (LG - sh)) * SROW + (tid & (ns - 1))] : &s_dump[tid];
         *dst = s0 * unscale;
     };
 
     floatx16 oE, oO, accE, accO, own;
-    const int jb = 4 * sine;                     // first group of this wavefront's half of the record
+    const int jb = GH * sine;                    // first group of this wavefront's half of the record
     // ---- contraction of the tile in dec[b], and what leaves this wavefront through LDS ----
     auto contract = [&](int b) __attribute__((always_inline)) {
         const uint4* rowp = &dec[b][col * ROW + 2 * half + 4 * jb];     // + 4 jj (+ 1): even / odd codes of group jb + jj
         const float* srow = &scl[b][col * SROW];
-        const float code_n = (float)reinterpret_cast<const _Float16*>(&dec[b][col * ROW + 16])[0];
-        const float t_n = code_n * srow[4 >> sh] * c_nyq;
+        const float code_n = (float)reinterpret_cast<const _Float16*>(&dec[b][col * ROW + D / 16])[0];
+        const float t_n = code_n * srow[GH >> sh] * c_nyq;
         float sc = srow[jb >> sh], sc_next = sc;
         half8 fa_next = __builtin_bit_cast(half8, rowp[0]), fb = __builtin_bit_cast(half8, rowp[1]), fb_next = fb;
         accE = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[0][0], fa_next, floatx16{0}, 0, 0, 0);
@@ -142,10 +147,10 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
             __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
         };
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jj = 0; jj < GH; ++jj) {
             // O_jj on the matrix pipe, E_jj folded in
             __builtin_amdgcn_sched_barrier(0);
-            if (jj + 1 < 4) fa_next = __builtin_bit_cast(half8, rowp[4 * (jj + 1)]);
+            if (jj + 1 < GH) fa_next = __builtin_bit_cast(half8, rowp[4 * (jj + 1)]);
             accO = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[1][jj], fb, floatx16{0}, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 8; ++v) oE[v] = fmaf(accE[v], sc, jj == 0 ? ((v & 1) ? -t_n : t_n) : oE[v]);
@@ -155,17 +160,17 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
             pin_half_step();
             // E_{jj+1} on the matrix pipe, O_jj folded in
             __builtin_amdgcn_sched_barrier(0);
-            if (jj + 1 < 4) {
+            if (jj + 1 < GH) {
                 fb_next = __builtin_bit_cast(half8, rowp[4 * (jj + 1) + 1]);
                 sc_next = srow[(jb + jj + 1) >> sh];
                 accE = __builtin_amdgcn_mfma_f32_32x32x16_f16(rhi[0][jj + 1], fa_next, floatx16{0}, 0, 0, 0);
             }
 #pragma unroll
             for (int v = 0; v < 8; ++v) oO[v] = jj == 0 ? accO[v] * sc : fmaf(accO[v], sc, oO[v]);
-            if (jj + 1 < 4) accE = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[0][jj + 1], fa_next, accE, 0, 0, 0);
+            if (jj + 1 < GH) accE = __builtin_amdgcn_mfma_f32_32x32x16_f16(rlo[0][jj + 1], fa_next, accE, 0, 0, 0);
 #pragma unroll
             for (int v = 8; v < 16; ++v) oO[v] = jj == 0 ? accO[v] * sc : fmaf(accO[v], sc, oO[v]);
-            if (jj + 1 < 4) pin_half_step();
+            if (jj + 1 < GH) pin_half_step();
             sc = sc_next;
             fb = fb_next;
         }
@@ -188,7 +193,7 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
             *(half == 0 ? &s_c64[wave][col] : &s_dump[tid]) = __uint_as_float(r[0]) + __uint_as_float(r[1]);
         }
         // row m = 0 of the first sine wavefront's O slab carried -So_64
-        const bool hijack = (wave == 2) && (half == 0);
+        const bool hijack = (wave == NB) && (half == 0);
         *(hijack ? &s_neg64[col] : &s_dump[tid]) = oO[0];
         oO[0] = hijack ? 0.0f : oO[0];
         floatx16 snd;
@@ -197,18 +202,18 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
             own[v] = oE[v] + oO[v];
             snd[v] = oE[v] - oO[v];
         }
-        *((blk == 1 && half == 0) ? &s_own32[sine][col] : &s_dump[tid]) = own[0];
-        uint4* xw = &xch[((sine * 2 + blk) * 4) * 64 + lane];
+        if constexpr (NB == 2) *((blk == 1 && half == 0) ? &s_own32[sine][col] : &s_dump[tid]) = own[0];
+        uint4* xw = &xch[((sine * NB + blk) * 4) * 64 + lane];
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             xw[q * 64] = make_uint4(__float_as_uint(snd[4 * q]), __float_as_uint(snd[4 * q + 1]),
                                     __float_as_uint(snd[4 * q + 2]), __float_as_uint(snd[4 * q + 3]));
     };
     // ---- after the exchange: the two runs of this lane, rounded to fp16, signed, into the staging tile ----
-    const int uA = 16 * sine + 4 * blk + 2 * half;                      // 16-byte unit of the ascending run
-    const int uD = (sine ? 14 : 30) - 4 * blk - 2 * half;               // ... of the descending run's block
+    const int uA = (U / 2) * sine + 4 * blk + 2 * half;                    // 16-byte unit of the ascending run
+    const int uD = (sine ? U / 2 : U) - 2 - 4 * blk - 2 * half;              // ... of the descending run's block
     auto finish = [&]() __attribute__((always_inline)) {
-        const uint4* xr = &xch[(((1 - sine) * 2 + blk) * 4) * 64 + lane];
+        const uint4* xr = &xch[(((1 - sine) * NB + blk) * 4) * 64 + lane];
         float rc[16];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -219,9 +224,13 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
             rc[4 * q + 3] = __uint_as_float(t.w);
         }
         // bottom element of the descending block: (own - recv) at m0 + 16
-        const float above32 = s_own32[sine][col] - __uint_as_float(xch[(((1 - sine) * 2 + 1) * 4) * 64 + col].x);
-        const float c64 = (s_c64[0][col] + s_c64[1][col]) + (s_c64[2][col] + s_c64[3][col]);
-        const float above = blk == 0 ? above32 : fmaf(c64, sine ? -1.0f : 1.0f, s_neg64[col]);
+        float c64 = s_c64[0][col] + s_c64[1][col];
+        if constexpr (NW == 4) c64 += s_c64[2][col] + s_c64[3][col];
+        float above = fmaf(c64, sine ? -1.0f : 1.0f, s_neg64[col]);      // the row above the last block
+        if constexpr (NB == 2) {
+            const float above32 = s_own32[sine][col] - __uint_as_float(xch[(((1 - sine) * NB + 1) * 4) * 64 + col].x);
+            above = blk == 0 ? above32 : above;
+        }
         float des[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) des[v] = own[v] - rc[v];
@@ -302,21 +311,21 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
     }
 }
 
-template <int BITS>
-__global__ void __launch_bounds__(256, 2)
+template <int D, int BITS>
+__global__ void __launch_bounds__(D / 64 * 64, 2)
 srft_dequantize_fold4_kernel(const uint4* __restrict__ tab, const uint2* __restrict__ codes,
                              const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                              float unscale, int gw) {
     int t0, stride, t_end;
     if (!srft_tile_range(n_vec, t0, stride, t_end)) return;
-    srft_dequantize_fold4_tiles<BITS>(tab, codes, scales, n_vec, out, unscale, gw, t0, stride, t_end);
+    srft_dequantize_fold4_tiles<D, BITS>(tab, codes, scales, n_vec, out, unscale, gw, t0, stride, t_end);
 }
 
-template <int BITS>
-__global__ void __launch_bounds__(256, 2)
+template <int D, int BITS>
+__global__ void __launch_bounds__(D / 64 * 64, 2)
 srft_dequantize_fold4_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
-    srft_dequantize_fold4_tiles<BITS>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
+    srft_dequantize_fold4_tiles<D, BITS>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],
                                       (uint4*)a.out0[i], a.unscale[i], gw, blockIdx.x - a.first_block[i],
                                       a.first_block[i + 1] - a.first_block[i],
                                       (int)((a.n_vec[i] + kTileVecs - 1) / kTileVecs));

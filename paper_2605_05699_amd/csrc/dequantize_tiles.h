@@ -23,7 +23,8 @@
 // S : output slabs per wavefront (the workgroup has D / (32 S) wavefronts), as on the write path.
 // KS: MFMA k-steps (of 16 codes) contracted under one scale: 2 for g >= 32 (g = 32 * gw, gw slabs of codes
 //     share a scale), 1 for g = 16.  "Group" below means one such run of 16 * KS codes.
-// FOLD: half the matrix work, for d a multiple of 64 and g >= 32.  Every row of Q satisfies
+// FOLD: half the matrix work, for d a multiple of 64 and g >= 32 (run at d = 128 and 192; d = 256 has a kernel of its
+//     own, dequantize_fold4_tiles.h, that folds twice).  Every row of Q satisfies
 //     Q[p][n + d/2] = (-1)^p Q[p][n]   (DC and Nyquist rows: +1; cos and sin rows of bin k: (-1)^k, and the
 //     packed index p has the parity of k), so with  A_n = sum over even p,  B_n = sum over odd p  of
 //     Q[p][n] z_p  the outputs are  x_n = s_n (A_n + B_n)  and  x_{n+d/2} = s_{n+d/2} (A_n - B_n),  n < d/2.
@@ -420,8 +421,7 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
 }
 
 template <int D, int S, int KS, bool FOLD, int BITS>
-// (two workgroups per compute unit at d = 256: the register allocator stays within 256 VGPRs)
-__global__ void __launch_bounds__(2 * D / S, (FOLD && D == 256) ? 2 : 1)
+__global__ void __launch_bounds__(2 * D / S, 1)
 srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict__ codes,
                        const float* __restrict__ scales, long long n_vec, uint4* __restrict__ out,
                        float unscale, int gw) {
@@ -431,8 +431,7 @@ srft_dequantize_kernel(const uint4* __restrict__ rfrag, const uint2* __restrict_
 }
 
 template <int D, int S, int KS, bool FOLD, int BITS>
-// (two workgroups per compute unit at d = 256: the register allocator stays within 256 VGPRs)
-__global__ void __launch_bounds__(2 * D / S, (FOLD && D == 256) ? 2 : 1)
+__global__ void __launch_bounds__(2 * D / S, 1)
 srft_dequantize_batched_kernel(const srft_batch_args a, int gw) {
     const int i = srft_segment_of_block(a, blockIdx.x);
     srft_dequantize_tiles<D, S, KS, FOLD, BITS>(a.frag[i], (const uint2*)a.in0[i], (const float*)a.in1[i], a.n_vec[i],

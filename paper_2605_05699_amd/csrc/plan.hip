@@ -154,55 +154,56 @@ void build_fold4_table(const std::vector<int8_t>& signs, const std::vector<doubl
     std::memcpy(misc + 12, m3, 16);
 }
 
-// Table of the twice-folded read path (d = 256, g >= 32): see dequantize_fold4_tiles.h for what the kernel does with
-// it.  Wavefront w = 0, 1 holds cosine rows (packed indices p < h), w = 2, 3 sine rows (p > h; p = h, Nyquist, has a
-// zero column here and enters the cosine side as an addend), each for m = 32 (w mod 2) .. + 31; class 0 are the even,
-// class 1 the odd p of a group; the odd class of the sine wavefronts is negated, and its row m = 0 in wavefront 2
-// carries row m = 64 instead.  Entries are Q[p][m] / max(lambda_p, 1e-6), without the sign diagonal, which the kernel
-// applies through the masks.  Returns the exponent e of the fp16 scaling.
-int build_rfold4_table(const std::vector<int8_t>& signs, const std::vector<double>& lam, int bits,
+// Table of the twice-folded read path (d = 128 or 256, g >= 32): see dequantize_fold4_tiles.h for what the kernel
+// does with it.  With NB = d/128 blocks of 32 values of m per class, wavefront w < NB holds cosine rows (packed
+// indices p < h), w >= NB sine rows (p > h; p = h, Nyquist, has a zero column here and enters the cosine side as an
+// addend), each for m = 32 (w mod NB) .. + 31; class 0 are the even, class 1 the odd p of a group; the odd class of
+// the sine wavefronts is negated, and its row m = 0 in the first sine wavefront carries row m = d/4 instead.  Entries
+// are Q[p][m] / max(lambda_p, 1e-6), without the sign diagonal, which the kernel applies through the masks.
+// Returns the exponent e of the fp16 scaling.
+int build_rfold4_table(int d, const std::vector<int8_t>& signs, const std::vector<double>& lam, int bits,
                        std::vector<uint32_t>& out) {
-    const int d = 256, h = 128;
+    const int h = d / 2, NB = d / 128, NW = 2 * NB, GH = d / 64;
     static const int off4[8] = {0, 4, 2, 6, 8, 12, 10, 14}, off8[8] = {0, 2, 4, 6, 8, 10, 12, 14};
     const int* off = bits == 8 ? off8 : off4;
     auto entry = [&](int p, int m) { return q_entry(d, p, m) / std::fmax(lam[p], 1e-6); };
-    // [w][class][m row 0..31][group 0..3][16 codes], then the 64 coefficients of row m = 64 (even p < h)
-    std::vector<double> rows((size_t)4 * 2 * 32 * 4 * 16 + 64);
-    for (int w = 0; w < 4; ++w) {
-        const int sine = w >> 1, blk = w & 1;
+    // [w][class][m row 0..31][group 0..GH-1][16 codes], then the h/2 coefficients of row m = d/4 (even p < h)
+    const size_t coef0 = (size_t)NW * 2 * 32 * GH * 16;
+    std::vector<double> rows(coef0 + h / 2);
+    for (int w = 0; w < NW; ++w) {
+        const int sine = w / NB, blk = w % NB;
         for (int c = 0; c < 2; ++c)
             for (int r = 0; r < 32; ++r)
-                for (int jj = 0; jj < 4; ++jj)
+                for (int jj = 0; jj < GH; ++jj)
                     for (int i = 0; i < 16; ++i) {
-                        const int p = 32 * (4 * sine + jj) + 2 * i + c, m = 32 * blk + r;
-                        double v = (sine && p == h) ? 0.0 : entry(p, (w == 2 && c == 1 && m == 0) ? 64 : m);
+                        const int p = 32 * (GH * sine + jj) + 2 * i + c, m = 32 * blk + r;
+                        double v = (sine && p == h) ? 0.0 : entry(p, (w == NB && c == 1 && m == 0) ? d / 4 : m);
                         if (sine && c == 1) v = -v;
-                        rows[((((size_t)w * 2 + c) * 32 + r) * 4 + jj) * 16 + i] = v;
+                        rows[((((size_t)w * 2 + c) * 32 + r) * GH + jj) * 16 + i] = v;
                     }
     }
-    const size_t coef0 = (size_t)4 * 2 * 32 * 4 * 16;
-    for (int i = 0; i < 64; ++i) rows[coef0 + i] = entry(2 * i, 64);
+    for (int i = 0; i < h / 2; ++i) rows[coef0 + i] = entry(2 * i, d / 4);
     std::vector<uint16_t> hi, lo;
     const int e = split_hi_lo(rows, hi, lo);
-    out.assign((size_t)srft_rfold4_table_units() * 4, 0);
+    out.assign((size_t)srft_rfold4_table_units(d) * 4, 0);
     uint16_t* frag = reinterpret_cast<uint16_t*>(out.data());
-    for (int w = 0; w < 4; ++w)
+    for (int w = 0; w < NW; ++w)
         for (int c = 0; c < 2; ++c)
-            for (int jj = 0; jj < 4; ++jj)
+            for (int jj = 0; jj < GH; ++jj)
                 for (int l = 0; l < 64; ++l) {
                     const int r = slab_output_of_row(l % 32), kh = l / 32;
                     for (int el = 0; el < 8; ++el) {
                         const int i = (16 * kh + off[el]) / 2;          // even (or odd) code 2 i (+ 1) of the group
-                        const size_t src = ((((size_t)w * 2 + c) * 32 + r) * 4 + jj) * 16 + i;
-                        const size_t dst = ((((size_t)(w * 2 + c) * 4 + jj) * 2) * 64);
+                        const size_t src = ((((size_t)w * 2 + c) * 32 + r) * GH + jj) * 16 + i;
+                        const size_t dst = ((((size_t)(w * 2 + c) * GH + jj) * 2) * 64);
                         frag[((dst + 0) + l) * 8 + el] = hi[src];
                         frag[((dst + 64) + l) * 8 + el] = lo[src];
                     }
                 }
-    const size_t frag_units = (size_t)4 * 2 * 4 * 2 * 64, half_units = (size_t)4 * 2 * 6;
+    const size_t frag_units = (size_t)NW * 2 * GH * 2 * 64, half_units = (size_t)NW * 2 * 6;
     float* consts = reinterpret_cast<float*>(out.data() + (frag_units + half_units) * 4);
-    for (int w = 0; w < 4; ++w) {
-        const int sine = w >> 1, blk = w & 1;
+    for (int w = 0; w < NW; ++w) {
+        const int sine = w / NB, blk = w % NB;
         for (int kh = 0; kh < 2; ++kh) {         // what the 32 lanes of a half share: 16 mask dwords, 8 coefficients
             const int m0 = 32 * blk + 16 * kh;
             const int n_asc = (sine ? h : 0) + m0, n_des = (sine ? h : d) - m0 - 16;
@@ -213,9 +214,9 @@ int build_rfold4_table(const std::vector<int8_t>& signs, const std::vector<doubl
                 const bool lo_neg = (signs[n_des + 2 * i] < 0) != (sine != 0), hi_neg = (signs[n_des + 2 * i + 1] < 0) != (sine != 0);
                 mk[8 + i] = (lo_neg ? 0x8000u : 0u) | (hi_neg ? 0x80000000u : 0u);
             }
-            // row m = 64 over the even codes of cosine group w that a lane of this half reads as a B fragment
+            // row m = d/4 over the even codes of cosine group w that a lane of this half reads as a B fragment
             float* coef = reinterpret_cast<float*>(mk + 16);
-            for (int el = 0; el < 8; ++el) coef[el] = (float)std::ldexp(entry(32 * w + 16 * kh + off[el], 64), e);
+            for (int el = 0; el < 8; ++el) coef[el] = (float)std::ldexp(entry(32 * w + 16 * kh + off[el], d / 4), e);
         }
         consts[w * 4] = sine ? 0.0f : (float)std::ldexp(1.0 / (std::sqrt((double)d) * std::fmax(lam[h], 1e-6)), e);
     }
@@ -284,8 +285,8 @@ quantize_kernel_t srft_plan_quantize_kernel(const srft_plan* p, int out, int* th
 
 dequantize_kernel_t srft_plan_dequantize_kernel(const srft_plan* p, int* threads) {
     if (p->fold4_dq) {
-        *threads = 256;
-        return srft_pick_dequantize_fold4(p->bits);
+        *threads = p->d;
+        return srft_pick_dequantize_fold4(p->d, p->bits);
     }
     *threads = 2 * p->d / p->slabs_dq;
     return p->bits == 8 ? srft_pick_dequantize_b8(p->d, p->slabs_dq, p->gm, p->fold_dq)
@@ -387,8 +388,8 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     // Slabs of the matrix per wavefront: two where the table says so (and the number of groups is even).
     p->slabs_q = (d == 64) ? 2 : 1;
     p->slabs_dq = (d == 256 || d == 64) ? 2 : 1;
-    // Folded read path where it applies and pays (d = 128, 192, 256; g >= 32).
-    p->fold_dq = (d % 64 == 0) && d >= 128 && p->gm != kGroup16 &&    // at d = 64 it gains nothing
+    // Folded read path where it applies and pays (d = 192; g >= 32); d = 128 and 256 have the twice-folded form below.
+    p->fold_dq = (d % 64 == 0) && d >= 128 && d != 128 && d != 256 && p->gm != kGroup16 &&    // at d = 64 it gains nothing
                  transform == SRFT_TRANSFORM_DFT;                      // (the symmetries are the DFT's)
     std::vector<uint16_t> rfold;
     if (p->fold_dq) {
@@ -467,10 +468,10 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     p->fold4_q = (d == 256) && p->gm == kGroup32 && transform == SRFT_TRANSFORM_DFT;
     std::vector<uint32_t> wfold4;
     if (p->fold4_q) build_fold4_table(p->signs, lam, wfold4);
-    // Twice-folded read path at d = 256 (any g >= 32); it replaces the once-folded form there.
-    p->fold4_dq = (d == 256) && p->gm != kGroup16 && transform == SRFT_TRANSFORM_DFT;
+    // Twice-folded read path at d = 128 and 256 (any g >= 32); it replaces the once-folded form there.
+    p->fold4_dq = (d == 128 || d == 256) && p->gm != kGroup16 && transform == SRFT_TRANSFORM_DFT;
     std::vector<uint32_t> rfold4;
-    if (p->fold4_dq) p->unscale_r4 = (float)std::ldexp(1.0, -build_rfold4_table(p->signs, lam, bits, rfold4));
+    if (p->fold4_dq) p->unscale_r4 = (float)std::ldexp(1.0, -build_rfold4_table(d, p->signs, lam, bits, rfold4));
     // Butterfly form of the write path (comparison kernel): per packed index lambda times the packing constant of
     // Eq. 2 -- 1/sqrt d for DC and Nyquist, sqrt(2/d) elsewhere, halved where the unpack leaves a factor 2 (every
     // bin except 0, 32 and 64) -- then the sign diagonal as sign-bit masks of the packed fp16 pairs.

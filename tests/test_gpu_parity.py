@@ -433,9 +433,9 @@ def test_single_launch_beyond_4_gib(B):
 
 def test_plan_form_reports_the_factorisation_each_plan_runs(B):
     """srft_plan_form is what bench.py names the timed kernel by: once-folded write path at d = 128, twice-folded at
-    d = 256 with g = 32, plain elsewhere; folded read path at d = 128 and 192, twice-folded at d = 256, with g >= 32."""
+    d = 256 with g = 32, plain elsewhere; twice-folded read path at d = 128 and 256, once-folded at d = 192, with g >= 32."""
     L = B.lib()
-    expect = {(128, 32, "dft"): (1, 1), (256, 32, "dft"): (2, 2), (256, 64, "dft"): (1, 2), (96, 32, "dft"): (0, 0),
+    expect = {(128, 32, "dft"): (1, 2), (256, 32, "dft"): (2, 2), (256, 64, "dft"): (1, 2), (96, 32, "dft"): (0, 0),
               (192, 32, "dft"): (0, 1), (64, 32, "dft"): (0, 0), (128, 16, "dft"): (0, 0), (128, 32, "hadamard"): (0, 0)}
     for (d, g, tr), (fw, fr) in expect.items():
         plan = B.Plan(d, g, 1, None, transform=tr)
