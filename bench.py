@@ -37,9 +37,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # vectors per dispatch.
 MEASURED_TRAFFIC_PER_VECTOR = {
     ("srft_quantize_fold_batched_kernel", 128): 336.41,
-    ("srft_dequantize_batched_kernel", 128): 336.38,
+    ("srft_dequantize_fold4_batched_kernel", 128): 336.23,
     ("srft_quantize_fold4_batched_kernel", 256): 672.66,
-    ("srft_dequantize_batched_kernel", 256): 673.25,
+    ("srft_dequantize_fold4_batched_kernel", 256): 672.67,
 }
 
 # What a kernel that only streams the same bytes reaches on this machine (bench.py --ceiling, best over grid sizes and

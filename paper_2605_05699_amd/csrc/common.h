@@ -29,9 +29,10 @@
 // CONSECUTIVE outputs: 16 nibbles = one 8-byte store on the write path, 16 fp16 = two 16-byte
 // stores on the read path, with no cross-lane shuffles.
 //
-// Folded forms (d = 128 and 256 on the write path, 128 / 192 / 256 on the read path): two symmetries of Q
-// let every output pair share two half-length partial sums, which halves the matrix work; they are
-// described at srft_quantize_fold_tiles and at the FOLD parameter of srft_dequantize_tiles.
+// Folded forms (d = 128 and 256 on the write path, 128 / 192 / 256 on the read path): symmetries of Q let
+// outputs share half-length (folded once) or quarter-length (folded twice) partial sums, which halves or
+// quarters the matrix work; they are described at srft_quantize_fold_tiles, in quantize_fold4_tiles.h, at
+// the FOLD parameter of srft_dequantize_tiles and in dequantize_fold4_tiles.h.
 //
 // Around the two paths: the same kernels serving several plans in one launch (a segment table passed as a
 // kernel argument), the per-channel abs-max statistic lambda is calibrated from, an 8-bit code width, the
@@ -42,8 +43,9 @@
 // The kernels run at the socket's power limit with a throttled clock, so what shortens them is work per vector
 // (matrix instructions, vector instructions, LDS traffic), not more parallelism: see the folded forms.
 //
-// Source layout: the kernel templates live in quantize_tiles.h (write path, plain form), quantize_fold_tiles.h
-// (write path, folded form), dequantize_tiles.h (read path) and kernels/scores.hip; every file under kernels/
+// Source layout: the kernel templates live in quantize_tiles.h (write path, plain form), quantize_fold_tiles.h and
+// quantize_fold4_tiles.h (write path, folded forms), dequantize_tiles.h and dequantize_fold4_tiles.h (read path),
+// kernels/scores.hip and kernels/attend.hip; every file under kernels/
 // instantiates one family of them and exports a function that picks the instance for a plan; plan.hip builds
 // the constant tables, api.hip holds the C entry points, cache.hip the cache manager.
 #ifndef SRFT_COMMON_H

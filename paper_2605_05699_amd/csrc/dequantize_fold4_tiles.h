@@ -3,38 +3,41 @@
 //
 // With h = d/2 the inverse of Eq. 1-2 is  u_n = C_n + S_n,  C_n the sum over the packed indices p <= h (DC, the cosine
 // rows, Nyquist) and S_n the sum over p > h (the sine rows) of Q[p][n] z_p.  C is even and S is odd under n -> d - n,
-// and the two kinds of rows are whole groups of the record (p < h: groups 0..3, p >= h: groups 4..7), so each half
-// is contracted from four groups only.  Under n -> h - n a row of bin k keeps its sign when k is even and flips it
-// when k is odd (cosine), or the other way round (sine); p has the parity of k, and a code byte holds an even p in its
-// low and an odd p in its high nibble.  With Ce, Co (Se, So) the partial sums over even and odd p:
-//     C_m = Ce_m + Co_m,  C_{h-m} = Ce_m - Co_m,  S_m = So_m + Se_m,  S_{h-m} = So_m - Se_m,     m = 0 .. h/2,
+// and the two kinds of rows are whole groups of the record (p < h: the first d/64 groups, p >= h: the others), so each
+// half is contracted from half of the groups only.  Under n -> h - n a row of bin k keeps its sign when k is even and
+// flips it when k is odd (cosine), or the other way round (sine); p has the parity of k, and a code byte holds an even
+// p in its low and an odd p in its high nibble.  With Ce, Co (Se, So) the partial sums over even and odd p:
+//     C_m = Ce_m + Co_m,  C_{h-m} = Ce_m - Co_m,  S_m = So_m + Se_m,  S_{h-m} = So_m - Se_m,     m = 0 .. d/4,
 //     u_m = C_m + S_m,  u_{d-m} = C_m - S_m,  u_{h-m} = C_{h-m} + S_{h-m},  u_{h+m} = C_{h-m} - S_{h-m}.
-// Only m < 64 is contracted, per class from K = 16 codes per group: 64 MFMAs per tile of 32 vectors (128 once
-// folded, 256 dense), and every output sums four group partial results instead of eight.
+// Only m < d/4 is contracted, per class from K = 16 codes per group: d/4 MFMAs per tile of 32 vectors (d/2 once
+// folded, d dense: 64 / 128 / 256 at d = 256), and every output sums d/64 group partial results instead of d/32.
 //
-// Wavefront w = 0, 1 holds the cosine classes (E = Ce, O = Co) of m = 32w .. 32w + 31, wavefront 2, 3 the sine
-// classes (E = Se, O = -So, negated on the host) of m = 32(w-2) ..: every wavefront forms  own = E + O  and
-// send = E - O,  which is (C_m, C_{h-m}) on the cosine and (-S_{h-m}, S_m) on the sine side.  `send` crosses to the
-// partner wavefront through LDS (fp32), and every wavefront finishes two runs of 16 outputs per lane:
+// With NB = d/128 blocks of 32 values of m, wavefront w < NB holds the cosine classes (E = Ce, O = Co) of m = 32w ..
+// 32w + 31, wavefront NB + w the sine classes (E = Se, O = -So, negated on the host) of the same m: every wavefront
+// forms  own = E + O  and  send = E - O,  which is (C_m, C_{h-m}) on the cosine and (-S_{h-m}, S_m) on the sine side.
+// `send` crosses to the partner wavefront through LDS (fp32), and every wavefront finishes two runs of 16 outputs
+// per lane:
 //     ascending   own + recv  ->  n = m          (cosine)   n = h + m   (sine)
 //     descending  own - recv  ->  n = d - m      (cosine)   n = h - m   (sine, negated: undone by the sign masks)
 // The sign diagonal is applied to the packed fp16 bits (one mask per output).  A descending run covers
 // n0 - 15 .. n0 with n0 a multiple of 16: its top element belongs to the 16-byte block above, so every lane takes the
 // bottom element of its block from the lane that owns the next 16 values of m: the other half of the wavefront
-// (v_permlane32_swap), the next wavefront (through LDS), or, above m = 63, the row m = 64 that no slab holds:
-//     C_64 = Ce_64 (Co_64 = 0)  as a dot product on the vector ALU, one group of 16 even codes per wavefront,
-//     S_64 = So_64 (Se_64 = 0)  in row m = 0 of the first sine wavefront's O slab, which is otherwise zero.
-// The Nyquist code (packed index h, first code of group 4) is even under both reflections: it enters the cosine
-// wavefronts as the addend (-1)^m code scale c of the first multiply-add of the E class.
+// (v_permlane32_swap), the next wavefront (through LDS; d = 256 only), or, above the last block, the row m = d/4 that
+// no slab holds (Co and Se vanish there):
+//     Ce at m = d/4  as a dot product on the vector ALU, one group of 16 even codes per wavefront,
+//     So at m = d/4  in row m = 0 of the first sine wavefront's O slab, which is otherwise zero.
+// The Nyquist code (packed index h, first code of the first sine group) is even under both reflections: it enters the
+// cosine wavefronts as the addend (-1)^m code scale c of the first multiply-add of the E class.
 //
 // Stage k of a workgroup: barrier; flush T_{k-1} from the staging tile; contract T_k, write `send`; decode T_{k+1};
 // barrier; read `recv`, finish, stage T_k.  The second barrier lets the staging tile and the exchange be single
-// buffers.
+// buffers.  (Decoding T_{k+1} after the second barrier instead would let the decoded tile be a single buffer too, and
+// at d = 128 a fifth workgroup fit a compute unit: measured 2 - 3.5 % slower at both sizes.)
 //
-// Table (16-byte units): [4 wavefronts][E, O][4 groups][hi, lo][64 lanes] A-operand fragments;
-// [4][2 lane halves][6]: sign masks (8 dwords ascending run, 8 dwords descending run) and the 8 fp32 coefficients of
-// row m = 64 for the even codes of group w a lane of that half reads (the 32 lanes of a half share them: the kernel
-// keeps them in LDS and reads them as broadcasts); [4] per-wavefront constants (.x = Nyquist factor).
+// Table (16-byte units), NW = d/64 wavefronts: [NW][E, O][d/64 groups][hi, lo][64 lanes] A-operand fragments;
+// [NW][2 lane halves][6]: sign masks (8 dwords ascending run, 8 dwords descending run) and the 8 fp32 coefficients of
+// row m = d/4 for the even codes of group w a lane of that half reads (the 32 lanes of a half share them: the kernel
+// keeps them in LDS and reads them as broadcasts); [NW] per-wavefront constants (.x = Nyquist factor).
 #ifndef SRFT_DEQUANTIZE_FOLD4_TILES_H
 #define SRFT_DEQUANTIZE_FOLD4_TILES_H
 #include "device_util.h"
@@ -175,7 +178,7 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
             fb = fb_next;
         }
         __builtin_amdgcn_sched_barrier(0);
-        // Ce_64: this wavefront's share is cosine group `wave`; a lane holds 8 of its 16 even codes
+        // Ce at m = d/4: this wavefront's share is cosine group `wave`; a lane holds 8 of its 16 even codes
         {
             const half8 fx = __builtin_bit_cast(half8, dec[b][col * ROW + 2 * half + 4 * wave]);
             const uint4 cf0 = mine[4], cf1 = mine[5];
@@ -192,7 +195,7 @@ srft_dequantize_fold4_tiles(const uint4* __restrict__ tab, const uint2* __restri
             const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(part), __float_as_uint(part), false, false);
             *(half == 0 ? &s_c64[wave][col] : &s_dump[tid]) = __uint_as_float(r[0]) + __uint_as_float(r[1]);
         }
-        // row m = 0 of the first sine wavefront's O slab carried -So_64
+        // row m = 0 of the first sine wavefront's O slab carried -So at m = d/4
         const bool hijack = (wave == NB) && (half == 0);
         *(hijack ? &s_neg64[col] : &s_dump[tid]) = oO[0];
         oO[0] = hijack ? 0.0f : oO[0];

@@ -31,7 +31,8 @@
 //     A byte holds an even p in its low and an odd p in its high nibble, so the two operands are the low and
 //     the high nibbles.  Wavefront w owns n = 32w .. 32w+31: slab 0 is A, slab 1 is B (S = 2, KS = 1: per
 //     group of 32 codes one k-step of 16 even and one of 16 odd codes), rows scaled by s_n on the host;
-//     the relative sign s_n s_{n+d/2} is applied to the packed fp16 bits.  rfrag is then
+//     the relative sign s_n s_{n+d/2} is applied to the packed fp16 bits.  There is room for one accumulator per slab;
+//     the loop is pipelined at half-group granularity (see lean_body).  rfrag is then
 //     [D/64 waves][A, B][D/32 groups][hi, lo][64 lanes], followed by [D/64 waves][64 lanes][2] sign masks.
 // BITS: 4, or 8 (one two's-complement byte per code).  A "code unit" is 16 codes: 8 bytes at 4 bits, 16 at 8.
 //     At 8 bits a dword gives the pairs (b0, b2) and (b1, b3): again even and odd p apart, so FOLD applies as is.
@@ -243,18 +244,8 @@ srft_dequantize_tiles(const uint4* __restrict__ rfrag, const uint2* __restrict__
         }
     };
 
-    // With few groups two accumulator sets fit: group j + 1 is on the matrix cores while group j is folded in.
-    constexpr bool LEAN_ALT = LEAN && (S * G <= SRFT_LEAN_ALT_MAX);
     auto lean_body = [&](int b) __attribute__((always_inline)) {
-        if constexpr (LEAN_ALT) {
-            group(b, 0, acc0);
-#pragma unroll
-            for (int j = 1; j < G; ++j) {
-                group(b, j, (j & 1) ? acc1 : acc0);
-                fold((j & 1) ? acc0 : acc1, scale_of(b, j - 1), j == 1);
-            }
-            fold(((G - 1) & 1) ? acc1 : acc0, scale_of(b, G - 1), G == 1);
-        } else if constexpr (FOLD && SRFT_DQ_HALF_PIPE) {
+        if constexpr (FOLD && SRFT_DQ_HALF_PIPE) {
             // One accumulator per slab, software-pipelined at half-group granularity.  The MFMA pairs go A_0, B_0, A_1,
             // B_1, ...; each result is folded in (16 multiply-adds) one half-step after its pair, under the other
             // slab's pair.  A wavefront issues in order, and a second MFMA cannot issue while the first occupies the

@@ -20,10 +20,6 @@ __device__ __forceinline__ uint2 stream_load(const uint2* p) {
     return __builtin_bit_cast(uint2, __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p)));
 }
 
-#ifndef SRFT_LEAN_ALT_MAX
-#define SRFT_LEAN_ALT_MAX 8              // read path: slabs x groups up to which two accumulator sets alternate
-#endif
-
 // ------------------------------------------------------------------------------------------
 // device helpers
 // ------------------------------------------------------------------------------------------

@@ -5,7 +5,7 @@ namespace {
 template <int D>
 dequantize_kernel_t pick(int slabs, int gm, bool fold) {
     if constexpr ((D / 32) % 2 == 0) {
-        if constexpr (D != 256)                  // d = 256 runs the twice-folded kernel instead
+        if constexpr (D != 128 && D != 256)      // d = 128 and 256 run the twice-folded kernel instead
             if (fold && gm != kGroup16) return srft_dequantize_kernel<D, 2, 1, true, 4>;
         if (slabs == 2)
             return gm == kGroup16 ? srft_dequantize_kernel<D, 2, 1, false, 4>
@@ -16,7 +16,7 @@ dequantize_kernel_t pick(int slabs, int gm, bool fold) {
 template <int D>
 batched_kernel_t pick_batched(int slabs, int gm, bool fold) {
     if constexpr ((D / 32) % 2 == 0) {
-        if constexpr (D != 256)                  // d = 256 runs the twice-folded kernel instead
+        if constexpr (D != 128 && D != 256)      // d = 128 and 256 run the twice-folded kernel instead
             if (fold && gm != kGroup16) return srft_dequantize_batched_kernel<D, 2, 1, true, 4>;
         if (slabs == 2)
             return gm == kGroup16 ? srft_dequantize_batched_kernel<D, 2, 1, false, 4>
