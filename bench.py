@@ -73,7 +73,10 @@ def main() -> int:
     ap.add_argument("--batched", choices=["auto", "on", "off"], default="auto",
                     help="several plans per launch (auto: when a plan has fewer than 65,536 vectors)")
     ap.add_argument("--plans-per-launch", type=int, default=0,
-                    help="plans per batched launch (at most 64); 0 = 64 for small plans, 4 for plans of 65536 vectors or more")
+                    help="plans per batched launch, both directions (at most 64); 0 = 64 for small plans, and for plans of "
+                         "65536 vectors or more 16 on the write path and 4 on the read path")
+    ap.add_argument("--plans-per-launch-write", type=int, default=0, help="the same for the write path only")
+    ap.add_argument("--plans-per-launch-read", type=int, default=0, help="the same for the read path only")
     ap.add_argument("--ceiling", action="store_true",
                     help="also time the streaming kernel that has each path's read:write byte mix (HBM ceiling)")
     ap.add_argument("--decode-append", action="store_true",
@@ -134,19 +137,23 @@ def main() -> int:
     stream = torch.cuda.current_stream()
     h = [pl.handle for pl in plans]
     # Plans per launch.  Small plans go 64 to a launch (a launch per plan would be launch-bound).  With plans of a
-    # million vectors a few per launch are best: measured on this workload, 4 plans per launch against a launch per
-    # plan and against 64 per launch: write 5.35 / 5.25 / 5.0 TB/s, read 5.3 / 5.0 / 4.95 TB/s.
+    # million vectors a few per launch are best, and the two directions differ: measured on this workload with 2 / 4 /
+    # 8 / 16 plans per launch, write 5.36-5.56 / 5.43-5.60 / 5.56-5.61 / 5.61-5.70 TB/s (fewer launch tails), read
+    # 5.29-5.32 / 5.40-5.55 / 5.33-5.44 / 5.18-5.21 TB/s (its workgroups spread over as many output buffers).
     batched_q = args.batched == "on" or (args.batched == "auto" and n_plans > 1)
     batched_d = args.batched == "on" or (args.batched == "auto" and n_plans > 1)
-    per_launch = args.plans_per_launch if args.plans_per_launch > 0 else (64 if n < 65536 else 4)
-    per_launch = min(per_launch, 64)
-    launches_q = -(-n_plans // per_launch) if batched_q else n_plans      # per step
-    launches_d = -(-n_plans // per_launch) if batched_d else n_plans
-    chunks = [slice(i, min(i + per_launch, n_plans)) for i in range(0, n_plans, per_launch)]
+    small = n < 65536
+    per_launch_q = args.plans_per_launch_write or args.plans_per_launch or (64 if small else 16)
+    per_launch_d = args.plans_per_launch_read or args.plans_per_launch or (64 if small else 4)
+    per_launch_q, per_launch_d = min(per_launch_q, 64), min(per_launch_d, 64)
+    launches_q = -(-n_plans // per_launch_q) if batched_q else n_plans      # per step
+    launches_d = -(-n_plans // per_launch_d) if batched_d else n_plans
+    chunks_q = [slice(i, min(i + per_launch_q, n_plans)) for i in range(0, n_plans, per_launch_q)]
+    chunks_d = [slice(i, min(i + per_launch_d, n_plans)) for i in range(0, n_plans, per_launch_d)]
     if batched_q:
-        tables_q = [B.BatchTable(h[c], list(x[c]), list(codes[c]), list(scales[c])) for c in chunks]
+        tables_q = [B.BatchTable(h[c], list(x[c]), list(codes[c]), list(scales[c])) for c in chunks_q]
     if batched_d:
-        tables_d = [B.BatchTable(h[c], list(out[c]), list(codes[c]), list(scales[c])) for c in chunks]
+        tables_d = [B.BatchTable(h[c], list(out[c]), list(codes[c]), list(scales[c])) for c in chunks_d]
 
     def step(ev=None):
         if ev:
@@ -208,6 +215,8 @@ def main() -> int:
         "config": {"workload": w.name, "d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
                    "total_vectors": total_vec, "bytes_per_vector_each_direction": bytes_per_vec,
                    "launches_per_step": launches_q + launches_d,
+                   "plans_per_launch": {"quantize": per_launch_q if batched_q else 1,
+                                        "dequantize": per_launch_d if batched_d else 1},
                    "batched": {"quantize": batched_q, "dequantize": batched_d}},
         "quantize": {"vectors_per_s": total_vec / tq, "ns_per_vec": tq / total_vec * 1e9, "GBps": qa,
                      "hbm_frac": qa / HBM_PEAK_GBPS, "avg_launch_ms": ql * 1e3},
@@ -227,7 +236,7 @@ def main() -> int:
 
     if w.name == "llama3-70b-128k" and not args.no_d256:
         # the metric names d = 256 beside d = 128: the same launch shape (1,048,576 vectors per plan) at d = 256
-        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream, per_launch=per_launch)
+        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream, per_launch=per_launch_d)
     if args.butterfly and d == 128 and g == 32:
         def b_pass():
             for p in range(n_plans):
