@@ -136,6 +136,35 @@ def test_every_nibble_value_at_every_position_is_decoded(B, d):
     plan.close()
 
 
+@pytest.mark.parametrize("d,g", [(128, 32), (128, 64), (128, 128), (256, 32), (256, 128), (256, 256)])
+def test_codes_the_twice_folded_read_form_treats_apart(B, d, g):
+    # The read kernel at d = 128 / 256 contracts cosine and sine rows, even and odd packed indices, in four separate
+    # classes, brings Nyquist (p = d/2) in as an addend and takes the outputs n = d/4, 3d/4 from a row of its own.
+    # One-hot records at the indices where those paths meet, every code value, wide groups included; also two vectors
+    # in which only one class is populated.  Element by element against the oracle (n = 0, d/4, d/2, 3d/4 included).
+    h = d // 2
+    special = [0, 1, 2, 3, h // 2, h - 2, h - 1, h, h + 1, h + 2, h + h // 2, d - 2, d - 1]
+    vals = list(range(-8, 8))
+    q = np.zeros((len(special) * len(vals) + 4, d), dtype=np.int8)
+    for a, p in enumerate(special):
+        for i, v in enumerate(vals):
+            q[a * len(vals) + i, p] = v
+    rng = np.random.RandomState(d + g)
+    tail = len(special) * len(vals)
+    q[tail + 0, 0:h:2] = rng.randint(-7, 8, size=h // 2)          # even cosine codes only
+    q[tail + 1, 1:h:2] = rng.randint(-7, 8, size=h // 2)          # odd cosine codes only
+    q[tail + 2, h + 2:d:2] = rng.randint(-7, 8, size=h // 2 - 1)  # even sine codes only (Nyquist left out)
+    q[tail + 3, h + 1:d:2] = rng.randint(-7, 8, size=h // 2)      # odd sine codes only
+    codes = O.pack_nibbles(q)
+    scales = rng.uniform(0.25, 4.0, size=(q.shape[0], d // g)).astype(np.float32)
+    lam = W.lognormal_lambda(d, seed=d)
+    plan = B.Plan(d, g, 21, lam)
+    assert B.lib().srft_plan_form(plan.handle, 1) == 2
+    out = plan.dequantize(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda()).cpu().numpy()
+    P.check_dequantize(codes, scales, plan.signs, lam, g, out)
+    plan.close()
+
+
 @pytest.mark.parametrize("d", MAIN_D)
 def test_random_bytes_are_decoded(B, d):
     rng = np.random.RandomState(d)
