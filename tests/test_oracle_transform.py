@@ -292,3 +292,37 @@ def test_srft_and_srht_gaussianize_alike():
     sc = np.abs(xr).max(axis=-1, keepdims=True) / 7
     raw_mse = np.mean((np.rint(xr / sc) * sc - xr) ** 2)
     assert mse["dense"] < raw_mse and mse["hadamard"] < raw_mse
+
+
+@pytest.mark.parametrize("d", [96, 128, 256])
+def test_inverse_transform_folds_twice_over_cosine_sine_and_code_parity(d):
+    """The symmetries of Q (Eq. 1-2) that the read kernels at d = 128 and 256 rest on, checked on the oracle's matrix.
+
+    With h = d/2, C the part of Q^T z from the packed indices p <= h (DC, cosine rows, Nyquist) and S the part from
+    p > h (sine rows): C_{d-n} = C_n, S_{d-n} = -S_n; and under n -> h - n an even p keeps (cosine) or flips (sine) its
+    sign, an odd p the other way round.  So with Ce, Co, Se, So the sums over even / odd p, the four outputs m, d - m,
+    h - m, h + m follow from four numbers, for m = 0 .. d/4; Co and Se vanish at m = d/4, So and Se at m = 0.
+    """
+    rng = np.random.RandomState(d)
+    h = d // 2
+    Q = O.srft_matrix(d)
+    z = rng.standard_normal(d)
+    u = Q.T @ z
+    p = np.arange(d)
+    cos_side, sin_side = p <= h, p > h
+    even, odd = p % 2 == 0, p % 2 == 1
+
+    def part(mask, n):
+        return Q[mask, n] @ z[mask]
+
+    for m in range(d // 4 + 1):
+        ce, co = part(cos_side & even, m), part(cos_side & odd, m)
+        se, so = part(sin_side & even, m), part(sin_side & odd, m)
+        assert abs(u[m] - (ce + co + so + se)) < 1e-12
+        assert abs(u[(d - m) % d] - (ce + co - so - se)) < 1e-12
+        assert abs(u[h - m] - (ce - co + so - se)) < 1e-12
+        assert abs(u[(h + m) % d] - (ce - co - so + se)) < 1e-12
+        if m == 0:
+            assert abs(so) < 1e-12 and abs(se) < 1e-12
+        if m == d // 4:
+            assert abs(co) < 1e-12 and abs(se) < 1e-12
