@@ -236,7 +236,7 @@ def main() -> int:
 
     if w.name == "llama3-70b-128k" and not args.no_d256:
         # the metric names d = 256 beside d = 128: the same launch shape (1,048,576 vectors per plan) at d = 256
-        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream, per_launch=per_launch_d)
+        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream, per_launch_q=per_launch_q, per_launch_d=per_launch_d)
     if args.butterfly and d == 128 and g == 32:
         def b_pass():
             for p in range(n_plans):
@@ -442,8 +442,8 @@ def all_configs(B, W, torch, dev, stream):
     return res
 
 
-def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10, per_launch=4):
-    """Write pass and read pass (per_launch plans per launch, as in the main step) over n_plans x n vectors of d = 256, g = 32:
+def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10, per_launch_q=16, per_launch_d=4):
+    """Write pass and read pass (plans per launch as in the main step, at most n_plans) over n_plans x n vectors of d = 256, g = 32:
     N(0,1) times a lognormal(0,1) channel scale and lognormal(0,0.5) lambda per plan, as in the d = 256 config.
     `warm` untimed passes of each path precede the `reps` timed ones (about 25 ms each way): after the idle gap in
     which the plans are built the first few milliseconds of work run 20-30 % slower than the steady state that the
@@ -462,9 +462,11 @@ def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10, 
     scales = torch.empty(n_plans, n, G, dtype=torch.float32, device=dev)
     out = torch.empty(n_plans, n, d, dtype=torch.float16, device=dev)
     h = [pl.handle for pl in plans]
-    chunks = [slice(i, min(i + per_launch, n_plans)) for i in range(0, n_plans, per_launch)]
-    tables_q = [B.BatchTable(h[c], list(x[c]), list(codes[c]), list(scales[c])) for c in chunks]
-    tables_d = [B.BatchTable(h[c], list(out[c]), list(codes[c]), list(scales[c])) for c in chunks]
+    per_launch_q, per_launch_d = min(per_launch_q, n_plans), min(per_launch_d, n_plans)
+    chunks_q = [slice(i, min(i + per_launch_q, n_plans)) for i in range(0, n_plans, per_launch_q)]
+    chunks_d = [slice(i, min(i + per_launch_d, n_plans)) for i in range(0, n_plans, per_launch_d)]
+    tables_q = [B.BatchTable(h[c], list(x[c]), list(codes[c]), list(scales[c])) for c in chunks_q]
+    tables_d = [B.BatchTable(h[c], list(out[c]), list(codes[c]), list(scales[c])) for c in chunks_d]
 
     def pass_q():
         for t in tables_q:
@@ -493,7 +495,8 @@ def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10, 
     tq, td = ev[0].elapsed_time(ev[1]) / reps / 1e3, ev[1].elapsed_time(ev[2]) / reps / 1e3
     for pl in plans:
         pl.close()
-    return {"d": d, "group": g, "plans": n_plans, "vectors_per_plan": n, "plans_per_launch": per_launch,
+    return {"d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
+            "plans_per_launch": {"quantize": per_launch_q, "dequantize": per_launch_d},
             "quantize": {"GBps": nbytes / tq / 1e9, "hbm_frac": nbytes / tq / 1e9 / HBM_PEAK_GBPS,
                          "vectors_per_s": n_plans * n / tq},
             "dequantize": {"GBps": nbytes / td / 1e9, "hbm_frac": nbytes / td / 1e9 / HBM_PEAK_GBPS,

@@ -426,10 +426,10 @@ def test_d256_at_the_launch_size_the_bench_times(B):
         pl.close()
 
 
-@pytest.mark.parametrize("name,n_write,n_read", [("llama3-70b-128k", 16, 4), ("gemma3-1b-4k", 4, 4)])
+@pytest.mark.parametrize("name,n_write,n_read", [("llama3-70b-128k", 16, 4), ("gemma3-1b-4k", 8, 4)])
 def test_plans_per_launch_as_the_bench_times_them(B, name, n_write, n_read):
     # bench.py puts 16 (write path) and 4 (read path) plans of 1,048,576 vectors into every launch of the headline
-    # workload (d = 128), and 4 both ways into its d = 256 side measurement.  The batched launches must produce the
+    # workload (d = 128), and 8 (write: all of its plans) and 4 (read) into its d = 256 side measurement.  The batched launches must produce the
     # bytes of the per-plan launches, which _sampled_parity holds against the oracle at this size (plans 0 and 159 /
     # 0 and 51 above).
     w = W.WORKLOADS[name]
