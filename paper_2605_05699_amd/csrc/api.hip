@@ -167,7 +167,7 @@ int srft_kv_quantize(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_v
 int srft_kv_quantize_butterfly(const srft_plan_t* plan, const void* x_f16_dev, int64_t n_vec, uint8_t* codes_dev,
                                float* scales_dev, void* hip_stream) {
     if (!plan) return SRFT_ERR_NULL;
-    if (plan->d != 128) return SRFT_ERR_BAD_D;
+    if (plan->d != 128 && plan->d != 256) return SRFT_ERR_BAD_D;
     if (plan->gm != kGroup32) return SRFT_ERR_BAD_GROUP;
     if (plan->bits != 4) return SRFT_ERR_BAD_BITS;
     if (plan->transform != SRFT_TRANSFORM_DFT) return SRFT_ERR_BAD_TRANSFORM;
@@ -175,7 +175,7 @@ int srft_kv_quantize_butterfly(const srft_plan_t* plan, const void* x_f16_dev, i
     if (n_vec == 0) return SRFT_OK;
     if (!x_f16_dev || !codes_dev || !scales_dev || !plan->bfly) return SRFT_ERR_NULL;
     if (!srft_aligned(x_f16_dev, 16) || !srft_aligned(codes_dev, 16) || !srft_aligned(scales_dev, 16)) return SRFT_ERR_ALIGN;
-    return srft_launch_quantize_butterfly(plan->bfly, x_f16_dev, n_vec, codes_dev, scales_dev, plan->max_wgs,
+    return srft_launch_quantize_butterfly(plan->d, plan->bfly, x_f16_dev, n_vec, codes_dev, scales_dev, plan->max_wgs,
                                           (hipStream_t)hip_stream);
 }
 

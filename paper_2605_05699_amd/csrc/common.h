@@ -116,7 +116,7 @@ struct srft_plan {
     float* rmat_f32 = nullptr;  // R^T in fp32, [k][n] = s_n Q[k][n] / max(lambda_k, 1e-6) (device): the one inverse transform per
                                 // query of srft_kv_attend
     int compute_units = 0;
-    float* bfly = nullptr;      // table of the butterfly form of the write path (device), d = 128 / g = 32 / 4-bit only
+    float* bfly = nullptr;      // table of the butterfly form of the write path (device), d = 128 or 256 / g = 32 / 4-bit only
     float* inv_lam2 = nullptr;  // 1 / (lambda * max(lambda, 1e-6)) per channel (device): scores in the rotated domain
     int grid_scores = 0;        // persistent grid of the scores kernel (32 rows of queries)
     int grid_scores16 = 0;      // the same with 16 rows
@@ -167,9 +167,9 @@ batched_kernel_t srft_pick_dequantize_batched_b8(int d, int slabs, int gm, bool 
 dequantize_kernel_t srft_pick_dequantize_fold4(int d, int bits);
 batched_kernel_t srft_pick_dequantize_fold4_batched(int d, int bits);
 int srft_rfold4_table_units(int d);
-// write path with the transform as FFT butterflies on the vector ALU (d = 128, g = 32, 4-bit; the comparison form)
-int srft_launch_quantize_butterfly(const float* table_dev, const void* x, long long n_vec, uint8_t* codes, float* scales,
-                                   int max_workgroups, hipStream_t st);
+// write path with the transform as FFT butterflies on the vector ALU (d = 128 or 256, g = 32, 4-bit; the comparison form)
+int srft_launch_quantize_butterfly(int d, const float* table_dev, const void* x, long long n_vec, uint8_t* codes,
+                                   float* scales, int max_workgroups, hipStream_t st);
 // scores in the rotated domain: launch of the scan (kernels/scores.hip) and its resident workgroups per unit
 // row_max: nullptr, or kRowMaxCopies x 32 cleared words: copy (workgroup mod kRowMaxCopies) receives, per query, the
 // ordered code (srft_ordered_code) of the maximum of sign * score over that workgroup's keys

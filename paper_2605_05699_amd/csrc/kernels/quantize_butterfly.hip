@@ -1,4 +1,4 @@
-// Write path at d = 128 with the transform as FFT butterflies on the vector ALU instead of a matrix-core
+// Write path at d = 128 (and, further down, d = 256) with the transform as FFT butterflies on the vector ALU instead of a matrix-core
 // contraction: the form the paper's kernel has (Sec. 3.2: the real transform through a complex FFT of half the
 // length and a Hermitian unpack; Sec. 7.1), kept so that the two forms can be timed side by side on this machine.
 // Same record as srft_kv_quantize (Sec. 3.2 steps 1-4, Sec. 5.1, Sec. 7.1); fp32 arithmetic throughout, as in the
@@ -190,19 +190,193 @@ srft_quantize_butterfly_kernel(const float* __restrict__ cl, const uint4* __rest
     }
 }
 
+
+// ---- d = 256: one vector on two lanes ------------------------------------------------------------------------
+// 256 fp32 values and the temporaries of the transform do not fit one lane, so lanes l and l + 32 share vector l
+// (32 vectors per wavefront and step).  The complex FFT of length 128 over z_m = u_2m + i u_2m+1 is split by one
+// decimation-in-time step: lane part 0 transforms the even m, part 1 the odd m (each a length-64 FFT in registers,
+// the same code as above), both publish their 64 complex values in LDS, and every pair index j = 0 .. 32 is then
+// worked by both lanes from the same four values A_j, B_j, A_{64-j}, B_{64-j} with the same compile-time twiddles:
+//   Z_j = A_j + W^j B_j,  Z_{64+j} = A_j - W^j B_j,  Z_{64-j} = A_{64-j} + W^{64-j} B_{64-j},  Z_{128-j} = A_{64-j} - ...
+// Part 0 takes the pair of bins (j, 128 - j), part 1 the pair (64 - j, 64 + j), whose unpack twiddle exp(-2 pi i k/256)
+// at k = 64 - j is the one at k = j with cosine and sine exchanged.  Each pair gives four packed values; they land in
+// four groups per lane -- part 0: packed 0..31, 128..159, 96..127, 224..255; part 1: 64..95, 192..223, 32..63, 160..191 --
+// so the quantizer stays inside the lane.  j = 0 gives DC and Nyquist (part 0) and the two values of bin 64 (part 1).
+//
+// cl: 256 floats as for d = 128 (bins 0 and 64 are the ones without the factor 1/2), then 32 x 4 dwords of sign masks.
+
+// pair j of the two-lane unpack; X / Xi collect positions j, Y / Yi positions 32 - j of this lane's four groups
+template <int J>
+__device__ __forceinline__ void unpack256(float (&X)[32], float (&Xi)[32], float (&Y)[32], float (&Yi)[32],
+                                          const float* __restrict__ are, const float* __restrict__ aim,
+                                          const float* __restrict__ bre, const float* __restrict__ bim,
+                                          const float4* __restrict__ clp, bool part) {
+    if constexpr (J <= 32) {
+        constexpr float c1 = (float)cos_turn(J, 128), s1 = (float)sin_turn(J, 128);            // W_128^J
+        constexpr float c2 = (float)cos_turn(64 - J, 128), s2 = (float)sin_turn(64 - J, 128);  // W_128^(64-J)
+        constexpr float cu = (float)cos_turn(J, 256), su = (float)sin_turn(J, 256);            // W_256^J
+        const float ar = are[J], ai = aim[J], br = bre[J], bi = bim[J];
+        const float ar2 = are[64 - J], ai2 = aim[64 - J], br2 = bre[64 - J], bi2 = bim[64 - J];
+        const float tr1 = fmaf(c1, br, s1 * bi), ti1 = fmaf(c1, bi, -s1 * br);
+        const float tr2 = fmaf(c2, br2, s2 * bi2), ti2 = fmaf(c2, bi2, -s2 * br2);
+        // part 0: (Z_J, Z_{128-J});  part 1: (Z_{64-J}, Z_{64+J})
+        const float zkr = part ? ar2 + tr2 : ar + tr1, zki = part ? ai2 + ti2 : ai + ti1;
+        const float zmr = part ? ar - tr1 : ar2 - tr2, zmi = part ? ai - ti1 : ai2 - ti2;
+        const float c = part ? su : cu, s = part ? cu : su;                                     // W_256^k, k = J or 64 - J
+        const float er = zkr + zmr, ei = zki - zmi;
+        const float orr = zki + zmi, oi = zmr - zkr;
+        const float tr = fmaf(c, orr, s * oi), ti = fmaf(c, oi, -s * orr);
+        const float4 k4 = clp[J];                   // lambda and packing constants of bins k (re, im) and 128 - k (re, im)
+        const float skr = (er + tr) * k4.x, ski = (ei + ti) * k4.y, smr = (er - tr) * k4.z, smi = (ti - ei) * k4.w;
+        if constexpr (J < 32) {
+            X[J] = part ? smr : skr;
+            Xi[J] = part ? smi : ski;
+        }
+        Y[32 - J] = part ? skr : smr;
+        Yi[32 - J] = part ? ski : smi;
+        unpack256<J + 1>(X, Xi, Y, Yi, are, aim, bre, bim, clp, part);
+    }
+}
+
+// abs-max, scale and nibble pack of one group of 32 values held by a lane
+__device__ __forceinline__ void quantize_group32(const float (&z)[32], uint4& packed, float& scale_out) {
+    float mx = fmaxf(fabsf(z[0]), fabsf(z[1]));
+#pragma unroll
+    for (int v = 2; v < 32; ++v) mx = fmaxf(mx, fabsf(z[v]));
+    float scale = mx * (1.0f / 7.0f);
+    float inv = __builtin_amdgcn_rcpf(scale);
+    if (!(scale >= kMinScale)) { scale = 0.0f; inv = 0.0f; }
+    scale_out = scale;
+    uint32_t w[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        constexpr float kMagic = 12582912.0f + 8.0f;
+        constexpr uint32_t kMagicBits = 0x4B400000u;
+        uint32_t p = __float_as_uint(fmaf(z[8 * q + 7], inv, kMagic));
+#pragma unroll
+        for (int i = 6; i >= 0; --i) p = shl4_add(p, __float_as_uint(fmaf(z[8 * q + i], inv, kMagic)));
+        uint32_t k = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) k += kMagicBits << (4 * i);
+        w[q] = (p - k) ^ 0x88888888u;
+    }
+    packed = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__global__ void __launch_bounds__(64, 1)
+srft_quantize_butterfly256_kernel(const float* __restrict__ cl, const uint4* __restrict__ x, long long n_vec,
+                                  uint4* __restrict__ codes, float* __restrict__ scales) {
+    constexpr int U = 32, ROW = U + 1;           // 16-byte units per input row, padded
+    constexpr int XS = 65;                       // floats per (vector, part) row of the exchange, padded
+    // the input tile (32 rows) and the exchange (64 rows of 64 complex values, real and imaginary planes) take turns
+    __shared__ uint4 buf[2 * 64 * XS / 4];
+    __shared__ float4 clp_s[2][33];
+    uint4* tile = buf;
+    float* xre = reinterpret_cast<float*>(buf);
+    float* xim = xre + 64 * XS;
+    const int lane = threadIdx.x, vec = lane & 31;
+    const bool part = lane >= 32;
+    // constants of the pairs, per part: bins k and 128 - k with k = j (part 0) or 64 - j (part 1); j = 0: bins 0, 128, 64, 192
+    for (int t = lane; t < 66; t += 64) {
+        const int pt = t / 33, j = t % 33, k = pt ? 64 - j : j;
+        clp_s[pt][j] = j == 0 ? make_float4(cl[0], cl[128], cl[64], cl[192])
+                              : make_float4(cl[k], cl[128 + k], cl[128 - k], cl[256 - k]);
+    }
+    const uint4* masks = reinterpret_cast<const uint4*>(cl + 256);
+    const long long n_blocks = (n_vec + 31) / 32;
+    for (long long blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
+        const long long row0 = blk * 32;
+        const int lim = (int)min((long long)31, n_vec - 1 - row0);       // rows past the end alias to the last row
+        __syncthreads();                         // the exchange of the previous step has been read
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int u = lane + 64 * i, r = u / U, c = u % U;
+            tile[r * ROW + c] = x[(row0 + min(r, lim)) * U + c];
+        }
+        __syncthreads();
+        float re[64], im[64];
+#pragma unroll
+        for (int c = 0; c < U; ++c) {            // unit c holds the complex samples m = 4c .. 4c+3; this lane takes m = 2j + part
+            uint4 v = tile[vec * ROW + c];
+            const uint4 m = masks[c];
+            v.x ^= m.x; v.y ^= m.y; v.z ^= m.z; v.w ^= m.w;               // u = s * x
+            const half2v h0 = __builtin_bit_cast(half2v, part ? v.y : v.x);   // j = 2c
+            const half2v h1 = __builtin_bit_cast(half2v, part ? v.w : v.z);   // j = 2c + 1
+            re[bit_reverse6(2 * c)] = (float)h0[0];
+            im[bit_reverse6(2 * c)] = (float)h0[1];
+            re[bit_reverse6(2 * c + 1)] = (float)h1[0];
+            im[bit_reverse6(2 * c + 1)] = (float)h1[1];
+        }
+        __syncthreads();                         // the tile is read: its memory becomes the exchange
+        fft64_stage<2>(re, im);
+        fft64_stage<4>(re, im);
+        fft64_stage<8>(re, im);
+        fft64_stage<16>(re, im);
+        fft64_stage<32>(re, im);
+        fft64_stage<64>(re, im);
+        {
+            float* wr = xre + lane * XS;         // row (part, vec): lane = 32 part + vec
+            float* wi = xim + lane * XS;
+#pragma unroll
+            for (int k = 0; k < 64; ++k) {
+                wr[k] = re[k];
+                wi[k] = im[k];
+            }
+        }
+        __syncthreads();
+        const float* are = xre + vec * XS;       // A: the even samples' transform (part 0's row), B: the odd samples'
+        const float* aim = xim + vec * XS;
+        const float* bre = xre + (32 + vec) * XS;
+        const float* bim = xim + (32 + vec) * XS;
+        const float4* clp = clp_s[part ? 1 : 0];
+        float X[32], Xi[32], Y[32], Yi[32];
+        {
+            const float pr = are[0] + bre[0], pi = aim[0] + bim[0];       // Z_0
+            const float qr = are[0] - bre[0], qi = aim[0] - bim[0];       // Z_64
+            const float4 k4 = clp[0];
+            X[0] = part ? qr * k4.z : (pr + pi) * k4.x;                   // bin 64 (real part) | DC
+            Xi[0] = part ? -qi * k4.w : (pr - pi) * k4.y;                 // bin 64 (imaginary part) | Nyquist
+        }
+        unpack256<1>(X, Xi, Y, Yi, are, aim, bre, bim, clp, part);
+        uint4 pk[4];
+        float sc[4];
+        quantize_group32(X, pk[0], sc[0]);
+        quantize_group32(Xi, pk[1], sc[1]);
+        quantize_group32(Y, pk[2], sc[2]);
+        quantize_group32(Yi, pk[3], sc[3]);
+        // groups of this lane: X, Xi, Y, Yi = 0, 4, 3, 7 (part 0) or 2, 6, 1, 5 (part 1)
+        const int g0 = part ? 2 : 0, g1 = part ? 6 : 4, g2 = part ? 1 : 3, g3 = part ? 5 : 7;
+        const long long row = row0 + min(vec, lim);       // lanes past the end rewrite the last row with the same bytes
+        codes[row * 8 + g0] = pk[0];
+        codes[row * 8 + g1] = pk[1];
+        codes[row * 8 + g2] = pk[2];
+        codes[row * 8 + g3] = pk[3];
+        scales[row * 8 + g0] = sc[0];
+        scales[row * 8 + g1] = sc[1];
+        scales[row * 8 + g2] = sc[2];
+        scales[row * 8 + g3] = sc[3];
+    }
+}
+
 }  // namespace
 
-int srft_launch_quantize_butterfly(const float* table_dev, const void* x, long long n_vec, uint8_t* codes, float* scales,
-                                   int max_workgroups, hipStream_t st) {
+int srft_launch_quantize_butterfly(int d, const float* table_dev, const void* x, long long n_vec, uint8_t* codes,
+                                   float* scales, int max_workgroups, hipStream_t st) {
     int blocks = 0, dev = 0, cus = 0;
-    SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, srft_quantize_butterfly_kernel, 64, 0));
+    const int per_block = d == 256 ? 32 : 64;    // vectors per wavefront and step
+    if (d == 256) SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, srft_quantize_butterfly256_kernel, 64, 0));
+    else SRFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, srft_quantize_butterfly_kernel, 64, 0));
     SRFT_HIP(hipGetDevice(&dev));
     SRFT_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     long long grid = max_workgroups > 0 ? max_workgroups : (long long)cus * (blocks > 0 ? blocks : 1);
-    const long long n_blocks = (n_vec + 63) / 64;
+    const long long n_blocks = (n_vec + per_block - 1) / per_block;
     if (grid > n_blocks) grid = n_blocks;
-    hipLaunchKernelGGL(srft_quantize_butterfly_kernel, dim3((unsigned)grid), dim3(64), 0, st, table_dev,
-                       (const uint4*)x, n_vec, (uint4*)codes, (float4*)scales);
+    if (d == 256)
+        hipLaunchKernelGGL(srft_quantize_butterfly256_kernel, dim3((unsigned)grid), dim3(64), 0, st, table_dev,
+                           (const uint4*)x, n_vec, (uint4*)codes, scales);
+    else
+        hipLaunchKernelGGL(srft_quantize_butterfly_kernel, dim3((unsigned)grid), dim3(64), 0, st, table_dev,
+                           (const uint4*)x, n_vec, (uint4*)codes, (float4*)scales);
     SRFT_HIP(hipGetLastError());
     return SRFT_OK;
 }

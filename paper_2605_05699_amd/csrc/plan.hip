@@ -474,19 +474,20 @@ int srft_plan_create_ex(srft_plan_t** out, int d, int group_size, int bits, int 
     if (p->fold4_dq) p->unscale_r4 = (float)std::ldexp(1.0, -build_rfold4_table(d, p->signs, lam, bits, rfold4));
     // Butterfly form of the write path (comparison kernel): per packed index lambda times the packing constant of
     // Eq. 2 -- 1/sqrt d for DC and Nyquist, sqrt(2/d) elsewhere, halved where the unpack leaves a factor 2 (every
-    // bin except 0, 32 and 64) -- then the sign diagonal as sign-bit masks of the packed fp16 pairs.
+    // bin except 0, d/4 and d/2) -- then the sign diagonal as sign-bit masks of the packed fp16 pairs.
     std::vector<float> bfly;
-    if (d == 128 && p->gm == kGroup32 && bits == 4 && transform == SRFT_TRANSFORM_DFT) {
-        bfly.resize(128 + 64);
-        for (int k = 0; k < 128; ++k) {
-            const int bin = k < 64 ? k : k - 64;
-            double c = (k == 0 || k == 64) ? 1.0 / std::sqrt(128.0) : std::sqrt(2.0 / 128.0);
-            if (bin != 0 && bin != 32) c *= 0.5;
+    if ((d == 128 || d == 256) && p->gm == kGroup32 && bits == 4 && transform == SRFT_TRANSFORM_DFT) {
+        const int h = d / 2;
+        bfly.resize(d + h);
+        for (int k = 0; k < d; ++k) {
+            const int bin = k < h ? k : k - h;
+            double c = (k == 0 || k == h) ? 1.0 / std::sqrt((double)d) : std::sqrt(2.0 / d);
+            if (bin != 0 && bin != d / 4) c *= 0.5;
             bfly[k] = (float)(lam[k] * c);
         }
-        for (int j = 0; j < 64; ++j) {
+        for (int j = 0; j < h; ++j) {
             const uint32_t m = (p->signs[2 * j] < 0 ? 0x8000u : 0u) | (p->signs[2 * j + 1] < 0 ? 0x80000000u : 0u);
-            std::memcpy(&bfly[128 + j], &m, 4);
+            std::memcpy(&bfly[d + j], &m, 4);
         }
     }
     hipError_t e = hipGetDevice(&p->device);

@@ -27,12 +27,14 @@ def _butterfly(B, plan, x):
     return codes, scales
 
 
-@pytest.mark.parametrize("n", [1, 63, 64, 65, 1003, 70_001])
-def test_butterfly_form_matches_the_oracle(B, n):
-    d, g = 128, 32
-    lam = W.lognormal_lambda(d, seed=n)
-    plan = B.Plan(d, g, 900 + n, lam)
-    xh = W.gaussian_with_outliers(n, d, seed=n, outliers=1, gain=20.0)
+@pytest.mark.parametrize("d,n", [(128, 1), (128, 63), (128, 64), (128, 65), (128, 1003), (128, 70_001),
+                                 (256, 1), (256, 31), (256, 32), (256, 33), (256, 1003), (256, 70_001)])
+def test_butterfly_form_matches_the_oracle(B, d, n):
+    # d = 128: a vector per lane, 64 per step; d = 256: a vector on two lanes, 32 per step
+    g = 32
+    lam = W.lognormal_lambda(d, seed=n + d)
+    plan = B.Plan(d, g, 900 + n + d, lam)
+    xh = W.gaussian_with_outliers(n, d, seed=n + d, outliers=d // 128, gain=20.0)
     x = torch.from_numpy(xh).cuda()
     codes, scales = _butterfly(B, plan, x)
     q = P.check_quantize(xh, plan.signs, lam, g, codes.cpu().numpy(), scales.cpu().numpy())
@@ -66,7 +68,7 @@ def test_butterfly_form_on_the_llama_shaped_workload_and_its_argument_checks(B):
     assert L.srft_kv_quantize_butterfly(plan.handle, None, -1, None, None, None) == -7
     assert L.srft_kv_quantize_butterfly(plan.handle, None, 0, None, None, None) == 0
     assert L.srft_kv_quantize_butterfly(plan.handle, None, 1, None, None, None) == -1
-    other = B.Plan(256, 32, 1)
+    other = B.Plan(96, 32, 1)
     assert L.srft_kv_quantize_butterfly(other.handle, x.data_ptr(), 1, codes.data_ptr(), scales.data_ptr(), None) == -2
     other.close()
     wide = B.Plan(128, 64, 1)
