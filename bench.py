@@ -87,7 +87,8 @@ def main() -> int:
                          "beside dequantizing those keys")
     ap.add_argument("--butterfly", action="store_true",
                     help="also time the write path in its butterfly form (fp32 FFT on the vector ALU, "
-                         "srft_kv_quantize_butterfly; d = 128 only) over the same plans, a launch per plan")
+                         "srft_kv_quantize_butterfly) over the same plans, a launch per plan; also on the d = 256 side "
+                         "measurement unless --no-d256")
     ap.add_argument("--power", action="store_true",
                     help="also run each path at d = 128 and d = 256 (8 x 1,048,576 vectors), on N(0,1) and on all-zero "
                          "data, and the streaming kernel with its byte mix, for about 3 s each while sampling socket "
@@ -236,7 +237,8 @@ def main() -> int:
 
     if w.name == "llama3-70b-128k" and not args.no_d256:
         # the metric names d = 256 beside d = 128: the same launch shape (1,048,576 vectors per plan) at d = 256
-        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream, per_launch_q=per_launch_q, per_launch_d=per_launch_d)
+        result["d256_same_launch_shape"] = side_d256(B, W, torch, dev, stream, per_launch_q=per_launch_q, per_launch_d=per_launch_d,
+                                                     butterfly=args.butterfly)
     if args.butterfly and d == 128 and g == 32:
         def b_pass():
             for p in range(n_plans):
@@ -442,7 +444,8 @@ def all_configs(B, W, torch, dev, stream):
     return res
 
 
-def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10, per_launch_q=16, per_launch_d=4):
+def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10, per_launch_q=16, per_launch_d=4,
+              butterfly=False):
     """Write pass and read pass (plans per launch as in the main step, at most n_plans) over n_plans x n vectors of d = 256, g = 32:
     N(0,1) times a lognormal(0,1) channel scale and lognormal(0,0.5) lambda per plan, as in the d = 256 config.
     `warm` untimed passes of each path precede the `reps` timed ones (about 25 ms each way): after the idle gap in
@@ -493,10 +496,26 @@ def side_d256(B, W, torch, dev, stream, n_plans=8, n=1 << 20, reps=10, warm=10, 
     torch.cuda.synchronize()
     nbytes = n_plans * n * (2 * d + d // 2 + 4 * G)
     tq, td = ev[0].elapsed_time(ev[1]) / reps / 1e3, ev[1].elapsed_time(ev[2]) / reps / 1e3
+    bfly = None
+    if butterfly:                                # the same record through the butterfly form, a launch per plan both ways
+        def b_pass():
+            for p in range(n_plans):
+                B.srft_kv_quantize_butterfly(h[p], x[p], codes[p], scales[p], stream)
+        def m_pass():
+            for p in range(n_plans):
+                B.srft_kv_quantize(h[p], x[p], codes[p], scales[p], stream)
+        tb, _ = timed_passes(torch, stream, b_pass, None, reps, warm=2)
+        tm, _ = timed_passes(torch, stream, m_pass, None, reps, warm=2)
+        bfly = {"what": "the transform as fp32 FFT butterflies on the vector ALU, a vector on two lanes (length-64 FFTs in "
+                        "registers, one decimation step and the Hermitian unpack across the lane pair); a launch per plan",
+                "GBps": nbytes / tb / 1e9, "hbm_frac": nbytes / tb / 1e9 / HBM_PEAK_GBPS,
+                "avg_launch_ms": tb / n_plans * 1e3, "matrix_core_form_GBps": nbytes / tm / 1e9,
+                "ratio_matrix_core_over_butterfly": tb / tm}
     for pl in plans:
         pl.close()
     return {"d": d, "group": g, "plans": n_plans, "vectors_per_plan": n,
             "plans_per_launch": {"quantize": per_launch_q, "dequantize": per_launch_d},
+            **({"quantize_butterfly_form": bfly} if bfly else {}),
             "quantize": {"GBps": nbytes / tq / 1e9, "hbm_frac": nbytes / tq / 1e9 / HBM_PEAK_GBPS,
                          "vectors_per_s": n_plans * n / tq},
             "dequantize": {"GBps": nbytes / td / 1e9, "hbm_frac": nbytes / td / 1e9 / HBM_PEAK_GBPS,

@@ -138,7 +138,8 @@ int srft_kv_dequantize_batched(const srft_plan_t* const* plans, const uint8_t* c
  * length and a Hermitian unpack (Sec. 3.2; the form of the kernel of Sec. 7.1) in place of the matrix-core contraction
  * that srft_kv_quantize uses.  Same arguments and the same record, except that scales_dev must be 16-byte aligned; for
  * plans with d = 128 or 256, g = 32, 4-bit codes and the DFT (else SRFT_ERR_BAD_D / _BAD_GROUP / _BAD_BITS /
- * _BAD_TRANSFORM).  At d = 128 a lane holds a whole vector; at d = 256 two lanes share one and meet through LDS.
+ * _BAD_TRANSFORM).  At d = 128 a lane holds a whole vector; at d = 256 two lanes share one and exchange
+ * registers.
  * It exists so that the two forms can be timed side by side (bench.py --butterfly); it is the slower one on this
  * machine, and codes may differ from srft_kv_quantize's where a value sits at a rounding boundary.
  */

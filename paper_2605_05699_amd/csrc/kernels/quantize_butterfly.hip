@@ -194,29 +194,40 @@ srft_quantize_butterfly_kernel(const float* __restrict__ cl, const uint4* __rest
 // ---- d = 256: one vector on two lanes ------------------------------------------------------------------------
 // 256 fp32 values and the temporaries of the transform do not fit one lane, so lanes l and l + 32 share vector l
 // (32 vectors per wavefront and step).  The complex FFT of length 128 over z_m = u_2m + i u_2m+1 is split by one
-// decimation-in-time step: lane part 0 transforms the even m, part 1 the odd m (each a length-64 FFT in registers,
-// the same code as above), both publish their 64 complex values in LDS, and every pair index j = 0 .. 32 is then
-// worked by both lanes from the same four values A_j, B_j, A_{64-j}, B_{64-j} with the same compile-time twiddles:
+// decimation-in-time step: lane part 0 transforms the even m (A), part 1 the odd m (B), each a length-64 FFT in
+// registers (the same code as above).  One v_permlane32_swap of a register with itself leaves the lower lanes' value
+// and the upper lanes' value in both lanes, so every pair index j = 0 .. 32 is worked by both lanes from the same four
+// values A_j, B_j, A_{64-j}, B_{64-j} with the same compile-time twiddles, without LDS:
 //   Z_j = A_j + W^j B_j,  Z_{64+j} = A_j - W^j B_j,  Z_{64-j} = A_{64-j} + W^{64-j} B_{64-j},  Z_{128-j} = A_{64-j} - ...
 // Part 0 takes the pair of bins (j, 128 - j), part 1 the pair (64 - j, 64 + j), whose unpack twiddle exp(-2 pi i k/256)
-// at k = 64 - j is the one at k = j with cosine and sine exchanged.  Each pair gives four packed values; they land in
-// four groups per lane -- part 0: packed 0..31, 128..159, 96..127, 224..255; part 1: 64..95, 192..223, 32..63, 160..191 --
-// so the quantizer stays inside the lane.  j = 0 gives DC and Nyquist (part 0) and the two values of bin 64 (part 1).
+// at k = 64 - j is the one at k = j with cosine and sine exchanged.  Each pair consumes four registers and gives four
+// packed values; they land in four groups per lane -- part 0: packed 0..31, 128..159, 96..127, 224..255; part 1:
+// 64..95, 192..223, 32..63, 160..191 -- so the quantizer stays inside the lane.  j = 0 gives DC and Nyquist (part 0)
+// and the two values of bin 64 (part 1).
 //
 // cl: 256 floats as for d = 128 (bins 0 and 64 are the ones without the factor 1/2), then 32 x 4 dwords of sign masks.
+
+// the lower lanes' (part 0) and the upper lanes' (part 1) value of v, in every lane
+__device__ __forceinline__ void both_parts(float v, float& lower, float& upper) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    lower = __uint_as_float(r[0]);
+    upper = __uint_as_float(r[1]);
+}
 
 // pair j of the two-lane unpack; X / Xi collect positions j, Y / Yi positions 32 - j of this lane's four groups
 template <int J>
 __device__ __forceinline__ void unpack256(float (&X)[32], float (&Xi)[32], float (&Y)[32], float (&Yi)[32],
-                                          const float* __restrict__ are, const float* __restrict__ aim,
-                                          const float* __restrict__ bre, const float* __restrict__ bim,
+                                          const float (&re)[64], const float (&im)[64],
                                           const float4* __restrict__ clp, bool part) {
     if constexpr (J <= 32) {
         constexpr float c1 = (float)cos_turn(J, 128), s1 = (float)sin_turn(J, 128);            // W_128^J
         constexpr float c2 = (float)cos_turn(64 - J, 128), s2 = (float)sin_turn(64 - J, 128);  // W_128^(64-J)
         constexpr float cu = (float)cos_turn(J, 256), su = (float)sin_turn(J, 256);            // W_256^J
-        const float ar = are[J], ai = aim[J], br = bre[J], bi = bim[J];
-        const float ar2 = are[64 - J], ai2 = aim[64 - J], br2 = bre[64 - J], bi2 = bim[64 - J];
+        float ar, ai, br, bi, ar2, ai2, br2, bi2;
+        both_parts(re[J], ar, br);
+        both_parts(im[J], ai, bi);
+        both_parts(re[64 - J], ar2, br2);
+        both_parts(im[64 - J], ai2, bi2);
         const float tr1 = fmaf(c1, br, s1 * bi), ti1 = fmaf(c1, bi, -s1 * br);
         const float tr2 = fmaf(c2, br2, s2 * bi2), ti2 = fmaf(c2, bi2, -s2 * br2);
         // part 0: (Z_J, Z_{128-J});  part 1: (Z_{64-J}, Z_{64+J})
@@ -234,7 +245,7 @@ __device__ __forceinline__ void unpack256(float (&X)[32], float (&Xi)[32], float
         }
         Y[32 - J] = part ? skr : smr;
         Yi[32 - J] = part ? ski : smi;
-        unpack256<J + 1>(X, Xi, Y, Yi, are, aim, bre, bim, clp, part);
+        unpack256<J + 1>(X, Xi, Y, Yi, re, im, clp, part);
     }
 }
 
@@ -263,17 +274,13 @@ __device__ __forceinline__ void quantize_group32(const float (&z)[32], uint4& pa
     packed = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// (one wavefront per SIMD: within 256 registers the compiler spills 444 bytes and the kernel is a quarter slower)
 __global__ void __launch_bounds__(64, 1)
 srft_quantize_butterfly256_kernel(const float* __restrict__ cl, const uint4* __restrict__ x, long long n_vec,
                                   uint4* __restrict__ codes, float* __restrict__ scales) {
     constexpr int U = 32, ROW = U + 1;           // 16-byte units per input row, padded
-    constexpr int XS = 65;                       // floats per (vector, part) row of the exchange, padded
-    // the input tile (32 rows) and the exchange (64 rows of 64 complex values, real and imaginary planes) take turns
-    __shared__ uint4 buf[2 * 64 * XS / 4];
+    __shared__ uint4 tile[32 * ROW];
     __shared__ float4 clp_s[2][33];
-    uint4* tile = buf;
-    float* xre = reinterpret_cast<float*>(buf);
-    float* xim = xre + 64 * XS;
     const int lane = threadIdx.x, vec = lane & 31;
     const bool part = lane >= 32;
     // constants of the pairs, per part: bins k and 128 - k with k = j (part 0) or 64 - j (part 1); j = 0: bins 0, 128, 64, 192
@@ -287,7 +294,7 @@ srft_quantize_butterfly256_kernel(const float* __restrict__ cl, const uint4* __r
     for (long long blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
         const long long row0 = blk * 32;
         const int lim = (int)min((long long)31, n_vec - 1 - row0);       // rows past the end alias to the last row
-        __syncthreads();                         // the exchange of the previous step has been read
+        __syncthreads();                         // the tile of the previous step has been read
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int u = lane + 64 * i, r = u / U, c = u % U;
@@ -307,37 +314,25 @@ srft_quantize_butterfly256_kernel(const float* __restrict__ cl, const uint4* __r
             re[bit_reverse6(2 * c + 1)] = (float)h1[0];
             im[bit_reverse6(2 * c + 1)] = (float)h1[1];
         }
-        __syncthreads();                         // the tile is read: its memory becomes the exchange
         fft64_stage<2>(re, im);
         fft64_stage<4>(re, im);
         fft64_stage<8>(re, im);
         fft64_stage<16>(re, im);
         fft64_stage<32>(re, im);
         fft64_stage<64>(re, im);
-        {
-            float* wr = xre + lane * XS;         // row (part, vec): lane = 32 part + vec
-            float* wi = xim + lane * XS;
-#pragma unroll
-            for (int k = 0; k < 64; ++k) {
-                wr[k] = re[k];
-                wi[k] = im[k];
-            }
-        }
-        __syncthreads();
-        const float* are = xre + vec * XS;       // A: the even samples' transform (part 0's row), B: the odd samples'
-        const float* aim = xim + vec * XS;
-        const float* bre = xre + (32 + vec) * XS;
-        const float* bim = xim + (32 + vec) * XS;
         const float4* clp = clp_s[part ? 1 : 0];
         float X[32], Xi[32], Y[32], Yi[32];
         {
-            const float pr = are[0] + bre[0], pi = aim[0] + bim[0];       // Z_0
-            const float qr = are[0] - bre[0], qi = aim[0] - bim[0];       // Z_64
+            float a0r, b0r, a0i, b0i;
+            both_parts(re[0], a0r, b0r);
+            both_parts(im[0], a0i, b0i);
+            const float pr = a0r + b0r, pi = a0i + b0i;                   // Z_0
+            const float qr = a0r - b0r, qi = a0i - b0i;                   // Z_64
             const float4 k4 = clp[0];
             X[0] = part ? qr * k4.z : (pr + pi) * k4.x;                   // bin 64 (real part) | DC
             Xi[0] = part ? -qi * k4.w : (pr - pi) * k4.y;                 // bin 64 (imaginary part) | Nyquist
         }
-        unpack256<1>(X, Xi, Y, Yi, are, aim, bre, bim, clp, part);
+        unpack256<1>(X, Xi, Y, Yi, re, im, clp, part);
         uint4 pk[4];
         float sc[4];
         quantize_group32(X, pk[0], sc[0]);
